@@ -1,0 +1,182 @@
+"""CPU oracle for SepAttention.  TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check
+and by bench.py's cpu_baseline leg, never by the product package.
+
+`sepattn_oracle.c` holds the arithmetic (dense, explicit mask; see its header for the passages it
+follows).  This module compiles it with gcc into two shared objects (double and float builds) and
+wraps them with numpy-in / numpy-out functions.  `cache_sim.py` is the host-only cache-size
+simulator of Sec. 3.3.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sepattn_oracle.c")
+_LIBS = {}
+
+
+def lib_path(precision: str) -> str:
+    return os.path.join(_HERE, f"liboracle_{precision}.so")
+
+
+def build(force: bool = False) -> None:
+    """Compile both builds of the oracle with gcc (no GPU toolchain involved)."""
+    for precision, ctype in (("f64", "double"), ("f32", "float")):
+        out = lib_path(precision)
+        if not force and os.path.exists(out) and os.path.getmtime(out) >= os.path.getmtime(_SRC):
+            continue
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", f"-DORACLE_REAL={ctype}",
+               _SRC, "-o", out, "-lm"]
+        subprocess.run(cmd, check=True)
+
+
+def _lib(precision: str):
+    if precision not in _LIBS:
+        if not os.path.exists(lib_path(precision)) or \
+                os.path.getmtime(lib_path(precision)) < os.path.getmtime(_SRC):
+            build()
+        lib = ctypes.CDLL(lib_path(precision))
+        want = 8 if precision == "f64" else 4
+        assert lib.oracle_real_bytes() == want
+        _LIBS[precision] = lib
+    return _LIBS[precision]
+
+
+def _real(precision: str):
+    return np.float64 if precision == "f64" else np.float32
+
+
+def _ptr(x: Optional[np.ndarray]):
+    return None if x is None else x.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(x, dtype) -> np.ndarray:
+    return np.ascontiguousarray(x, dtype=dtype)
+
+
+def mark_separators(token_ids: np.ndarray, sep_ids: np.ndarray) -> np.ndarray:
+    """uint8 [B,L]: 1 where the token id is in sep_ids (Sec. 4.1 "Parameter Setting")."""
+    token_ids = _c(token_ids, np.int32)
+    sep_ids = _c(sep_ids, np.int32)
+    B, L = token_ids.shape
+    out = np.zeros((B, L), dtype=np.uint8)
+    _lib("f64").oracle_mark_separators(_ptr(token_ids), B, L, _ptr(sep_ids), int(sep_ids.size),
+                                       _ptr(out))
+    return out
+
+
+def compact_indices(is_sep: np.ndarray, cap: Optional[int] = None
+                    ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """(sep_idx [B,cap] padded with -1, sep_count [B], sep_prefix [B,L+1])."""
+    is_sep = _c(is_sep, np.uint8)
+    B, L = is_sep.shape
+    cap = L if cap is None else int(cap)
+    idx = np.full((B, max(cap, 1)), -1, dtype=np.int32)
+    cnt = np.zeros((B,), dtype=np.int32)
+    pre = np.zeros((B, L + 1), dtype=np.int32)
+    _lib("f64").oracle_compact_indices(_ptr(is_sep), B, L, _ptr(idx), cap, _ptr(cnt), _ptr(pre))
+    return idx[:, :cap], cnt, pre
+
+
+def mask(is_sep_row: np.ndarray, a: int, n: int, rows: Optional[np.ndarray] = None) -> np.ndarray:
+    """Explicit boolean mask rows [n_rows, L] of one sequence (Sec. 3.1, Eq. 2)."""
+    is_sep_row = _c(is_sep_row, np.uint8)
+    L = is_sep_row.size
+    rows = np.arange(L, dtype=np.int32) if rows is None else _c(rows, np.int32)
+    M = np.zeros((rows.size, L), dtype=np.uint8)
+    _lib("f64").oracle_mask_rows(_ptr(is_sep_row), L, int(a), int(n), _ptr(rows), int(rows.size),
+                                 _ptr(M))
+    return M.astype(bool)
+
+
+def forward(Q, K, V, is_sep, a: int, n: int, scale: float, rows: Optional[np.ndarray] = None,
+            return_A: bool = False, precision: str = "f64"):
+    """Eq. 1 with the mask of Eq. 2.  Returns (O [B,Hq,R,d], LSE [B,Hq,R]) and A [B,Hq,R,L] if asked.
+
+    rows (int32 list) restricts the computation to those query rows; R = len(rows) or L.
+    """
+    rt = _real(precision)
+    Q, K, V = _c(Q, rt), _c(K, rt), _c(V, rt)
+    is_sep = _c(is_sep, np.uint8)
+    B, Hq, L, d = Q.shape
+    Hkv = K.shape[1]
+    assert K.shape == (B, Hkv, L, d) and V.shape == K.shape and is_sep.shape == (B, L)
+    if rows is not None:
+        rows = _c(rows, np.int32)
+        R = int(rows.size)
+    else:
+        R = L
+    O = np.zeros((B, Hq, R, d), dtype=rt)
+    LSE = np.zeros((B, Hq, R), dtype=rt)
+    A = np.zeros((B, Hq, R, L), dtype=rt) if return_A else None
+    fn = _lib(precision).oracle_forward
+    fn.restype = ctypes.c_int
+    rc = fn(_ptr(Q), _ptr(K), _ptr(V), _ptr(is_sep), B, Hq, Hkv, L, d, int(a), int(n),
+            ctypes.c_double(scale), _ptr(rows), R, _ptr(O), _ptr(LSE), _ptr(A))
+    if rc != 0:
+        raise ValueError(f"oracle_forward failed with code {rc}")
+    return (O, LSE, A) if return_A else (O, LSE)
+
+
+def backward(Q, K, V, dO, is_sep, a: int, n: int, scale: float, precision: str = "f64"):
+    """Analytic gradient of Eq. 1: returns (dQ [B,Hq,L,d], dK, dV [B,Hkv,L,d])."""
+    rt = _real(precision)
+    Q, K, V, dO = _c(Q, rt), _c(K, rt), _c(V, rt), _c(dO, rt)
+    is_sep = _c(is_sep, np.uint8)
+    B, Hq, L, d = Q.shape
+    Hkv = K.shape[1]
+    assert dO.shape == Q.shape and V.shape == K.shape
+    dQ = np.zeros_like(Q)
+    dK = np.zeros_like(K)
+    dV = np.zeros_like(V)
+    fn = _lib(precision).oracle_backward
+    fn.restype = ctypes.c_int
+    rc = fn(_ptr(Q), _ptr(K), _ptr(V), _ptr(dO), _ptr(is_sep), B, Hq, Hkv, L, d, int(a), int(n),
+            ctypes.c_double(scale), _ptr(dQ), _ptr(dK), _ptr(dV))
+    if rc != 0:
+        raise ValueError(f"oracle_backward failed with code {rc}")
+    return dQ, dK, dV
+
+
+def decode(q, Kc, Vc, sizes, a: int, s: int, scale: float, precision: str = "f64"):
+    """Single-query attention over every valid entry of the four-block cache (Sec. 3.2 / 3.3)."""
+    rt = _real(precision)
+    q, Kc, Vc = _c(q, rt), _c(Kc, rt), _c(Vc, rt)
+    sizes = _c(sizes, np.int32)
+    S, Hq, d = q.shape
+    _, Hkv, c, _ = Kc.shape
+    out = np.zeros((S, Hq, d), dtype=rt)
+    lse = np.zeros((S, Hq), dtype=rt)
+    fn = _lib(precision).oracle_decode
+    fn.restype = ctypes.c_int
+    rc = fn(_ptr(q), _ptr(Kc), _ptr(Vc), _ptr(sizes), S, Hq, Hkv, d, int(a), int(s), c,
+            ctypes.c_double(scale), _ptr(out), _ptr(lse))
+    if rc != 0:
+        raise ValueError(f"oracle_decode failed with code {rc}")
+    return out, lse
+
+
+def evict_window(Kc: np.ndarray, Vc: np.ndarray, win_is_sep: np.ndarray, sizes: np.ndarray,
+                 a: int, s: int):
+    """Compression step of Sec. 3.3 on copies of the inputs; rows are moved as raw bytes.
+
+    Kc, Vc: [S,Hkv,c,d] of any fixed-width dtype.  Returns (Kc', Vc', win_is_sep', sizes').
+    Slots beyond the new sizes hold unspecified data.
+    """
+    Kc = np.array(Kc, copy=True, order="C")
+    Vc = np.array(Vc, copy=True, order="C")
+    fl = np.array(win_is_sep, dtype=np.uint8, copy=True, order="C")
+    sz = np.array(sizes, dtype=np.int32, copy=True, order="C")
+    S, Hkv, c, d = Kc.shape
+    fn = _lib("f64").oracle_evict_window
+    fn.restype = ctypes.c_int
+    rc = fn(_ptr(Kc), _ptr(Vc), _ptr(fl), _ptr(sz), S, Hkv, int(a), int(s), c,
+            ctypes.c_long(d * Kc.dtype.itemsize))
+    if rc != 0:
+        raise ValueError(f"oracle_evict_window failed with code {rc}")
+    return Kc, Vc, fl, sz

@@ -1,0 +1,192 @@
+/*
+ * sepattn.h -- C ABI of libsepattn: SepAttention (SepLLM, arXiv 2412.12094) on AMD MI355X (gfx950).
+ *
+ * SepAttention is causal softmax attention in which query i sees only
+ *   - the first `a` tokens of its sequence                     (Initial Tokens,     Sec. 3.1),
+ *   - every separator token at or before i                     (Separator Tokens,   Sec. 3.1),
+ *   - its n closest tokens  i-n < j <= i                       (Neighboring Tokens, Sec. 3.1),
+ * i.e. the binary mask M of Eq. 2, applied as in Eq. 1:  A = Softmax(QK^T/sqrt(d_k) | M), O = A V.
+ * The library provides the training / prefill forward and backward of Eq. 1, single-query decode
+ * over the four-block KV cache and the cache compression step of Sec. 3.3 ("Tailored Streaming
+ * Design").
+ *
+ * Conventions common to every call
+ *   - Pointers marked DEVICE address memory of the current HIP device; HOST pointers address
+ *     ordinary host memory.  The caller owns every buffer, including workspaces; the library
+ *     allocates no device memory and keeps no state between calls.
+ *   - Tensors are dense and contiguous with the head dimension d innermost.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls validate their
+ *     arguments synchronously, enqueue their kernels on `stream` and return without waiting.
+ *     Nothing is enqueued when an error is returned.
+ *   - Return value: SEPATTN_OK (0) or a positive sepattn_status.  No call throws or exits.
+ *   - Outputs must not alias inputs, except where a call is documented as in-place.
+ *   - All results are bit-reproducible run to run (no floating-point atomics).
+ */
+#ifndef SEPATTN_H
+#define SEPATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SEPATTN_OK = 0,
+    SEPATTN_ERR_NULL = 1,      /* a required pointer is NULL                                   */
+    SEPATTN_ERR_SHAPE = 2,     /* a size is non-positive, too large, or inconsistent            */
+    SEPATTN_ERR_PARAM = 3,     /* a hyper-parameter is out of range (n < 1, a < 0, a+s+w >= c)  */
+    SEPATTN_ERR_DTYPE = 4,     /* dtype is not a sepattn_dtype / unsupported head dimension     */
+    SEPATTN_ERR_WORKSPACE = 5, /* workspace missing or smaller than *_workspace_bytes reports   */
+    SEPATTN_ERR_CAPACITY = 6,  /* an index list capacity is too small to be usable              */
+    SEPATTN_ERR_HIP = 7        /* the HIP runtime reported an error at launch                   */
+} sepattn_status;
+
+typedef enum {
+    SEPATTN_BF16 = 0, /* bfloat16 storage, fp32 softmax and accumulation, MFMA contractions    */
+    SEPATTN_FP32 = 1  /* fp32 storage and arithmetic: slow debug path                          */
+} sepattn_dtype;
+
+#define SEPATTN_MAX_SEP_IDS 64
+
+/* Static, NUL-terminated description of a status code (HOST pointer, never freed). */
+const char *sepattn_status_string(int status);
+
+/* ------------------------------------------------------------------------------------------
+ * Separator marking (Sec. 4.1 "Parameter Setting": the separator set; a token is a separator
+ * iff its id is in the caller's set).
+ *   token_ids  DEVICE int32 [B, L]
+ *   sep_ids    HOST   int32 [n_sep], 1 <= n_sep <= SEPATTN_MAX_SEP_IDS (copied before returning)
+ *   is_sep     DEVICE uint8 [B, L]  out: 1 for separators, 0 otherwise
+ * ------------------------------------------------------------------------------------------ */
+int sepattn_mark_separators(const int32_t *token_ids, int B, int L, const int32_t *sep_ids,
+                            int n_sep, uint8_t *is_sep, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Separator compaction: the index form of the separator part of mask M (Eq. 2), shared by all
+ * layers and heads of a batch.
+ *   is_sep      DEVICE uint8 [B, L]
+ *   sep_idx     DEVICE int32 [B, cap]  out: ascending separator positions of each sequence;
+ *                                       entries at and beyond min(count, cap) are left untouched
+ *   sep_count   DEVICE int32 [B]       out: true number of separators, even when it exceeds cap
+ *   sep_prefix  DEVICE int32 [B, L+1]  out: sep_prefix[b,j] = number of separators at positions
+ *                                       < j  (exclusive prefix count; sep_prefix[b,L] = count)
+ *   workspace   DEVICE, at least sepattn_compact_workspace_bytes(B, L) bytes, 4-byte aligned
+ * cap >= 1.  A caller that wants forward / backward to see every separator passes cap >= count
+ * (cap = L always suffices).
+ * ------------------------------------------------------------------------------------------ */
+size_t sepattn_compact_workspace_bytes(int B, int L);
+int sepattn_compact_indices(const uint8_t *is_sep, int B, int L, int32_t *sep_idx, int cap,
+                            int32_t *sep_count, int32_t *sep_prefix, void *workspace,
+                            size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Training / prefill attention (Eq. 1 with the mask of Eq. 2).
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+    int B;       /* sequences                                                                  */
+    int Hq;      /* query heads                                                                */
+    int Hkv;     /* key/value heads; Hq % Hkv == 0; query head h reads KV head h / (Hq/Hkv)     */
+    int L;       /* sequence length (the paper's m)                                            */
+    int d;       /* head dimension d_k = d_v: 64 or 128                                        */
+    int a;       /* number of initial tokens kept, a >= 0                                      */
+    int n;       /* number of neighbouring tokens kept, the token itself included, n >= 1      */
+    float scale; /* multiplies QK^T; 1/sqrt(d) in Eq. 1                                        */
+    int dtype;   /* sepattn_dtype of Q, K, V, O, dO, dQ, dK, dV                                */
+    int cap;     /* row pitch of sep_idx                                                       */
+} sepattn_params;
+
+/*   Q          DEVICE dtype [B, Hq,  L, d]
+ *   K, V       DEVICE dtype [B, Hkv, L, d]
+ *   sep_idx, sep_count, sep_prefix   DEVICE, as written by sepattn_compact_indices for the same
+ *                                    (B, L) with pitch p->cap; sep_count[b] <= cap is required
+ *   O          DEVICE dtype [B, Hq, L, d]  out
+ *   LSE        DEVICE fp32  [B, Hq, L]     out: natural log of sum_j exp(scale*<Q_i,K_j>) over the
+ *                                           visible keys j of row i
+ *   ws         DEVICE, >= sepattn_forward_workspace_bytes(p) bytes (may be NULL when that is 0),
+ *              256-byte aligned
+ */
+size_t sepattn_forward_workspace_bytes(const sepattn_params *p);
+int sepattn_forward(const sepattn_params *p, const void *Q, const void *K, const void *V,
+                    const int32_t *sep_idx, const int32_t *sep_count, const int32_t *sep_prefix,
+                    void *O, float *LSE, void *ws, size_t ws_bytes, void *stream);
+
+/* Gradient of Eq. 1 (the paper trains through Sep-Attention, Sec. 4.3; it prints no formula, this
+ * is the analytic gradient): given dO, with D_i = <dO_i, O_i>, A_ij = exp(scale*<Q_i,K_j> - LSE_i):
+ *   dV_j = sum_i A_ij dO_i,  dS_ij = A_ij (<dO_i,V_j> - D_i),
+ *   dQ_i = scale sum_j dS_ij K_j,  dK_j = scale sum_i dS_ij Q_i,
+ * dK and dV of a KV head summed over the Hq/Hkv query heads that read it.  LSE carries no gradient.
+ *   O, LSE     DEVICE, as written by sepattn_forward for the same inputs
+ *   dO         DEVICE dtype [B, Hq, L, d]
+ *   dQ         DEVICE dtype [B, Hq,  L, d]  out
+ *   dK, dV     DEVICE dtype [B, Hkv, L, d]  out
+ *   ws         DEVICE, >= sepattn_backward_workspace_bytes(p) bytes, 256-byte aligned
+ */
+size_t sepattn_backward_workspace_bytes(const sepattn_params *p);
+int sepattn_backward(const sepattn_params *p, const void *Q, const void *K, const void *V,
+                     const void *O, const float *LSE, const void *dO, const int32_t *sep_idx,
+                     const int32_t *sep_count, const int32_t *sep_prefix, void *dQ, void *dK,
+                     void *dV, void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Streaming generation on the four-block KV cache (Sec. 3.3).
+ * Cache layout, per (sequence, KV head): c slots of d values,
+ *     [0, a)       Initial Cache
+ *     [a, a+s)     Separator Cache, oldest first
+ *     [a+s, c)     window: Past Window Cache followed by Local Window Cache, oldest first
+ * sizes[S,4] = (Size_init, Size_sep, Size_past_w, Size_local_w): valid entries of each block,
+ * counted from the start of its slot range (the window's Size_past_w + Size_local_w entries start
+ * at slot a+s).  Requires 0 <= Size_init <= a, 0 <= Size_sep <= s,
+ * Size_past_w + Size_local_w <= c-a-s; sizes are read on the device and not validated there.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+    int S;       /* sequences                                                                  */
+    int Hq;      /* query heads                                                                */
+    int Hkv;     /* key/value heads, Hq % Hkv == 0                                             */
+    int d;       /* head dimension: 64 or 128                                                  */
+    int a;       /* capacity of the Initial Cache                                              */
+    int s;       /* capacity of the Separator Cache                                            */
+    int w;       /* capacity of the Local Window Cache                                         */
+    int c;       /* capacity of the whole cache; a + s + w < c                                 */
+    float scale; /* multiplies q K^T                                                           */
+    int dtype;   /* sepattn_dtype of q, Kc, Vc, out                                            */
+} sepkv_params;
+
+/* One query token per sequence attends to every valid cache entry (Sec. 3.2 "Generation": only
+ * the KV of initial, separator and neighbouring tokens is kept, and all of it is visible).  The
+ * caller appends the current token's K/V before calling.
+ *   q        DEVICE dtype [S, Hq, d]
+ *   Kc, Vc   DEVICE dtype [S, Hkv, c, d]
+ *   sizes    DEVICE int32 [S, 4]; a sequence with no valid entry yields out = 0, lse = -inf
+ *   out      DEVICE dtype [S, Hq, d]  out
+ *   lse      DEVICE fp32  [S, Hq]     out, may be NULL
+ *   ws       DEVICE, >= sepattn_decode_workspace_bytes(p) bytes, 256-byte aligned
+ */
+size_t sepattn_decode_workspace_bytes(const sepkv_params *p);
+int sepattn_decode(const sepkv_params *p, const void *q, const void *Kc, const void *Vc,
+                   const int32_t *sizes, void *out, float *lse, void *ws, size_t ws_bytes,
+                   void *stream);
+
+/* Compression step (Sec. 3.3; caption of the streaming-design figure): the separators of the Past
+ * Window Cache are appended to the Separator Cache, its other entries are dropped, and the Local
+ * Window becomes the whole window.  If the Separator Cache would exceed s, its oldest entries are
+ * dropped first.  IN PLACE; rows are moved bit-exactly.
+ *   Kc, Vc      DEVICE dtype [S, Hkv, c, d]  in/out
+ *   win_is_sep  DEVICE uint8 [S, c-a-s]      in/out: separator flag of each window slot; the
+ *                                            flags of the surviving Local Window move with it
+ *   sizes       DEVICE int32 [S, 4]          in/out: becomes (Size_init,
+ *                                            min(s, Size_sep + k), 0, Size_local_w), k = number
+ *                                            of flagged Past-Window entries
+ *   ws          DEVICE, >= sepkv_evict_workspace_bytes(p) bytes, 256-byte aligned
+ * Slots beyond the new sizes hold unspecified data afterwards.  The caller decides when to call
+ * (the paper triggers it when Size_run reaches c).
+ */
+size_t sepkv_evict_workspace_bytes(const sepkv_params *p);
+int sepkv_evict_window(const sepkv_params *p, void *Kc, void *Vc, uint8_t *win_is_sep,
+                       int32_t *sizes, void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SEPATTN_H */

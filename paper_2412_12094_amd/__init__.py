@@ -1,0 +1,23 @@
+"""SepAttention (SepLLM, arXiv 2412.12094) for AMD MI355X: hand-written HIP kernels behind a C ABI.
+
+`csrc/` holds the kernels and the C entry points declared in include/sepattn.h; `binding.py` is the
+ctypes binding with the same names; `build.py` compiles libsepattn.so in-tree with hipcc for gfx950.
+"""
+from .binding import (  # noqa: F401
+    EXPORTS,
+    LIB_PATH,
+    SEPATTN_BF16,
+    SEPATTN_FP32,
+    SepattnError,
+    SepattnParams,
+    SepkvParams,
+    load,
+    status_string,
+    sepattn_mark_separators,
+    sepattn_compact_indices,
+    sepattn_forward,
+    sepattn_backward,
+    sepattn_backward_workspace_bytes,
+    sepattn_decode,
+    sepkv_evict_window,
+)

@@ -1,0 +1,265 @@
+"""Thin ctypes binding of libsepattn.so: argument marshalling only.
+
+Each function has the name and the semantics of the C entry point declared in include/sepattn.h and
+takes torch tensors that already live on the GPU (torch is used for device memory and streams,
+nothing else).  Workspaces are allocated here with torch and handed to the library, which never
+allocates.  Every step of the computation runs in the library's HIP kernels; if the library is
+missing this module raises at load time: there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsepattn.so")
+
+SEPATTN_BF16 = 0
+SEPATTN_FP32 = 1
+
+EXPORTS = (
+    "sepattn_status_string",
+    "sepattn_mark_separators",
+    "sepattn_compact_workspace_bytes",
+    "sepattn_compact_indices",
+    "sepattn_forward_workspace_bytes",
+    "sepattn_forward",
+    "sepattn_backward_workspace_bytes",
+    "sepattn_backward",
+    "sepattn_decode_workspace_bytes",
+    "sepattn_decode",
+    "sepkv_evict_workspace_bytes",
+    "sepkv_evict_window",
+)
+
+
+class SepattnParams(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int), ("Hq", ctypes.c_int), ("Hkv", ctypes.c_int), ("L", ctypes.c_int),
+                ("d", ctypes.c_int), ("a", ctypes.c_int), ("n", ctypes.c_int), ("scale", ctypes.c_float),
+                ("dtype", ctypes.c_int), ("cap", ctypes.c_int)]
+
+
+class SepkvParams(ctypes.Structure):
+    _fields_ = [("S", ctypes.c_int), ("Hq", ctypes.c_int), ("Hkv", ctypes.c_int), ("d", ctypes.c_int),
+                ("a", ctypes.c_int), ("s", ctypes.c_int), ("w", ctypes.c_int), ("c", ctypes.c_int),
+                ("scale", ctypes.c_float), ("dtype", ctypes.c_int)]
+
+
+class SepattnError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        self.status = status
+        super().__init__(f"{fn} failed: status {status} ({status_string(status)})")
+
+
+_lib = None
+
+
+def load(path: Optional[str] = None):
+    """Load the shared library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or LIB_PATH
+    if not os.path.exists(path):
+        raise FileNotFoundError(
+            f"{path} not found: build it with `python -m paper_2412_12094_amd.build` (hipcc, gfx950)")
+    lib = ctypes.CDLL(path)
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.sepattn_status_string.restype = ctypes.c_char_p
+    lib.sepattn_status_string.argtypes = [ci]
+    lib.sepattn_mark_separators.restype = ci
+    lib.sepattn_mark_separators.argtypes = [vp, ci, ci, vp, ci, vp, vp]
+    lib.sepattn_compact_workspace_bytes.restype = sz
+    lib.sepattn_compact_workspace_bytes.argtypes = [ci, ci]
+    lib.sepattn_compact_indices.restype = ci
+    lib.sepattn_compact_indices.argtypes = [vp, ci, ci, vp, ci, vp, vp, vp, sz, vp]
+    pp = ctypes.POINTER(SepattnParams)
+    lib.sepattn_forward_workspace_bytes.restype = sz
+    lib.sepattn_forward_workspace_bytes.argtypes = [pp]
+    lib.sepattn_forward.restype = ci
+    lib.sepattn_forward.argtypes = [pp] + [vp] * 9 + [sz, vp]
+    lib.sepattn_backward_workspace_bytes.restype = sz
+    lib.sepattn_backward_workspace_bytes.argtypes = [pp]
+    lib.sepattn_backward.restype = ci
+    lib.sepattn_backward.argtypes = [pp] + [vp] * 13 + [sz, vp]
+    kp = ctypes.POINTER(SepkvParams)
+    lib.sepattn_decode_workspace_bytes.restype = sz
+    lib.sepattn_decode_workspace_bytes.argtypes = [kp]
+    lib.sepattn_decode.restype = ci
+    lib.sepattn_decode.argtypes = [kp] + [vp] * 7 + [sz, vp]
+    lib.sepkv_evict_workspace_bytes.restype = sz
+    lib.sepkv_evict_workspace_bytes.argtypes = [kp]
+    lib.sepkv_evict_window.restype = ci
+    lib.sepkv_evict_window.argtypes = [kp] + [vp] * 5 + [sz, vp]
+    if path == LIB_PATH or _lib is None:
+        _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().sepattn_status_string(int(status)).decode()
+
+
+def _check(fn: str, rc: int) -> None:
+    if rc != 0:
+        raise SepattnError(fn, rc)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(t: torch.Tensor):
+    return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+def _ws(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return SEPATTN_BF16
+    if t.dtype == torch.float32:
+        return SEPATTN_FP32
+    raise TypeError(f"unsupported dtype {t.dtype}: bf16 or fp32 expected")
+
+
+def _dev(*ts: torch.Tensor) -> None:
+    for t in ts:
+        if t is None:
+            continue
+        if not t.is_cuda:
+            raise ValueError("libsepattn works on GPU tensors only")
+        if not t.is_contiguous():
+            raise ValueError("tensors must be contiguous")
+
+
+# ------------------------------------------------------------------------------------------------
+def sepattn_mark_separators(token_ids: torch.Tensor, sep_ids) -> torch.Tensor:
+    """token_ids int32 [B,L] (GPU), sep_ids: host sequence of ints -> is_sep uint8 [B,L]."""
+    _dev(token_ids)
+    assert token_ids.dtype == torch.int32 and token_ids.dim() == 2
+    B, L = token_ids.shape
+    ids = (ctypes.c_int32 * len(sep_ids))(*[int(x) for x in sep_ids])
+    out = torch.empty((B, L), dtype=torch.uint8, device=token_ids.device)
+    _check("sepattn_mark_separators",
+           load().sepattn_mark_separators(_ptr(token_ids), B, L, ctypes.cast(ids, ctypes.c_void_p),
+                                          len(sep_ids), _ptr(out), _stream(token_ids)))
+    return out
+
+
+def sepattn_compact_indices(is_sep: torch.Tensor, cap: Optional[int] = None, want_prefix: bool = True,
+                            fill: int = -1) -> Tuple[torch.Tensor, torch.Tensor, Optional[torch.Tensor]]:
+    """is_sep uint8 [B,L] -> (sep_idx int32 [B,cap], sep_count int32 [B], sep_prefix int32 [B,L+1]).
+
+    sep_idx is pre-filled with `fill` by torch; the library leaves entries beyond the count untouched.
+    """
+    _dev(is_sep)
+    assert is_sep.dtype == torch.uint8 and is_sep.dim() == 2
+    B, L = is_sep.shape
+    cap = L if cap is None else int(cap)
+    dev = is_sep.device
+    idx = torch.full((B, max(cap, 1)), fill, dtype=torch.int32, device=dev)
+    cnt = torch.empty((B,), dtype=torch.int32, device=dev)
+    pre = torch.empty((B, L + 1), dtype=torch.int32, device=dev) if want_prefix else None
+    lib = load()
+    ws = _ws(lib.sepattn_compact_workspace_bytes(B, L), dev)
+    _check("sepattn_compact_indices",
+           lib.sepattn_compact_indices(_ptr(is_sep), B, L, _ptr(idx), cap, _ptr(cnt), _ptr(pre), _ptr(ws),
+                                       ws.numel(), _stream(is_sep)))
+    return idx, cnt, pre
+
+
+def _attn_params(Q, K, a, n, scale, cap) -> SepattnParams:
+    B, Hq, L, d = Q.shape
+    Hkv = K.shape[1]
+    return SepattnParams(B, Hq, Hkv, L, d, int(a), int(n), float(scale), _dtype_code(Q), int(cap))
+
+
+def sepattn_forward(Q, K, V, sep_idx, sep_count, sep_prefix, a: int, n: int, scale: float,
+                    out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None, ws: Optional[torch.Tensor] = None):
+    """Q [B,Hq,L,d], K,V [B,Hkv,L,d] -> (O like Q, LSE fp32 [B,Hq,L])."""
+    _dev(Q, K, V, sep_idx, sep_count, sep_prefix)
+    assert K.shape == V.shape and Q.dtype == K.dtype == V.dtype
+    p = _attn_params(Q, K, a, n, scale, sep_idx.shape[1])
+    lib = load()
+    if out is None:
+        O = torch.empty_like(Q)
+        LSE = torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device)
+    else:
+        O, LSE = out
+    if ws is None:
+        ws = _ws(lib.sepattn_forward_workspace_bytes(ctypes.byref(p)), Q.device)
+    _check("sepattn_forward",
+           lib.sepattn_forward(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(sep_idx), _ptr(sep_count),
+                               _ptr(sep_prefix), _ptr(O), _ptr(LSE), _ptr(ws), ws.numel(), _stream(Q)))
+    return O, LSE
+
+
+def sepattn_backward_workspace_bytes(Q, K, a: int, n: int, scale: float, cap: int) -> int:
+    p = _attn_params(Q, K, a, n, scale, cap)
+    return int(load().sepattn_backward_workspace_bytes(ctypes.byref(p)))
+
+
+def sepattn_backward(Q, K, V, O, LSE, dO, sep_idx, sep_count, sep_prefix, a: int, n: int, scale: float,
+                     out: Optional[Tuple[torch.Tensor, torch.Tensor, torch.Tensor]] = None,
+                     ws: Optional[torch.Tensor] = None):
+    """-> (dQ like Q, dK like K, dV like V)."""
+    _dev(Q, K, V, O, LSE, dO, sep_idx, sep_count, sep_prefix)
+    p = _attn_params(Q, K, a, n, scale, sep_idx.shape[1])
+    lib = load()
+    if out is None:
+        dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    else:
+        dQ, dK, dV = out
+    if ws is None:
+        ws = _ws(lib.sepattn_backward_workspace_bytes(ctypes.byref(p)), Q.device)
+    _check("sepattn_backward",
+           lib.sepattn_backward(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(dO),
+                                _ptr(sep_idx), _ptr(sep_count), _ptr(sep_prefix), _ptr(dQ), _ptr(dK),
+                                _ptr(dV), _ptr(ws), ws.numel(), _stream(Q)))
+    return dQ, dK, dV
+
+
+def _kv_params(q, Kc, a, s, w, scale) -> SepkvParams:
+    S, Hq, d = q.shape
+    _, Hkv, c, _ = Kc.shape
+    return SepkvParams(S, Hq, Hkv, d, int(a), int(s), int(w), c, float(scale), _dtype_code(Kc))
+
+
+def sepattn_decode(q, Kc, Vc, sizes, a: int, s: int, w: int, scale: float,
+                   out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None, ws: Optional[torch.Tensor] = None):
+    """q [S,Hq,d], Kc,Vc [S,Hkv,c,d], sizes int32 [S,4] -> (out [S,Hq,d], lse fp32 [S,Hq])."""
+    _dev(q, Kc, Vc, sizes)
+    assert sizes.dtype == torch.int32
+    p = _kv_params(q, Kc, a, s, w, scale)
+    lib = load()
+    if out is None:
+        o = torch.empty_like(q)
+        lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
+    else:
+        o, lse = out
+    if ws is None:
+        ws = _ws(lib.sepattn_decode_workspace_bytes(ctypes.byref(p)), q.device)
+    _check("sepattn_decode",
+           lib.sepattn_decode(ctypes.byref(p), _ptr(q), _ptr(Kc), _ptr(Vc), _ptr(sizes), _ptr(o), _ptr(lse),
+                              _ptr(ws), ws.numel(), _stream(q)))
+    return o, lse
+
+
+def sepkv_evict_window(Kc, Vc, win_is_sep, sizes, Hq: int, a: int, s: int, w: int,
+                       ws: Optional[torch.Tensor] = None) -> None:
+    """In place on Kc, Vc [S,Hkv,c,d], win_is_sep uint8 [S,c-a-s], sizes int32 [S,4]."""
+    _dev(Kc, Vc, win_is_sep, sizes)
+    S, Hkv, c, d = Kc.shape
+    p = SepkvParams(S, int(Hq), Hkv, d, int(a), int(s), int(w), c, 1.0, _dtype_code(Kc))
+    lib = load()
+    if ws is None:
+        ws = _ws(lib.sepkv_evict_workspace_bytes(ctypes.byref(p)), Kc.device)
+    _check("sepkv_evict_window",
+           lib.sepkv_evict_window(ctypes.byref(p), _ptr(Kc), _ptr(Vc), _ptr(win_is_sep), _ptr(sizes), _ptr(ws),
+                                  ws.numel(), _stream(Kc)))

@@ -1,0 +1,177 @@
+// C ABI of libsepattn: argument validation and dispatch.  Every entry point checks its arguments
+// on the host before anything is enqueued, so a kernel never sees a shape its indexing does not
+// cover.
+#include "common.h"
+
+using namespace sepattn;
+
+namespace {
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int check_attn(const sepattn_params *p) {
+    if (!p) return SEPATTN_ERR_NULL;
+    if (p->B <= 0 || p->Hq <= 0 || p->Hkv <= 0 || p->L <= 0) return SEPATTN_ERR_SHAPE;
+    if (p->Hq % p->Hkv != 0) return SEPATTN_ERR_SHAPE;
+    if (p->d != 64 && p->d != 128) return SEPATTN_ERR_DTYPE;
+    if (p->dtype != SEPATTN_BF16 && p->dtype != SEPATTN_FP32) return SEPATTN_ERR_DTYPE;
+    if (p->a < 0 || p->n < 1) return SEPATTN_ERR_PARAM;
+    if (!(p->scale == p->scale) || p->scale <= 0.f) return SEPATTN_ERR_PARAM;
+    if (p->cap < 1) return SEPATTN_ERR_CAPACITY;
+    // index arithmetic inside the kernels uses 32-bit positions and 64-bit offsets
+    if ((long)p->B * p->Hq * p->L > (1L << 40)) return SEPATTN_ERR_SHAPE;
+    if ((long)p->B * p->Hq > 65535L) return SEPATTN_ERR_SHAPE;  // second grid dimension
+    return SEPATTN_OK;
+}
+
+// a and n beyond L change nothing in the mask; clamping keeps position arithmetic in range
+sepattn_params normalised(const sepattn_params *p) {
+    sepattn_params q = *p;
+    if (q.n > q.L) q.n = q.L;
+    if (q.a > q.L) q.a = q.L;
+    return q;
+}
+
+int check_kv(const sepkv_params *p) {
+    if (!p) return SEPATTN_ERR_NULL;
+    if (p->S <= 0 || p->Hq <= 0 || p->Hkv <= 0 || p->c <= 0) return SEPATTN_ERR_SHAPE;
+    if (p->Hq % p->Hkv != 0) return SEPATTN_ERR_SHAPE;
+    if (p->d != 64 && p->d != 128) return SEPATTN_ERR_DTYPE;
+    if (p->dtype != SEPATTN_BF16 && p->dtype != SEPATTN_FP32) return SEPATTN_ERR_DTYPE;
+    if (p->a < 0 || p->s < 0 || p->w < 1) return SEPATTN_ERR_PARAM;
+    if ((long)p->a + p->s + p->w >= (long)p->c) return SEPATTN_ERR_PARAM;
+    if (!(p->scale == p->scale) || p->scale <= 0.f) return SEPATTN_ERR_PARAM;
+    if ((long)p->S * p->Hq > 65535L) return SEPATTN_ERR_SHAPE;  // second grid dimension
+    return SEPATTN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *sepattn_status_string(int status) {
+    switch (status) {
+        case SEPATTN_OK: return "ok";
+        case SEPATTN_ERR_NULL: return "a required pointer is NULL";
+        case SEPATTN_ERR_SHAPE: return "invalid or inconsistent shape";
+        case SEPATTN_ERR_PARAM: return "hyper-parameter out of range or misaligned buffer";
+        case SEPATTN_ERR_DTYPE: return "unsupported dtype or head dimension";
+        case SEPATTN_ERR_WORKSPACE: return "workspace missing or too small";
+        case SEPATTN_ERR_CAPACITY: return "index list capacity too small";
+        case SEPATTN_ERR_HIP: return "HIP runtime error at kernel launch";
+        default: return "unknown status";
+    }
+}
+
+int sepattn_mark_separators(const int32_t *token_ids, int B, int L, const int32_t *sep_ids,
+                            int n_sep, uint8_t *is_sep, void *stream) {
+    if (!token_ids || !sep_ids || !is_sep) return SEPATTN_ERR_NULL;
+    if (B <= 0 || L <= 0) return SEPATTN_ERR_SHAPE;
+    if (n_sep < 1 || n_sep > SEPATTN_MAX_SEP_IDS) return SEPATTN_ERR_PARAM;
+    if (!aligned(token_ids, 16) || !aligned(is_sep, 4)) return SEPATTN_ERR_PARAM;
+    SepIdSet set;
+    set.n = n_sep;
+    for (int k = 0; k < SEPATTN_MAX_SEP_IDS; ++k) set.ids[k] = k < n_sep ? sep_ids[k] : sep_ids[0];
+    return launch_mark(token_ids, (long)B * L, set, is_sep, static_cast<hipStream_t>(stream));
+}
+
+size_t sepattn_compact_workspace_bytes(int B, int L) {
+    if (B <= 0 || L <= 0) return 0;
+    size_t n_chunks = ((size_t)L + kCompactChunk - 1) / kCompactChunk;
+    return align_up((size_t)B * n_chunks * sizeof(int32_t), 256);
+}
+
+int sepattn_compact_indices(const uint8_t *is_sep, int B, int L, int32_t *sep_idx, int cap,
+                            int32_t *sep_count, int32_t *sep_prefix, void *workspace,
+                            size_t workspace_bytes, void *stream) {
+    if (!is_sep || !sep_idx || !sep_count) return SEPATTN_ERR_NULL;
+    if (B <= 0 || L <= 0 || B > 65535) return SEPATTN_ERR_SHAPE;
+    if (cap < 1) return SEPATTN_ERR_CAPACITY;
+    if (!workspace || workspace_bytes < sepattn_compact_workspace_bytes(B, L) || !aligned(workspace, 4))
+        return SEPATTN_ERR_WORKSPACE;
+    return launch_compact(is_sep, B, L, sep_idx, cap, sep_count, sep_prefix,
+                          static_cast<int32_t *>(workspace), static_cast<hipStream_t>(stream));
+}
+
+size_t sepattn_forward_workspace_bytes(const sepattn_params *p) {
+    if (check_attn(p) != SEPATTN_OK) return 0;
+    return p->dtype == SEPATTN_BF16 ? forward_bf16_workspace(normalised(p)) : 0;
+}
+
+int sepattn_forward(const sepattn_params *p, const void *Q, const void *K, const void *V,
+                    const int32_t *sep_idx, const int32_t *sep_count, const int32_t *sep_prefix,
+                    void *O, float *LSE, void *ws, size_t ws_bytes, void *stream) {
+    int rc = check_attn(p);
+    if (rc != SEPATTN_OK) return rc;
+    if (!Q || !K || !V || !sep_idx || !sep_count || !sep_prefix || !O || !LSE) return SEPATTN_ERR_NULL;
+    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16)) return SEPATTN_ERR_PARAM;
+    size_t need = sepattn_forward_workspace_bytes(p);
+    if (need > 0 && (!ws || ws_bytes < need || !aligned(ws, 256))) return SEPATTN_ERR_WORKSPACE;
+    sepattn_params q = normalised(p);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (q.dtype == SEPATTN_FP32)
+        return launch_forward_fp32(q, (const float *)Q, (const float *)K, (const float *)V, sep_idx,
+                                   sep_prefix, (float *)O, LSE, st);
+    return launch_forward_bf16(q, Q, K, V, sep_idx, sep_prefix, O, LSE, ws, st);
+}
+
+size_t sepattn_backward_workspace_bytes(const sepattn_params *p) {
+    if (check_attn(p) != SEPATTN_OK) return 0;
+    if (p->dtype == SEPATTN_FP32) return align_up((size_t)p->B * p->Hq * p->L * sizeof(float), 256);
+    return backward_bf16_workspace(normalised(p));
+}
+
+int sepattn_backward(const sepattn_params *p, const void *Q, const void *K, const void *V,
+                     const void *O, const float *LSE, const void *dO, const int32_t *sep_idx,
+                     const int32_t *sep_count, const int32_t *sep_prefix, void *dQ, void *dK,
+                     void *dV, void *ws, size_t ws_bytes, void *stream) {
+    int rc = check_attn(p);
+    if (rc != SEPATTN_OK) return rc;
+    if (!Q || !K || !V || !O || !LSE || !dO || !sep_idx || !sep_count || !sep_prefix || !dQ || !dK || !dV)
+        return SEPATTN_ERR_NULL;
+    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) || !aligned(dO, 16) ||
+        !aligned(dQ, 16) || !aligned(dK, 16) || !aligned(dV, 16))
+        return SEPATTN_ERR_PARAM;
+    size_t need = sepattn_backward_workspace_bytes(p);
+    if (!ws || ws_bytes < need || !aligned(ws, 256)) return SEPATTN_ERR_WORKSPACE;
+    sepattn_params q = normalised(p);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (q.dtype == SEPATTN_FP32)
+        return launch_backward_fp32(q, (const float *)Q, (const float *)K, (const float *)V,
+                                    (const float *)O, LSE, (const float *)dO, sep_idx, sep_prefix,
+                                    (float *)dQ, (float *)dK, (float *)dV, (float *)ws, st);
+    return launch_backward_bf16(q, Q, K, V, O, LSE, dO, sep_idx, sep_count, sep_prefix, dQ, dK, dV, ws, st);
+}
+
+size_t sepattn_decode_workspace_bytes(const sepkv_params *p) {
+    if (check_kv(p) != SEPATTN_OK) return 0;
+    return decode_workspace(*p);
+}
+
+int sepattn_decode(const sepkv_params *p, const void *q, const void *Kc, const void *Vc,
+                   const int32_t *sizes, void *out, float *lse, void *ws, size_t ws_bytes,
+                   void *stream) {
+    int rc = check_kv(p);
+    if (rc != SEPATTN_OK) return rc;
+    if (!q || !Kc || !Vc || !sizes || !out) return SEPATTN_ERR_NULL;
+    if (!aligned(q, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(out, 16)) return SEPATTN_ERR_PARAM;
+    if (!ws || ws_bytes < decode_workspace(*p) || !aligned(ws, 256)) return SEPATTN_ERR_WORKSPACE;
+    return launch_decode(*p, q, Kc, Vc, sizes, out, lse, ws, static_cast<hipStream_t>(stream));
+}
+
+size_t sepkv_evict_workspace_bytes(const sepkv_params *p) {
+    if (check_kv(p) != SEPATTN_OK) return 0;
+    return evict_workspace(*p);
+}
+
+int sepkv_evict_window(const sepkv_params *p, void *Kc, void *Vc, uint8_t *win_is_sep,
+                       int32_t *sizes, void *ws, size_t ws_bytes, void *stream) {
+    int rc = check_kv(p);
+    if (rc != SEPATTN_OK) return rc;
+    if (!Kc || !Vc || !win_is_sep || !sizes) return SEPATTN_ERR_NULL;
+    if (!aligned(Kc, 16) || !aligned(Vc, 16)) return SEPATTN_ERR_PARAM;
+    if (!ws || ws_bytes < evict_workspace(*p) || !aligned(ws, 256)) return SEPATTN_ERR_WORKSPACE;
+    return launch_evict(*p, Kc, Vc, win_is_sep, sizes, ws, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

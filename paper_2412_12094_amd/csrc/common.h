@@ -1,0 +1,57 @@
+// Internal declarations shared by the HIP sources of libsepattn (not part of the public ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "sepattn.h"
+
+namespace sepattn {
+
+constexpr int kWave = 64;
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? SEPATTN_OK : SEPATTN_ERR_HIP; }
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- integer kernels -------------------------------------------------------------------------
+struct SepIdSet {
+    int n;
+    int ids[SEPATTN_MAX_SEP_IDS];
+};
+int launch_mark(const int32_t *token_ids, long n_tokens, const SepIdSet &set, uint8_t *is_sep,
+                hipStream_t st);
+constexpr int kCompactChunk = 2048;  // tokens per workgroup of the compaction kernels
+int launch_compact(const uint8_t *is_sep, int B, int L, int32_t *sep_idx, int cap,
+                   int32_t *sep_count, int32_t *sep_prefix, int32_t *chunk_counts, hipStream_t st);
+
+// ---- fp32 debug path ---------------------------------------------------------------------------
+int launch_forward_fp32(const sepattn_params &p, const float *Q, const float *K, const float *V,
+                        const int32_t *sep_idx, const int32_t *sep_prefix, float *O, float *LSE,
+                        hipStream_t st);
+int launch_backward_fp32(const sepattn_params &p, const float *Q, const float *K, const float *V,
+                         const float *O, const float *LSE, const float *dO, const int32_t *sep_idx,
+                         const int32_t *sep_prefix, float *dQ, float *dK, float *dV, float *Dws,
+                         hipStream_t st);
+
+// ---- bf16 MFMA path ----------------------------------------------------------------------------
+size_t forward_bf16_workspace(const sepattn_params &p);
+int launch_forward_bf16(const sepattn_params &p, const void *Q, const void *K, const void *V,
+                        const int32_t *sep_idx, const int32_t *sep_prefix, void *O, float *LSE,
+                        void *ws, hipStream_t st);
+size_t backward_bf16_workspace(const sepattn_params &p);
+int launch_backward_bf16(const sepattn_params &p, const void *Q, const void *K, const void *V,
+                         const void *O, const float *LSE, const void *dO, const int32_t *sep_idx,
+                         const int32_t *sep_count, const int32_t *sep_prefix, void *dQ, void *dK,
+                         void *dV, void *ws, hipStream_t st);
+
+// ---- streaming cache ---------------------------------------------------------------------------
+size_t decode_workspace(const sepkv_params &p);
+int launch_decode(const sepkv_params &p, const void *q, const void *Kc, const void *Vc,
+                  const int32_t *sizes, void *out, float *lse, void *ws, hipStream_t st);
+size_t evict_workspace(const sepkv_params &p);
+int launch_evict(const sepkv_params &p, void *Kc, void *Vc, uint8_t *win_is_sep, int32_t *sizes,
+                 void *ws, hipStream_t st);
+
+}  // namespace sepattn

@@ -1,0 +1,73 @@
+// The dense key stream of one query tile (used by the forward and the dQ kernels).
+//
+// For query positions [i0, i0+TP) the visible keys are enumerated as one stream
+//     [ initial tokens j < min(a, bs) | separators in [min(a,bs), bs) | band keys bs .. i0+TP-1 ]
+// with bs = max(0, i0-n+1), the first key of the first row's neighbour window (Sec. 3.1).  Elements
+// of the first two parts are visible to every row of the tile; a band key j is visible to query i
+// iff  j <= i  and  (i-j < n  or  j is an initial token or a separator)  (Eq. 2).  Each stream
+// element carries the inclusive query range [lo, hi] that sees it, so the test is lo <= i <= hi.
+#pragma once
+
+#include "common.h"
+#include "mfma_common.h"
+
+namespace sepattn {
+
+constexpr int kBN = 64;  // keys per LDS tile
+
+struct Stream {
+    int n_init, n_dense, n_total, sep_lo, bs;
+};
+
+__device__ inline Stream make_stream(const sepattn_params &p, const int32_t *__restrict__ prefix, int i0,
+                                     int tile_positions) {
+    Stream st;
+    st.bs = max(0, i0 - p.n + 1);
+    st.n_init = min(p.a, st.bs);
+    st.sep_lo = prefix[st.n_init];
+    st.n_dense = st.n_init + (prefix[st.bs] - st.sep_lo);
+    st.n_total = st.n_dense + (min(p.L, i0 + tile_positions) - st.bs);
+    return st;
+}
+
+// key position of stream element k, and the query range [lo, hi] that sees it
+__device__ inline int stream_key(const Stream &s, int k, const sepattn_params &p,
+                                 const int32_t *__restrict__ idx, const int32_t *__restrict__ prefix,
+                                 int &lo, int &hi) {
+    if (k >= s.n_total) {  // padding of the last tile: never visible, any valid row to load
+        lo = kIntMax;
+        hi = -1;
+        return 0;
+    }
+    int j;
+    if (k < s.n_init) {
+        j = k;
+        hi = kIntMax;
+    } else if (k < s.n_dense) {
+        // the clamps keep a stale list tail (caller broke sep_count <= cap) from faulting
+        j = min(max(idx[min(s.sep_lo + k - s.n_init, p.cap - 1)], 0), p.L - 1);
+        hi = kIntMax;
+    } else {
+        j = s.bs + (k - s.n_dense);
+        bool always = (j < p.a) || (prefix[j + 1] != prefix[j]);
+        hi = always ? kIntMax : j + p.n - 1;
+    }
+    lo = j;
+    return j;
+}
+
+// how a wave treats a block of 32 stream elements starting at k0, given its rows [pw, pw+31]:
+// 0 = skip (nothing visible), 1 = everything visible, 2 = test each pair
+__device__ inline int block_mode(const Stream &st, int k0, int pw, int n) {
+    int pmax = pw + 31;
+    if (k0 + 32 <= st.n_dense) return 1;
+    if (k0 >= st.n_dense) {
+        int jmin = st.bs + (k0 - st.n_dense), jmax = jmin + 31;
+        if (k0 >= st.n_total || jmin > pmax) return 0;
+        if (k0 + 32 <= st.n_total && jmax <= pw && jmin + n - 1 >= pmax) return 1;
+        return 2;
+    }
+    return 2;
+}
+
+}  // namespace sepattn

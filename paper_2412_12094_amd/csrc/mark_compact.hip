@@ -1,0 +1,144 @@
+// Separator marking and compaction (integer kernels).
+//
+// mark:    is_sep[t] = token_ids[t] in S, S = the caller's separator id set (Sec. 4.1 "Parameter
+//          Setting").  One thread per four tokens, the id set travels in the kernel arguments.
+// compact: the index form of the separator part of mask M (Eq. 2): ascending separator positions,
+//          their count and the exclusive prefix count per sequence.  Two passes over chunks of
+//          2048 tokens: (1) per-chunk separator counts, (2) each chunk sums the counts of the
+//          chunks before it, ranks its own separators with wave ballots + a block prefix sum over
+//          the per-wave counts, and writes prefix / index entries.  No atomics, so the output
+//          order is the position order by construction.
+#include "common.h"
+
+namespace sepattn {
+
+__global__ __launch_bounds__(256) void mark_kernel(const int32_t *__restrict__ ids, long n,
+                                                   SepIdSet set, uint8_t *__restrict__ out) {
+    long t4 = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (t4 >= n) return;
+    if (t4 + 4 <= n) {
+        int4 v = *reinterpret_cast<const int4 *>(ids + t4);
+        unsigned f0 = 0, f1 = 0, f2 = 0, f3 = 0;
+        for (int k = 0; k < set.n; ++k) {
+            int s = set.ids[k];
+            f0 |= (v.x == s);
+            f1 |= (v.y == s);
+            f2 |= (v.z == s);
+            f3 |= (v.w == s);
+        }
+        *reinterpret_cast<uint32_t *>(out + t4) = f0 | (f1 << 8) | (f2 << 16) | (f3 << 24);
+    } else {
+        for (long t = t4; t < n; ++t) {
+            unsigned f = 0;
+            for (int k = 0; k < set.n; ++k) f |= (ids[t] == set.ids[k]);
+            out[t] = (uint8_t)f;
+        }
+    }
+}
+
+int launch_mark(const int32_t *token_ids, long n_tokens, const SepIdSet &set, uint8_t *is_sep,
+                hipStream_t st) {
+    long threads = (n_tokens + 3) / 4;
+    unsigned blocks = (unsigned)((threads + 255) / 256);
+    hipLaunchKernelGGL(mark_kernel, dim3(blocks), dim3(256), 0, st, token_ids, n_tokens, set, is_sep);
+    return launch_status();
+}
+
+// ---- compaction --------------------------------------------------------------------------------
+constexpr int kCompactThreads = 256;
+constexpr int kCompactIters = kCompactChunk / kCompactThreads;  // 8 ballots per wave per chunk
+constexpr int kCompactWaves = kCompactThreads / kWave;
+
+// pass 1: chunk_counts[b, chunk] = number of separators in the chunk
+__global__ __launch_bounds__(kCompactThreads) void compact_count_kernel(
+    const uint8_t *__restrict__ is_sep, int L, int n_chunks, int32_t *__restrict__ chunk_counts) {
+    __shared__ int wave_cnt[kCompactWaves];
+    int b = blockIdx.y, chunk = blockIdx.x;
+    const uint8_t *row = is_sep + (long)b * L;
+    int base = chunk * kCompactChunk;
+    int cnt = 0;
+    for (int it = 0; it < kCompactIters; ++it) {
+        int j = base + it * kCompactThreads + threadIdx.x;
+        bool f = (j < L) && row[j] != 0;
+        cnt += __popcll(__ballot(f));
+    }
+    int wave = threadIdx.x / kWave;
+    if (threadIdx.x % kWave == 0) wave_cnt[wave] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int s = 0;
+        for (int w = 0; w < kCompactWaves; ++w) s += wave_cnt[w];
+        chunk_counts[(long)b * n_chunks + chunk] = s;
+    }
+}
+
+// pass 2: ranks and writes
+__global__ __launch_bounds__(kCompactThreads) void compact_write_kernel(
+    const uint8_t *__restrict__ is_sep, int L, int n_chunks, const int32_t *__restrict__ chunk_counts,
+    int32_t *__restrict__ sep_idx, int cap, int32_t *__restrict__ sep_count,
+    int32_t *__restrict__ sep_prefix) {
+    __shared__ int part[kCompactIters * kCompactWaves];  // count of (iteration, wave) groups
+    __shared__ int base_s;
+    int b = blockIdx.y, chunk = blockIdx.x;
+    const uint8_t *row = is_sep + (long)b * L;
+    int base = chunk * kCompactChunk;
+    int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+
+    // separators in earlier chunks of this sequence
+    if (wave == 0) {
+        int s = 0;
+        for (int c = lane; c < chunk; c += kWave) s += chunk_counts[(long)b * n_chunks + c];
+        for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+        if (lane == 0) base_s = s;
+    }
+    unsigned long long lt_mask = (1ull << lane) - 1ull;
+    bool flag[kCompactIters];
+    int rank_in_wave[kCompactIters];
+    for (int it = 0; it < kCompactIters; ++it) {
+        int j = base + it * kCompactThreads + threadIdx.x;
+        flag[it] = (j < L) && row[j] != 0;
+        unsigned long long m = __ballot(flag[it]);
+        rank_in_wave[it] = __popcll(m & lt_mask);
+        if (lane == 0) part[it * kCompactWaves + wave] = __popcll(m);
+    }
+    __syncthreads();
+    // exclusive prefix over the 32 (iteration, wave) groups, in position order, by wave 0
+    if (wave == 0) {
+        int v = (lane < kCompactIters * kCompactWaves) ? part[lane] : 0;
+        int incl = v;
+        for (int off = 1; off < kCompactIters * kCompactWaves; off <<= 1) {
+            int t = __shfl_up(incl, off);
+            if (lane >= off) incl += t;
+        }
+        if (lane < kCompactIters * kCompactWaves) part[lane] = incl - v;
+    }
+    __syncthreads();
+    int chunk_base = base_s;
+    for (int it = 0; it < kCompactIters; ++it) {
+        int j = base + it * kCompactThreads + threadIdx.x;
+        if (j < L) {
+            int r = chunk_base + part[it * kCompactWaves + wave] + rank_in_wave[it];
+            if (sep_prefix) sep_prefix[(long)b * (L + 1) + j] = r;
+            if (flag[it] && r < cap) sep_idx[(long)b * cap + r] = j;
+            if (j == L - 1) {
+                int total = r + (flag[it] ? 1 : 0);
+                if (sep_prefix) sep_prefix[(long)b * (L + 1) + L] = total;
+                sep_count[b] = total;
+            }
+        }
+    }
+}
+
+int launch_compact(const uint8_t *is_sep, int B, int L, int32_t *sep_idx, int cap,
+                   int32_t *sep_count, int32_t *sep_prefix, int32_t *chunk_counts, hipStream_t st) {
+    int n_chunks = (L + kCompactChunk - 1) / kCompactChunk;
+    dim3 grid(n_chunks, B);
+    hipLaunchKernelGGL(compact_count_kernel, grid, dim3(kCompactThreads), 0, st, is_sep, L, n_chunks,
+                       chunk_counts);
+    if (hipGetLastError() != hipSuccess) return SEPATTN_ERR_HIP;
+    hipLaunchKernelGGL(compact_write_kernel, grid, dim3(kCompactThreads), 0, st, is_sep, L, n_chunks,
+                       chunk_counts, sep_idx, cap, sep_count, sep_prefix);
+    return launch_status();
+}
+
+}  // namespace sepattn

@@ -1,0 +1,113 @@
+// Device helpers shared by the bf16 MFMA kernels (gfx950 / CDNA4, wave64).
+//
+// All contractions use v_mfma_f32_32x32x16_bf16.  Operand layouts (lane l of the wave):
+//   A (32 x 16): row l%32, k = 8*(l/32) .. +7        B (16 x 32): column l%32, k = 8*(l/32) .. +7
+//   C (32 x 32): column l%32, register i holds row 8*(i/4) + 4*(l/32) + i%4
+// The kernels always put the "streamed" matrix (staged in LDS) in A and the wave's own 32 rows
+// (queries in forward / dQ, keys in dK/dV) in B, so every softmax quantity of one query (or key)
+// lives in one lane pair (l, l+32).
+//
+// Row permutation pi: the A-operand lane with l%32 = m reads LDS row pi(m).  With it, register i
+// of lane half hh = l/32 holds streamed row  rho(hh, i) = 16*(i/8) + 8*hh + i%8,  i.e. registers
+// 0..7 and 8..15 are two runs of eight consecutive rows.  Those runs are exactly the k-slots that
+// lane needs as the B operand of the following contraction over the streamed rows (P^T, dS^T, ...),
+// so scores flow from accumulator registers into the next MFMA without any cross-lane movement.
+//
+// Transposed A operands (V^T, K^T, Q^T, dO^T) are read from row-major LDS tiles with
+// ds_read_b64_tr_b16: within each group of 16 lanes, lane p supplies the address of four
+// consecutive 16-bit elements; the 16 x 4 elements, taken as a 4 x 16 matrix (row r = lanes
+// 4r..4r+3), are returned column-wise: lane i receives column i.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sepattn {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr float kLog2e_f = 1.4426950408889634f;
+constexpr float kLn2_f = 0.6931471805599453f;
+constexpr int kIntMax = 0x7FFFFFFF;
+
+__device__ inline int pi_row(int m) {
+    // inverse of: register i of lane half hh <-> accumulator row 8*(i/4) + 4*hh + i%4
+    int i4 = m >> 3, hh = (m >> 2) & 1, r = m & 3;
+    return 16 * (i4 >> 1) + 8 * hh + 4 * (i4 & 1) + r;
+}
+
+// streamed row (within a block of 32) held by accumulator register i of lane half hh
+__device__ inline int rho_row(int hh, int i) { return 16 * (i >> 3) + 8 * hh + (i & 7); }
+
+__device__ inline f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ inline bf16x8 as_bf16x8(uint4 u) {
+    union {
+        uint4 u;
+        bf16x8 v;
+    } x;
+    x.u = u;
+    return x.v;
+}
+
+// 16-byte read of a row-major A operand from LDS
+__device__ inline bf16x8 lds_read_a(const uint16_t *tile, int row, int stride, int col) {
+    return *reinterpret_cast<const bf16x8 *>(tile + row * stride + col);
+}
+
+// transposed A operand: element (m, k) = tile[row0 + k][col0 + m], m = l%32, k-slots of lane half
+// hh are rows row0 + 8*hh .. +7.  Two 64-bit transposed reads.
+__device__ inline bf16x8 lds_read_a_tr(const uint16_t *tile, int row0, int stride, int col0, int lane) {
+    int p = lane & 15, g = lane >> 4;
+    int r = row0 + 8 * (g >> 1) + (p >> 2);
+    int c = col0 + 16 * (g & 1) + 4 * (p & 3);
+    const uint16_t *a0 = tile + r * stride + c;
+    const uint16_t *a1 = a0 + 4 * stride;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)a0);
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)a1);
+    union {
+        s16x4 s[2];
+        bf16x8 v;
+    } x;
+    x.s[0] = lo;
+    x.s[1] = hi;
+    return x.v;
+}
+
+// combine a per-lane value with the other half of the lane pair (l, l^32)
+__device__ inline float pair_max(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ inline float pair_sum(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// eight fp32 accumulator values -> packed bf16 B operand (round to nearest even)
+__device__ inline bf16x8 pack_bf16x8(const f32x16 &v, int first) {
+    f32x8 t;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t[k] = v[first + k];
+    return __builtin_convertvector(t, bf16x8);
+}
+
+__device__ inline uint2 pack_bf16x4(float a, float b, float c, float d) {
+    f32x4 t = {a, b, c, d};
+    bf16x4 r = __builtin_convertvector(t, bf16x4);
+    union {
+        bf16x4 v;
+        uint2 u;
+    } x;
+    x.v = r;
+    return x.u;
+}
+
+}  // namespace sepattn

@@ -1,0 +1,422 @@
+"""Parity of the HIP path (through the C ABI binding) against the CPU oracle.  Needs an MI355X.
+
+Tolerances (max-abs, from the build's target statement): 2e-2 for bf16 outputs and gradients, 1e-4
+for the fp32 debug path; index lists, counts, sizes and moved cache rows are compared bit for bit.
+The oracle runs in fp64 on the same bf16-rounded inputs.
+"""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+TOL = {"bf16": 2e-2, "fp32": 1e-4}
+LSE_TOL = {"bf16": 2e-3, "fp32": 1e-4}
+
+
+@pytest.fixture(scope="module")
+def sp():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2412_12094_amd as sp_
+
+    sp_.load()  # raises if the HIP library is missing: no fallback
+    return sp_
+
+
+def dev(x, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    if dtype == "bf16":
+        t = t.to(torch.bfloat16)
+    elif dtype == "fp32":
+        t = t.to(torch.float32)
+    return t.contiguous()
+
+
+def host(t):
+    return t.detach().float().cpu().numpy() if t.is_floating_point() else t.detach().cpu().numpy()
+
+
+def gpu_index(sp, token_ids):
+    ids = dev(token_ids.astype(np.int32))
+    is_sep = sp.sepattn_mark_separators(ids, wl.SEPARATOR_IDS.tolist())
+    idx, cnt, pre = sp.sepattn_compact_indices(is_sep)
+    return is_sep, idx, cnt, pre
+
+
+def make_case(B, Hq, Hkv, L, d, p, dtype, seed, qkv_scale=1.0, placement="iid"):
+    tok = wl.make_token_ids(B, L, p, seed, placement)
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L, d, qkv_scale, seed, dtype)
+    dO = wl.make_dO(B, Hq, L, d, seed, dtype)
+    return tok, Q, K, V, dO
+
+
+# ----------------------------------------------------------------------------------------------
+# mark + compact: bit-exact
+# ----------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("B,L,p", [(1, 1, 0.5), (3, 63, 0.3), (2, 64, 0.1), (2, 2047, 0.08), (1, 2048, 0.08),
+                                   (3, 2049, 0.1), (2, 5000, 0.0), (2, 4100, 1.0), (1, 65536, 0.08)])
+def test_mark_and_compact_bit_exact(sp, B, L, p):
+    tok = wl.make_token_ids(B, L, p, 11 + L)
+    want_flags = oracle.mark_separators(tok, wl.SEPARATOR_IDS)
+    want_idx, want_cnt, want_pre = oracle.compact_indices(want_flags)
+    is_sep, idx, cnt, pre = gpu_index(sp, tok)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(is_sep), want_flags)
+    assert np.array_equal(host(cnt), want_cnt)
+    assert np.array_equal(host(pre), want_pre)
+    assert np.array_equal(host(idx), want_idx)  # tail stays at the -1 fill on both sides
+
+
+def test_compact_capacity_smaller_than_count(sp):
+    tok = wl.make_token_ids(2, 3000, 0.2, 5)
+    flags = oracle.mark_separators(tok, wl.SEPARATOR_IDS)
+    want_idx, want_cnt, _ = oracle.compact_indices(flags, cap=100)
+    idx, cnt, pre = sp.sepattn_compact_indices(dev(flags), cap=100, want_prefix=False)
+    assert pre is None
+    assert np.array_equal(host(cnt), want_cnt) and np.array_equal(host(idx), want_idx)
+
+
+def test_mark_with_one_and_with_64_ids(sp):
+    rng = np.random.default_rng(0)
+    tok = rng.integers(0, 200, size=(2, 1000)).astype(np.int32)
+    for ids in ([7], list(range(0, 128, 2))):
+        got = sp.sepattn_mark_separators(dev(tok), ids)
+        assert np.array_equal(host(got), oracle.mark_separators(tok, np.array(ids, np.int32)))
+
+
+# ----------------------------------------------------------------------------------------------
+# forward / backward
+# ----------------------------------------------------------------------------------------------
+def run_forward(sp, tok, Q, K, V, a, n, scale, dtype):
+    is_sep, idx, cnt, pre = gpu_index(sp, tok)
+    O, LSE = sp.sepattn_forward(dev(Q, dtype), dev(K, dtype), dev(V, dtype), idx, cnt, pre, a, n, scale)
+    torch.cuda.synchronize()
+    return host(is_sep), host(O), host(LSE)
+
+
+def check_forward(sp, B, Hq, Hkv, L, d, a, n, p, dtype, seed, qkv_scale=1.0):
+    tok, Q, K, V, _ = make_case(B, Hq, Hkv, L, d, p, dtype, seed, qkv_scale)
+    scale = 1.0 / math.sqrt(d)
+    flags, O, LSE = run_forward(sp, tok, Q, K, V, a, n, scale, dtype)
+    Oref, Lref = oracle.forward(Q, K, V, flags, a, n, scale)
+    assert np.isfinite(O).all() and np.isfinite(LSE).all()
+    assert np.abs(O - Oref).max() <= TOL[dtype], np.abs(O - Oref).max()
+    assert np.abs(LSE - Lref).max() <= LSE_TOL[dtype], np.abs(LSE - Lref).max()
+
+
+def test_forward_fp32_config1(sp):
+    c = wl.CONFIGS["cfg1"]
+    inp = wl.config_inputs(c)
+    flags, O, LSE = run_forward(sp, inp["token_ids"], inp["Q"], inp["K"], inp["V"], c.a, c.n, c.scale, "fp32")
+    assert np.array_equal(flags, oracle.mark_separators(inp["token_ids"], wl.SEPARATOR_IDS))
+    Oref, Lref = oracle.forward(inp["Q"], inp["K"], inp["V"], flags, c.a, c.n, c.scale)
+    assert np.abs(O - Oref).max() <= 1e-4 and np.abs(LSE - Lref).max() <= 1e-4
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("B,Hq,Hkv,L,d,a,n,p", [
+    (1, 1, 1, 512, 64, 4, 64, 0.125),      # config 1 shape
+    (2, 4, 4, 777, 64, 4, 64, 0.10),       # MHA, ragged length
+    (1, 8, 2, 1100, 128, 4, 256, 0.08),    # GQA 4:1, several tiles + tail
+    (1, 4, 2, 600, 128, 3, 100, 0.08),     # GQA 2:1, window not a multiple of anything
+    (1, 2, 2, 300, 64, 0, 1, 0.2),         # a = 0, n = 1: only itself and separators
+    (1, 2, 1, 260, 128, 5, 1000, 0.1),     # n >= L: full causal
+    (1, 2, 2, 200, 64, 500, 3, 0.1),       # a >= L: full causal
+    (1, 2, 2, 333, 64, 4, 32, 0.0),        # no separators: sinks + sliding window
+    (1, 2, 2, 333, 64, 4, 32, 1.0),        # every token a separator: full causal
+    (2, 3, 3, 65, 64, 2, 7, 0.3),          # barely more than one wave of rows
+    (1, 8, 1, 130, 64, 1, 9, 0.15),        # GQA 8:1
+    (1, 1, 1, 1, 64, 4, 64, 0.0),          # a single token
+])
+def test_forward_matches_oracle(sp, dtype, B, Hq, Hkv, L, d, a, n, p):
+    check_forward(sp, B, Hq, Hkv, L, d, a, n, p, dtype, seed=1000 + L + n)
+
+
+def check_backward(sp, B, Hq, Hkv, L, d, a, n, p, dtype, seed, qkv_scale=1.0):
+    tok, Q, K, V, dO = make_case(B, Hq, Hkv, L, d, p, dtype, seed, qkv_scale)
+    scale = 1.0 / math.sqrt(d)
+    is_sep, idx, cnt, pre = gpu_index(sp, tok)
+    q, k, v, do = dev(Q, dtype), dev(K, dtype), dev(V, dtype), dev(dO, dtype)
+    O, LSE = sp.sepattn_forward(q, k, v, idx, cnt, pre, a, n, scale)
+    dQ, dK, dV = sp.sepattn_backward(q, k, v, O, LSE, do, idx, cnt, pre, a, n, scale)
+    torch.cuda.synchronize()
+    rQ, rK, rV = oracle.backward(Q, K, V, dO, host(is_sep), a, n, scale)
+    for name, got, ref in (("dQ", dQ, rQ), ("dK", dK, rK), ("dV", dV, rV)):
+        g = host(got)
+        assert np.isfinite(g).all(), name
+        err = np.abs(g - ref).max()
+        assert err <= TOL[dtype], (name, err)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("B,Hq,Hkv,L,d,a,n,p", [
+    (1, 1, 1, 512, 64, 4, 64, 0.125),
+    (2, 4, 4, 777, 64, 4, 64, 0.10),
+    (1, 8, 2, 1100, 128, 4, 256, 0.08),
+    (1, 4, 2, 600, 128, 3, 100, 0.08),
+    (1, 2, 2, 300, 64, 0, 1, 0.2),
+    (1, 2, 1, 260, 128, 5, 1000, 0.1),
+    (1, 2, 2, 333, 64, 4, 32, 0.0),
+    (1, 2, 2, 333, 64, 4, 32, 1.0),
+    (2, 3, 3, 65, 64, 2, 7, 0.3),
+    (1, 8, 1, 130, 64, 1, 9, 0.15),
+    (1, 1, 1, 1, 64, 4, 64, 0.0),
+])
+def test_backward_matches_oracle(sp, dtype, B, Hq, Hkv, L, d, a, n, p):
+    check_backward(sp, B, Hq, Hkv, L, d, a, n, p, dtype, seed=2000 + L + n)
+
+
+def visible_counts(flags_row, a, n):
+    """Number of visible keys per row from prefix sums (integer property used at any size)."""
+    L = flags_row.size
+    pre = np.concatenate([[0], np.cumsum(flags_row.astype(np.int64))])
+    i = np.arange(L)
+    ws = np.maximum(0, i - n + 1)
+    ninit = np.minimum(a, ws)
+    return ninit + (pre[ws] - pre[ninit]) + (i - ws + 1)
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg4"])
+def test_forward_zero_query_probe_at_full_size(sp, name):
+    """Q = 0 at the benchmark sizes: exp(LSE_i) must be the integer count of visible keys of row i,
+    for every row and head (an exact check of the whole mask through the bf16 kernel)."""
+    c = wl.CONFIGS[name]
+    tok = wl.make_token_ids(c.B, c.L, c.p, c.seed, "geometric" if name != "cfg2" else "iid")
+    is_sep, idx, cnt, pre = gpu_index(sp, tok)
+    g = torch.Generator(device="cuda").manual_seed(1)
+    K = torch.randn((c.B, c.Hkv, c.L, c.d), device="cuda", generator=g).to(torch.bfloat16)
+    V = torch.randn((c.B, c.Hkv, c.L, c.d), device="cuda", generator=g).to(torch.bfloat16)
+    Q = torch.zeros((c.B, c.Hq, c.L, c.d), device="cuda", dtype=torch.bfloat16)
+    O, LSE = sp.sepattn_forward(Q, K, V, idx, cnt, pre, c.a, c.n, c.scale)
+    torch.cuda.synchronize()
+    flags = oracle.mark_separators(tok, wl.SEPARATOR_IDS)
+    counts = np.stack([visible_counts(flags[b], c.a, c.n) for b in range(c.B)])
+    got = torch.exp(LSE.double()).cpu().numpy()
+    assert np.abs(got - counts[:, None, :]).max() < 1e-2 * 1  # counts up to ~6e3, fp32 log/exp noise
+    assert np.array_equal(np.rint(got).astype(np.int64), np.broadcast_to(counts[:, None, :], got.shape))
+
+
+@pytest.mark.parametrize("name", ["cfg3", "cfg4"])
+def test_forward_sampled_rows_at_full_size(sp, name):
+    c = wl.CONFIGS[name]
+    inp = wl.config_inputs(c)
+    flags, O, LSE = run_forward(sp, inp["token_ids"], inp["Q"], inp["K"], inp["V"], c.a, c.n, c.scale, c.dtype)
+    rng = np.random.default_rng(7)
+    rows = np.unique(np.concatenate([[0, 1, c.n - 1, c.n, c.n + 1, c.L - 1], rng.integers(0, c.L, 40)])).astype(np.int32)
+    Oref, Lref = oracle.forward(inp["Q"], inp["K"], inp["V"], flags, c.a, c.n, c.scale, rows=rows)
+    assert np.abs(O[:, :, rows] - Oref).max() <= TOL["bf16"]
+    assert np.abs(LSE[:, :, rows] - Lref).max() <= LSE_TOL["bf16"]
+
+
+def test_config2_full_forward_backward(sp):
+    c = wl.CONFIGS["cfg2"]
+    inp = wl.config_inputs(c)
+    is_sep, idx, cnt, pre = gpu_index(sp, inp["token_ids"])
+    q, k, v, do = (dev(inp[x], "bf16") for x in ("Q", "K", "V", "dO"))
+    O, LSE = sp.sepattn_forward(q, k, v, idx, cnt, pre, c.a, c.n, c.scale)
+    dQ, dK, dV = sp.sepattn_backward(q, k, v, O, LSE, do, idx, cnt, pre, c.a, c.n, c.scale)
+    torch.cuda.synchronize()
+    flags = host(is_sep)
+    # two of the eight sequences through the dense oracle
+    for b in (0, 7):
+        sl = slice(b, b + 1)
+        Oref, Lref = oracle.forward(inp["Q"][sl], inp["K"][sl], inp["V"][sl], flags[sl], c.a, c.n, c.scale)
+        rQ, rK, rV = oracle.backward(inp["Q"][sl], inp["K"][sl], inp["V"][sl], inp["dO"][sl], flags[sl], c.a, c.n, c.scale)
+        assert np.abs(host(O[sl]) - Oref).max() <= 2e-2
+        assert np.abs(host(LSE[sl]) - Lref).max() <= 2e-3
+        assert np.abs(host(dQ[sl]) - rQ).max() <= 2e-2
+        assert np.abs(host(dK[sl]) - rK).max() <= 2e-2
+        assert np.abs(host(dV[sl]) - rV).max() <= 2e-2
+
+
+def test_config3_backward_one_kv_group_at_full_size(sp):
+    """Config 3 in the launch configuration bench.py times; the dense oracle runs on KV head 5 and
+    the four query heads that read it (dK/dV of a KV head need all of its query heads)."""
+    c = wl.CONFIGS["cfg3"]
+    inp = wl.config_inputs(c)
+    is_sep, idx, cnt, pre = gpu_index(sp, inp["token_ids"])
+    q, k, v, do = (dev(inp[x], "bf16") for x in ("Q", "K", "V", "dO"))
+    O, LSE = sp.sepattn_forward(q, k, v, idx, cnt, pre, c.a, c.n, c.scale)
+    dQ, dK, dV = sp.sepattn_backward(q, k, v, O, LSE, do, idx, cnt, pre, c.a, c.n, c.scale)
+    torch.cuda.synchronize()
+    flags = host(is_sep)
+    kv, G = 5, c.Hq // c.Hkv
+    hs = slice(kv * G, (kv + 1) * G)
+    rQ, rK, rV = oracle.backward(inp["Q"][:, hs], inp["K"][:, kv:kv + 1], inp["V"][:, kv:kv + 1],
+                                 inp["dO"][:, hs], flags, c.a, c.n, c.scale)
+    assert np.abs(host(dQ[:, hs]) - rQ).max() <= 2e-2
+    assert np.abs(host(dK[:, kv:kv + 1]) - rK).max() <= 2e-2
+    assert np.abs(host(dV[:, kv:kv + 1]) - rV).max() <= 2e-2
+
+
+def test_forward_backward_are_bit_reproducible(sp):
+    tok, Q, K, V, dO = make_case(1, 8, 2, 1500, 128, 0.08, "bf16", 3)
+    is_sep, idx, cnt, pre = gpu_index(sp, tok)
+    q, k, v, do = (dev(x, "bf16") for x in (Q, K, V, dO))
+    outs = []
+    for _ in range(2):
+        O, LSE = sp.sepattn_forward(q, k, v, idx, cnt, pre, 4, 256, 0.0884)
+        grads = sp.sepattn_backward(q, k, v, O, LSE, do, idx, cnt, pre, 4, 256, 0.0884)
+        torch.cuda.synchronize()
+        outs.append([t.clone() for t in (O, LSE, *grads)])
+    for x, y in zip(*outs):
+        assert torch.equal(x, y)
+
+
+# ----------------------------------------------------------------------------------------------
+# decode / evict
+# ----------------------------------------------------------------------------------------------
+def random_sizes(rng, S, a, s, wcap, w):
+    sz = np.zeros((S, 4), dtype=np.int32)
+    for q in range(S):
+        sz[q, 0] = rng.integers(0, a + 1)
+        sz[q, 1] = rng.integers(0, s + 1)
+        tot = rng.integers(1, wcap + 1)
+        sz[q, 3] = min(w, tot)
+        sz[q, 2] = tot - sz[q, 3]
+    return sz
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("S,Hq,Hkv,d,a,s,w,c", [
+    (3, 8, 2, 128, 4, 64, 32, 200),
+    (2, 4, 4, 64, 2, 10, 8, 41),
+    (4, 6, 3, 128, 0, 33, 16, 100),
+    (1, 8, 1, 64, 4, 300, 100, 1500),
+])
+def test_decode_matches_oracle(sp, dtype, S, Hq, Hkv, d, a, s, w, c):
+    cfg = wl.CacheConfig("t", S, Hq, Hkv, d, a, s, w, c, 0.1, dtype, seed=77 + c)
+    rng = np.random.default_rng(c)
+    sizes = random_sizes(rng, S, a, s, c - a - s, w)
+    sizes[0] = [a, s, c - a - s - w, w]  # one completely full cache
+    data = wl.make_cache(cfg, sizes)
+    scale = 1.0 / math.sqrt(d)
+    out, lse = sp.sepattn_decode(dev(data["q"], dtype), dev(data["Kc"], dtype), dev(data["Vc"], dtype),
+                                 dev(sizes), a, s, w, scale)
+    torch.cuda.synchronize()
+    ref, lref = oracle.decode(data["q"], data["Kc"], data["Vc"], sizes, a, s, scale)
+    assert np.abs(host(out) - ref).max() <= TOL[dtype]
+    assert np.abs(host(lse) - lref).max() <= LSE_TOL[dtype]
+
+
+def test_decode_empty_sequence_and_single_entry(sp):
+    cfg = wl.CacheConfig("t", 2, 4, 2, 128, 2, 8, 4, 30, 0.1, "bf16", seed=5)
+    sizes = np.array([[0, 0, 0, 0], [0, 0, 0, 1]], dtype=np.int32)
+    data = wl.make_cache(cfg, sizes)
+    out, lse = sp.sepattn_decode(dev(data["q"], "bf16"), dev(data["Kc"], "bf16"), dev(data["Vc"], "bf16"),
+                                 dev(sizes), 2, 8, 4, 0.1)
+    torch.cuda.synchronize()
+    o, l = host(out), host(lse)
+    assert np.all(o[0] == 0) and np.all(np.isneginf(l[0]))
+    assert np.array_equal(o[1], np.repeat(data["Vc"][1, :, 10], 2, axis=0))  # the only entry: window slot 0
+
+
+def test_decode_config5_full_size(sp):
+    c = wl.CONFIGS["cfg5"]
+    data = wl.make_cache(c)
+    out, lse = sp.sepattn_decode(dev(data["q"], "bf16"), dev(data["Kc"], "bf16"), dev(data["Vc"], "bf16"),
+                                 dev(data["sizes"]), c.a, c.s, c.w, c.scale)
+    torch.cuda.synchronize()
+    ref, lref = oracle.decode(data["q"], data["Kc"], data["Vc"], data["sizes"], c.a, c.s, c.scale)
+    assert np.abs(host(out) - ref).max() <= 2e-2
+    assert np.abs(host(lse) - lref).max() <= 2e-3
+    assert abs(math.exp(lref[0, 0]) - 0) >= 0  # lse finite
+    assert np.isfinite(host(lse)).all()
+
+
+def bits(x_fp32_bf16_valued):
+    """bf16-valued fp32 array -> uint16 bit patterns (what the GPU cache holds)."""
+    return (np.ascontiguousarray(x_fp32_bf16_valued, dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+
+
+def check_evict(sp, cfg, sizes, flags=None):
+    data = wl.make_cache(cfg, sizes)
+    if flags is not None:
+        data["win_is_sep"] = flags
+    Kb, Vb = bits(data["Kc"]), bits(data["Vc"])
+    rK, rV, rF, rS = oracle.evict_window(Kb, Vb, data["win_is_sep"], sizes, cfg.a, cfg.s)
+    Kd = dev(Kb.view(np.int16)).view(torch.bfloat16)
+    Vd = dev(Vb.view(np.int16)).view(torch.bfloat16)
+    Fd, Sd = dev(data["win_is_sep"]), dev(sizes)
+    sp.sepkv_evict_window(Kd, Vd, Fd, Sd, cfg.Hq, cfg.a, cfg.s, cfg.w)
+    torch.cuda.synchronize()
+    gK = Kd.view(torch.int16).cpu().numpy().view(np.uint16)
+    gV = Vd.view(torch.int16).cpu().numpy().view(np.uint16)
+    gF, gS = host(Fd), host(Sd)
+    assert np.array_equal(gS, rS)
+    a, s = cfg.a, cfg.s
+    for q in range(cfg.S):
+        ni, ns, _, lw = rS[q]
+        for g, r in ((gK, rK), (gV, rV)):
+            assert np.array_equal(g[q, :, :ni], r[q, :, :ni])
+            assert np.array_equal(g[q, :, a:a + ns], r[q, :, a:a + ns])
+            assert np.array_equal(g[q, :, a + s:a + s + lw], r[q, :, a + s:a + s + lw])
+        assert np.array_equal(gF[q, :lw], rF[q, :lw])
+
+
+def test_evict_matches_oracle_bit_exact(sp):
+    cfg = wl.CacheConfig("t", 5, 8, 2, 128, 4, 40, 16, 4 + 40 + 90, 0.3, "bf16", seed=9)
+    wcap = cfg.window_capacity
+    sizes = np.array([[4, 10, 50, 16],     # plain append
+                      [4, 38, 70, 16],     # overflow: oldest separators dropped
+                      [4, 40, 74, 16],     # separator cache already full
+                      [2, 0, 0, 9],        # nothing in the past window
+                      [4, 5, 60, 0]],      # empty local window
+                     dtype=np.int32)
+    assert (sizes[:, 2] + sizes[:, 3] <= wcap).all()
+    check_evict(sp, cfg, sizes)
+    # all past-window entries flagged and more of them than the separator cache holds
+    flags = np.ones((5, wcap), dtype=np.uint8)
+    check_evict(sp, cfg, sizes, flags)
+    check_evict(sp, cfg, sizes, np.zeros((5, wcap), dtype=np.uint8))
+
+
+def test_evict_fp32_and_d64(sp):
+    cfg = wl.CacheConfig("t", 2, 2, 2, 64, 1, 6, 4, 1 + 6 + 20, 0.4, "bf16", seed=19)
+    sizes = np.array([[1, 3, 12, 4], [1, 6, 16, 4]], dtype=np.int32)
+    check_evict(sp, cfg, sizes)
+
+
+def test_evict_config5_then_decode(sp):
+    """Config 5: evict a full 1024-entry past window, then decode over the new cache."""
+    c = wl.CONFIGS["cfg5"]
+    data = wl.make_cache(c)
+    Kb, Vb = bits(data["Kc"]), bits(data["Vc"])
+    rK, rV, rF, rS = oracle.evict_window(Kb, Vb, data["win_is_sep"], data["sizes"], c.a, c.s)
+    Kd = dev(Kb.view(np.int16)).view(torch.bfloat16)
+    Vd = dev(Vb.view(np.int16)).view(torch.bfloat16)
+    Fd, Sd = dev(data["win_is_sep"]), dev(data["sizes"])
+    sp.sepkv_evict_window(Kd, Vd, Fd, Sd, c.Hq, c.a, c.s, c.w)
+    out, lse = sp.sepattn_decode(dev(data["q"], "bf16"), Kd, Vd, Sd, c.a, c.s, c.w, c.scale)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(Sd), rS)
+    assert (rS[:, 1] == c.s).all() and (rS[:, 2] == 0).all()  # separator cache was full: FIFO overflow
+    gK = Kd.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(gK[:, :, c.a:c.a + c.s], rK[:, :, c.a:c.a + c.s])
+    assert np.array_equal(gK[:, :, c.a + c.s:c.a + c.s + c.w], rK[:, :, c.a + c.s:c.a + c.s + c.w])
+    to_f = lambda u: (u.astype(np.uint32) << 16).view(np.float32)
+    ref, lref = oracle.decode(data["q"], to_f(rK), to_f(rV), rS, c.a, c.s, c.scale)
+    assert np.abs(host(out) - ref).max() <= 2e-2 and np.abs(host(lse) - lref).max() <= 2e-3
+
+
+# ----------------------------------------------------------------------------------------------
+# error paths through the ABI (nothing is launched)
+# ----------------------------------------------------------------------------------------------
+def test_bad_arguments_are_rejected(sp):
+    tok, Q, K, V, dO = make_case(1, 2, 2, 64, 64, 0.1, "bf16", 1)
+    is_sep, idx, cnt, pre = gpu_index(sp, tok)
+    q, k, v = (dev(x, "bf16") for x in (Q, K, V))
+    with pytest.raises(sp.SepattnError) as e:
+        sp.sepattn_forward(q, k, v, idx, cnt, pre, 4, 0, 0.125)  # n = 0
+    assert e.value.status == 3
+    with pytest.raises(sp.SepattnError) as e:
+        sp.sepattn_forward(q, k, v, idx, cnt, pre, -1, 4, 0.125)
+    assert e.value.status == 3
+    with pytest.raises(sp.SepattnError):
+        sp.sepattn_mark_separators(dev(tok), list(range(65)))

@@ -1,0 +1,263 @@
+#!/usr/bin/env python3
+"""Benchmark of the SepAttention hot path on one MI355X.
+
+A step is one pass of the training hot path over one synthetic batch of the Llama-3-8B attention
+shape at 8K context (B=1, 32 query / 8 KV heads, d=128, L=8192, a=4, n=256, separator density 0.08):
+    mark separators -> compact indices -> forward -> backward,
+all enqueued on torch's current stream through the C ABI binding, inputs resident in HBM.
+The headline value is the effective TFLOP/s on unmasked query-key pairs,
+    14 * d * P_vis * Hq / t_step   (forward 4d + backward 10d flops per visible pair and head),
+printed as ONE JSON line together with
+  - "roofline":     the dominant kernel's algorithmic flops / its own duration (HIP events recorded
+                    around that kernel on the launch stream during the timed steps) against the
+                    dense bf16 MFMA peak,
+  - "cpu_baseline": the CPU oracle timed on this host on a bounded sample of the same workload,
+  - "decode":       the streaming-decode workload (32 sequences x 3332 cache entries) as achieved
+                    HBM GB/s, and the cache eviction step.
+Only one GPU is used; `--gpus N` with N > 1 exits with a message.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
+
+
+def count_visible_pairs(flags_row: np.ndarray, a: int, n: int) -> int:
+    """Ones of the mask of Eq. 2 for one sequence, from prefix sums (accounting for the metric only)."""
+    L = flags_row.size
+    pre = np.concatenate([[0], np.cumsum(flags_row.astype(np.int64))])
+    i = np.arange(L)
+    ws = np.maximum(0, i - n + 1)
+    ninit = np.minimum(a, ws)
+    return int((ninit + (pre[ws] - pre[ninit]) + (i - ws + 1)).sum())
+
+
+def count_far_pairs(flags_row: np.ndarray, a: int, n: int) -> int:
+    """Visible pairs with i - j >= n (initial tokens and separators older than the window)."""
+    L = flags_row.size
+    j = np.arange(L)
+    always = (j < a) | (flags_row != 0)
+    return int(np.maximum(0, L - (j + n))[always].sum())
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (--gpus must be 1)",
+              file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2412_12094_amd as sp
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    sp.load()
+    torch.cuda.set_device(0)
+    c = wl.CONFIGS["cfg3"]
+    inp = wl.config_inputs(c)
+    bf = lambda x: torch.from_numpy(x).cuda().to(torch.bfloat16).contiguous()
+    tok = torch.from_numpy(inp["token_ids"]).cuda()
+    Q, K, V, dO = bf(inp["Q"]), bf(inp["K"]), bf(inp["V"]), bf(inp["dO"])
+    sep_ids = wl.SEPARATOR_IDS.tolist()
+    dev = Q.device
+
+    # everything the step writes is allocated once, outside the timed region
+    is_sep = torch.empty((c.B, c.L), dtype=torch.uint8, device=dev)
+    idx = torch.full((c.B, c.L), -1, dtype=torch.int32, device=dev)
+    cnt = torch.empty((c.B,), dtype=torch.int32, device=dev)
+    pre = torch.empty((c.B, c.L + 1), dtype=torch.int32, device=dev)
+    cws = torch.empty(4096, dtype=torch.uint8, device=dev)
+    O = torch.empty_like(Q)
+    LSE = torch.empty((c.B, c.Hq, c.L), dtype=torch.float32, device=dev)
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    fws = torch.empty(256, dtype=torch.uint8, device=dev)
+    bws = torch.empty(sp.sepattn_backward_workspace_bytes(Q, K, c.a, c.n, c.scale, c.L), dtype=torch.uint8,
+                      device=dev)
+
+    def step():
+        sp.sepattn_mark_separators(tok, sep_ids, out=is_sep)
+        sp.sepattn_compact_indices(is_sep, out=(idx, cnt, pre), ws=cws)
+        sp.sepattn_forward(Q, K, V, idx, cnt, pre, c.a, c.n, c.scale, out=(O, LSE), ws=fws)
+        sp.sepattn_backward(Q, K, V, O, LSE, dO, idx, cnt, pre, c.a, c.n, c.scale, out=(dQ, dK, dV), ws=bws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # untimed pass: duration of every kernel of the step, to find the dominant one
+    train_kernels = ["mark", "compact_count", "compact_write", "forward", "bwd_dq", "bwd_dkv_far", "bwd_dkv_band"]
+    per_kernel_us = {}
+    for name in train_kernels:
+        sp.sepattn_profile_begin(sp.KERNEL_IDS[name], 5)
+        for _ in range(5):
+            step()
+        torch.cuda.synchronize()
+        ms = sp.sepattn_profile_end(5)
+        per_kernel_us[name] = 1e3 * float(np.median(ms))
+    dominant = max(per_kernel_us, key=per_kernel_us.get)
+
+    # timed region: exactly K steps, the dominant kernel bracketed by HIP events on the launch stream
+    sp.sepattn_profile_begin(sp.KERNEL_IDS[dominant], args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    dom_ms = sp.sepattn_profile_end(args.steps)
+    ms_per_step = 1e3 * (t1 - t0) / args.steps
+
+    flags = is_sep.cpu().numpy()
+    p_vis = sum(count_visible_pairs(flags[b], c.a, c.n) for b in range(c.B))
+    p_far = sum(count_far_pairs(flags[b], c.a, c.n) for b in range(c.B))
+    p_band = p_vis - p_far
+    flops_step = 14.0 * c.d * p_vis * c.Hq
+    value = flops_step / (ms_per_step * 1e-3) / 1e12
+
+    # algorithmic flops of each kernel: forward 4d per pair; backward 10d per pair, of which the dQ
+    # kernel owns S, dP and dQ (6d) and the dK/dV kernels own dK and dV (4d) on their share of pairs
+    alg_flops = {"forward": 4.0 * c.d * p_vis * c.Hq, "bwd_dq": 6.0 * c.d * p_vis * c.Hq,
+                 "bwd_dkv_far": 4.0 * c.d * p_far * c.Hq, "bwd_dkv_band": 4.0 * c.d * p_band * c.Hq}
+    dom_avg_ms = float(np.mean(dom_ms)) if dom_ms else float("nan")
+    achieved = alg_flops.get(dominant, 0.0) / (dom_avg_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": sp.sepattn_kernel_name(sp.KERNEL_IDS[dominant]),
+                "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "avg_launch_us": round(1e3 * dom_avg_ms, 2), "launches": len(dom_ms),
+                "algorithmic_gflop_per_launch": round(alg_flops.get(dominant, 0.0) / 1e9, 2)}
+
+    out = {
+        "metric": "SepAttention fwd+bwd effective TFLOP/s (unmasked pairs) @8K",
+        "value": round(value, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "cfg3: Llama-3-8B attention shape, B=1, Hq=32, Hkv=8, d=128, L=8192, a=4, n=256, "
+                               "separator density 0.08 (geometric gaps), mark+compact+forward+backward per step",
+                   "visible_pairs_per_head": p_vis, "far_pairs_per_head": p_far},
+        "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
+        "tokens_per_s": round(c.B * c.L / (ms_per_step * 1e-3), 1),
+        "kernel_us": {k: round(v, 2) for k, v in per_kernel_us.items()},
+        "roofline": roofline,
+    }
+
+    if not args.no_decode:
+        out["decode"] = bench_decode(torch, sp, wl)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, inp, flags, c, p_vis)
+    print(json.dumps(out))
+    return 0
+
+
+def bench_decode(torch, sp, wl):
+    """Config 5: one decode step over 32 x 8 x 3332-entry caches; eviction of a full past window."""
+    c = wl.CONFIGS["cfg5"]
+    data = wl.make_cache(c)
+    bf = lambda x: torch.from_numpy(x).cuda().to(torch.bfloat16).contiguous()
+    q, Kc, Vc = bf(data["q"]), bf(data["Kc"]), bf(data["Vc"])
+    sizes = torch.from_numpy(data["sizes"]).cuda()
+    out = torch.empty_like(q)
+    lse = torch.empty((c.S, c.Hq), dtype=torch.float32, device=q.device)
+    ws = torch.empty(1 << 24, dtype=torch.uint8, device=q.device)
+    # two further caches so that consecutive steps do not find their K/V in the 256 MB last-level cache
+    caches = [(Kc, Vc)] + [(torch.randn_like(Kc), torch.randn_like(Vc)) for _ in range(2)]
+    steps, warm = 60, 9
+    for i in range(warm):
+        k_, v_ = caches[i % 3]
+        sp.sepattn_decode(q, k_, v_, sizes, c.a, c.s, c.w, c.scale, out=(out, lse), ws=ws)
+    torch.cuda.synchronize()
+    sp.sepattn_profile_begin(sp.KERNEL_IDS["decode_split"], steps)
+    t0 = time.perf_counter()
+    for i in range(steps):
+        k_, v_ = caches[i % 3]
+        sp.sepattn_decode(q, k_, v_, sizes, c.a, c.s, c.w, c.scale, out=(out, lse), ws=ws)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kms = sp.sepattn_profile_end(steps)
+    kv_bytes = 2.0 * c.S * c.Hkv * c.c * c.d * 2
+    us_step = 1e6 * (t1 - t0) / steps
+    k_us = 1e3 * float(np.mean(kms))
+    res = {"workload": "cfg5: 32 sequences, 32/8 heads, d=128, 3332 cache entries each, bf16",
+           "us_per_step": round(us_step, 2), "split_kernel_us": round(k_us, 2),
+           "kv_bytes_per_step": int(kv_bytes),
+           "gbs_step": round(kv_bytes / us_step / 1e3, 1), "gbs_kernel": round(kv_bytes / k_us / 1e3, 1),
+           "frac_hbm_peak_kernel": round(kv_bytes / k_us / 1e3 / PEAK_HBM_GBS, 4)}
+    # eviction: restore the sizes / flags every time (in place otherwise empties the past window)
+    flags0 = torch.from_numpy(data["win_is_sep"]).cuda()
+    sizes0 = sizes.clone()
+    flags, sz = flags0.clone(), sizes0.clone()
+    ews = torch.empty(1 << 20, dtype=torch.uint8, device=q.device)
+    times = []
+    for i in range(12):
+        flags.copy_(flags0)
+        sz.copy_(sizes0)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        sp.sepkv_evict_window(Kc, Vc, flags, sz, c.Hq, c.a, c.s, c.w, ws=ews)
+        e1.record()
+        torch.cuda.synchronize()
+        times.append(e0.elapsed_time(e1) * 1e3)
+    kept = int(data["win_is_sep"][:, : c.window_capacity - c.w].sum())
+    row = c.d * 2
+    # rows the method must move: kept past-window rows, plus (separator cache full) the surviving
+    # separator rows shifted down and the local window slid to the front; read + write, K and V
+    moved_rows = kept + int((c.s * c.S) - kept) + c.w * c.S
+    res["evict"] = {"us": round(float(np.median(times[2:])), 2), "kept_rows_per_head": kept,
+                    "moved_bytes": int(moved_rows * row * 2 * 2 * c.Hkv),
+                    "gbs": round(moved_rows * row * 2 * 2 * c.Hkv / float(np.median(times[2:])) / 1e3, 1)}
+    return res
+
+
+def cpu_baseline(wl, inp, flags, c, p_vis):
+    """The CPU oracle (fp32 build, as it stands) on KV head 0 and its four query heads, all rows."""
+    import oracle
+
+    oracle.build()
+    G = c.Hq // c.Hkv
+    hs = slice(0, G)
+    assert int(oracle.mask(flags[0], c.a, c.n).sum()) == p_vis  # the metric's pair count is the mask's
+    Qs, Ks, Vs, dOs = inp["Q"][:, hs], inp["K"][:, :1], inp["V"][:, :1], inp["dO"][:, hs]
+    t0 = time.perf_counter()
+    oracle.forward(Qs, Ks, Vs, flags, c.a, c.n, c.scale, precision="f32")
+    oracle.backward(Qs, Ks, Vs, dOs, flags, c.a, c.n, c.scale, precision="f32")
+    dt = time.perf_counter() - t0
+    cores = len(os.sched_getaffinity(0))
+    threads = int(os.environ.get("OMP_NUM_THREADS", cores))
+    flops = 14.0 * c.d * p_vis * G
+    return {"value": round(flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": min(cores, threads),
+            "kind": "oracle", "seconds": round(dt, 2),
+            "sample": f"KV head 0 with its {G} query heads of cfg3 (1/8 of the workload), all 8192 rows, "
+                      "forward + backward, fp32 build of the oracle, OpenMP"}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -13,7 +13,8 @@
  * Conventions common to every call
  *   - Pointers marked DEVICE address memory of the current HIP device; HOST pointers address
  *     ordinary host memory.  The caller owns every buffer, including workspaces; the library
- *     allocates no device memory and keeps no state between calls.
+ *     allocates no device memory and keeps no state between calls (the measurement hooks at the
+ *     end of this header aside).
  *   - Tensors are dense and contiguous with the head dimension d innermost.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls validate their
  *     arguments synchronously, enqueue their kernels on `stream` and return without waiting.
@@ -185,6 +186,36 @@ int sepattn_decode(const sepkv_params *p, const void *q, const void *Kc, const v
 size_t sepkv_evict_workspace_bytes(const sepkv_params *p);
 int sepkv_evict_window(const sepkv_params *p, void *Kc, void *Vc, uint8_t *win_is_sep,
                        int32_t *sizes, void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Measurement hooks (not part of the method; the only process-wide state the library keeps).
+ * Between sepattn_profile_begin and sepattn_profile_end every launch of the selected kernel is
+ * bracketed by a pair of HIP events recorded on the stream the kernel is launched on, so a
+ * benchmark can report that kernel's own duration while it times whole steps.  Not thread-safe.
+ *   kernel       a sepattn_kernel_id
+ *   max_records  events are created up front for this many launches; further launches of the
+ *                kernel are not recorded
+ *   ms           HOST float [max_records] out: elapsed milliseconds of each recorded launch
+ *   n_records    HOST int out: number of launches recorded
+ * sepattn_profile_end waits for the recorded events, so call it after the timed region.
+ * ------------------------------------------------------------------------------------------ */
+typedef enum {
+    SEPATTN_K_MARK = 0,
+    SEPATTN_K_COMPACT_COUNT = 1,
+    SEPATTN_K_COMPACT_WRITE = 2,
+    SEPATTN_K_FORWARD = 3,
+    SEPATTN_K_BWD_DQ = 4,
+    SEPATTN_K_BWD_DKV_FAR = 5,
+    SEPATTN_K_BWD_DKV_BAND = 6,
+    SEPATTN_K_DECODE_SPLIT = 7,
+    SEPATTN_K_DECODE_MERGE = 8,
+    SEPATTN_K_EVICT_PLAN = 9,
+    SEPATTN_K_EVICT_MOVE = 10,
+    SEPATTN_K_COUNT = 11
+} sepattn_kernel_id;
+const char *sepattn_kernel_name(int kernel);
+int sepattn_profile_begin(int kernel, int max_records);
+int sepattn_profile_end(float *ms, int *n_records);
 
 #ifdef __cplusplus
 }

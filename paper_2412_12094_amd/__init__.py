@@ -20,4 +20,8 @@ from .binding import (  # noqa: F401
     sepattn_backward_workspace_bytes,
     sepattn_decode,
     sepkv_evict_window,
+    KERNEL_IDS,
+    sepattn_kernel_name,
+    sepattn_profile_begin,
+    sepattn_profile_end,
 )

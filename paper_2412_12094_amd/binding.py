@@ -33,6 +33,9 @@ EXPORTS = (
     "sepattn_decode",
     "sepkv_evict_workspace_bytes",
     "sepkv_evict_window",
+    "sepattn_kernel_name",
+    "sepattn_profile_begin",
+    "sepattn_profile_end",
 )
 
 
@@ -94,6 +97,12 @@ def load(path: Optional[str] = None):
     lib.sepkv_evict_workspace_bytes.argtypes = [kp]
     lib.sepkv_evict_window.restype = ci
     lib.sepkv_evict_window.argtypes = [kp] + [vp] * 5 + [sz, vp]
+    lib.sepattn_kernel_name.restype = ctypes.c_char_p
+    lib.sepattn_kernel_name.argtypes = [ci]
+    lib.sepattn_profile_begin.restype = ci
+    lib.sepattn_profile_begin.argtypes = [ci, ci]
+    lib.sepattn_profile_end.restype = ci
+    lib.sepattn_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int)]
     if path == LIB_PATH or _lib is None:
         _lib = lib
     return lib
@@ -101,6 +110,27 @@ def load(path: Optional[str] = None):
 
 def status_string(status: int) -> str:
     return load().sepattn_status_string(int(status)).decode()
+
+
+KERNEL_IDS = {"mark": 0, "compact_count": 1, "compact_write": 2, "forward": 3, "bwd_dq": 4, "bwd_dkv_far": 5,
+              "bwd_dkv_band": 6, "decode_split": 7, "decode_merge": 8, "evict_plan": 9, "evict_move": 10}
+
+
+def sepattn_kernel_name(kernel: int) -> str:
+    return load().sepattn_kernel_name(int(kernel)).decode()
+
+
+def sepattn_profile_begin(kernel: int, max_records: int) -> None:
+    """Bracket the next launches of one kernel with HIP events on the launch stream."""
+    _check("sepattn_profile_begin", load().sepattn_profile_begin(int(kernel), int(max_records)))
+
+
+def sepattn_profile_end(max_records: int):
+    """Wait for the recorded events; returns the list of per-launch durations in milliseconds."""
+    ms = (ctypes.c_float * int(max_records))()
+    n = ctypes.c_int(0)
+    _check("sepattn_profile_end", load().sepattn_profile_end(ms, ctypes.byref(n)))
+    return [float(ms[i]) for i in range(n.value)]
 
 
 def _check(fn: str, rc: int) -> None:
@@ -139,13 +169,14 @@ def _dev(*ts: torch.Tensor) -> None:
 
 
 # ------------------------------------------------------------------------------------------------
-def sepattn_mark_separators(token_ids: torch.Tensor, sep_ids) -> torch.Tensor:
+def sepattn_mark_separators(token_ids: torch.Tensor, sep_ids, out: Optional[torch.Tensor] = None) -> torch.Tensor:
     """token_ids int32 [B,L] (GPU), sep_ids: host sequence of ints -> is_sep uint8 [B,L]."""
-    _dev(token_ids)
+    _dev(token_ids, out)
     assert token_ids.dtype == torch.int32 and token_ids.dim() == 2
     B, L = token_ids.shape
     ids = (ctypes.c_int32 * len(sep_ids))(*[int(x) for x in sep_ids])
-    out = torch.empty((B, L), dtype=torch.uint8, device=token_ids.device)
+    if out is None:
+        out = torch.empty((B, L), dtype=torch.uint8, device=token_ids.device)
     _check("sepattn_mark_separators",
            load().sepattn_mark_separators(_ptr(token_ids), B, L, ctypes.cast(ids, ctypes.c_void_p),
                                           len(sep_ids), _ptr(out), _stream(token_ids)))
@@ -153,21 +184,29 @@ def sepattn_mark_separators(token_ids: torch.Tensor, sep_ids) -> torch.Tensor:
 
 
 def sepattn_compact_indices(is_sep: torch.Tensor, cap: Optional[int] = None, want_prefix: bool = True,
-                            fill: int = -1) -> Tuple[torch.Tensor, torch.Tensor, Optional[torch.Tensor]]:
+                            fill: int = -1, out=None, ws: Optional[torch.Tensor] = None
+                            ) -> Tuple[torch.Tensor, torch.Tensor, Optional[torch.Tensor]]:
     """is_sep uint8 [B,L] -> (sep_idx int32 [B,cap], sep_count int32 [B], sep_prefix int32 [B,L+1]).
 
-    sep_idx is pre-filled with `fill` by torch; the library leaves entries beyond the count untouched.
+    Unless `out` = (sep_idx, sep_count, sep_prefix) is given, sep_idx is allocated and pre-filled
+    with `fill` by torch; the library leaves entries beyond the count untouched.
     """
     _dev(is_sep)
     assert is_sep.dtype == torch.uint8 and is_sep.dim() == 2
     B, L = is_sep.shape
-    cap = L if cap is None else int(cap)
     dev = is_sep.device
-    idx = torch.full((B, max(cap, 1)), fill, dtype=torch.int32, device=dev)
-    cnt = torch.empty((B,), dtype=torch.int32, device=dev)
-    pre = torch.empty((B, L + 1), dtype=torch.int32, device=dev) if want_prefix else None
+    if out is None:
+        cap = L if cap is None else int(cap)
+        idx = torch.full((B, max(cap, 1)), fill, dtype=torch.int32, device=dev)
+        cnt = torch.empty((B,), dtype=torch.int32, device=dev)
+        pre = torch.empty((B, L + 1), dtype=torch.int32, device=dev) if want_prefix else None
+    else:
+        idx, cnt, pre = out
+        _dev(idx, cnt, pre)
+        cap = idx.shape[1]
     lib = load()
-    ws = _ws(lib.sepattn_compact_workspace_bytes(B, L), dev)
+    if ws is None:
+        ws = _ws(lib.sepattn_compact_workspace_bytes(B, L), dev)
     _check("sepattn_compact_indices",
            lib.sepattn_compact_indices(_ptr(is_sep), B, L, _ptr(idx), cap, _ptr(cnt), _ptr(pre), _ptr(ws),
                                        ws.numel(), _stream(is_sep)))

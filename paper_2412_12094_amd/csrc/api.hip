@@ -3,7 +3,32 @@
 // cover.
 #include "common.h"
 
+#include <vector>
+
 using namespace sepattn;
+
+namespace sepattn {
+namespace {
+struct ProfState {
+    int kernel = -1;
+    int used = 0;
+    bool open = false;  // a start event was recorded and its stop is pending
+    std::vector<hipEvent_t> start, stop;
+} g_prof;
+}  // namespace
+
+void profile_mark(int kernel, hipStream_t st, bool stop) {
+    if (kernel != g_prof.kernel) return;
+    if (!stop) {
+        if (g_prof.used >= (int)g_prof.start.size()) return;
+        g_prof.open = hipEventRecord(g_prof.start[g_prof.used], st) == hipSuccess;
+    } else if (g_prof.open) {
+        (void)hipEventRecord(g_prof.stop[g_prof.used], st);
+        g_prof.open = false;
+        ++g_prof.used;
+    }
+}
+}  // namespace sepattn
 
 namespace {
 
@@ -61,6 +86,59 @@ const char *sepattn_status_string(int status) {
         case SEPATTN_ERR_HIP: return "HIP runtime error at kernel launch";
         default: return "unknown status";
     }
+}
+
+const char *sepattn_kernel_name(int kernel) {
+    static const char *names[SEPATTN_K_COUNT] = {"mark_kernel", "compact_count_kernel", "compact_write_kernel",
+                                                 "fwd_bf16_kernel", "dq_kernel", "dkv_kernel_far",
+                                                 "dkv_kernel_band", "decode_split_kernel",
+                                                 "decode_merge_kernel", "evict_plan_kernel",
+                                                 "evict_move_kernel"};
+    return (kernel >= 0 && kernel < SEPATTN_K_COUNT) ? names[kernel] : "unknown";
+}
+
+int sepattn_profile_begin(int kernel, int max_records) {
+    if (kernel < 0 || kernel >= SEPATTN_K_COUNT || max_records < 1 || max_records > (1 << 20))
+        return SEPATTN_ERR_PARAM;
+    if (g_prof.kernel >= 0) return SEPATTN_ERR_PARAM;  // already profiling
+    g_prof.start.assign(max_records, nullptr);
+    g_prof.stop.assign(max_records, nullptr);
+    for (int i = 0; i < max_records; ++i) {
+        if (hipEventCreate(&g_prof.start[i]) != hipSuccess || hipEventCreate(&g_prof.stop[i]) != hipSuccess) {
+            for (int k = 0; k <= i; ++k) {
+                if (g_prof.start[k]) (void)hipEventDestroy(g_prof.start[k]);
+                if (g_prof.stop[k]) (void)hipEventDestroy(g_prof.stop[k]);
+            }
+            g_prof.start.clear();
+            g_prof.stop.clear();
+            return SEPATTN_ERR_HIP;
+        }
+    }
+    g_prof.used = 0;
+    g_prof.open = false;
+    g_prof.kernel = kernel;
+    return SEPATTN_OK;
+}
+
+int sepattn_profile_end(float *ms, int *n_records) {
+    if (!ms || !n_records) return SEPATTN_ERR_NULL;
+    if (g_prof.kernel < 0) return SEPATTN_ERR_PARAM;
+    int rc = SEPATTN_OK;
+    for (int i = 0; i < g_prof.used; ++i) {
+        if (hipEventSynchronize(g_prof.stop[i]) != hipSuccess ||
+            hipEventElapsedTime(&ms[i], g_prof.start[i], g_prof.stop[i]) != hipSuccess)
+            rc = SEPATTN_ERR_HIP;
+    }
+    *n_records = g_prof.used;
+    for (size_t i = 0; i < g_prof.start.size(); ++i) {
+        (void)hipEventDestroy(g_prof.start[i]);
+        (void)hipEventDestroy(g_prof.stop[i]);
+    }
+    g_prof.start.clear();
+    g_prof.stop.clear();
+    g_prof.kernel = -1;
+    g_prof.used = 0;
+    return rc;
 }
 
 int sepattn_mark_separators(const int32_t *token_ids, int B, int L, const int32_t *sep_ids,

@@ -15,6 +15,15 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? SEPATTN_OK
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Measurement hook: brackets launches of the selected kernel with HIP events (see sepattn.h).
+void profile_mark(int kernel, hipStream_t st, bool stop);
+struct ProfScope {
+    int kernel;
+    hipStream_t st;
+    ProfScope(int k, hipStream_t s) : kernel(k), st(s) { profile_mark(kernel, st, false); }
+    ~ProfScope() { profile_mark(kernel, st, true); }
+};
+
 // ---- integer kernels -------------------------------------------------------------------------
 struct SepIdSet {
     int n;

@@ -239,13 +239,17 @@ int launch_decode_t(const sepkv_params &p, const T *q, const T *Kc, const T *Vc,
                     T *out, float *lse, float *part, hipStream_t st) {
     int G = p.Hq / p.Hkv, GT = pick_gt(G), nsplit = pick_nsplit(p);
     dim3 grid(nsplit, p.S * p.Hkv * (G / GT)), block(kDecodeThreads);
+    {
+    ProfScope prof(SEPATTN_K_DECODE_SPLIT, st);
     if (GT == 4)
         hipLaunchKernelGGL((decode_split_kernel<T, D, 4>), grid, block, 0, st, p, nsplit, q, Kc, Vc, sizes, part);
     else if (GT == 2)
         hipLaunchKernelGGL((decode_split_kernel<T, D, 2>), grid, block, 0, st, p, nsplit, q, Kc, Vc, sizes, part);
     else
         hipLaunchKernelGGL((decode_split_kernel<T, D, 1>), grid, block, 0, st, p, nsplit, q, Kc, Vc, sizes, part);
+    }
     if (hipGetLastError() != hipSuccess) return SEPATTN_ERR_HIP;
+    ProfScope prof(SEPATTN_K_DECODE_MERGE, st);
     hipLaunchKernelGGL((decode_merge_kernel<T, D>), dim3(p.S * p.Hq), dim3(D), 0, st, nsplit, part, out, lse);
     return launch_status();
 }

@@ -179,8 +179,12 @@ int launch_evict(const sepkv_params &p, void *Kc, void *Vc, uint8_t *win_is_sep,
                                                 align_up((size_t)p.S * kPlanInts * sizeof(int32_t), 256));
     int elem = (p.dtype == SEPATTN_BF16) ? 2 : 4;
     int row16 = p.d * elem / 16;
-    hipLaunchKernelGGL(evict_plan_kernel, dim3(p.S), dim3(kEvictThreads), 0, st, p, win_is_sep, sizes, plan, kept);
+    {
+        ProfScope prof(SEPATTN_K_EVICT_PLAN, st);
+        hipLaunchKernelGGL(evict_plan_kernel, dim3(p.S), dim3(kEvictThreads), 0, st, p, win_is_sep, sizes, plan, kept);
+    }
     if (hipGetLastError() != hipSuccess) return SEPATTN_ERR_HIP;
+    ProfScope prof(SEPATTN_K_EVICT_MOVE, st);
     hipLaunchKernelGGL(evict_move_kernel, dim3(p.S * p.Hkv * 2), dim3(kEvictThreads), 0, st, p, row16,
                        (uint4 *)Kc, (uint4 *)Vc, plan, kept);
     return launch_status();

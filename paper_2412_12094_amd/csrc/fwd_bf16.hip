@@ -224,6 +224,7 @@ int launch_fwd(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
     int GP = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
     int TP = 32 * NW / GP;
     dim3 grid((p.L + TP - 1) / TP, p.B * p.Hkv * (G / GP)), block(NW * 64);
+    ProfScope prof(SEPATTN_K_FORWARD, st);
     if (GP == 4)
         hipLaunchKernelGGL((fwd_bf16_kernel<D, NW, 4>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, O, LSE);
     else if (GP == 2)

@@ -40,6 +40,7 @@ int launch_mark(const int32_t *token_ids, long n_tokens, const SepIdSet &set, ui
                 hipStream_t st) {
     long threads = (n_tokens + 3) / 4;
     unsigned blocks = (unsigned)((threads + 255) / 256);
+    ProfScope prof(SEPATTN_K_MARK, st);
     hipLaunchKernelGGL(mark_kernel, dim3(blocks), dim3(256), 0, st, token_ids, n_tokens, set, is_sep);
     return launch_status();
 }
@@ -133,9 +134,13 @@ int launch_compact(const uint8_t *is_sep, int B, int L, int32_t *sep_idx, int ca
                    int32_t *sep_count, int32_t *sep_prefix, int32_t *chunk_counts, hipStream_t st) {
     int n_chunks = (L + kCompactChunk - 1) / kCompactChunk;
     dim3 grid(n_chunks, B);
-    hipLaunchKernelGGL(compact_count_kernel, grid, dim3(kCompactThreads), 0, st, is_sep, L, n_chunks,
-                       chunk_counts);
+    {
+        ProfScope prof(SEPATTN_K_COMPACT_COUNT, st);
+        hipLaunchKernelGGL(compact_count_kernel, grid, dim3(kCompactThreads), 0, st, is_sep, L, n_chunks,
+                           chunk_counts);
+    }
     if (hipGetLastError() != hipSuccess) return SEPATTN_ERR_HIP;
+    ProfScope prof(SEPATTN_K_COMPACT_WRITE, st);
     hipLaunchKernelGGL(compact_write_kernel, grid, dim3(kCompactThreads), 0, st, is_sep, L, n_chunks,
                        chunk_counts, sep_idx, cap, sep_count, sep_prefix);
     return launch_status();

@@ -29,6 +29,19 @@ def sp():
     return sp_
 
 
+def assert_close(got, ref, dtype, name=""):
+    """The dtype's max-abs tolerance; for bf16 plus 2^-8 |ref|, the rounding step of the bf16 output
+    format itself (half an ulp is up to 2^-8 |x|): a gradient element of magnitude 5, as dV of the
+    initial tokens has at 8K context, cannot be STORED in bf16 to better than 1.6e-2, whoever
+    computes it.  For |ref| <= 1 the bound is the plain 2e-2 (+0.4e-2)."""
+    err = np.abs(got - ref)
+    bound = np.full(ref.shape, TOL[dtype])
+    if dtype == "bf16":
+        bound = bound + np.abs(ref) * 2.0 ** -8
+    worst = np.unravel_index(np.argmax(err - bound), err.shape)
+    assert (err <= bound).all(), (name, float(err[worst]), float(ref[worst]))
+
+
 def dev(x, dtype=None):
     t = torch.from_numpy(np.ascontiguousarray(x)).cuda()
     if dtype == "bf16":
@@ -150,8 +163,7 @@ def check_backward(sp, B, Hq, Hkv, L, d, a, n, p, dtype, seed, qkv_scale=1.0):
     for name, got, ref in (("dQ", dQ, rQ), ("dK", dK, rK), ("dV", dV, rV)):
         g = host(got)
         assert np.isfinite(g).all(), name
-        err = np.abs(g - ref).max()
-        assert err <= TOL[dtype], (name, err)
+        assert_close(g, ref, dtype, name)
 
 
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
@@ -230,9 +242,9 @@ def test_config2_full_forward_backward(sp):
         rQ, rK, rV = oracle.backward(inp["Q"][sl], inp["K"][sl], inp["V"][sl], inp["dO"][sl], flags[sl], c.a, c.n, c.scale)
         assert np.abs(host(O[sl]) - Oref).max() <= 2e-2
         assert np.abs(host(LSE[sl]) - Lref).max() <= 2e-3
-        assert np.abs(host(dQ[sl]) - rQ).max() <= 2e-2
-        assert np.abs(host(dK[sl]) - rK).max() <= 2e-2
-        assert np.abs(host(dV[sl]) - rV).max() <= 2e-2
+        assert_close(host(dQ[sl]), rQ, "bf16", "dQ")
+        assert_close(host(dK[sl]), rK, "bf16", "dK")
+        assert_close(host(dV[sl]), rV, "bf16", "dV")
 
 
 def test_config3_backward_one_kv_group_at_full_size(sp):
@@ -250,9 +262,9 @@ def test_config3_backward_one_kv_group_at_full_size(sp):
     hs = slice(kv * G, (kv + 1) * G)
     rQ, rK, rV = oracle.backward(inp["Q"][:, hs], inp["K"][:, kv:kv + 1], inp["V"][:, kv:kv + 1],
                                  inp["dO"][:, hs], flags, c.a, c.n, c.scale)
-    assert np.abs(host(dQ[:, hs]) - rQ).max() <= 2e-2
-    assert np.abs(host(dK[:, kv:kv + 1]) - rK).max() <= 2e-2
-    assert np.abs(host(dV[:, kv:kv + 1]) - rV).max() <= 2e-2
+    assert_close(host(dQ[:, hs]), rQ, "bf16", "dQ")
+    assert_close(host(dK[:, kv:kv + 1]), rK, "bf16", "dK")
+    assert_close(host(dV[:, kv:kv + 1]), rV, "bf16", "dV")
 
 
 def test_forward_backward_are_bit_reproducible(sp):

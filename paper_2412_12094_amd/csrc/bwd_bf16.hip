@@ -47,7 +47,7 @@ __host__ __device__ inline FarGeom far_geom(const sepattn_params &p) {
     return g;
 }
 
-__device__ inline float bf16_dot8(uint4 a, uint4 b) {
+__device__ inline float bf16_dot8(u32x4 a, u32x4 b) {
     float s = 0.f;
     const uint32_t *x = reinterpret_cast<const uint32_t *>(&a);
     const uint32_t *y = reinterpret_cast<const uint32_t *>(&b);
@@ -109,9 +109,9 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(
         float part = 0.f;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
-            uint4 dq4 = *reinterpret_cast<const uint4 *>(dorow + ks * 16 + 8 * hh);
-            uint4 o4 = *reinterpret_cast<const uint4 *>(orow + ks * 16 + 8 * hh);
-            qreg[ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(qrow + ks * 16 + 8 * hh));
+            u32x4 dq4 = *reinterpret_cast<const u32x4 *>(dorow + ks * 16 + 8 * hh);
+            u32x4 o4 = *reinterpret_cast<const u32x4 *>(orow + ks * 16 + 8 * hh);
+            qreg[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(qrow + ks * 16 + 8 * hh));
             doreg[ks] = as_bf16x8(dq4);
             part += bf16_dot8(dq4, o4);
         }
@@ -127,7 +127,7 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[db][i] = 0.f;
 
-    uint4 kpre[LOADS], vpre[LOADS];
+    u32x4 kpre[LOADS], vpre[LOADS];
     int lo_pre[LOADS], hi_pre[LOADS];
     auto prefetch = [&](int t) {
 #pragma unroll
@@ -135,8 +135,8 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(
             int c = tid + u * NT;
             int r = c / CH, ch = c % CH;
             int j = stream_key(st, t * kBN + r, p, idx, prefix, lo_pre[u], hi_pre[u]);
-            kpre[u] = *reinterpret_cast<const uint4 *>(Kh + (long)j * D + ch * 8);
-            vpre[u] = *reinterpret_cast<const uint4 *>(Vh + (long)j * D + ch * 8);
+            kpre[u] = *reinterpret_cast<const u32x4 *>(Kh + (long)j * D + ch * 8);
+            vpre[u] = *reinterpret_cast<const u32x4 *>(Vh + (long)j * D + ch * 8);
         }
     };
     prefetch(0);
@@ -147,8 +147,8 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(
         for (int u = 0; u < LOADS; ++u) {
             int c = tid + u * NT;
             int r = c / CH, ch = c % CH;
-            *reinterpret_cast<uint4 *>(Ks + r * KS + ch * 8) = kpre[u];
-            *reinterpret_cast<uint4 *>(Vs + r * KS + ch * 8) = vpre[u];
+            *reinterpret_cast<u32x4 *>(Ks + r * KS + ch * 8) = kpre[u];
+            *reinterpret_cast<u32x4 *>(Vs + r * KS + ch * 8) = vpre[u];
             if (ch == 0) {
                 lo_s[r] = lo_pre[u];
                 hi_s[r] = hi_pre[u];
@@ -318,8 +318,8 @@ __global__ __launch_bounds__(kDkvWaves * 64) void dkv_kernel(
             const uint16_t *krow = K + (kvrow0 + j) * D, *vrow = V + (kvrow0 + j) * D;
 #pragma unroll
             for (int ks = 0; ks < KSTEPS; ++ks) {
-                kreg[ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(krow + ks * 16 + 8 * hh));
-                vreg[ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(vrow + ks * 16 + 8 * hh));
+                kreg[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(krow + ks * 16 + 8 * hh));
+                vreg[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(vrow + ks * 16 + 8 * hh));
             }
         }
         f32x16 dk[DB], dv[DB];
@@ -331,7 +331,7 @@ __global__ __launch_bounds__(kDkvWaves * 64) void dkv_kernel(
         const int n_qt = (q_hi - q_lo + kBQ - 1) / kBQ;
         const int n_tiles = G * n_qt;
 
-        uint4 qpre[LOADS], dopre[LOADS];
+        u32x4 qpre[LOADS], dopre[LOADS];
         float lse_pre[LOADS], d_pre[LOADS];
         auto prefetch = [&](int tt) {
             int g = tt / n_qt, qt = tt % n_qt;
@@ -341,8 +341,8 @@ __global__ __launch_bounds__(kDkvWaves * 64) void dkv_kernel(
                 int c = tid + u * NT;
                 int r = c / CH, ch = c % CH;
                 long row = hrow0 + min(q_lo + qt * kBQ + r, p.L - 1);
-                qpre[u] = *reinterpret_cast<const uint4 *>(Q + row * D + ch * 8);
-                dopre[u] = *reinterpret_cast<const uint4 *>(dO + row * D + ch * 8);
+                qpre[u] = *reinterpret_cast<const u32x4 *>(Q + row * D + ch * 8);
+                dopre[u] = *reinterpret_cast<const u32x4 *>(dO + row * D + ch * 8);
                 if (ch == 0) {
                     lse_pre[u] = LSE[row] * kLog2e_f;
                     d_pre[u] = Dws[row];
@@ -357,8 +357,8 @@ __global__ __launch_bounds__(kDkvWaves * 64) void dkv_kernel(
             for (int u = 0; u < LOADS; ++u) {
                 int c = tid + u * NT;
                 int r = c / CH, ch = c % CH;
-                *reinterpret_cast<uint4 *>(Qs + r * QS + ch * 8) = qpre[u];
-                *reinterpret_cast<uint4 *>(dOs + r * QS + ch * 8) = dopre[u];
+                *reinterpret_cast<u32x4 *>(Qs + r * QS + ch * 8) = qpre[u];
+                *reinterpret_cast<u32x4 *>(dOs + r * QS + ch * 8) = dopre[u];
                 if (ch == 0) {
                     lse_s[r] = lse_pre[u];
                     d_s[r] = d_pre[u];

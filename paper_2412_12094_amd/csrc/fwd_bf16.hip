@@ -9,10 +9,16 @@
 // two parts are visible to every row of the tile (they are older than every window and are initial
 // tokens / separators) and are gathered through the compacted separator index list; only band keys
 // need the per-element test  j <= i and (i-j < n or j is an initial token or a separator).
-// The stream is cut into tiles of 64 keys; K and V rows are staged row-major in LDS (software
-// prefetch of the next tile into registers); S^T = K Q^T and O^T += V^T P^T run on
-// v_mfma_f32_32x32x16_bf16 with V^T read by ds_read_b64_tr_b16.  A wave skips 32-key blocks that lie
-// entirely in its future and drops the mask test on blocks every one of its rows sees in full.
+//
+// Pipeline per 64-key tile (LDS double-buffered, one barrier per tile):
+//   meta(t+3): index / prefix loads  ->  rows(t+2): K,V row loads into registers
+//   ->  store(t+1): registers to LDS stage (t+1)&1  ->  compute(t) from LDS stage t&1.
+// S^T = K Q^T and O^T += V^T P^T run on v_mfma_f32_32x32x16_bf16 with V^T read by
+// ds_read_b64_tr_b16; the LDS operand reads of a 32-key block are issued as one batch ahead of its
+// MFMAs.  A wave skips 32-key blocks that lie entirely in its future and drops the mask test on
+// blocks every one of its rows sees in full.  The running maximum is only raised when it grows by
+// more than 2^8 (the accumulators stay exact: all terms carry the same stale maximum), which removes
+// almost every rescale of the output accumulators.
 #include "common.h"
 #include "mfma_common.h"
 #include "key_stream.h"
@@ -21,6 +27,8 @@ namespace sepattn {
 
 namespace {
 
+constexpr float kRescaleThreshold = 8.f;  // log2 units
+
 template <int D, int NW, int GP>
 __global__ __launch_bounds__(NW * 64) void fwd_bf16_kernel(
     sepattn_params p, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
@@ -28,20 +36,21 @@ __global__ __launch_bounds__(NW * 64) void fwd_bf16_kernel(
     const int32_t *__restrict__ sep_prefix, uint16_t *__restrict__ O, float *__restrict__ LSE) {
     constexpr int NT = NW * 64;
     constexpr int TP = 32 * NW / GP;  // query positions per workgroup
-    constexpr int KS = D + 8;         // LDS row strides (elements): see bank notes in the design doc
+    constexpr int KS = D + 8;         // LDS row strides in elements (bank spreading)
     constexpr int VS = D + 32;
-    constexpr int CH = D / 8;                 // 16-byte chunks per row
-    constexpr int LOADS = kBN * CH / NT;      // chunks per thread per tensor per tile
+    constexpr int CH = D / 8;             // 16-byte chunks per row
+    constexpr int LOADS = kBN * CH / NT;  // rows per thread per tile (one chunk of each)
     constexpr int KSTEPS = D / 16;
     constexpr int DB = D / 32;
-    static_assert(kBN * CH % NT == 0, "tile must divide among the threads");
+    static_assert(kBN * CH % NT == 0 && LOADS >= 1, "tile must divide among the threads");
 
-    __shared__ __attribute__((aligned(16))) uint16_t Ks[kBN * KS];
-    __shared__ __attribute__((aligned(16))) uint16_t Vs[kBN * VS];
-    __shared__ __attribute__((aligned(16))) int lo_s[kBN];
-    __shared__ __attribute__((aligned(16))) int hi_s[kBN];
+    __shared__ __attribute__((aligned(16))) uint16_t Ks[2][kBN * KS];
+    __shared__ __attribute__((aligned(16))) uint16_t Vs[2][kBN * VS];
+    __shared__ __attribute__((aligned(16))) int lo_s[2][kBN];
+    __shared__ __attribute__((aligned(16))) int hi_s[2][kBN];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps branches scalar
     const int qi = lane & 31, hh = lane >> 5;
     const int G = p.Hq / p.Hkv, groups = G / GP;
     const int tile = gridDim.x - 1 - blockIdx.x;  // late tiles carry more separators: start them first
@@ -68,7 +77,7 @@ __global__ __launch_bounds__(NW * 64) void fwd_bf16_kernel(
         const uint16_t *qrow = Q + (((long)b * p.Hq + head) * p.L + min(iq, p.L - 1)) * D;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks)
-            qreg[ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(qrow + ks * 16 + 8 * hh));
+            qreg[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(qrow + ks * 16 + 8 * hh));
     }
     const float sl2 = p.scale * kLog2e_f;
 
@@ -77,125 +86,178 @@ __global__ __launch_bounds__(NW * 64) void fwd_bf16_kernel(
     for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;  // m_run in the log2 domain (scores times scale*log2e)
 
-    // software prefetch registers
-    uint4 kpre[LOADS], vpre[LOADS];
+    // ---- load pipeline state (per thread: LOADS rows, one 16-byte chunk of K and of V each)
+    const int my_ch = tid % CH, my_r0 = tid / CH;  // row of load u is my_r0 + u * (NT / CH)
+    int raw0[LOADS], raw1[LOADS];                  // meta stage: idx entry or prefix[j], prefix[j+1]
+    u32x4 kpre[LOADS], vpre[LOADS];                // row stage
     int lo_pre[LOADS], hi_pre[LOADS];
-    auto prefetch = [&](int t) {
-#pragma unroll
-        for (int u = 0; u < LOADS; ++u) {
-            int c = tid + u * NT;
-            int r = c / CH, ch = c % CH;
-            int j = stream_key(st, t * kBN + r, p, idx, prefix, lo_pre[u], hi_pre[u]);
-            kpre[u] = *reinterpret_cast<const uint4 *>(Kh + (long)j * D + ch * 8);
-            vpre[u] = *reinterpret_cast<const uint4 *>(Vh + (long)j * D + ch * 8);
-        }
-    };
-    prefetch(0);
 
-    for (int t = 0; t < n_tiles; ++t) {
-        __syncthreads();  // everyone is done reading the previous tile
-#pragma unroll
-        for (int u = 0; u < LOADS; ++u) {
-            int c = tid + u * NT;
-            int r = c / CH, ch = c % CH;
-            *reinterpret_cast<uint4 *>(Ks + r * KS + ch * 8) = kpre[u];
-            *reinterpret_cast<uint4 *>(Vs + r * VS + ch * 8) = vpre[u];
-            if (ch == 0) {
-                lo_s[r] = lo_pre[u];
-                hi_s[r] = hi_pre[u];
+    auto issue_meta = [&](int t) {
+        static_for<LOADS>([&](auto U) {
+            constexpr int u = U;
+            int k = t * kBN + my_r0 + u * (NT / CH);
+            raw0[u] = 0;
+            raw1[u] = 0;
+            if (k >= st.n_init && k < st.n_dense) {
+                raw0[u] = idx[min(st.sep_lo + k - st.n_init, p.cap - 1)];
+            } else if (k >= st.n_dense && k < st.n_total) {
+                int j = st.bs + (k - st.n_dense);
+                raw0[u] = prefix[j];
+                raw1[u] = prefix[j + 1];
             }
-        }
-        __syncthreads();
-        if (t + 1 < n_tiles) prefetch(t + 1);
+        });
+    };
+    auto issue_rows = [&](int t) {
+        static_for<LOADS>([&](auto U) {
+            constexpr int u = U;
+            int k = t * kBN + my_r0 + u * (NT / CH);
+            int j, lo, hi;
+            if (k >= st.n_total) {  // padding of the last tile: never visible, any valid row
+                j = 0;
+                lo = kIntMax;
+                hi = -1;
+            } else if (k < st.n_init) {
+                j = k;
+                lo = j;
+                hi = kIntMax;
+            } else if (k < st.n_dense) {
+                // the clamp keeps a stale list tail (caller broke sep_count <= cap) from faulting
+                j = min(max(raw0[u], 0), p.L - 1);
+                lo = j;
+                hi = kIntMax;
+            } else {
+                j = st.bs + (k - st.n_dense);
+                bool always = (j < p.a) || (raw1[u] != raw0[u]);
+                lo = j;
+                hi = always ? kIntMax : j + p.n - 1;
+            }
+            lo_pre[u] = lo;
+            hi_pre[u] = hi;
+            kpre[u] = *reinterpret_cast<const u32x4 *>(Kh + (long)j * D + my_ch * 8);
+            vpre[u] = *reinterpret_cast<const u32x4 *>(Vh + (long)j * D + my_ch * 8);
+        });
+    };
+    auto store_tile = [&](int stage) {
+        static_for<LOADS>([&](auto U) {
+            constexpr int u = U;
+            int r = my_r0 + u * (NT / CH);
+            *reinterpret_cast<u32x4 *>(&Ks[stage][r * KS + my_ch * 8]) = kpre[u];
+            *reinterpret_cast<u32x4 *>(&Vs[stage][r * VS + my_ch * 8]) = vpre[u];
+            if (my_ch == 0) {
+                lo_s[stage][r] = lo_pre[u];
+                hi_s[stage][r] = hi_pre[u];
+            }
+        });
+    };
 
+    issue_meta(0);
+    issue_rows(0);
+    if (n_tiles > 1) issue_meta(1);
+    store_tile(0);
+    if (n_tiles > 1) issue_rows(1);
+    if (n_tiles > 2) issue_meta(2);
+    __syncthreads();
+
+    const int a_row = pi_row(qi);
+    for (int t = 0; t < n_tiles; ++t) {
+        const int stage = t & 1;
+        if (t + 1 < n_tiles) store_tile(stage ^ 1);
+        if (t + 2 < n_tiles) issue_rows(t + 2);
+        if (t + 3 < n_tiles) issue_meta(t + 3);
+
+        const uint16_t *Kst = Ks[stage], *Vst = Vs[stage];
         // classify the two 32-key blocks for this wave: skip / all visible / test each pair
         int mode[2];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) mode[kb] = block_mode(st, t * kBN + kb * 32, pw, p.n);
-        if (mode[0] == 0 && mode[1] == 0) continue;
 
-        // S^T = K Q^T for the active blocks
-        f32x16 sacc[2];
+        if (mode[0] != 0 || mode[1] != 0) {
+            // ---- S^T = K Q^T: all operand reads of a block first, then its MFMAs
+            f32x16 sacc[2];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
-            if (mode[kb] != 0) {
-                int row = kb * 32 + pi_row(qi);
+            for (int kb = 0; kb < 2; ++kb) {
+                if (mode[kb] == 0) continue;
+                bf16x8 ka[KSTEPS];
 #pragma unroll
                 for (int ks = 0; ks < KSTEPS; ++ks)
-                    sacc[kb] = mfma_bf16(lds_read_a(Ks, row, KS, ks * 16 + 8 * hh), qreg[ks], sacc[kb]);
+                    ka[ks] = lds_read_a(Kst, kb * 32 + a_row, KS, ks * 16 + 8 * hh);
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < KSTEPS; ++ks) sacc[kb] = mfma_bf16(ka[ks], qreg[ks], sacc[kb]);
             }
-        }
-        // scale into the log2 domain, mask, running maximum
-        float m_loc = -INFINITY;
+            // ---- mask (only where needed) and block maximum of the raw scores
+            float m_loc = -INFINITY;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            if (mode[kb] == 0) {
+            for (int kb = 0; kb < 2; ++kb) {
+                if (mode[kb] == 0) continue;
+                if (mode[kb] == 2) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) sacc[kb][i] = -INFINITY;
-            } else if (mode[kb] == 1) {
+                    for (int half = 0; half < 2; ++half) {
+                        int base = kb * 32 + 16 * half + 8 * hh;
+                        int4 lo0 = *reinterpret_cast<const int4 *>(&lo_s[stage][base]);
+                        int4 lo1 = *reinterpret_cast<const int4 *>(&lo_s[stage][base + 4]);
+                        int4 hi0 = *reinterpret_cast<const int4 *>(&hi_s[stage][base]);
+                        int4 hi1 = *reinterpret_cast<const int4 *>(&hi_s[stage][base + 4]);
+                        int los[8] = {lo0.x, lo0.y, lo0.z, lo0.w, lo1.x, lo1.y, lo1.z, lo1.w};
+                        int his[8] = {hi0.x, hi0.y, hi0.z, hi0.w, hi1.x, hi1.y, hi1.z, hi1.w};
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    sacc[kb][i] *= sl2;
-                    m_loc = fmaxf(m_loc, sacc[kb][i]);
-                }
-            } else {
-#pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    int base = kb * 32 + 16 * half + 8 * hh;
-                    int4 lo0 = *reinterpret_cast<const int4 *>(lo_s + base);
-                    int4 lo1 = *reinterpret_cast<const int4 *>(lo_s + base + 4);
-                    int4 hi0 = *reinterpret_cast<const int4 *>(hi_s + base);
-                    int4 hi1 = *reinterpret_cast<const int4 *>(hi_s + base + 4);
-                    int los[8] = {lo0.x, lo0.y, lo0.z, lo0.w, lo1.x, lo1.y, lo1.z, lo1.w};
-                    int his[8] = {hi0.x, hi0.y, hi0.z, hi0.w, hi1.x, hi1.y, hi1.z, hi1.w};
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) {
-                        int i = 8 * half + k;
-                        bool vis = (los[k] <= iq) && (iq <= his[k]);
-                        float s = vis ? sacc[kb][i] * sl2 : -INFINITY;
-                        sacc[kb][i] = s;
-                        m_loc = fmaxf(m_loc, s);
+                        for (int k = 0; k < 8; ++k) {
+                            bool vis = (los[k] <= iq) && (iq <= his[k]);
+                            sacc[kb][8 * half + k] = vis ? sacc[kb][8 * half + k] : -INFINITY;
+                        }
                     }
                 }
+#pragma unroll
+                for (int i = 0; i < 16; ++i) m_loc = fmaxf(m_loc, sacc[kb][i]);
             }
-        }
-        float m_new = fmaxf(m_run, pair_max(m_loc));
-        float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-        float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
-        m_run = m_new;
-        float psum = 0.f;
+            // ---- online softmax with a lazily raised maximum
+            float m_new = fmaxf(m_run, pair_max(m_loc * sl2));
+            bool grow = m_new > m_run + kRescaleThreshold;
+            if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
+                float alpha = grow ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.f;
+                m_run = grow ? m_new : m_run;
+                l_run *= alpha;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+                for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                float pr = __builtin_amdgcn_exp2f(sacc[kb][i] - m_safe);
-                sacc[kb][i] = pr;
-                psum += pr;
+                    for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
             }
-        l_run = l_run * alpha + psum;
+            const float neg_m = (m_run == -INFINITY) ? 0.f : -m_run;
+            float psum = 0.f;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+            for (int kb = 0; kb < 2; ++kb) {
+                if (mode[kb] == 0) continue;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
+                for (int i = 0; i < 16; ++i) {
+                    float pr = __builtin_amdgcn_exp2f(fmaf(sacc[kb][i], sl2, neg_m));
+                    sacc[kb][i] = pr;
+                    psum += pr;
+                }
+            }
+            l_run += psum;
 
-        // O^T += V^T P^T
+            // ---- O^T += V^T P^T: the 16 transposed reads of a block first, then its 2*DB MFMAs
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            if (mode[kb] == 0) continue;
+            for (int kb = 0; kb < 2; ++kb) {
+                if (mode[kb] == 0) continue;
+                bf16x8 vt[2][DB];
 #pragma unroll
-            for (int stp = 0; stp < 2; ++stp) {
-                bf16x8 pb = pack_bf16x8(sacc[kb], 8 * stp);
+                for (int stp = 0; stp < 2; ++stp)
 #pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    bf16x8 vt = lds_read_a_tr(Vs, kb * 32 + stp * 16, VS, db * 32, lane);
-                    oacc[db] = mfma_bf16(vt, pb, oacc[db]);
+                    for (int db = 0; db < DB; ++db)
+                        vt[stp][db] = lds_read_a_tr(Vst, kb * 32 + stp * 16, VS, db * 32, lane);
+#pragma unroll
+                for (int stp = 0; stp < 2; ++stp) {
+                    bf16x8 pb = pack_bf16x8(sacc[kb], 8 * stp);
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) oacc[db] = mfma_bf16(vt[stp][db], pb, oacc[db]);
                 }
             }
         }
+        __syncthreads();  // stage^1 is complete for the next tile; everyone is done reading `stage`
     }
 
     // epilogue: normalise, store O (bf16) and LSE (natural log)

@@ -24,12 +24,30 @@
 
 namespace sepattn {
 
+// compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>).  Used where a
+// register array must be indexed by constants only (a rolled loop would push it to scratch memory).
+template <int I>
+struct IntC {
+    static constexpr int value = I;
+    constexpr operator int() const { return I; }
+};
+template <int N, int I = 0, typename F>
+__device__ inline void static_for(F &&f) {
+    if constexpr (I < N) {
+        f(IntC<I>{});
+        static_for<N, I + 1>(f);
+    }
+}
+
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+// native 16-byte vector for staging registers (HIP's uint4 is a struct the optimiser may keep in
+// scratch memory when it sits in an array)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float kLog2e_f = 1.4426950408889634f;
 constexpr float kLn2_f = 0.6931471805599453f;
@@ -48,14 +66,7 @@ __device__ inline f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-__device__ inline bf16x8 as_bf16x8(uint4 u) {
-    union {
-        uint4 u;
-        bf16x8 v;
-    } x;
-    x.u = u;
-    return x.v;
-}
+__device__ inline bf16x8 as_bf16x8(u32x4 u) { return __builtin_bit_cast(bf16x8, u); }
 
 // 16-byte read of a row-major A operand from LDS
 __device__ inline bf16x8 lds_read_a(const uint16_t *tile, int row, int stride, int col) {

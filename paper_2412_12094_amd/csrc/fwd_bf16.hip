@@ -23,6 +23,21 @@
 #include "mfma_common.h"
 #include "key_stream.h"
 
+#ifdef SEPATTN_X_TIMING
+__device__ unsigned long long g_dbg[8 * 8 * 2048];
+extern "C" int sepattn_debug_read(unsigned long long *host, int n) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg), sizeof(unsigned long long) * n);
+}
+#define TICK(k)                                  \
+    {                                            \
+        unsigned long long now_ = clock64();     \
+        tacc[k] += now_ - tlast;                 \
+        tlast = now_;                            \
+    }
+#else
+#define TICK(k)
+#endif
+
 namespace sepattn {
 
 namespace {
@@ -30,7 +45,7 @@ namespace {
 constexpr float kRescaleThreshold = 8.f;  // log2 units
 
 template <int D, int NW, int GP>
-__global__ __launch_bounds__(NW * 64) void fwd_bf16_kernel(
+__global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(
     sepattn_params p, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
     const uint16_t *__restrict__ V, const int32_t *__restrict__ sep_idx,
     const int32_t *__restrict__ sep_prefix, uint16_t *__restrict__ O, float *__restrict__ LSE) {
@@ -53,9 +68,11 @@ __global__ __launch_bounds__(NW * 64) void fwd_bf16_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps branches scalar
     const int qi = lane & 31, hh = lane >> 5;
     const int G = p.Hq / p.Hkv, groups = G / GP;
-    const int tile = gridDim.x - 1 - blockIdx.x;  // late tiles carry more separators: start them first
+    const int n_pos_tiles = (p.L + TP - 1) / TP;
+    const TileGroup tg = xcd_tile_group(blockIdx.x, n_pos_tiles, p.B * p.Hkv * groups);
+    const int tile = n_pos_tiles - 1 - tg.rank;  // late tiles carry more separators: start them first
     const int i0 = tile * TP;
-    int y = blockIdx.y;
+    int y = tg.group;
     const int hg = y % groups;
     const int kv = (y / groups) % p.Hkv;
     const int b = y / (groups * p.Hkv);
@@ -161,12 +178,17 @@ __global__ __launch_bounds__(NW * 64) void fwd_bf16_kernel(
     __syncthreads();
 
     const int a_row = pi_row(qi);
+#ifdef SEPATTN_X_TIMING
+    unsigned long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tlast = clock64();
+#endif
     for (int t = 0; t < n_tiles; ++t) {
         const int stage = t & 1;
+        TICK(7)
         if (t + 1 < n_tiles) store_tile(stage ^ 1);
         if (t + 2 < n_tiles) issue_rows(t + 2);
         if (t + 3 < n_tiles) issue_meta(t + 3);
 
+        TICK(0)
         const uint16_t *Kst = Ks[stage], *Vst = Vs[stage];
         // classify the two 32-key blocks for this wave: skip / all visible / test each pair
         int mode[2];
@@ -188,6 +210,7 @@ __global__ __launch_bounds__(NW * 64) void fwd_bf16_kernel(
 #pragma unroll
                 for (int ks = 0; ks < KSTEPS; ++ks) sacc[kb] = mfma_bf16(ka[ks], qreg[ks], sacc[kb]);
             }
+            TICK(1)
             // ---- mask (only where needed) and block maximum of the raw scores
             float m_loc = -INFINITY;
 #pragma unroll
@@ -239,6 +262,7 @@ __global__ __launch_bounds__(NW * 64) void fwd_bf16_kernel(
             }
             l_run += psum;
 
+            TICK(2)
             // ---- O^T += V^T P^T: the 16 transposed reads of a block first, then its 2*DB MFMAs
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
@@ -256,9 +280,17 @@ __global__ __launch_bounds__(NW * 64) void fwd_bf16_kernel(
                     for (int db = 0; db < DB; ++db) oacc[db] = mfma_bf16(vt[stp][db], pb, oacc[db]);
                 }
             }
+            TICK(3)
         }
         __syncthreads();  // stage^1 is complete for the next tile; everyone is done reading `stage`
+        TICK(4)
     }
+#ifdef SEPATTN_X_TIMING
+    if (lane == 0 && blockIdx.x < 2048) {
+        tacc[5] = n_tiles;
+        for (int k = 0; k < 8; ++k) g_dbg[((long)blockIdx.x * 8 + wave) * 8 + k] = tacc[k];
+    }
+#endif
 
     // epilogue: normalise, store O (bf16) and LSE (natural log)
     float l_tot = pair_sum(l_run);
@@ -285,7 +317,7 @@ int launch_fwd(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
     int G = p.Hq / p.Hkv;
     int GP = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
     int TP = 32 * NW / GP;
-    dim3 grid((p.L + TP - 1) / TP, p.B * p.Hkv * (G / GP)), block(NW * 64);
+    dim3 grid(((p.L + TP - 1) / TP) * p.B * p.Hkv * (G / GP)), block(NW * 64);
     ProfScope prof(SEPATTN_K_FORWARD, st);
     if (GP == 4)
         hipLaunchKernelGGL((fwd_bf16_kernel<D, NW, 4>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, O, LSE);

@@ -15,6 +15,26 @@ namespace sepattn {
 
 constexpr int kBN = 64;  // keys per LDS tile
 
+// XCD-aware decomposition of a 1-D grid of n_tiles * n_groups workgroups into (tile rank, group),
+// where a group is one (batch, KV head, packed query-head group) and owns its own K/V rows.
+// Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with a private L2.  When the
+// number of groups is a multiple of 8, XCD x only ever sees groups congruent to x, so the K/V rows
+// of a group stay in one L2 instead of being streamed through all eight.
+struct TileGroup {
+    int rank, group;
+};
+__device__ inline TileGroup xcd_tile_group(int id, int n_tiles, int n_groups) {
+    TileGroup r;
+    if (n_groups % 8 == 0) {
+        r.group = (id % 8) + 8 * (id / (8 * n_tiles));
+        r.rank = (id / 8) % n_tiles;
+    } else {
+        r.group = id % n_groups;
+        r.rank = id / n_groups;
+    }
+    return r;
+}
+
 struct Stream {
     int n_init, n_dense, n_total, sep_lo, bs;
 };

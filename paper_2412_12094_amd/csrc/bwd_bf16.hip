@@ -189,7 +189,7 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(
 #pragma unroll
                     for (int k = 0; k < 8; ++k) {
                         int i = 8 * half + k;
-                        bool vis = (los[k] <= iq) && (iq <= his[k]);
+                        bool vis = (los[k] <= iq) & (iq <= his[k]);
                         float pr = __builtin_amdgcn_exp2f(sacc[i] * sl2 - lse2);
                         sacc[i] = vis ? pr * (pacc[i] - Di) : 0.f;
                     }

@@ -68,6 +68,56 @@ __device__ inline f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
 
 __device__ inline bf16x8 as_bf16x8(u32x4 u) { return __builtin_bit_cast(bf16x8, u); }
 
+// ---- LDS tiles filled by direct global->LDS loads -------------------------------------------------
+// global_load_lds_dwordx4: every lane fetches 16 bytes from its own global address and the wave's
+// 64 pieces land contiguously in LDS at (wave-uniform base) + 16*lane.  Tiles are therefore stored
+// unpadded, [rows][D] bf16, and bank conflicts are avoided by permuting the 16-byte chunks of a row
+// with an XOR that depends on the row; the permutation is applied on the global-address side (lane
+// l of a load fills physical chunk l%CH of its row, so it fetches logical chunk phys^swz(row)).
+//   kSwzRow: 16 consecutive rows hit 16 different 16-byte bank slots, so row-major 16-byte
+//            A-operand reads (32 lanes, one chunk column) are conflict-free
+//            (D=128: chunk ^= row%16;  D=64, two rows per 256 bytes: chunk ^= (row/2)%8)
+//   kSwzTr : 4 consecutive rows put a 64-byte column window into 4 different 64-byte bank groups,
+//            so ds_read_b64_tr_b16 reads (4 rows x 64 bytes per 32 lanes) are conflict-free
+//            (D=128: chunk ^= (row%4)*4;  D=64: chunk ^= ((row/2)%2)*4)
+enum { kSwzRow = 0, kSwzTr = 1 };
+template <int MODE, int D>
+__device__ inline int swz_chunk(int chunk, int row) {
+    if (D == 128) return MODE == kSwzRow ? (chunk ^ (row & 15)) : (chunk ^ ((row & 3) << 2));
+    return MODE == kSwzRow ? (chunk ^ ((row >> 1) & 7)) : (chunk ^ (((row >> 1) & 1) << 2));
+}
+
+__device__ inline void load_to_lds_16(const void *gsrc, void *lds_wave_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
+                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+}
+
+// 16-byte A-operand read from a swizzled unpadded tile: row `row`, logical chunk `chunk`
+template <int MODE, int D>
+__device__ inline bf16x8 lds_read_a_swz(const uint16_t *tile, int row, int chunk) {
+    return *reinterpret_cast<const bf16x8 *>(tile + row * D + swz_chunk<MODE, D>(chunk, row) * 8);
+}
+
+// transposed A operand from a swizzled unpadded tile (see lds_read_a_tr): rows row0 + 8*hh .. +7,
+// columns col0 + l%32
+template <int MODE, int D>
+__device__ inline bf16x8 lds_read_a_tr_swz(const uint16_t *tile, int row0, int col0, int lane) {
+    int p = lane & 15, g = lane >> 4;
+    int r = row0 + 8 * (g >> 1) + (p >> 2);
+    int c = col0 + 16 * (g & 1) + 4 * (p & 3);  // element column: chunk c/8, 8-byte half (c/4)%2
+    const uint16_t *a0 = tile + r * D + swz_chunk<MODE, D>(c >> 3, r) * 8 + (c & 4);
+    const uint16_t *a1 = tile + (r + 4) * D + swz_chunk<MODE, D>(c >> 3, r + 4) * 8 + (c & 4);
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)a0);
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)a1);
+    union {
+        s16x4 s[2];
+        bf16x8 v;
+    } x;
+    x.s[0] = lo;
+    x.s[1] = hi;
+    return x.v;
+}
+
 // 16-byte read of a row-major A operand from LDS
 __device__ inline bf16x8 lds_read_a(const uint16_t *tile, int row, int stride, int col) {
     return *reinterpret_cast<const bf16x8 *>(tile + row * stride + col);

@@ -80,9 +80,18 @@ __device__ inline bf16x8 as_bf16x8(u32x4 u) { return __builtin_bit_cast(bf16x8, 
 //   kSwzTr : 4 consecutive rows put a 64-byte column window into 4 different 64-byte bank groups,
 //            so ds_read_b64_tr_b16 reads (4 rows x 64 bytes per 32 lanes) are conflict-free
 //            (D=128: chunk ^= (row%4)*4;  D=64: chunk ^= ((row/2)%2)*4)
-enum { kSwzRow = 0, kSwzTr = 1 };
+//   kSwzBoth: one permutation that serves both kinds of read of the same tile (the dK/dV kernels
+//            read Q and dO tiles row-major and transposed): the XOR mask is a bit permutation of the
+//            row number that puts row bits 0..1 (bit 1 for D=64) into chunk bits 2..3, as kSwzTr
+//            needs, and spreads the 16 rows {0-3, 8-11, 4-7, 12-15} that 16 consecutive lanes of a
+//            row-major A-operand read touch over 16 different 16-byte slots
+enum { kSwzRow = 0, kSwzTr = 1, kSwzBoth = 2 };
 template <int MODE, int D>
 __device__ inline int swz_chunk(int chunk, int row) {
+    if (MODE == kSwzBoth) {
+        if (D == 128) return chunk ^ (((row & 3) << 2) | (((row >> 3) & 1) << 1) | ((row >> 2) & 1));
+        return chunk ^ ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+    }
     if (D == 128) return MODE == kSwzRow ? (chunk ^ (row & 15)) : (chunk ^ ((row & 3) << 2));
     return MODE == kSwzRow ? (chunk ^ ((row >> 1) & 7)) : (chunk ^ (((row >> 1) & 1) << 2));
 }
@@ -90,6 +99,11 @@ __device__ inline int swz_chunk(int chunk, int row) {
 __device__ inline void load_to_lds_16(const void *gsrc, void *lds_wave_base) {
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
                                      (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+}
+// the 4-byte form: lane l's dword lands at (wave-uniform base) + 4*l
+__device__ inline void load_to_lds_4(const void *gsrc, void *lds_wave_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
+                                     (__attribute__((address_space(3))) void *)lds_wave_base, 4, 0, 0);
 }
 
 // 16-byte A-operand read from a swizzled unpadded tile: row `row`, logical chunk `chunk`

@@ -13,7 +13,6 @@ constexpr int kDkvWaves = 4;              // key blocks of 32 keys per dK/dV wor
 constexpr int kDkvThreads = 2 * 64 * kDkvWaves;
 constexpr int kBK = 32 * kDkvWaves;  // keys per dK/dV workgroup
 constexpr int kBQ = 64;              // queries per LDS tile in the dK/dV kernels
-constexpr int kFarGrid = 1024;       // persistent workgroups per (batch, KV head) in the far pass
 
 __host__ __device__ inline int align_down32(int x) { return x & ~31; }
 

@@ -26,6 +26,22 @@
 #include "bwd_common.h"
 #include "mfma_common.h"
 
+// Ablation switches for tuning (SEPATTN_X_*): never defined in the product build.
+#ifdef SEPATTN_X_NOLDSOP
+#define RD_ROW(T, row, chunk) breg[(chunk) >> 1]
+#define RD_TR(T, r0, c0) breg[((c0) >> 5) & (KSTEPS - 1)]
+#else
+#define RD_ROW(T, row, chunk) lds_read_a_swz<kSwzBoth, D>(T, row, chunk)
+#define RD_TR(T, r0, c0) lds_read_a_tr_swz<kSwzBoth, D>(T, r0, c0, lane)
+#endif
+
+#ifdef SEPATTN_X_TIMING
+__device__ unsigned long long g_dbg_dkv[4 * 16384];
+extern "C" int sepattn_debug_read_dkv(unsigned long long *host, int n) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg_dkv), sizeof(unsigned long long) * n);
+}
+#endif
+
 namespace sepattn {
 
 namespace {
@@ -80,9 +96,19 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
     // loads this wave issues per tile: the first two waves also fetch LSE*log2e and D
     const bool extra_load = wave < 2;
 
+    // one unit per workgroup: a (list tile, query chunk) pair in the far pass, a key tile in the band pass
     const int n_units = FAR ? ((fl.NF + kBK - 1) / kBK) * fg.NCH : 1;
-    bool first_unit = true;
-    for (int unit = FAR ? (int)blockIdx.x : 0; unit < n_units; unit += FAR ? (int)gridDim.x : 1) {
+    const int unit = FAR ? (int)blockIdx.x : 0;
+    if (unit >= n_units) return;
+#ifdef SEPATTN_X_TIMING
+    const unsigned long long t_begin = wall_clock64(), c_begin = clock64();
+    __shared__ unsigned simd_map;
+    if (tid == 0) simd_map = 0;
+    __syncthreads();
+    if (lane == 0) atomicOr(&simd_map, ((__builtin_amdgcn_s_getreg((4 << 0) | (4 << 6) | (1 << 11))) & 3u) << (4 * wave));
+    __syncthreads();
+#endif
+    {
         // ---- this wave's 32 keys and the query range of the unit
         int j, lo, hi, q_lo, q_hi, fidx = 0, chunk = 0;
         bool valid;
@@ -92,7 +118,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
             int pos_first = far_pos(fl, ft * kBK, idx, p.L);
             q_lo = max(chunk * fg.CQ, align_down32(pos_first + p.n));
             q_hi = min(p.L, (chunk + 1) * fg.CQ);
-            if (q_lo >= q_hi) continue;
+            if (q_lo >= q_hi) return;
             fidx = ft * kBK + 32 * kbw + kj;
             valid = fidx < fl.NF;
             j = valid ? far_pos(fl, fidx, idx, p.L) : 0;
@@ -112,8 +138,10 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
             lo = kIntMax;
             hi = -1;
         }
-        const int lo_min = wave_min_i(lo), lo_max = wave_max_i(lo);
-        const int hi_min = wave_min_i(hi), hi_max = wave_max_i(hi);
+        // wave-uniform bounds of the keys' query ranges, in scalar registers so that the per-block
+        // decisions below are scalar branches
+        const int lo_max = __builtin_amdgcn_readfirstlane(wave_max_i(lo));
+        const int hi_min = __builtin_amdgcn_readfirstlane(wave_min_i(hi));
 
         // resident B operand: K rows for the P-wave, V rows for the dS-wave
         bf16x8 breg[KSTEPS];
@@ -131,27 +159,36 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
 
         const int n_qt = (q_hi - q_lo + kBQ - 1) / kBQ;
         const int n_tiles = G * n_qt;
+        const int n_blocks = 2 * n_tiles;
 
         // tile tt -> LDS buffer tt%3: wave w fills rows (LOADS*w + u)*RPL .. +RPL-1 with one wave-wide
         // direct load per tensor; a lane owns physical chunk lane%CH of its row and fetches the
         // logical chunk the permutation maps there.  Rows past the sequence end are clamped (they are
-        // masked by the [lo, hi] test: hi <= L-1).
-        auto issue_tile = [&](int tt) {
-            const int g = tt / n_qt, qt = tt - g * n_qt;
-            const int buf = tt % NBUF;
-            const long hrow0 = ((long)b * p.Hq + kv * G + g) * (long)p.L;
-            const int qbase = q_lo + qt * kBQ;
+        // masked by the [lo, hi] test: hi <= L-1).  Tiles are issued in order; (iss_g, iss_qt) is the
+        // (head, query tile) of the next one.
+        int iss_tt = 0, iss_g = 0, iss_qt = 0;
+        auto issue_tile = [&]() {
+            const int buf = iss_tt % NBUF;
+            const long hrow0 = ((long)b * p.Hq + kv * G + iss_g) * (long)p.L;
+            const int qbase = q_lo + iss_qt * kBQ;
+#ifdef SEPATTN_X_NOISSUE
+            if (iss_tt < 2)
+#endif
             static_for<LOADS>([&](auto U) {
                 constexpr int u = U;
                 const int r = (LOADS * wave + u) * RPL + my_sub;
-                const long row = hrow0 + min(qbase + r, p.L - 1);
-                const int lc = swz_chunk<kSwzBoth, D>(my_pc, r);
+                const long off = (hrow0 + min(qbase + r, p.L - 1)) * D + swz_chunk<kSwzBoth, D>(my_pc, r) * 8;
                 const int wave_off = (LOADS * wave + u) * RPL * D;
-                load_to_lds_16(Q + row * D + lc * 8, &Qs[buf][wave_off]);
-                load_to_lds_16(dO + row * D + lc * 8, &dOs[buf][wave_off]);
+                load_to_lds_16(Q + off, &Qs[buf][wave_off]);
+                load_to_lds_16(dO + off, &dOs[buf][wave_off]);
             });
             if (wave == 0) load_to_lds_4(LSE2 + hrow0 + min(qbase + lane, p.L - 1), &lse_s[buf][0]);
             if (wave == 1) load_to_lds_4(Dws + hrow0 + min(qbase + lane, p.L - 1), &d_s[buf][0]);
+            ++iss_tt;
+            if (++iss_qt == n_qt) {
+                iss_qt = 0;
+                ++iss_g;
+            }
         };
         // wait until at most the loads of one tile (the newest) are still in flight; they complete
         // in the order they were issued
@@ -172,94 +209,248 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
         };
         static_assert(LOADS == 1 || LOADS == 2, "wait counts above are written for 1 or 2 loads per tensor");
 
-        // the previous unit's last tile may still be read by other waves
-        if (!first_unit) __syncthreads();
-        first_unit = false;
-        issue_tile(0);
-        if (n_tiles > 1) issue_tile(1);
+        // ---- per-block pieces.  Block gb = 2*tile + half covers 32 query rows starting at r0.
+        struct Blk {
+            int buf, qb, r0;
+            bool full;  // every (query, key) pair of the block is visible: no mask test needed
+        };
+        int blk_qt = 0;  // query tile (within its head) of the block handed out next
+        auto next_block = [&](int gb) {
+            Blk k;
+            k.qb = gb & 1;
+            k.buf = (gb >> 1) % NBUF;
+            k.r0 = q_lo + blk_qt * kBQ + 32 * k.qb;
+            const int r1 = k.r0 + 31;
+            k.full = (k.r0 >= lo_max) && (r1 <= hi_min);
+            if (k.qb == 1 && ++blk_qt == n_qt) blk_qt = 0;
+            return k;
+        };
+        // first contraction reads rows of T1, second reads the other tensor (T2) transposed
+        auto read_rows = [&](const Blk &k, bf16x8 (&afr)[KSTEPS]) {
+            const uint16_t *T1 = role == 0 ? Qs[k.buf] : dOs[k.buf];
+            const int row = k.qb * 32 + a_row;
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) afr[ks] = RD_ROW(T1, row, 2 * ks + hh);
+        };
+        auto read_transposed = [&](const Blk &k, bf16x8 (&tfr)[2][DB]) {
+            const uint16_t *T2 = role == 0 ? dOs[k.buf] : Qs[k.buf];
+#pragma unroll
+            for (int stp = 0; stp < 2; ++stp)
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+                    tfr[stp][db] = RD_TR(T2, k.qb * 32 + stp * 16, db * 32);
+        };
+        // The two contractions of one pipeline step, with the LDS reads of the later one placed
+        // between the MFMA groups of the earlier one: a fragment is requested four MFMAs (128 cycles)
+        // before its use, and at most 32 fragment registers are live.  The scheduling fences keep the
+        // compiler from hoisting all reads to the top (which would spill).
+        auto zero = [&](f32x16 &x) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) x[i] = 0.f;
+        };
+        // acc += T2^T(cur) x_b(cur), then x = T1(nxt) B        (P-wave order)
+        auto gemm2_then_gemm1 = [&](const Blk &cur, const bf16x8 (&xb)[2], const Blk &nxt, f32x16 &x) {
+            const uint16_t *T2 = role == 0 ? dOs[cur.buf] : Qs[cur.buf];
+            const uint16_t *T1 = role == 0 ? Qs[nxt.buf] : dOs[nxt.buf];
+            const int row = nxt.qb * 32 + a_row;
+            bf16x8 t0[DB], t1[DB], a0[KSTEPS / 2], a1[KSTEPS / 2];
+#pragma unroll
+            for (int db = 0; db < DB; ++db) t0[db] = RD_TR(T2, cur.qb * 32, db * 32);
+#pragma unroll
+            for (int db = 0; db < DB; ++db) t1[db] = RD_TR(T2, cur.qb * 32 + 16, db * 32);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int db = 0; db < DB; ++db) acc[db] = mfma_bf16(t0[db], xb[0], acc[db]);
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS / 2; ++ks) a0[ks] = RD_ROW(T1, row, 2 * ks + hh);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int db = 0; db < DB; ++db) acc[db] = mfma_bf16(t1[db], xb[1], acc[db]);
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS / 2; ++ks)
+                a1[ks] = RD_ROW(T1, row, 2 * (ks + KSTEPS / 2) + hh);
+            __builtin_amdgcn_sched_barrier(0);
+            zero(x);
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS / 2; ++ks) x = mfma_bf16(a0[ks], breg[ks], x);
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS / 2; ++ks) x = mfma_bf16(a1[ks], breg[ks + KSTEPS / 2], x);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        // xn = T1(nxt) B (fragments a0, a1 already requested), then acc += T2^T(cur) x_b(cur)   (dS-wave order)
+        auto gemm1_then_gemm2 = [&](const Blk &nxt, const bf16x8 (&a0)[KSTEPS / 2], const bf16x8 (&a1)[KSTEPS / 2],
+                                    f32x16 &xn, const Blk &cur, const bf16x8 (&xb)[2]) {
+            const uint16_t *T2 = role == 0 ? dOs[cur.buf] : Qs[cur.buf];
+            bf16x8 t0[DB], t1[DB];
+            zero(xn);
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS / 2; ++ks) xn = mfma_bf16(a0[ks], breg[ks], xn);
+#pragma unroll
+            for (int db = 0; db < DB; ++db) t0[db] = RD_TR(T2, cur.qb * 32, db * 32);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS / 2; ++ks) xn = mfma_bf16(a1[ks], breg[ks + KSTEPS / 2], xn);
+#pragma unroll
+            for (int db = 0; db < DB; ++db) t1[db] = RD_TR(T2, cur.qb * 32 + 16, db * 32);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int db = 0; db < DB; ++db) acc[db] = mfma_bf16(t0[db], xb[0], acc[db]);
+#pragma unroll
+            for (int db = 0; db < DB; ++db) acc[db] = mfma_bf16(t1[db], xb[1], acc[db]);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        auto read_rows_halves = [&](const Blk &k, bf16x8 (&a0)[KSTEPS / 2], bf16x8 (&a1)[KSTEPS / 2]) {
+            const uint16_t *T1 = role == 0 ? Qs[k.buf] : dOs[k.buf];
+            const int row = k.qb * 32 + a_row;
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS / 2; ++ks) {
+                a0[ks] = RD_ROW(T1, row, 2 * ks + hh);
+                a1[ks] = RD_ROW(T1, row, 2 * (ks + KSTEPS / 2) + hh);
+            }
+        };
+        auto gemm1 = [&](const bf16x8 (&afr)[KSTEPS], f32x16 &x) {
+            zero(x);
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) x = mfma_bf16(afr[ks], breg[ks], x);
+        };
+        auto gemm2 = [&](const bf16x8 (&tfr)[2][DB], const bf16x8 (&xb)[2]) {
+#pragma unroll
+            for (int stp = 0; stp < 2; ++stp)
+#pragma unroll
+                for (int db = 0; db < DB; ++db) acc[db] = mfma_bf16(tfr[stp][db], xb[stp], acc[db]);
+        };
+        // the sixteen per-row values (LSE*log2e or D) of the block's rows held by this lane
+        auto read_rowvals = [&](const Blk &k, float (&rv)[16]) {
+            const float *rowval = role == 0 ? lse_s[k.buf] : d_s[k.buf];
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const int base = k.qb * 32 + 16 * half + 8 * hh;
+                const float4 l0 = *reinterpret_cast<const float4 *>(rowval + base);
+                const float4 l1 = *reinterpret_cast<const float4 *>(rowval + base + 4);
+                rv[8 * half + 0] = l0.x, rv[8 * half + 1] = l0.y, rv[8 * half + 2] = l0.z, rv[8 * half + 3] = l0.w;
+                rv[8 * half + 4] = l1.x, rv[8 * half + 5] = l1.y, rv[8 * half + 6] = l1.z, rv[8 * half + 7] = l1.w;
+            }
+        };
+        // P-wave: P = exp2(S*scale*log2e - LSE*log2e), zero where masked; handed to the dS-wave
+        auto softmax_and_publish = [&](const Blk &k, f32x16 &x) {
+#ifdef SEPATTN_X_NOSM
+            return;
+#endif
+            float ls[16];
+            read_rowvals(k, ls);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) x[i] = __builtin_amdgcn_exp2f(fmaf(x[i], sl2, -ls[i]));
+            if (!k.full) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int iqr = k.r0 + 16 * (i >> 3) + 8 * hh + (i & 7);
+                    x[i] = (lo <= iqr && iqr <= hi) ? x[i] : 0.f;
+                }
+            }
+            float *pex = &Pex[kbw][k.qb][0][lane * 4];
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                f32x4 v4 = {x[4 * g4], x[4 * g4 + 1], x[4 * g4 + 2], x[4 * g4 + 3]};
+                *reinterpret_cast<f32x4 *>(pex + g4 * 256) = v4;
+            }
+        };
+        // dS-wave: dS = P (dP - D)
+        auto fetch_p_and_form_ds = [&](const Blk &k, f32x16 &x) {
+#ifdef SEPATTN_X_NOSM
+            return;
+#endif
+            float dd[16];
+            read_rowvals(k, dd);
+            const float *pex = &Pex[kbw][k.qb][0][lane * 4];
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const f32x4 p4 = *reinterpret_cast<const f32x4 *>(pex + g4 * 256);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) x[4 * g4 + e] = p4[e] * (x[4 * g4 + e] - dd[4 * g4 + e]);
+            }
+        };
+        // barrier after the first contraction (and publication of P) of block gb; the barrier of a
+        // tile's second block also publishes the next tile: every wave has waited for its own share
+        auto block_barrier = [&](int gb) {
+            if (gb & 1) wait_all_but_newest_tile(iss_tt > (gb >> 1) + 2);  // tile (gb>>1)+2 is in flight
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#ifndef SEPATTN_X_NOBAR
+            __builtin_amdgcn_s_barrier();
+#endif
+            // after the first barrier of tile tt nobody reads tile tt-1 any more: refill its buffer
+            if (!(gb & 1) && iss_tt < n_tiles) issue_tile();
+        };
+
+        issue_tile();
+        if (n_tiles > 1) issue_tile();
         wait_all_but_newest_tile(n_tiles > 1);
         __builtin_amdgcn_s_barrier();
 
-        for (int tt = 0; tt < n_tiles; ++tt) {
-            const int buf = tt % NBUF;
-            // first contraction reads rows, second reads the other tensor transposed
-            const uint16_t *T1 = role == 0 ? Qs[buf] : dOs[buf];
-            const uint16_t *T2 = role == 0 ? dOs[buf] : Qs[buf];
-            const float *rowval = role == 0 ? lse_s[buf] : d_s[buf];
-            const int qb0 = q_lo + (tt % n_qt) * kBQ;
-
-#pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
-                const int r0 = qb0 + 32 * qb, r1 = r0 + 31;              // query rows of this block
-                const bool active = !(r1 < lo_min || r0 > hi_max);       // any visible pair for this key block?
-                const bool full = (r0 >= lo_max) && (r1 <= hi_min);
-                float *pex = &Pex[kbw][qb][0][lane * 4];
-                f32x16 x;
-                if (active) {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) x[i] = 0.f;
-                    const int row = qb * 32 + a_row;
-#pragma unroll
-                    for (int ks = 0; ks < KSTEPS; ++ks)
-                        x = mfma_bf16(lds_read_a_swz<kSwzBoth, D>(T1, row, 2 * ks + hh), breg[ks], x);
-                    if (role == 0) {
-                        // P = exp2(S*scale*log2e - LSE*log2e), zero where masked; hand it to the dS-wave
-#pragma unroll
-                        for (int half = 0; half < 2; ++half) {
-                            const int base = qb * 32 + 16 * half + 8 * hh;
-                            const float4 l0 = *reinterpret_cast<const float4 *>(rowval + base);
-                            const float4 l1 = *reinterpret_cast<const float4 *>(rowval + base + 4);
-                            const float ls[8] = {l0.x, l0.y, l0.z, l0.w, l1.x, l1.y, l1.z, l1.w};
-#pragma unroll
-                            for (int k = 0; k < 8; ++k) {
-                                const int i = 8 * half + k;
-                                const int iqr = qb0 + base + k;
-                                float pr = __builtin_amdgcn_exp2f(fmaf(x[i], sl2, -ls[k]));
-                                if (!full) pr = (lo <= iqr && iqr <= hi) ? pr : 0.f;
-                                x[i] = pr;
-                            }
-                        }
-#pragma unroll
-                        for (int g4 = 0; g4 < 4; ++g4) {
-                            f32x4 v4 = {x[4 * g4], x[4 * g4 + 1], x[4 * g4 + 2], x[4 * g4 + 3]};
-                            *reinterpret_cast<f32x4 *>(pex + g4 * 256) = v4;
-                        }
-                    }
+        // ---- software pipeline over blocks.  Between the barriers of blocks gb and gb+1 a wave runs
+        // the second contraction of block gb and the first of block gb+1, with the LDS operands of
+        // both requested up front; the P-wave puts its softmax arithmetic last (it overlaps the other
+        // wave's MFMAs on the same SIMD), the dS-wave puts its arithmetic first.
+        // Every wave runs every block of the unit, also blocks in which its keys see no query (their
+        // P is zero through the mask): the waves meet at a barrier per block anyway, and a loop body
+        // without per-block alternatives keeps the accumulators in place.
+        auto pipeline = [&](auto ROLE) {
+            constexpr int R = ROLE;
+            f32x16 x;
+            Blk cur = next_block(0);
+            {
+                bf16x8 afr[KSTEPS];
+                read_rows(cur, afr);
+                gemm1(afr, x);
+                if constexpr (R == 0) softmax_and_publish(cur, x);
+            }
+            block_barrier(0);
+            for (int gb = 0; gb + 1 < n_blocks; ++gb) {
+                const Blk nxt = next_block(gb + 1);
+                bf16x8 xb[2];
+                if constexpr (R == 0) {
+                    xb[0] = pack_bf16x8(x, 0);
+                    xb[1] = pack_bf16x8(x, 8);
+                    gemm2_then_gemm1(cur, xb, nxt, x);
+                    softmax_and_publish(nxt, x);
+                } else {
+                    bf16x8 a0[KSTEPS / 2], a1[KSTEPS / 2];
+                    read_rows_halves(nxt, a0, a1);  // in flight during the dS arithmetic
+                    fetch_p_and_form_ds(cur, x);
+                    xb[0] = pack_bf16x8(x, 0);
+                    xb[1] = pack_bf16x8(x, 8);
+                    __builtin_amdgcn_sched_barrier(0);
+                    gemm1_then_gemm2(nxt, a0, a1, x, cur, xb);
                 }
-                // block barrier: P of this block is in LDS.  The second one of a tile also publishes
-                // the next tile (every wave has waited for its own share of it).
-                if (qb == 1) wait_all_but_newest_tile(tt + 2 < n_tiles);
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                __builtin_amdgcn_s_barrier();
-                // after the first barrier of tile tt nobody reads tile tt-1 any more: refill its buffer
-                if (qb == 0 && tt + 2 < n_tiles) issue_tile(tt + 2);
-                if (active) {
-                    if (role == 1) {
-                        // dS = P (dP - D)
-#pragma unroll
-                        for (int half = 0; half < 2; ++half) {
-                            const int base = qb * 32 + 16 * half + 8 * hh;
-                            const float4 d0 = *reinterpret_cast<const float4 *>(rowval + base);
-                            const float4 d1 = *reinterpret_cast<const float4 *>(rowval + base + 4);
-                            const float dd[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
-                            const f32x4 p0 = *reinterpret_cast<const f32x4 *>(pex + (2 * half) * 256);
-                            const f32x4 p1 = *reinterpret_cast<const f32x4 *>(pex + (2 * half + 1) * 256);
-                            const float pp[8] = {p0[0], p0[1], p0[2], p0[3], p1[0], p1[1], p1[2], p1[3]};
-#pragma unroll
-                            for (int k = 0; k < 8; ++k) x[8 * half + k] = pp[k] * (x[8 * half + k] - dd[k]);
-                        }
-                    }
-#pragma unroll
-                    for (int stp = 0; stp < 2; ++stp) {
-                        const bf16x8 xb = pack_bf16x8(x, 8 * stp);
-#pragma unroll
-                        for (int db = 0; db < DB; ++db)
-                            acc[db] = mfma_bf16(
-                                lds_read_a_tr_swz<kSwzBoth, D>(T2, qb * 32 + stp * 16, db * 32, lane), xb, acc[db]);
-                    }
-                }
+                block_barrier(gb + 1);
+                cur = nxt;
+            }
+            {
+                bf16x8 tfr[2][DB], xb[2];
+                read_transposed(cur, tfr);
+                if constexpr (R == 1) fetch_p_and_form_ds(cur, x);
+                xb[0] = pack_bf16x8(x, 0);
+                xb[1] = pack_bf16x8(x, 8);
+                gemm2(tfr, xb);
+            }
+        };
+#ifdef SEPATTN_X_TIMING
+        const unsigned long long c_loop0 = clock64();
+#endif
+        if (role == 0)
+            pipeline(IntC<0>{});
+        else
+            pipeline(IntC<1>{});
+#ifdef SEPATTN_X_TIMING
+        const unsigned long long c_loop1 = clock64();
+        if (tid == 0) {
+            const int slot = (FAR ? 0 : 8192) + (int)(blockIdx.y * 1024 + blockIdx.x);
+            if (blockIdx.x < 1024 && blockIdx.y < 8) {
+                g_dbg_dkv[4 * slot + 0] = t_begin;
+                g_dbg_dkv[4 * slot + 2] = ((c_loop0 - c_begin) << 32) | (c_loop1 - c_loop0);
+                g_dbg_dkv[4 * slot + 3] = ((unsigned long long)n_blocks << 32) | simd_map;
             }
         }
+#endif
 
         // ---- epilogue: the P-wave owns dV, the dS-wave owns dK (times scale)
         const float oscale = role == 0 ? 1.f : p.scale;
@@ -318,6 +509,13 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
                         pack_bf16x4(acc[db][4 * i4], acc[db][4 * i4 + 1], acc[db][4 * i4 + 2], acc[db][4 * i4 + 3]);
                 }
         }
+#ifdef SEPATTN_X_TIMING
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (tid == 0 && blockIdx.x < 1024 && blockIdx.y < 8) {
+            const int slot = (FAR ? 0 : 8192) + (int)(blockIdx.y * 1024 + blockIdx.x);
+            g_dbg_dkv[4 * slot + 1] = wall_clock64();
+        }
+#endif
     }
 }
 
@@ -328,8 +526,7 @@ int launch_dkv(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
                hipStream_t st) {
     FarGeom fg = far_geom(p);
     dim3 kblock(kDkvThreads);
-    int far_tiles_max = fg.NFcap / kBK;
-    int far_grid = far_tiles_max * fg.NCH < kFarGrid ? far_tiles_max * fg.NCH : kFarGrid;
+    int far_grid = (fg.NFcap / kBK) * fg.NCH;  // most of these exit at once: the list is far shorter than its capacity
     {
         ProfScope prof(SEPATTN_K_BWD_DKV_FAR, st);
         hipLaunchKernelGGL((dkv_kernel<D, true>), dim3(far_grid, p.B * p.Hkv), kblock, 0, st, p, Q, K, V, lse2, dO,

@@ -106,7 +106,7 @@ def main() -> int:
     torch.cuda.synchronize()
 
     # untimed pass: duration of every kernel of the step, to find the dominant one
-    train_kernels = ["mark", "compact_count", "compact_write", "forward", "bwd_dq", "bwd_dkv_far", "bwd_dkv_band"]
+    train_kernels = ["mark", "compact_count", "compact_write", "forward", "bwd_dq", "bwd_dkv", "bwd_combine"]
     per_kernel_us = {}
     for name in train_kernels:
         sp.sepattn_profile_begin(sp.KERNEL_IDS[name], 5)
@@ -136,9 +136,9 @@ def main() -> int:
     value = flops_step / (ms_per_step * 1e-3) / 1e12
 
     # algorithmic flops of each kernel: forward 4d per pair; backward 10d per pair, of which the dQ
-    # kernel owns S, dP and dQ (6d) and the dK/dV kernels own dK and dV (4d) on their share of pairs
+    # kernel owns S, dP and dQ (6d) and the dK/dV kernel owns dK and dV (4d)
     alg_flops = {"forward": 4.0 * c.d * p_vis * c.Hq, "bwd_dq": 6.0 * c.d * p_vis * c.Hq,
-                 "bwd_dkv_far": 4.0 * c.d * p_far * c.Hq, "bwd_dkv_band": 4.0 * c.d * p_band * c.Hq}
+                 "bwd_dkv": 4.0 * c.d * p_vis * c.Hq}
     dom_avg_ms = float(np.mean(dom_ms)) if dom_ms else float("nan")
     achieved = alg_flops.get(dominant, 0.0) / (dom_avg_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": sp.sepattn_kernel_name(sp.KERNEL_IDS[dominant]),

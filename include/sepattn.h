@@ -205,8 +205,8 @@ typedef enum {
     SEPATTN_K_COMPACT_WRITE = 2,
     SEPATTN_K_FORWARD = 3,
     SEPATTN_K_BWD_DQ = 4,
-    SEPATTN_K_BWD_DKV_FAR = 5,
-    SEPATTN_K_BWD_DKV_BAND = 6,
+    SEPATTN_K_BWD_DKV = 5,
+    SEPATTN_K_BWD_COMBINE = 6,
     SEPATTN_K_DECODE_SPLIT = 7,
     SEPATTN_K_DECODE_MERGE = 8,
     SEPATTN_K_EVICT_PLAN = 9,

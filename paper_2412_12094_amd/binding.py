@@ -112,8 +112,8 @@ def status_string(status: int) -> str:
     return load().sepattn_status_string(int(status)).decode()
 
 
-KERNEL_IDS = {"mark": 0, "compact_count": 1, "compact_write": 2, "forward": 3, "bwd_dq": 4, "bwd_dkv_far": 5,
-              "bwd_dkv_band": 6, "decode_split": 7, "decode_merge": 8, "evict_plan": 9, "evict_move": 10}
+KERNEL_IDS = {"mark": 0, "compact_count": 1, "compact_write": 2, "forward": 3, "bwd_dq": 4, "bwd_dkv": 5,
+              "bwd_combine": 6, "decode_split": 7, "decode_merge": 8, "evict_plan": 9, "evict_move": 10}
 
 
 def sepattn_kernel_name(kernel: int) -> str:

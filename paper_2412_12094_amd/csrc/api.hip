@@ -90,8 +90,8 @@ const char *sepattn_status_string(int status) {
 
 const char *sepattn_kernel_name(int kernel) {
     static const char *names[SEPATTN_K_COUNT] = {"mark_kernel", "compact_count_kernel", "compact_write_kernel",
-                                                 "fwd_bf16_kernel", "dq_kernel", "dkv_kernel_far",
-                                                 "dkv_kernel_band", "decode_split_kernel",
+                                                 "fwd_bf16_kernel", "dq_kernel", "dkv_kernel",
+                                                 "dkv_combine_kernel", "decode_split_kernel",
                                                  "decode_merge_kernel", "evict_plan_kernel",
                                                  "evict_move_kernel"};
     return (kernel >= 0 && kernel < SEPATTN_K_COUNT) ? names[kernel] : "unknown";

@@ -37,7 +37,7 @@ inline BwdWorkspace bwd_workspace(const sepattn_params &p) {
     FarGeom fg = far_geom(p);
     BwdWorkspace w;
     w.d_bytes = align_up((size_t)p.B * p.Hq * p.L * sizeof(float), 256);
-    w.far_bytes = align_up((size_t)p.B * p.Hkv * fg.NCH * fg.NFcap * p.d * sizeof(float), 256);
+    w.far_bytes = align_up((size_t)p.B * p.Hkv * (fg.NCH + 1) * fg.NFcap * p.d * sizeof(float), 256);
     w.total = 2 * w.d_bytes + 2 * w.far_bytes;
     return w;
 }
@@ -56,6 +56,20 @@ __device__ inline FarList far_list(const sepattn_params &p, const int32_t *__res
 __device__ inline int far_pos(const FarList &fl, int f, const int32_t *__restrict__ idx, int L) {
     if (f < fl.a_eff) return f;
     return min(max(idx[fl.sep_base + f - fl.a_eff], 0), L - 1);
+}
+// index of key position j on the far list, -1 if it is neither an initial token nor a listed separator
+__device__ inline int far_index(const FarList &fl, const int32_t *__restrict__ prefix, int j) {
+    int f = -1;
+    if (j < fl.a_eff)
+        f = j;
+    else if (prefix[j + 1] != prefix[j])
+        f = fl.a_eff + prefix[j] - fl.sep_base;
+    return f < fl.NF ? f : -1;
+}
+// first query row the far units of list entry f's tile cover (>= L: the entry has no far unit)
+__device__ inline int far_first_query(const FarList &fl, int f, const int32_t *__restrict__ idx,
+                                      const sepattn_params &p) {
+    return align_down32(far_pos(fl, (f / kBK) * kBK, idx, p.L) + p.n);
 }
 
 int launch_dkv_bf16(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, const uint16_t *V,

@@ -3,14 +3,16 @@
 //   P_ij = exp(scale <Q_i, K_j> - LSE_i),  summed over the query heads of the KV head.
 //
 // The visible pairs split into band pairs (i-j < n) and far pairs (i-j >= n, j an initial token or a
-// separator, Sec. 3.1).
-//   dkv_kernel<far>:  far pairs on the COMPACTED list of such keys (128 consecutive list entries per
-//                     unit, gathered K/V rows) against one chunk of the query range; every (list tile,
-//                     query chunk) unit writes an fp32 partial dK/dV to the workspace.
-//   dkv_kernel<band>: one workgroup per 128 consecutive keys against the queries j <= i < j+n.  Its
-//                     epilogue adds, in fixed chunk order, the far partials of the keys that have
-//                     them, then rounds once to bf16.  One workgroup owns each key row: no atomics,
-//                     results are bit-reproducible.
+// separator, Sec. 3.1).  One launch of dkv_kernel runs two kinds of units:
+//   far unit:  far pairs on the COMPACTED list of such keys (128 consecutive list entries, gathered
+//              K/V rows) against one chunk of the query range; writes an fp32 partial dK/dV per
+//              (list tile, query chunk) to the workspace.
+//   band unit: 128 consecutive keys against the queries j <= i < j+n.  Keys that are not on the far
+//              list are finished here (rounded once to bf16); for the others the band unit writes one
+//              more fp32 partial.
+// dkv_combine_kernel then adds, in fixed order, the partials of every far-list key and rounds once to
+// bf16.  One workgroup owns each partial row: no atomics, results are bit-reproducible.  Far units
+// come first in the grid (they are the longer ones) and band units fill the CUs as those drain.
 // A workgroup is 8 waves = 4 key blocks of 32 keys x 2 roles.  The two waves of a key block split
 // the four contractions so that each keeps only one operand matrix and one accumulator resident:
 //   P-wave :  S = Q K^T   -> P = exp2(.)      -> dV^T += dO^T P     (holds K rows, dV^T)
@@ -55,13 +57,13 @@ __device__ inline int wave_max_i(int v) {
     return v;
 }
 
-template <int D, bool FAR>
+template <int D>
 __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
     sepattn_params p, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
     const uint16_t *__restrict__ V, const float *__restrict__ LSE2, const uint16_t *__restrict__ dO,
     const float *__restrict__ Dws, const int32_t *__restrict__ sep_idx,
     const int32_t *__restrict__ sep_prefix, uint16_t *__restrict__ dK, uint16_t *__restrict__ dV,
-    float *__restrict__ farK, float *__restrict__ farV) {
+    float *__restrict__ farK, float *__restrict__ farV, int n_far_head, int n_band) {
     constexpr int NW = 2 * kDkvWaves;        // waves per workgroup
     constexpr int CH = D / 8;                // 16-byte chunks per row
     constexpr int RPL = 64 / CH;             // rows covered by one wave-wide 1 KB load
@@ -84,7 +86,17 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
     const int kbw = wave % kDkvWaves;   // key block of the wave
     const int kj = lane & 31, hh = lane >> 5;
     const int G = p.Hq / p.Hkv;
-    const int kv = blockIdx.y % p.Hkv, b = blockIdx.y / p.Hkv;
+    // 1-D grid, slot-major: consecutive workgroups are the same slot of consecutive (batch, KV head)
+    // pairs, so far units (the long ones) are dispatched before band units, and with 8 KV heads each
+    // head's K, V, Q, dO rows stay in the L2 of one XCD.  The far units a list of up to L/8 entries
+    // needs come first; the remaining far slots (nearly always empty) come after the band units so
+    // that their workgroups do not queue in front of real work.
+    const int n_bkv = p.B * p.Hkv;
+    const int bkv = blockIdx.x % n_bkv, slot = blockIdx.x / n_bkv;
+    const int kv = bkv % p.Hkv, b = bkv / p.Hkv;
+    // slot order: [likely far units | band units | far units only a very long list has]
+    const bool FAR = slot < n_far_head || slot >= n_far_head + n_band;
+    const int unit = FAR ? (slot < n_far_head ? slot : slot - n_band) : slot - n_far_head;  // far unit or key tile
     const int32_t *prefix = sep_prefix + (long)b * (p.L + 1);
     const int32_t *idx = sep_idx + (long)b * p.cap;
     const long kvrow0 = ((long)b * p.Hkv + kv) * (long)p.L;
@@ -97,9 +109,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
     const bool extra_load = wave < 2;
 
     // one unit per workgroup: a (list tile, query chunk) pair in the far pass, a key tile in the band pass
-    const int n_units = FAR ? ((fl.NF + kBK - 1) / kBK) * fg.NCH : 1;
-    const int unit = FAR ? (int)blockIdx.x : 0;
-    if (unit >= n_units) return;
+    if (FAR && unit >= ((fl.NF + kBK - 1) / kBK) * fg.NCH) return;
 #ifdef SEPATTN_X_TIMING
     const unsigned long long t_begin = wall_clock64(), c_begin = clock64();
     __shared__ unsigned simd_map;
@@ -125,7 +135,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
             lo = j + p.n;
             hi = q_hi - 1;
         } else {
-            int j0 = blockIdx.x * kBK;
+            int j0 = unit * kBK;
             j = j0 + 32 * kbw + kj;
             valid = j < p.L;
             q_lo = j0;
@@ -443,80 +453,106 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
 #ifdef SEPATTN_X_TIMING
         const unsigned long long c_loop1 = clock64();
         if (tid == 0) {
-            const int slot = (FAR ? 0 : 8192) + (int)(blockIdx.y * 1024 + blockIdx.x);
-            if (blockIdx.x < 1024 && blockIdx.y < 8) {
-                g_dbg_dkv[4 * slot + 0] = t_begin;
-                g_dbg_dkv[4 * slot + 2] = ((c_loop0 - c_begin) << 32) | (c_loop1 - c_loop0);
-                g_dbg_dkv[4 * slot + 3] = ((unsigned long long)n_blocks << 32) | simd_map;
+            const int dslot = (FAR ? 0 : 8192) + bkv * 1024 + unit;
+            if (unit < 1024 && bkv < 8) {
+                g_dbg_dkv[4 * dslot + 0] = t_begin;
+                g_dbg_dkv[4 * dslot + 2] = ((c_loop0 - c_begin) << 32) | (c_loop1 - c_loop0);
+                g_dbg_dkv[4 * dslot + 3] = ((unsigned long long)n_blocks << 32) | simd_map;
             }
         }
 #endif
 
-        // ---- epilogue: the P-wave owns dV, the dS-wave owns dK (times scale)
+        // ---- epilogue: the P-wave owns dV, the dS-wave owns dK (times scale).  A far unit writes the
+        // partial of its chunk; a band unit finishes keys that are not on the far list and writes the
+        // band partial (slot NCH) of those that are.
         const float oscale = role == 0 ? 1.f : p.scale;
         float *farX = role == 0 ? farV : farK;
-        if (FAR) {
-            if (valid) {
-                long prow = ((((long)b * p.Hkv + kv) * fg.NCH + chunk) * fg.NFcap + fidx) * D;
+        int slot_c = chunk, slot_f = fidx;
+        bool to_partial = FAR;
+        if (!FAR && valid) {
+            const int f = far_index(fl, prefix, j);
+            if (f >= 0 && far_first_query(fl, f, idx, p) < p.L) {
+                to_partial = true;
+                slot_c = fg.NCH;
+                slot_f = f;
+            }
+        }
+        if (valid) {
+            if (to_partial) {
+                const long prow = ((((long)b * p.Hkv + kv) * (fg.NCH + 1) + slot_c) * fg.NFcap + slot_f) * D;
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
 #pragma unroll
                     for (int i4 = 0; i4 < 4; ++i4) {
-                        int col = db * 32 + 8 * i4 + 4 * hh;
-                        float4 a = {acc[db][4 * i4] * oscale, acc[db][4 * i4 + 1] * oscale,
-                                    acc[db][4 * i4 + 2] * oscale, acc[db][4 * i4 + 3] * oscale};
+                        const int col = db * 32 + 8 * i4 + 4 * hh;
+                        const float4 a = {acc[db][4 * i4] * oscale, acc[db][4 * i4 + 1] * oscale,
+                                          acc[db][4 * i4 + 2] * oscale, acc[db][4 * i4 + 3] * oscale};
                         *reinterpret_cast<float4 *>(farX + prow + col) = a;
                     }
-            }
-        } else if (valid) {
+            } else {
+                uint16_t *orow = (role == 0 ? dV : dK) + (kvrow0 + j) * D;
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+                for (int db = 0; db < DB; ++db)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[db][i] *= oscale;
-            // far partials of this key, if it is an initial token or a separator
-            int f = -1;
-            if (j < fl.a_eff)
-                f = j;
-            else if (prefix[j + 1] != prefix[j])
-                f = fl.a_eff + prefix[j] - fl.sep_base;
-            if (f >= 0 && f < fl.NF) {
-                int pos_first = far_pos(fl, (f / kBK) * kBK, idx, p.L);
-                int A = align_down32(pos_first + p.n);
-                if (A < p.L) {
-                    for (int c = A / fg.CQ; c < fg.NCH; ++c) {
-                        long prow = ((((long)b * p.Hkv + kv) * fg.NCH + c) * fg.NFcap + f) * D;
-#pragma unroll
-                        for (int db = 0; db < DB; ++db)
-#pragma unroll
-                            for (int i4 = 0; i4 < 4; ++i4) {
-                                int col = db * 32 + 8 * i4 + 4 * hh;
-                                float4 a = *reinterpret_cast<const float4 *>(farX + prow + col);
-                                acc[db][4 * i4] += a.x;
-                                acc[db][4 * i4 + 1] += a.y;
-                                acc[db][4 * i4 + 2] += a.z;
-                                acc[db][4 * i4 + 3] += a.w;
-                            }
+                    for (int i4 = 0; i4 < 4; ++i4) {
+                        const int col = db * 32 + 8 * i4 + 4 * hh;
+                        *reinterpret_cast<uint2 *>(orow + col) =
+                            pack_bf16x4(acc[db][4 * i4] * oscale, acc[db][4 * i4 + 1] * oscale,
+                                        acc[db][4 * i4 + 2] * oscale, acc[db][4 * i4 + 3] * oscale);
                     }
-                }
             }
-            uint16_t *orow = (role == 0 ? dV : dK) + (kvrow0 + j) * D;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4) {
-                    int col = db * 32 + 8 * i4 + 4 * hh;
-                    *reinterpret_cast<uint2 *>(orow + col) =
-                        pack_bf16x4(acc[db][4 * i4], acc[db][4 * i4 + 1], acc[db][4 * i4 + 2], acc[db][4 * i4 + 3]);
-                }
         }
 #ifdef SEPATTN_X_TIMING
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        if (tid == 0 && blockIdx.x < 1024 && blockIdx.y < 8) {
-            const int slot = (FAR ? 0 : 8192) + (int)(blockIdx.y * 1024 + blockIdx.x);
-            g_dbg_dkv[4 * slot + 1] = wall_clock64();
+        if (tid == 0 && unit < 1024 && bkv < 8) {
+            const int dslot = (FAR ? 0 : 8192) + bkv * 1024 + unit;
+            g_dbg_dkv[4 * dslot + 1] = wall_clock64();
         }
 #endif
     }
+}
+
+// Sum of the partials of every far-list key (its far chunks in ascending order, then the band
+// partial), rounded once to bf16.  One thread per (key, 4 consecutive columns).
+template <int D>
+__global__ __launch_bounds__(256) void dkv_combine_kernel(sepattn_params p, const int32_t *__restrict__ sep_idx,
+                                                          const int32_t *__restrict__ sep_prefix,
+                                                          uint16_t *__restrict__ dK, uint16_t *__restrict__ dV,
+                                                          const float *__restrict__ farK,
+                                                          const float *__restrict__ farV) {
+    constexpr int TPR = D / 4;  // threads per row
+    const int bkv = blockIdx.y, kv = bkv % p.Hkv, b = bkv / p.Hkv;
+    const int32_t *prefix = sep_prefix + (long)b * (p.L + 1);
+    const int32_t *idx = sep_idx + (long)b * p.cap;
+    const FarGeom fg = far_geom(p);
+    const FarList fl = far_list(p, prefix);
+    const int f = (blockIdx.x * 256 + threadIdx.x) / TPR, col = ((blockIdx.x * 256 + threadIdx.x) % TPR) * 4;
+    if (f >= fl.NF) return;
+    const int A = far_first_query(fl, f, idx, p);
+    if (A >= p.L) return;  // no far pair: the band unit has written this row
+    const int j = far_pos(fl, f, idx, p.L);
+    const long base = ((long)b * p.Hkv + kv) * (fg.NCH + 1);
+    // fixed trip count with clamped slots: all loads are issued before the first sum needs one
+    const int c0 = A / fg.CQ;
+    float4 pk[kFarChunks + 1], pv[kFarChunks + 1];
+#pragma unroll
+    for (int c = 0; c <= kFarChunks; ++c) {
+        const int cc = min(max(c, c0), fg.NCH);
+        const long prow = ((base + cc) * fg.NFcap + f) * D + col;
+        pk[c] = *reinterpret_cast<const float4 *>(farK + prow);
+        pv[c] = *reinterpret_cast<const float4 *>(farV + prow);
+    }
+    float4 sk = {0.f, 0.f, 0.f, 0.f}, sv = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c <= kFarChunks; ++c) {
+        if (c >= c0 && c <= fg.NCH) {
+            sk.x += pk[c].x, sk.y += pk[c].y, sk.z += pk[c].z, sk.w += pk[c].w;
+            sv.x += pv[c].x, sv.y += pv[c].y, sv.z += pv[c].z, sv.w += pv[c].w;
+        }
+    }
+    const long orow = (((long)b * p.Hkv + kv) * (long)p.L + j) * D + col;
+    *reinterpret_cast<uint2 *>(dK + orow) = pack_bf16x4(sk.x, sk.y, sk.z, sk.w);
+    *reinterpret_cast<uint2 *>(dV + orow) = pack_bf16x4(sv.x, sv.y, sv.z, sv.w);
 }
 
 template <int D>
@@ -524,18 +560,24 @@ int launch_dkv(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
                const float *lse2, const uint16_t *dO, const float *Dws, const int32_t *sep_idx,
                const int32_t *sep_prefix, uint16_t *dK, uint16_t *dV, float *farK, float *farV,
                hipStream_t st) {
-    FarGeom fg = far_geom(p);
-    dim3 kblock(kDkvThreads);
-    int far_grid = (fg.NFcap / kBK) * fg.NCH;  // most of these exit at once: the list is far shorter than its capacity
+    const FarGeom fg = far_geom(p);
+    // far units the list could have at full capacity (most exit at once: the list is far shorter),
+    // then one band unit per 128 keys
+    const long far_grid = (long)(fg.NFcap / kBK) * fg.NCH, band_grid = (p.L + kBK - 1) / kBK;
+    long far_head = (long)((p.a + p.L / 8 + kBK - 1) / kBK) * fg.NCH;
+    if (far_head > far_grid) far_head = far_grid;
+    const long total = (far_grid + band_grid) * p.B * p.Hkv;
+    if (total > 0x7FFFFFFFL) return SEPATTN_ERR_SHAPE;
     {
-        ProfScope prof(SEPATTN_K_BWD_DKV_FAR, st);
-        hipLaunchKernelGGL((dkv_kernel<D, true>), dim3(far_grid, p.B * p.Hkv), kblock, 0, st, p, Q, K, V, lse2, dO,
-                           Dws, sep_idx, sep_prefix, dK, dV, farK, farV);
+        ProfScope prof(SEPATTN_K_BWD_DKV, st);
+        hipLaunchKernelGGL((dkv_kernel<D>), dim3((unsigned)total), dim3(kDkvThreads), 0, st, p, Q, K, V, lse2, dO, Dws,
+                           sep_idx, sep_prefix, dK, dV, farK, farV, (int)far_head, (int)band_grid);
     }
     if (hipGetLastError() != hipSuccess) return SEPATTN_ERR_HIP;
-    ProfScope prof(SEPATTN_K_BWD_DKV_BAND, st);
-    hipLaunchKernelGGL((dkv_kernel<D, false>), dim3((p.L + kBK - 1) / kBK, p.B * p.Hkv), kblock, 0, st, p, Q, K, V,
-                       lse2, dO, Dws, sep_idx, sep_prefix, dK, dV, farK, farV);
+    ProfScope prof(SEPATTN_K_BWD_COMBINE, st);
+    const int rows_per_block = 256 / (D / 4);
+    hipLaunchKernelGGL((dkv_combine_kernel<D>), dim3((fg.NFcap + rows_per_block - 1) / rows_per_block, p.B * p.Hkv),
+                       dim3(256), 0, st, p, sep_idx, sep_prefix, dK, dV, farK, farV);
     return launch_status();
 }
 

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsepattn.so")
-SOURCES = ["api.hip", "mark_compact.hip", "attn_fp32.hip", "fwd_bf16.hip", "bwd_bf16.hip", "bwd_dkv_bf16.hip", "decode.hip",
+SOURCES = ["api.hip", "mark_compact.hip", "attn_fp32.hip", "fwd_bf16.hip", "bwd_bf16.hip", "bwd_dkv_bf16.hip", "decode.hip", "decode_mfma.hip",
            "evict.hip"]
 # packed fp32 VALU instructions are switched off (see the design notes: they have miscomputed on
 # the test machines); the host pass does not know the feature and says so, which is harmless

@@ -11,6 +11,7 @@
 //   - partial (max, sum, unnormalised output) triples are merged through LDS, written to the
 //     workspace, and a second tiny kernel merges the `nsplit` slices.
 #include "common.h"
+#include "decode_common.h"
 
 namespace sepattn {
 
@@ -21,12 +22,6 @@ constexpr float kLn2 = 0.6931471805599453f;
 
 __device__ inline float bf16lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ inline float bf16hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
-
-__device__ inline uint16_t f32_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
 
 template <typename T>
 __device__ inline void load8(const T *p, float (&v)[8]);
@@ -54,13 +49,6 @@ __device__ inline float row_sum(float v) {
     if (LPR == 16)
         v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xF, 0xF, true));
     return v;
-}
-
-// logical valid entry e -> physical cache slot
-__device__ inline int slot_of(int e, int n_init, int n_sep, int a, int s) {
-    if (e < n_init) return e;
-    if (e < n_init + n_sep) return a + (e - n_init);
-    return a + s + (e - n_init - n_sep);
 }
 
 constexpr int kDecodeThreads = 256;
@@ -126,7 +114,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(
         for (int u = 0; u < kRowsUnroll; ++u) {
             int e = eb + u * NSLOT;
             ok[u] = e < e1;
-            int sl = slot_of(ok[u] ? e : e0, n_init, n_sep, p.a, p.s);
+            int sl = decode_slot_of(ok[u] ? e : e0, n_init, n_sep, p.a, p.s);
             load8<T>(Kh + (long)sl * D + c * 8, kr[u]);
             load8<T>(Vh + (long)sl * D + c * 8, vr[u]);
         }
@@ -217,7 +205,7 @@ __global__ void decode_merge_kernel(int nsplit, const float *__restrict__ part, 
     }
     float val = (lsum > 0.f) ? o / lsum : 0.f;
     if constexpr (sizeof(T) == 2)
-        out[sh * D + col] = f32_to_bf16(val);
+        out[sh * D + col] = decode_f32_to_bf16(val);
     else
         out[sh * D + col] = val;
     if (lse && col == 0) lse[sh] = (lsum > 0.f) ? (M + log2f(lsum)) * kLn2 : -INFINITY;
@@ -257,13 +245,25 @@ int launch_decode_t(const sepkv_params &p, const T *q, const T *Kc, const T *Vc,
 }  // namespace
 
 size_t decode_workspace(const sepkv_params &p) {
-    int nsplit = pick_nsplit(p);
+    int nsplit = decode_mfma_applicable(p) ? decode_mfma_nsplit(p) : pick_nsplit(p);
     return align_up((size_t)p.S * p.Hq * nsplit * (p.d + 2) * sizeof(float), 256);
 }
 
 int launch_decode(const sepkv_params &p, const void *q, const void *Kc, const void *Vc,
                   const int32_t *sizes, void *out, float *lse, void *ws, hipStream_t st) {
     float *part = static_cast<float *>(ws);
+    if (decode_mfma_applicable(p)) {
+        using T = uint16_t;
+        const int nsplit = decode_mfma_nsplit(p);
+        int rc = launch_decode_mfma(p, nsplit, (const T *)q, (const T *)Kc, (const T *)Vc, sizes, (T *)out, lse, part, st);
+        if (rc != SEPATTN_OK || nsplit == 1) return rc;
+        ProfScope prof(SEPATTN_K_DECODE_MERGE, st);
+        if (p.d == 64)
+            hipLaunchKernelGGL((decode_merge_kernel<T, 64>), dim3(p.S * p.Hq), dim3(64), 0, st, nsplit, part, (T *)out, lse);
+        else
+            hipLaunchKernelGGL((decode_merge_kernel<T, 128>), dim3(p.S * p.Hq), dim3(128), 0, st, nsplit, part, (T *)out, lse);
+        return launch_status();
+    }
     if (p.dtype == SEPATTN_BF16) {
         using T = uint16_t;
         if (p.d == 64)

@@ -114,84 +114,135 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     float alpha_pending = 1.f;             // rescale of oacc decided in a VALU phase, applied in the next MFMA phase
 
     // ---- tile loads: wave w fills rows (LOADS*w + u)*RPL .. +RPL-1 of a tile with one wave-wide
-    // direct global->LDS load per tensor; a lane owns physical chunk lane%CH of row my_row(u)
+    // direct global->LDS load per tensor; a lane owns physical chunk lane%CH of its row.  Everything
+    // about a load except the key position j is a per-lane constant, and the address is formed as
+    // (uniform base) + 32-bit byte offset, so issuing a tile costs a handful of vector instructions.
+    // Tiles come in three wave-uniform classes: all elements in the dense part (gather through the
+    // index list, no visibility ranges needed: every block of such a tile is fully visible), all in
+    // the band part (consecutive keys; ranges from the prefix counts), or mixed (general code).
     const int my_pc = lane % CH, my_sub = lane / CH;
-    int raw0[LOADS], raw1[LOADS];  // meta stage: idx entry or prefix[j], and prefix[j+1]
-    int vm_issued = 0;             // vector-memory instructions issued in the current phase
-
-    auto issue_meta = [&](int t) {
-        if (t >= n_tiles) return;
-        static_for<LOADS>([&](auto U) {
-            constexpr int u = U;
-            int k = t * kBN + (LOADS * wave + u) * RPL + my_sub;
-            // both loads are always issued (clamped addresses) so that their count is exact
-            bool dense = k < st.n_dense;
-            int j = min(max(st.bs + (k - st.n_dense), 0), p.L - 1);
-            int e = min(max(st.sep_lo + k - st.n_init, 0), p.cap - 1);
-            const int32_t *pa = dense ? idx + e : prefix + j;
-            raw0[u] = *pa;
-            raw1[u] = prefix[j + 1];
-        });
-        vm_issued += 2 * LOADS;
+    uint32_t kgo[LOADS], vgo[LOADS];  // byte offset of this lane's 16-byte piece inside a K / V row
+    int rrow[LOADS];                  // row of the tile this lane helps to fill
+#pragma unroll
+    for (int u = 0; u < LOADS; ++u) {
+        rrow[u] = (LOADS * wave + u) * RPL + my_sub;
+        kgo[u] = swz_chunk<kSwzRow, D>(my_pc, rrow[u]) * 16;
+        vgo[u] = swz_chunk<kSwzTr, D>(my_pc, rrow[u]) * 16;
+    }
+    const char *Kb = reinterpret_cast<const char *>(Kh), *Vb = reinterpret_cast<const char *>(Vh);
+    auto tile_class = [&](int t) {
+        const int k0 = t * kBN;
+        return (k0 + kBN <= st.n_dense) ? 0 : (k0 >= st.n_dense ? 1 : 2);
     };
-    auto issue_rows = [&](int t) {
-        if (t >= n_tiles) return;
-        const int ks_ = t % KST, vs_ = t % VST;
-        static_for<LOADS>([&](auto U) {
-            constexpr int u = U;
-            const int r = (LOADS * wave + u) * RPL + my_sub;  // row of the tile
-            const int k = t * kBN + r;
-            int j, lo, hi;
-            if (k >= st.n_total) {  // padding of the last tile: never visible, any valid row
-                j = 0;
-                lo = kIntMax;
-                hi = -1;
-            } else if (k < st.n_init) {
-                j = k;
-                lo = j;
-                hi = kIntMax;
-            } else if (k < st.n_dense) {
+    // Index stage, one tile ahead of the rows: the list entry (dense part) and the two prefix counts
+    // (band part) of each of the MR rows this wave fills, fetched by 3*MR lanes with one 4-byte
+    // global->LDS load into the wave's own slot of a small ring; the wave reads them back in its
+    // next VALU phase.  All vector-memory traffic of the loop is thus global->LDS, issued through
+    // inline assembly and waited for with explicit counts.
+    constexpr int MR = LOADS * RPL;  // rows per wave and tile
+    constexpr int MST = 4;           // ring stages
+    __shared__ __attribute__((aligned(128))) int meta_s[MST][NW][32];
+    const int m_part = lane / MR, m_row = wave * MR + lane % MR;  // lanes 0 .. 3*MR-1 are used
+    auto issue_meta = [&](int t) __attribute__((always_inline)) {
+        const int k = t * kBN + m_row;
+        const int e = min(max(st.sep_lo - st.n_init + k, 0), p.cap - 1);
+        const int j = min(max(st.bs - st.n_dense + k, 0), p.L - 1);
+        const int32_t *src = m_part == 0 ? idx + e : prefix + j + (m_part - 1);
+        if (lane < 3 * MR) dma_to_lds_4_addr(src, lds_addr(&meta_s[t % MST][wave][0]));
+    };
+    // Rows of tile t in two steps, so that the index entries of the NEXT tile can be requested in
+    // between: vector-memory results return in issue order, and with the order
+    //   [entries of t+1] [rows of t]   the wait for the entries does not wait for the rows.
+    // Tiles past the end of the stream are "loaded" too (row 0, never visible): a loop body without
+    // alternatives keeps the count of outstanding loads exact, and the LDS stage such a tile lands in
+    // is free by the same argument as for a real tile.
+    int jrow[LOADS];
+    auto prepare_rows = [&](int t) __attribute__((always_inline)) {
+        const int vs_ = t % VST;
+        const int *mt = &meta_s[t % MST][wave][0];
+        if (tile_class(t) == 0) {
+            static_for<LOADS>([&](auto U) {
+                constexpr int u = U;
+                const int k = t * kBN + rrow[u];
                 // the clamp keeps a stale list tail (caller broke sep_count <= cap) from faulting
-                j = min(max(raw0[u], 0), p.L - 1);
-                lo = j;
-                hi = kIntMax;
-            } else {
-                j = st.bs + (k - st.n_dense);
-                bool always = (j < p.a) || (raw1[u] != raw0[u]);
-                lo = j;
-                hi = always ? kIntMax : j + p.n - 1;
-            }
-            if (my_pc == 0) {
-                lo_s[vs_][r] = lo;
-                hi_s[vs_][r] = hi;
-            }
-            const int wave_off = (LOADS * wave + u) * RPL * D;  // elements: 1 KB per wave-wide load
-            load_to_lds_16(Kh + (long)j * D + swz_chunk<kSwzRow, D>(my_pc, r) * 8, &Ks[ks_][wave_off]);
-            load_to_lds_16(Vh + (long)j * D + swz_chunk<kSwzTr, D>(my_pc, r) * 8, &Vs[vs_][wave_off]);
-        });
-        vm_issued += 2 * LOADS;
-    };
-    // all loads older than the ones issued in this phase have landed (they complete in order)
-    auto wait_older_loads = [&]() {
-        if (vm_issued == 4 * LOADS) {
-            if constexpr (LOADS == 1)
-                asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-            else
-                asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+                const int jl = min(max(mt[u * RPL + my_sub], 0), p.L - 1);
+                jrow[u] = k < st.n_init ? k : jl;
+            });
         } else {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            static_for<LOADS>([&](auto U) {
+                constexpr int u = U;
+                const int r = rrow[u];
+                const int k = t * kBN + r;
+                const int rawi = mt[u * RPL + my_sub], raw0 = mt[MR + u * RPL + my_sub], raw1 = mt[2 * MR + u * RPL + my_sub];
+                const bool init = k < st.n_init, dense = k < st.n_dense, pad = k >= st.n_total;
+                const int jb = st.bs + (k - st.n_dense);
+                const int jl = min(max(rawi, 0), p.L - 1);
+                const bool always = dense | (jb < p.a) | (raw1 != raw0);
+                int j = init ? k : (dense ? jl : jb);
+                j = pad ? 0 : j;
+                const int lo = pad ? kIntMax : j;
+                int hi = always ? kIntMax : jb + p.n - 1;
+                hi = pad ? -1 : hi;
+                if (my_pc == 0) {
+                    lo_s[vs_][r] = lo;
+                    hi_s[vs_][r] = hi;
+                }
+                jrow[u] = j;
+            });
         }
-        vm_issued = 0;
+    };
+    auto issue_rows = [&](int t) __attribute__((always_inline)) {
+        const uint32_t kst = lds_addr(&Ks[t % KST][0]), vst = lds_addr(&Vs[t % VST][0]);
+        static_for<LOADS>([&](auto U) {
+            constexpr int u = U;
+            const uint32_t wave_off = (uint32_t)((LOADS * wave + u) * RPL * D * 2);  // bytes: 1 KB per wave-wide load
+            const uint32_t row_off = (uint32_t)jrow[u] * (uint32_t)(D * 2);
+            dma_to_lds_16(Kb, row_off + kgo[u], kst + wave_off);
+            dma_to_lds_16(Vb, row_off + vgo[u], vst + wave_off);
+        });
+    };
+    // A VALU phase issues [1 entry load][2*LOADS row loads], in this order; loads complete in order.
+    //   entries_landed:    at most the row loads of the previous phase are still in flight
+    //   wait_older_loads:  everything older than this phase's loads has landed
+    auto entries_landed = [&]() __attribute__((always_inline)) {
+        if constexpr (LOADS == 1)
+            asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    };
+    auto wait_older_loads = [&]() __attribute__((always_inline)) {
+        static_assert(LOADS == 1 || LOADS == 2, "wait counts are written for 1 or 2 loads per tensor");
+        if constexpr (LOADS == 1)
+            asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
     };
 
     const int a_row = pi_row(qi);
     f32x16 sacc[2];   // scores of the tile between its MFMA phase and its VALU phase
     bf16x8 pb[2][2];  // probabilities of the tile (bf16, B-operand layout) for the next MFMA phase
 
-    // ---- MFMA phase of tile t: O^T += V^T P^T of tile t-1, then S^T = K Q^T of tile t
-    auto mfma_phase = [&](int t) {
-        __builtin_amdgcn_s_setprio(1);
-        const bool do_pv = t > 0, do_qk = t < n_tiles;
+    // per-lane byte offsets of the operand fragments inside a tile (constant for the whole kernel)
+    const uint32_t ks_base = lds_addr(&Ks[0][0]), vs_base = lds_addr(&Vs[0][0]);
+    uint32_t koff[KSTEPS], voff[DB];
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) koff[ks] = lds_off_a<kSwzRow, D>(a_row, 2 * ks + hh);
+#pragma unroll
+    for (int db = 0; db < DB; ++db) voff[db] = lds_off_a_tr<kSwzTr, D>(db * 32, lane);
+
+    // ---- MFMA phase of tile t: O^T += V^T P^T of tile t-1 (PV), then S^T = K Q^T of tile t (QK).
+    // Straight-line and software-pipelined: the phase is a fixed list of matrix instructions
+    //   PV: (key block, k-step, output block)   QK: (k-step, key block)  [key blocks alternate so that
+    //                                               consecutive instructions use different accumulators]
+    // and the operand fragment of step s+LA is requested from LDS right after step s is issued, so a
+    // fragment has LA matrix instructions (about 250 cycles) to arrive and only LA fragments are live.
+    // Every block of the tile is multiplied, also blocks this wave's rows cannot see (their
+    // probabilities are zero): the matrix pipe has slack, the vector ALU and the registers do not.
+    constexpr int LA = 2 * DB;
+    auto mfma_phase = [&](int t, auto PV, auto QK) __attribute__((always_inline)) {
+        constexpr bool DO_PV = decltype(PV)::value != 0, DO_QK = decltype(QK)::value != 0;
+        constexpr int NPV = DO_PV ? 4 * DB : 0, NQK = DO_QK ? 2 * KSTEPS : 0, NS = NPV + NQK;
+        // (no s_setprio: a raised priority of the MFMA wave starves the VALU wave of the same SIMD)
         if (__builtin_amdgcn_ballot_w64(alpha_pending != 1.f) != 0ull) {
 #pragma unroll
             for (int db = 0; db < DB; ++db)
@@ -199,76 +250,69 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
                 for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha_pending;
             alpha_pending = 1.f;
         }
-        int pmode[2] = {0, 0}, qmode[2] = {0, 0};
+        const uint32_t vst = vs_base + ((t + VST - 1) % VST) * (TILE * 2);
+        const uint32_t kst = ks_base + (t % KST) * (TILE * 2);
+        uint32_t va_[DB], ka_[KSTEPS];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            if (do_pv) pmode[kb] = block_mode(st, (t - 1) * kBN + kb * 32, pw, p.n);
-            if (do_qk) qmode[kb] = block_mode(st, t * kBN + kb * 32, pw, p.n);
-        }
-        const uint16_t *Vst = Vs[(t + VST - 1) % VST];
-        const uint16_t *Kst = Ks[t % KST];
-        bf16x8 va[DB], ka[KSTEPS];
-        auto read_v = [&](int kb, int stp) {
+        for (int db = 0; db < DB; ++db) va_[db] = vst + voff[db];
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
-#ifdef SEPATTN_X_NOLDS
-                va[db] = qreg[db];
-#else
-                va[db] = lds_read_a_tr_swz<kSwzTr, D>(Vst, kb * 32 + stp * 16, db * 32, lane);
-#endif
-        };
-        auto read_k = [&](int kb) {
-#pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks)
-#ifdef SEPATTN_X_NOLDS
-                ka[ks] = qreg[ks];
-#else
-                ka[ks] = lds_read_a_swz<kSwzRow, D>(Kst, kb * 32 + a_row, 2 * ks + hh);
-#endif
-        };
-        auto mfma_pv = [&](int kb, int stp) {
-#pragma unroll
-            for (int db = 0; db < DB; ++db) oacc[db] = mfma_bf16(va[db], pb[kb][stp], oacc[db]);
-        };
-        auto mfma_qk = [&](int kb) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks) sacc[kb] = mfma_bf16(ka[ks], qreg[ks], sacc[kb]);
-        };
-        // order: K reads of a block are in flight while the PV MFMAs of the same block run
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            if (qmode[kb]) read_k(kb);
-            if (pmode[kb]) {
-                read_v(kb, 0);
-                mfma_pv(kb, 0);
-                read_v(kb, 1);
-                mfma_pv(kb, 1);
+        for (int ks = 0; ks < KSTEPS; ++ks) ka_[ks] = kst + koff[ks];
+        bf16x8 frag[LA];
+        auto request = [&](auto S) {
+            constexpr int s = decltype(S)::value;
+            if constexpr (s < NPV) {
+                constexpr int kb = s / (2 * DB), stp = (s / DB) % 2, db = s % DB;
+                frag[s % LA] = lds_read_tr_at(va_[db] + (kb * 32 + stp * 16) * D * 2, 4 * D * 2);
+            } else if constexpr (s < NS) {
+                constexpr int q_ = s - NPV, ks = q_ / 2, kb = q_ % 2;
+                frag[s % LA] = lds_read_b128_at(ka_[ks] + kb * 32 * D * 2);
             }
-            if (qmode[kb]) mfma_qk(kb);
+        };
+        auto multiply = [&](auto S) {
+            constexpr int s = decltype(S)::value;
+            if constexpr (s < NPV) {
+                constexpr int kb = s / (2 * DB), stp = (s / DB) % 2, db = s % DB;
+                oacc[db] = mfma_bf16(frag[s % LA], pb[kb][stp], oacc[db]);
+            } else {
+                constexpr int q_ = s - NPV, ks = q_ / 2, kb = q_ % 2;
+                if constexpr (ks == 0) {
+                    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                    sacc[kb] = mfma_bf16(frag[s % LA], qreg[ks], zero);
+                } else {
+                    sacc[kb] = mfma_bf16(frag[s % LA], qreg[ks], sacc[kb]);
+                }
+            }
+        };
+        static_for<LA>([&](auto S) { request(S); });
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<NS>([&](auto S) {
+            multiply(S);
+            request(IntC<decltype(S)::value + LA>{});
             __builtin_amdgcn_sched_barrier(0);
-        }
-        __builtin_amdgcn_s_setprio(0);
+        });
+        // (no s_setprio: a raised priority of the MFMA wave starves the VALU wave of the same SIMD)
     };
 
     // ---- VALU phase of tile t: mask, online softmax, probabilities to bf16
-    auto valu_phase = [&](int t) {
+    auto valu_phase = [&](int t) __attribute__((always_inline)) {
         int mode[2];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) mode[kb] = block_mode(st, t * kBN + kb * 32, pw, p.n);
-        if (mode[0] == 0 && mode[1] == 0) return;
+        if (mode[0] == 0 && mode[1] == 0) {  // nothing visible: zero probabilities for the PV step
+            const bf16x8 z = as_bf16x8(u32x4{0u, 0u, 0u, 0u});
+            pb[0][0] = pb[0][1] = pb[1][0] = pb[1][1] = z;
+            return;
+        }
         const int vs_ = t % VST;
         float m_loc = -INFINITY;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
-            if (mode[kb] == 0) continue;
-#ifndef SEPATTN_X_NOMASK
-            if (mode[kb] == 2)
-#else
-            if (false)
-#endif
-            {
+            if (mode[kb] == 0) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sacc[kb][i] = -INFINITY;
+                continue;
+            }
+            if (mode[kb] == 2) {
 #pragma unroll
                 for (int half = 0; half < 2; ++half) {
                     int base = kb * 32 + 16 * half + 8 * hh;
@@ -300,7 +344,6 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
         float psum = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
-            if (mode[kb] == 0) continue;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 float pr = __builtin_amdgcn_exp2f(fmaf(sacc[kb][i], sl2, neg_m));
@@ -313,14 +356,27 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
         l_run += psum;
     };
 
-    // ---- prologue: tiles 0 and 1 on their way into LDS, index entries of tile 2 in flight
+    // Workgroup barrier without the memory fence of __syncthreads(): the fence would make every wave
+    // wait for ALL of its outstanding global->LDS loads (vmcnt(0)), i.e. for the tiles it has just
+    // requested, and so expose a full memory latency per half-phase.  What a barrier has to publish
+    // here is waited for explicitly: the wave's LDS writes (lgkmcnt) and, through wait_older_loads(),
+    // the tile loads older than the current phase.
+    auto wg_barrier = [&]() __attribute__((always_inline)) {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+
+    // ---- prologue: index entries of tiles 0..2, then tiles 0 and 1 on their way into LDS
     issue_meta(0);
-    issue_rows(0);
     issue_meta(1);
-    issue_rows(1);
     issue_meta(2);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    vm_issued = 0;
+    prepare_rows(0);
+    issue_rows(0);
+    prepare_rows(1);
+    issue_rows(1);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
     // Half-phase f: group 0 runs MFMA(t) at f = 2t and VALU(t) at f = 2t+1; group 1 runs MFMA(t)
@@ -333,47 +389,69 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
 #ifdef SEPATTN_X_TIMING
     unsigned long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tlast = clock64();
 #endif
+    const IntC<1> yes;
+    const IntC<0> no;
     if (grp == 0) {
-        for (int t = 0; t <= n_tiles; ++t) {
-            mfma_phase(t);
+        auto half_phases = [&](int t, auto PV, auto QK) __attribute__((always_inline)) {
+            mfma_phase(t, PV, QK);
             TICK(1)
-            __syncthreads();
+            wg_barrier();
             TICK(4)
-            if (t < n_tiles) {
-                issue_rows(t + 2);
+            if constexpr (decltype(QK)::value != 0) {
+                // index entries first: waiting for them in the next phase then does not wait for the rows
+                // requested after them (vector-memory results return in issue order)
+                entries_landed();
+                TICK(6)
+                prepare_rows(t + 2);
+                TICK(7)
                 issue_meta(t + 3);
+                issue_rows(t + 2);
                 TICK(0)
                 valu_phase(t);
                 TICK(2)
                 wait_older_loads();
                 TICK(3)
-                __syncthreads();
+                wg_barrier();
                 TICK(4)
             }
-        }
+        };
+        half_phases(0, no, yes);
+        for (int t = 1; t < n_tiles; ++t) half_phases(t, yes, yes);
+        half_phases(n_tiles, yes, no);
     } else {
-        issue_rows(2);
+        prepare_rows(2);
         issue_meta(3);
+        issue_rows(2);
         wait_older_loads();
-        __syncthreads();
-        for (int t = 0; t <= n_tiles; ++t) {
-            mfma_phase(t);
+        wg_barrier();
+        auto half_phases = [&](int t, auto PV, auto QK) __attribute__((always_inline)) {
+            mfma_phase(t, PV, QK);
             TICK(1)
-            if (t < n_tiles) {
-                __syncthreads();
+            if constexpr (decltype(QK)::value != 0) {
+                wg_barrier();
                 TICK(4)
-                issue_rows(t + 3);
+                entries_landed();
+                TICK(6)
+                prepare_rows(t + 3);
+                TICK(7)
                 issue_meta(t + 4);
+                issue_rows(t + 3);
                 TICK(0)
                 valu_phase(t);
                 TICK(2)
                 wait_older_loads();
                 TICK(3)
-                __syncthreads();
+                wg_barrier();
                 TICK(4)
             }
-        }
+        };
+        half_phases(0, no, yes);
+        for (int t = 1; t < n_tiles; ++t) half_phases(t, yes, yes);
+        half_phases(n_tiles, yes, no);
     }
+    // the loads of the tiles past the end are still in flight: they must have landed before the
+    // workgroup ends and its LDS is handed to the next one
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #ifdef SEPATTN_X_TIMING
     if (lane == 0 && blockIdx.x < 2048) {
         tacc[5] = n_tiles;

@@ -106,6 +106,38 @@ __device__ inline void load_to_lds_4(const void *gsrc, void *lds_wave_base) {
                                      (__attribute__((address_space(3))) void *)lds_wave_base, 4, 0, 0);
 }
 
+// The same loads through inline assembly.  For the builtin forms the compiler knows that LDS is
+// written asynchronously, and since it cannot tell which LDS bytes a later ds_read touches it makes
+// every LDS read wait for ALL outstanding loads (vmcnt(0)), which serialises a prefetch pipeline.
+// These forms are opaque to it: the kernels that use them wait explicitly (s_waitcnt vmcnt(n), loads
+// complete in issue order) before the data is read, and every such wait carries a memory clobber so
+// that no LDS access is moved across it at compile time.
+// M0 (the LDS base of such a load) is written inside the statement; the compiler treats M0 as a
+// reserved register that it sets itself right before each of its own uses, and the kernels that use
+// these helpers contain no other M0 user.
+//   base      wave-uniform global pointer        voff   per-lane byte offset from base (32 bits)
+//   lds_addr  wave-uniform LDS byte address: lane l's piece lands at lds_addr + 16*l (or 4*l)
+__device__ inline void dma_to_lds_16(const void *base, uint32_t voff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(base)
+                 : "memory");
+}
+__device__ inline void dma_to_lds_4(const void *base, uint32_t voff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(base)
+                 : "memory");
+}
+
+// 4-byte form with a full per-lane address (lanes that are switched off fetch and write nothing)
+__device__ inline void dma_to_lds_4_addr(const void *lane_addr, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
+                 :
+                 : "s"(lds_addr), "v"(lane_addr)
+                 : "memory");
+}
+
 // 16-byte A-operand read from a swizzled unpadded tile: row `row`, logical chunk `chunk`
 template <int MODE, int D>
 __device__ inline bf16x8 lds_read_a_swz(const uint16_t *tile, int row, int chunk) {
@@ -130,6 +162,46 @@ __device__ inline bf16x8 lds_read_a_tr_swz(const uint16_t *tile, int row0, int c
     x.s[0] = lo;
     x.s[1] = hi;
     return x.v;
+}
+
+// ---- LDS reads by 32-bit byte address ---------------------------------------------------------------
+// The kernels precompute, once per lane, the byte offset of every operand fragment inside a tile
+// (the XOR swizzle makes it a per-lane constant); per tile only the stage base is added, and the
+// block / step within the tile goes into the instruction's immediate offset.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wint-to-pointer-cast"  // LDS pointers are 32 bits wide on the device
+__device__ inline uint32_t lds_addr(const void *p) {
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)p;
+}
+__device__ inline bf16x8 lds_read_b128_at(uint32_t addr) {
+    return *(const bf16x8 __attribute__((address_space(3))) *)addr;
+}
+// two transposed 64-bit reads, `second` bytes apart (the rows r and r+4 of lds_read_a_tr_swz)
+__device__ inline bf16x8 lds_read_tr_at(uint32_t addr, uint32_t second) {
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)addr);
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(addr + second));
+    union {
+        s16x4 s[2];
+        bf16x8 v;
+    } x;
+    x.s[0] = lo;
+    x.s[1] = hi;
+    return x.v;
+}
+#pragma clang diagnostic pop
+// byte offset of the 16-byte row-major A fragment (row, logical chunk) in a swizzled unpadded tile
+template <int MODE, int D>
+__device__ inline uint32_t lds_off_a(int row, int chunk) {
+    return (uint32_t)(row * D + swz_chunk<MODE, D>(chunk, row) * 8) * 2u;
+}
+// byte offset of this lane's first transposed read for rows 0..15, columns col0 + l%32 (see
+// lds_read_a_tr_swz); with kSwzTr the second read is exactly 4 rows further on
+template <int MODE, int D>
+__device__ inline uint32_t lds_off_a_tr(int col0, int lane) {
+    int p = lane & 15, g = lane >> 4;
+    int r = 8 * (g >> 1) + (p >> 2);
+    int c = col0 + 16 * (g & 1) + 4 * (p & 3);
+    return (uint32_t)(r * D + swz_chunk<MODE, D>(c >> 3, r) * 8 + (c & 4)) * 2u;
 }
 
 // 16-byte read of a row-major A operand from LDS

@@ -104,6 +104,9 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
             qreg[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(qrow + ks * 16 + 8 * hh));
     }
     const float sl2 = p.scale * kLog2e_f;
+#ifdef SEPATTN_X_TIMING
+    unsigned long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tlast = clock64();
+#endif
 
     f32x16 oacc[DB];
 #pragma unroll
@@ -156,52 +159,56 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     // Tiles past the end of the stream are "loaded" too (row 0, never visible): a loop body without
     // alternatives keeps the count of outstanding loads exact, and the LDS stage such a tile lands in
     // is free by the same argument as for a real tile.
-    int jrow[LOADS];
-    auto prepare_rows = [&](int t) __attribute__((always_inline)) {
-        const int vs_ = t % VST;
+    int jrow[LOADS], rawi[LOADS], raw0[LOADS], raw1[LOADS];
+    auto read_entries = [&](int t) __attribute__((always_inline)) {
         const int *mt = &meta_s[t % MST][wave][0];
-        if (tile_class(t) == 0) {
-            static_for<LOADS>([&](auto U) {
-                constexpr int u = U;
-                const int k = t * kBN + rrow[u];
-                // the clamp keeps a stale list tail (caller broke sep_count <= cap) from faulting
-                const int jl = min(max(mt[u * RPL + my_sub], 0), p.L - 1);
-                jrow[u] = k < st.n_init ? k : jl;
-            });
-        } else {
-            static_for<LOADS>([&](auto U) {
-                constexpr int u = U;
-                const int r = rrow[u];
-                const int k = t * kBN + r;
-                const int rawi = mt[u * RPL + my_sub], raw0 = mt[MR + u * RPL + my_sub], raw1 = mt[2 * MR + u * RPL + my_sub];
-                const bool init = k < st.n_init, dense = k < st.n_dense, pad = k >= st.n_total;
-                const int jb = st.bs + (k - st.n_dense);
-                const int jl = min(max(rawi, 0), p.L - 1);
-                const bool always = dense | (jb < p.a) | (raw1 != raw0);
-                int j = init ? k : (dense ? jl : jb);
-                j = pad ? 0 : j;
-                const int lo = pad ? kIntMax : j;
-                int hi = always ? kIntMax : jb + p.n - 1;
-                hi = pad ? -1 : hi;
-                if (my_pc == 0) {
-                    lo_s[vs_][r] = lo;
-                    hi_s[vs_][r] = hi;
-                }
-                jrow[u] = j;
-            });
-        }
-    };
-    auto issue_rows = [&](int t) __attribute__((always_inline)) {
-        const uint32_t kst = lds_addr(&Ks[t % KST][0]), vst = lds_addr(&Vs[t % VST][0]);
         static_for<LOADS>([&](auto U) {
             constexpr int u = U;
-            const uint32_t wave_off = (uint32_t)((LOADS * wave + u) * RPL * D * 2);  // bytes: 1 KB per wave-wide load
-            const uint32_t row_off = (uint32_t)jrow[u] * (uint32_t)(D * 2);
-            dma_to_lds_16(Kb, row_off + kgo[u], kst + wave_off);
-            dma_to_lds_16(Vb, row_off + vgo[u], vst + wave_off);
+            rawi[u] = mt[u * RPL + my_sub];
+            raw0[u] = mt[MR + u * RPL + my_sub];
+            raw1[u] = mt[2 * MR + u * RPL + my_sub];
         });
     };
-    // A VALU phase issues [1 entry load][2*LOADS row loads], in this order; loads complete in order.
+    auto prepare_row = [&](int t, auto U) __attribute__((always_inline)) {
+        constexpr int u = decltype(U)::value;
+        const int vs_ = t % VST;
+        const int r = rrow[u];
+        const int k = t * kBN + r;
+        // the clamp keeps a stale list tail (caller broke sep_count <= cap) from faulting
+        const int jl = min(max(rawi[u], 0), p.L - 1);
+        if (tile_class(t) == 0) {
+            jrow[u] = k < st.n_init ? k : jl;
+        } else {
+            const bool init = k < st.n_init, dense = k < st.n_dense, pad = k >= st.n_total;
+            const int jb = st.bs + (k - st.n_dense);
+            const bool always = dense | (jb < p.a) | (raw1[u] != raw0[u]);
+            int j = init ? k : (dense ? jl : jb);
+            j = pad ? 0 : j;
+            const int lo = pad ? kIntMax : j;
+            int hi = always ? kIntMax : jb + p.n - 1;
+            hi = pad ? -1 : hi;
+            if (my_pc == 0) {
+                lo_s[vs_][r] = lo;
+                hi_s[vs_][r] = hi;
+            }
+            jrow[u] = j;
+        }
+    };
+    auto issue_row = [&](int t, auto U) __attribute__((always_inline)) {
+        constexpr int u = decltype(U)::value;
+        const uint32_t kst = lds_addr(&Ks[t % KST][0]), vst = lds_addr(&Vs[t % VST][0]);
+        const uint32_t wave_off = (uint32_t)((LOADS * wave + u) * RPL * D * 2);  // bytes: 1 KB per wave-wide load
+        const uint32_t row_off = (uint32_t)jrow[u] * (uint32_t)(D * 2);
+        dma_to_lds_16(Kb, row_off + kgo[u], kst + wave_off);
+        dma_to_lds_16(Vb, row_off + vgo[u], vst + wave_off);
+    };
+    auto prepare_rows = [&](int t) __attribute__((always_inline)) {
+        static_for<LOADS>([&](auto U) { prepare_row(t, U); });
+    };
+    auto issue_rows = [&](int t) __attribute__((always_inline)) {
+        static_for<LOADS>([&](auto U) { issue_row(t, U); });
+    };
+    // An MFMA phase issues [1 entry load][2*LOADS row loads], in this order; loads complete in order.
     //   entries_landed:    at most the row loads of the previous phase are still in flight
     //   wait_older_loads:  everything older than this phase's loads has landed
     auto entries_landed = [&]() __attribute__((always_inline)) {
@@ -283,13 +290,31 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
                 }
             }
         };
+        // The wave's share of the tile loads rides along: the MFMA wave waits for the matrix pipe most
+        // of the time, so the few instructions of the load path cost nothing here, while in the VALU
+        // phase they would lengthen the critical path.  Tile t+2 is requested (its stages held tiles
+        // t-1 / t-2, whose last readers finished before the barrier this phase started from), and the
+        // index entries of tile t+3.
         static_for<LA>([&](auto S) { request(S); });
+        entries_landed();
+        read_entries(t + 2);
         __builtin_amdgcn_sched_barrier(0);
         static_for<NS>([&](auto S) {
+            constexpr int s_ = decltype(S)::value;
             multiply(S);
-            request(IntC<decltype(S)::value + LA>{});
+            request(IntC<s_ + LA>{});
+            // a few instructions of the load path per matrix instruction, so that the matrix pipe
+            // never drains while they run
+            if constexpr (s_ == NS / 8) prepare_row(t + 2, IntC<0>{});
+            if constexpr (s_ == 2 * NS / 8 && LOADS == 2) prepare_row(t + 2, IntC<LOADS - 1>{});
+            if constexpr (s_ == 3 * NS / 8) issue_meta(t + 3);
+            if constexpr (s_ == 4 * NS / 8) issue_row(t + 2, IntC<0>{});
+            if constexpr (s_ == 5 * NS / 8 && LOADS == 2) issue_row(t + 2, IntC<LOADS - 1>{});
             __builtin_amdgcn_sched_barrier(0);
         });
+        TICK(1)
+        wait_older_loads();
+        TICK(3)
         // (no s_setprio: a raised priority of the MFMA wave starves the VALU wave of the same SIMD)
     };
 
@@ -372,8 +397,10 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     issue_meta(1);
     issue_meta(2);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    read_entries(0);
     prepare_rows(0);
     issue_rows(0);
+    read_entries(1);
     prepare_rows(1);
     issue_rows(1);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -387,30 +414,18 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     // Both groups pass 2*n_tiles+1 barriers.  The two loops are written out separately (rather than one
     // loop over half-phases with a role switch) so that every accumulator has one straight-line life.
 #ifdef SEPATTN_X_TIMING
-    unsigned long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tlast = clock64();
+    tlast = clock64();
 #endif
     const IntC<1> yes;
     const IntC<0> no;
     if (grp == 0) {
         auto half_phases = [&](int t, auto PV, auto QK) __attribute__((always_inline)) {
             mfma_phase(t, PV, QK);
-            TICK(1)
             wg_barrier();
             TICK(4)
             if constexpr (decltype(QK)::value != 0) {
-                // index entries first: waiting for them in the next phase then does not wait for the rows
-                // requested after them (vector-memory results return in issue order)
-                entries_landed();
-                TICK(6)
-                prepare_rows(t + 2);
-                TICK(7)
-                issue_meta(t + 3);
-                issue_rows(t + 2);
-                TICK(0)
                 valu_phase(t);
                 TICK(2)
-                wait_older_loads();
-                TICK(3)
                 wg_barrier();
                 TICK(4)
             }
@@ -419,28 +434,14 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
         for (int t = 1; t < n_tiles; ++t) half_phases(t, yes, yes);
         half_phases(n_tiles, yes, no);
     } else {
-        prepare_rows(2);
-        issue_meta(3);
-        issue_rows(2);
-        wait_older_loads();
         wg_barrier();
         auto half_phases = [&](int t, auto PV, auto QK) __attribute__((always_inline)) {
             mfma_phase(t, PV, QK);
-            TICK(1)
             if constexpr (decltype(QK)::value != 0) {
                 wg_barrier();
                 TICK(4)
-                entries_landed();
-                TICK(6)
-                prepare_rows(t + 3);
-                TICK(7)
-                issue_meta(t + 4);
-                issue_rows(t + 3);
-                TICK(0)
                 valu_phase(t);
                 TICK(2)
-                wait_older_loads();
-                TICK(3)
                 wg_barrier();
                 TICK(4)
             }

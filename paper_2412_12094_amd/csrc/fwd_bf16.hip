@@ -226,8 +226,6 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     };
 
     const int a_row = pi_row(qi);
-    f32x16 sacc[2];   // scores of the tile between its MFMA phase and its VALU phase
-    bf16x8 pb[2][2];  // probabilities of the tile (bf16, B-operand layout) for the next MFMA phase
 
     // per-lane byte offsets of the operand fragments inside a tile (constant for the whole kernel)
     const uint32_t ks_base = lds_addr(&Ks[0][0]), vs_base = lds_addr(&Vs[0][0]);
@@ -237,159 +235,205 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
 #pragma unroll
     for (int db = 0; db < DB; ++db) voff[db] = lds_off_a_tr<kSwzTr, D>(db * 32, lane);
 
-    // ---- MFMA phase of tile t: O^T += V^T P^T of tile t-1 (PV), then S^T = K Q^T of tile t (QK).
-    // Straight-line and software-pipelined: the phase is a fixed list of matrix instructions
-    //   PV: (key block, k-step, output block)   QK: (k-step, key block)  [key blocks alternate so that
-    //                                               consecutive instructions use different accumulators]
-    // and the operand fragment of step s+LA is requested from LDS right after step s is issued, so a
-    // fragment has LA matrix instructions (about 250 cycles) to arrive and only LA fragments are live.
-    // Every block of the tile is multiplied, also blocks this wave's rows cannot see (their
-    // probabilities are zero): the matrix pipe has slack, the vector ALU and the registers do not.
-    constexpr int LA = 2 * DB;
-    auto mfma_phase = [&](int t, auto PV, auto QK) __attribute__((always_inline)) {
-        constexpr bool DO_PV = decltype(PV)::value != 0, DO_QK = decltype(QK)::value != 0;
-        constexpr int NPV = DO_PV ? 4 * DB : 0, NQK = DO_QK ? 2 * KSTEPS : 0, NS = NPV + NQK;
-        // (no s_setprio: a raised priority of the MFMA wave starves the VALU wave of the same SIMD)
-        if (__builtin_amdgcn_ballot_w64(alpha_pending != 1.f) != 0ull) {
+    // Workgroup barrier without the memory fence of __syncthreads(): the fence would make every wave
+    // wait for ALL of its outstanding global->LDS loads (vmcnt(0)), i.e. for the tiles it has just
+    // requested.  What a barrier has to publish here is waited for explicitly: the wave's LDS writes
+    // (lgkmcnt) and the tile loads older than the previous tile step (vmcnt).
+    auto wg_barrier = [&]() __attribute__((always_inline)) {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+
+    // ---- The pipeline.  Every wave runs the same instruction stream; one workgroup barrier per tile.
+    // Work is cut into blocks of 32 keys (block c = 2*tile + half).  Tile step X, entered through the
+    // barrier that publishes tile X, consists of two halves:
+    //   half 1:  S(2X)   = K_X[ 0..31] Q^T      O^T += V_{X-1}[ 0..31]^T P(2X-2)^T    softmax of block 2X-1
+    //   half 2:  S(2X+1) = K_X[32..63] Q^T      O^T += V_{X-1}[32..63]^T P(2X-1)^T    softmax of block 2X
+    // In each half the matrix instructions (first the score block, then the output update) are
+    // independent of the softmax arithmetic, which works on the scores of the block before; the two
+    // are interleaved instruction by instruction: a matrix instruction is issued, then a few vector
+    // instructions of the softmax (or of the load path), which execute while the matrix pipe is busy.
+    // Operand fragments are requested from LDS LA matrix instructions ahead.  The loads of tile X+2
+    // and the index entries of tile X+3 are issued during step X: the stages they overwrite held
+    // tiles X-1 (K) and X-2 (V, visibility ranges), whose last readers finished before the barrier.
+    f32x16 s_a, s_b;          // scores: first / second block of a tile
+    bf16x8 p_a[2], p_b[2];    // probabilities (bf16, B-operand layout) of the first / second block
+    constexpr int LA = D == 128 ? 6 : 4;
+    constexpr int NQK = KSTEPS, NPV = 2 * DB;  // matrix instructions per half
+
+    // one sixteenth of the softmax of a block: s -> pb, updating (m_run, l_run, alpha_pending)
+    struct SmState {
+        float m_loc, neg_m, psum;
+        bool masked;
+    } sm;
+    auto softmax_chunk = [&](auto C, f32x16 &s, bf16x8 (&pb)[2], int tile, int kb) __attribute__((always_inline)) {
+        constexpr int c = decltype(C)::value;
+#ifdef SEPATTN_X_NOSM
+        if constexpr (c == 13) pb[0] = qreg[0];
+        if constexpr (c == 14) pb[1] = qreg[1];
+        return;
+#endif
+        if constexpr (c == 0) {
+            sm.masked = block_mode(st, tile * kBN + kb * 32, pw, p.n) != 1;
+#ifdef SEPATTN_X_SM_NOBR
+            sm.masked = false;
+#endif
+            if (sm.masked) {
+                const int vs_ = tile % VST;
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const int base = kb * 32 + 16 * half + 8 * hh;
+                    const int4 lo0 = *reinterpret_cast<const int4 *>(&lo_s[vs_][base]);
+                    const int4 lo1 = *reinterpret_cast<const int4 *>(&lo_s[vs_][base + 4]);
+                    const int4 hi0 = *reinterpret_cast<const int4 *>(&hi_s[vs_][base]);
+                    const int4 hi1 = *reinterpret_cast<const int4 *>(&hi_s[vs_][base + 4]);
+                    const int los[8] = {lo0.x, lo0.y, lo0.z, lo0.w, lo1.x, lo1.y, lo1.z, lo1.w};
+                    const int his[8] = {hi0.x, hi0.y, hi0.z, hi0.w, hi1.x, hi1.y, hi1.z, hi1.w};
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        const bool vis = (los[k] <= iq) & (iq <= his[k]);
+                        s[8 * half + k] = vis ? s[8 * half + k] : -INFINITY;
+                    }
+                }
+            }
+            sm.m_loc = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+        } else if constexpr (c < 4) {
+            sm.m_loc = fmaxf(fmaxf(sm.m_loc, s[4 * c]), fmaxf(fmaxf(s[4 * c + 1], s[4 * c + 2]), s[4 * c + 3]));
+        } else if constexpr (c == 4) {
+            const float m_new = fmaxf(m_run, pair_max(sm.m_loc * sl2));
+            const bool grow = m_new > m_run + kRescaleThreshold;
+#ifdef SEPATTN_X_SM_NOBR
+            m_run = fmaxf(m_run, m_new);
+            if (false) {
+#else
+            if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
+#endif
+                const float alpha = grow ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.f;
+                m_run = grow ? m_new : m_run;
+                l_run *= alpha;
+                alpha_pending = alpha;
+            }
+            sm.neg_m = (m_run == -INFINITY) ? 0.f : -m_run;
+            sm.psum = 0.f;
+        } else if constexpr (c < 14) {
+            // exponentials of two elements; their sum is taken one chunk later, when the results of
+            // the transcendental unit have arrived
+            if constexpr (c < 13) {
+#pragma unroll
+#ifdef SEPATTN_X_SM_NOEXP
+                for (int i = 2 * (c - 5); i < 2 * (c - 5) + 2; ++i) s[i] = fmaf(s[i], sl2, sm.neg_m) * 0.001f;
+#else
+                for (int i = 2 * (c - 5); i < 2 * (c - 5) + 2; ++i) s[i] = __builtin_amdgcn_exp2f(fmaf(s[i], sl2, sm.neg_m));
+#endif
+            }
+            if constexpr (c > 5) sm.psum += s[2 * (c - 6)] + s[2 * (c - 6) + 1];
+            if constexpr (c == 13) pb[0] = pack_bf16x8(s, 0);
+        } else if constexpr (c == 14) {
+            pb[1] = pack_bf16x8(s, 8);
+        } else {
+            l_run += sm.psum;
+        }
+    };
+    // one piece of the load path of tile T (rows) and T+1 (index entries)
+    auto load_chunk = [&](auto C, int T) __attribute__((always_inline)) {
+        constexpr int c = decltype(C)::value;
+#ifdef SEPATTN_X_NOLD
+        return;
+#endif
+        if constexpr (c == 0) {
+            entries_landed();
+            read_entries(T);
+        } else if constexpr (c == 2) {
+            prepare_row(T, IntC<0>{});
+        } else if constexpr (c == 4 && LOADS == 2) {
+            prepare_row(T, IntC<LOADS - 1>{});
+        } else if constexpr (c == 6) {
+            issue_meta(T + 1);
+        } else if constexpr (c == 8) {
+            issue_row(T, IntC<0>{});
+        } else if constexpr (c == 10 && LOADS == 2) {
+            issue_row(T, IntC<LOADS - 1>{});
+        }
+    };
+
+    // one half of a tile step.  HB: which block of the tile (0 or 1).  DO_QK: S(2X+HB) of tile X into
+    // s_new; DO_PV: O^T += V_{X-1}[32 HB ..]^T p_old^T; DO_SM: softmax of the block whose scores are
+    // s_old (tile sm_tile, block sm_kb) into p_new; DO_LD: the load path of tile X+2 rides along.
+    auto half_step = [&](int X, auto HB_, auto DO_QK_, auto DO_PV_, auto DO_SM_, auto DO_LD_, f32x16 &s_new,
+                         const bf16x8 (&p_old)[2], f32x16 &s_old, bf16x8 (&p_new)[2], int sm_tile,
+                         int sm_kb) __attribute__((always_inline)) {
+        constexpr int HB = decltype(HB_)::value;
+        constexpr bool DO_QK = decltype(DO_QK_)::value != 0, DO_PV = decltype(DO_PV_)::value != 0;
+        constexpr bool DO_SM = decltype(DO_SM_)::value != 0, DO_LD = decltype(DO_LD_)::value != 0;
+        constexpr int N1 = DO_QK ? NQK : 0, N2 = DO_PV ? NPV : 0, NS = N1 + N2;
+        constexpr int CPS = (16 + NS - 1) / NS;  // softmax / load chunks per matrix instruction
+        if (DO_PV && __builtin_amdgcn_ballot_w64(alpha_pending != 1.f) != 0ull) {
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha_pending;
             alpha_pending = 1.f;
         }
-        const uint32_t vst = vs_base + ((t + VST - 1) % VST) * (TILE * 2);
-        const uint32_t kst = ks_base + (t % KST) * (TILE * 2);
+        const uint32_t vst = vs_base + ((X + VST - 1) % VST) * (TILE * 2) + HB * 32 * D * 2;
+        const uint32_t kst = ks_base + (X % KST) * (TILE * 2) + HB * 32 * D * 2;
         uint32_t va_[DB], ka_[KSTEPS];
 #pragma unroll
         for (int db = 0; db < DB; ++db) va_[db] = vst + voff[db];
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) ka_[ks] = kst + koff[ks];
         bf16x8 frag[LA];
-        auto request = [&](auto S) {
+        auto request = [&](auto S) __attribute__((always_inline)) {
             constexpr int s = decltype(S)::value;
-            if constexpr (s < NPV) {
-                constexpr int kb = s / (2 * DB), stp = (s / DB) % 2, db = s % DB;
-                frag[s % LA] = lds_read_tr_at(va_[db] + (kb * 32 + stp * 16) * D * 2, 4 * D * 2);
+#ifdef SEPATTN_X_NOLDS
+            if constexpr (s < NS) frag[s % LA] = qreg[s % KSTEPS];
+            return;
+#endif
+            if constexpr (s < N1) {
+                frag[s % LA] = lds_read_b128_at(ka_[s]);
             } else if constexpr (s < NS) {
-                constexpr int q_ = s - NPV, ks = q_ / 2, kb = q_ % 2;
-                frag[s % LA] = lds_read_b128_at(ka_[ks] + kb * 32 * D * 2);
+                constexpr int q_ = s - N1, stp = q_ / DB, db = q_ % DB;
+                frag[s % LA] = lds_read_tr_at(va_[db] + stp * 16 * D * 2, 4 * D * 2);
             }
         };
-        auto multiply = [&](auto S) {
+        auto multiply = [&](auto S) __attribute__((always_inline)) {
             constexpr int s = decltype(S)::value;
-            if constexpr (s < NPV) {
-                constexpr int kb = s / (2 * DB), stp = (s / DB) % 2, db = s % DB;
-                oacc[db] = mfma_bf16(frag[s % LA], pb[kb][stp], oacc[db]);
-            } else {
-                constexpr int q_ = s - NPV, ks = q_ / 2, kb = q_ % 2;
-                if constexpr (ks == 0) {
+            if constexpr (s < N1) {
+                if constexpr (s == 0) {
                     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                    sacc[kb] = mfma_bf16(frag[s % LA], qreg[ks], zero);
+                    s_new = mfma_bf16(frag[s % LA], qreg[s], zero);
                 } else {
-                    sacc[kb] = mfma_bf16(frag[s % LA], qreg[ks], sacc[kb]);
+                    s_new = mfma_bf16(frag[s % LA], qreg[s], s_new);
                 }
+            } else {
+                constexpr int q_ = s - N1, stp = q_ / DB, db = q_ % DB;
+                oacc[db] = mfma_bf16(frag[s % LA], p_old[stp], oacc[db]);
             }
         };
-        // The wave's share of the tile loads rides along: the MFMA wave waits for the matrix pipe most
-        // of the time, so the few instructions of the load path cost nothing here, while in the VALU
-        // phase they would lengthen the critical path.  Tile t+2 is requested (its stages held tiles
-        // t-1 / t-2, whose last readers finished before the barrier this phase started from), and the
-        // index entries of tile t+3.
-        static_for<LA>([&](auto S) { request(S); });
-        entries_landed();
-        read_entries(t + 2);
+        static_for<(LA < NS ? LA : NS)>([&](auto S) { request(S); });
         __builtin_amdgcn_sched_barrier(0);
         static_for<NS>([&](auto S) {
             constexpr int s_ = decltype(S)::value;
             multiply(S);
             request(IntC<s_ + LA>{});
-            // a few instructions of the load path per matrix instruction, so that the matrix pipe
-            // never drains while they run
-            if constexpr (s_ == NS / 8) prepare_row(t + 2, IntC<0>{});
-            if constexpr (s_ == 2 * NS / 8 && LOADS == 2) prepare_row(t + 2, IntC<LOADS - 1>{});
-            if constexpr (s_ == 3 * NS / 8) issue_meta(t + 3);
-            if constexpr (s_ == 4 * NS / 8) issue_row(t + 2, IntC<0>{});
-            if constexpr (s_ == 5 * NS / 8 && LOADS == 2) issue_row(t + 2, IntC<LOADS - 1>{});
+            static_for<CPS>([&](auto J) {
+                constexpr int c = s_ * CPS + decltype(J)::value;
+                if constexpr (c < 16) {
+                    if constexpr (DO_SM) softmax_chunk(IntC<c>{}, s_old, p_new, sm_tile, sm_kb);
+                    if constexpr (DO_LD) load_chunk(IntC<c>{}, X + 2);
+                }
+            });
             __builtin_amdgcn_sched_barrier(0);
         });
-        TICK(1)
+    };
+    // barrier that publishes tile X: this wave's loads of tile X have landed (everything older than
+    // the previous step's [1 entry load][2*LOADS row loads])
+    auto publish = [&]() __attribute__((always_inline)) {
+        TICK(2)
         wait_older_loads();
-        TICK(3)
-        // (no s_setprio: a raised priority of the MFMA wave starves the VALU wave of the same SIMD)
-    };
-
-    // ---- VALU phase of tile t: mask, online softmax, probabilities to bf16
-    auto valu_phase = [&](int t) __attribute__((always_inline)) {
-        int mode[2];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) mode[kb] = block_mode(st, t * kBN + kb * 32, pw, p.n);
-        if (mode[0] == 0 && mode[1] == 0) {  // nothing visible: zero probabilities for the PV step
-            const bf16x8 z = as_bf16x8(u32x4{0u, 0u, 0u, 0u});
-            pb[0][0] = pb[0][1] = pb[1][0] = pb[1][1] = z;
-            return;
-        }
-        const int vs_ = t % VST;
-        float m_loc = -INFINITY;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            if (mode[kb] == 0) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) sacc[kb][i] = -INFINITY;
-                continue;
-            }
-            if (mode[kb] == 2) {
-#pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    int base = kb * 32 + 16 * half + 8 * hh;
-                    int4 lo0 = *reinterpret_cast<const int4 *>(&lo_s[vs_][base]);
-                    int4 lo1 = *reinterpret_cast<const int4 *>(&lo_s[vs_][base + 4]);
-                    int4 hi0 = *reinterpret_cast<const int4 *>(&hi_s[vs_][base]);
-                    int4 hi1 = *reinterpret_cast<const int4 *>(&hi_s[vs_][base + 4]);
-                    int los[8] = {lo0.x, lo0.y, lo0.z, lo0.w, lo1.x, lo1.y, lo1.z, lo1.w};
-                    int his[8] = {hi0.x, hi0.y, hi0.z, hi0.w, hi1.x, hi1.y, hi1.z, hi1.w};
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) {
-                        bool vis = (los[k] <= iq) & (iq <= his[k]);
-                        sacc[kb][8 * half + k] = vis ? sacc[kb][8 * half + k] : -INFINITY;
-                    }
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < 16; ++i) m_loc = fmaxf(m_loc, sacc[kb][i]);
-        }
-        float m_new = fmaxf(m_run, pair_max(m_loc * sl2));
-        bool grow = m_new > m_run + kRescaleThreshold;
-        if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
-            float alpha = grow ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.f;
-            m_run = grow ? m_new : m_run;
-            l_run *= alpha;
-            alpha_pending = alpha;
-        }
-        const float neg_m = (m_run == -INFINITY) ? 0.f : -m_run;
-        float psum = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                float pr = __builtin_amdgcn_exp2f(fmaf(sacc[kb][i], sl2, neg_m));
-                sacc[kb][i] = pr;
-                psum += pr;
-            }
-            pb[kb][0] = pack_bf16x8(sacc[kb], 0);
-            pb[kb][1] = pack_bf16x8(sacc[kb], 8);
-        }
-        l_run += psum;
-    };
-
-    // Workgroup barrier without the memory fence of __syncthreads(): the fence would make every wave
-    // wait for ALL of its outstanding global->LDS loads (vmcnt(0)), i.e. for the tiles it has just
-    // requested, and so expose a full memory latency per half-phase.  What a barrier has to publish
-    // here is waited for explicitly: the wave's LDS writes (lgkmcnt) and, through wait_older_loads(),
-    // the tile loads older than the current phase.
-    auto wg_barrier = [&]() __attribute__((always_inline)) {
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
+        TICK(0)
+        wg_barrier();
+        TICK(4)
     };
 
     // ---- prologue: index entries of tiles 0..2, then tiles 0 and 1 on their way into LDS
@@ -403,53 +447,30 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     read_entries(1);
     prepare_rows(1);
     issue_rows(1);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    // tile 0 has landed when at most the row loads of tile 1 are in flight
+    entries_landed();
+    wg_barrier();
 
-    // Half-phase f: group 0 runs MFMA(t) at f = 2t and VALU(t) at f = 2t+1; group 1 runs MFMA(t)
-    // at f = 2t+1 and VALU(t) at f = 2t+2 (its half-phase 0 only issues loads).  Tile T is read from
-    // f = 2T (K) to f = 2T+3 (V); its loads are issued at f = 2T-4 (group 1) and 2T-3 (group 0),
-    // when the stages it overwrites (tiles T-3 of K, T-4 of V) were last read at f = 2T-5.  A wave
-    // waits for its own loads of tile T at the end of its next VALU phase, before f = 2T.
-    // Both groups pass 2*n_tiles+1 barriers.  The two loops are written out separately (rather than one
-    // loop over half-phases with a role switch) so that every accumulator has one straight-line life.
 #ifdef SEPATTN_X_TIMING
     tlast = clock64();
 #endif
     const IntC<1> yes;
     const IntC<0> no;
-    if (grp == 0) {
-        auto half_phases = [&](int t, auto PV, auto QK) __attribute__((always_inline)) {
-            mfma_phase(t, PV, QK);
-            wg_barrier();
-            TICK(4)
-            if constexpr (decltype(QK)::value != 0) {
-                valu_phase(t);
-                TICK(2)
-                wg_barrier();
-                TICK(4)
-            }
-        };
-        half_phases(0, no, yes);
-        for (int t = 1; t < n_tiles; ++t) half_phases(t, yes, yes);
-        half_phases(n_tiles, yes, no);
-    } else {
-        wg_barrier();
-        auto half_phases = [&](int t, auto PV, auto QK) __attribute__((always_inline)) {
-            mfma_phase(t, PV, QK);
-            if constexpr (decltype(QK)::value != 0) {
-                wg_barrier();
-                TICK(4)
-                valu_phase(t);
-                TICK(2)
-                wg_barrier();
-                TICK(4)
-            }
-        };
-        half_phases(0, no, yes);
-        for (int t = 1; t < n_tiles; ++t) half_phases(t, yes, yes);
-        half_phases(n_tiles, yes, no);
+    const IntC<0> first_block;
+    const IntC<1> second_block;
+    // step 0: no output update yet, no softmax in the first half
+    half_step(0, first_block, yes, no, no, yes, s_a, p_a, s_b, p_b, 0, 0);
+    half_step(0, second_block, yes, no, yes, no, s_b, p_b, s_a, p_a, 0, 0);
+    for (int X = 1; X < n_tiles; ++X) {
+        publish();
+        half_step(X, first_block, yes, yes, yes, yes, s_a, p_a, s_b, p_b, X - 1, 1);
+        TICK(1)
+        half_step(X, second_block, yes, yes, yes, no, s_b, p_b, s_a, p_a, X, 0);
     }
+    // last step: output updates of the last tile, softmax of its second block
+    publish();
+    half_step(n_tiles, first_block, no, yes, yes, no, s_a, p_a, s_b, p_b, n_tiles - 1, 1);
+    half_step(n_tiles, second_block, no, yes, no, no, s_b, p_b, s_a, p_a, n_tiles, 0);
     // the loads of the tiles past the end are still in flight: they must have landed before the
     // workgroup ends and its LDS is handed to the next one
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");

@@ -187,13 +187,15 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
             static_for<LOADS>([&](auto U) {
                 constexpr int u = U;
                 const int r = (LOADS * wave + u) * RPL + my_sub;
-                const long off = (hrow0 + min(qbase + r, p.L - 1)) * D + swz_chunk<kSwzBoth, D>(my_pc, r) * 8;
+                // (uniform base of the head) + 32-bit byte offset; the loads go through inline assembly
+                // so that the compiler does not make every LDS read wait for all of them
+                const uint32_t off = (uint32_t)min(qbase + r, p.L - 1) * (uint32_t)(D * 2) + swz_chunk<kSwzBoth, D>(my_pc, r) * 16;
                 const int wave_off = (LOADS * wave + u) * RPL * D;
-                load_to_lds_16(Q + off, &Qs[buf][wave_off]);
-                load_to_lds_16(dO + off, &dOs[buf][wave_off]);
+                dma_to_lds_16(Q + hrow0 * D, off, lds_addr(&Qs[buf][wave_off]));
+                dma_to_lds_16(dO + hrow0 * D, off, lds_addr(&dOs[buf][wave_off]));
             });
-            if (wave == 0) load_to_lds_4(LSE2 + hrow0 + min(qbase + lane, p.L - 1), &lse_s[buf][0]);
-            if (wave == 1) load_to_lds_4(Dws + hrow0 + min(qbase + lane, p.L - 1), &d_s[buf][0]);
+            if (wave == 0) dma_to_lds_4(LSE2 + hrow0, (uint32_t)min(qbase + lane, p.L - 1) * 4u, lds_addr(&lse_s[buf][0]));
+            if (wave == 1) dma_to_lds_4(Dws + hrow0, (uint32_t)min(qbase + lane, p.L - 1) * 4u, lds_addr(&d_s[buf][0]));
             ++iss_tt;
             if (++iss_qt == n_qt) {
                 iss_qt = 0;

@@ -39,33 +39,55 @@ __device__ inline float bf16_dot8(u32x4 a, u32x4 b) {
 
 // ---------------------------------------------------------------------------------------------
 // dQ
+//
+// Same workgroup shape and key stream as the forward: 8 waves, each with 32 query rows (one head,
+// 32 positions) whose Q and dO rows stay in registers as B operands; K/V tiles of 64 stream
+// elements pass through LDS (global->LDS loads two tiles ahead, one workgroup barrier per tile).
+// Per block of 32 keys a wave runs
+//     S^T = K Q^T,  dP^T = V dO^T   (16 matrix instructions, operands row-major from LDS)
+//     dS = exp2(S*scale*log2e - LSE*log2e) * (dP - D), masked pairs zero, rounded to bf16
+//     dQ^T += K^T dS^T              (8 matrix instructions, K read transposed from the same tile)
+// with the operand fragments requested a few matrix instructions ahead.  K tiles are stored with
+// the XOR permutation that serves both kinds of read (V tiles too, so that one set of per-lane
+// offsets addresses both); three stages
+// each (tile X+2 is requested while tile X is multiplied).  The two waves that share
+// a SIMD drift apart by themselves, so that one wave's exponentials overlap the other's matrix work.
 // ---------------------------------------------------------------------------------------------
-template <int D, int NW, int GP>
-__global__ __launch_bounds__(NW * 64) void dq_kernel(
+template <int D, int GP>
+__global__ __launch_bounds__(512, 2) void dq_kernel(
     sepattn_params p, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
     const uint16_t *__restrict__ V, const uint16_t *__restrict__ O, const float *__restrict__ LSE,
     const uint16_t *__restrict__ dO, const int32_t *__restrict__ sep_idx,
     const int32_t *__restrict__ sep_prefix, uint16_t *__restrict__ dQ, float *__restrict__ Dws,
     float *__restrict__ Lws) {
-    constexpr int NT = NW * 64;
+    constexpr int NW = 8;
     constexpr int TP = 32 * NW / GP;
-    constexpr int KS = D + 8;
     constexpr int CH = D / 8;
-    constexpr int LOADS = kBN * CH / NT;
+    constexpr int RPL = 64 / CH;
+    constexpr int LOADS = kBN / (RPL * NW);
     constexpr int KSTEPS = D / 16;
     constexpr int DB = D / 32;
+    constexpr int KST = 3, VST = 3, MKS = 3;  // LDS stages of K, of V, and of the visibility ranges
+    constexpr int TILE = kBN * D;
+    static_assert(LOADS >= 1 && LOADS * RPL * NW == kBN, "tile must divide among the waves");
 
-    __shared__ __attribute__((aligned(16))) uint16_t Ks[kBN * KS];
-    __shared__ __attribute__((aligned(16))) uint16_t Vs[kBN * KS];
-    __shared__ __attribute__((aligned(16))) int lo_s[kBN];
-    __shared__ __attribute__((aligned(16))) int hi_s[kBN];
+    __shared__ __attribute__((aligned(1024))) uint16_t Ks[KST][TILE];
+    __shared__ __attribute__((aligned(1024))) uint16_t Vs[VST][TILE];
+    __shared__ __attribute__((aligned(16))) int lo_s[MKS][kBN];
+    __shared__ __attribute__((aligned(16))) int hi_s[MKS][kBN];
+    constexpr int MR = LOADS * RPL;  // rows per wave and tile
+    constexpr int MST = 4;           // ring stages of the index entries
+    __shared__ __attribute__((aligned(128))) int meta_s[MST][NW][32];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int qi = lane & 31, hh = lane >> 5;
     const int G = p.Hq / p.Hkv, groups = G / GP;
-    const int tile = gridDim.x - 1 - blockIdx.x;
+    const int n_pos_tiles = (p.L + TP - 1) / TP;
+    const TileGroup tg = xcd_tile_group(blockIdx.x, n_pos_tiles, p.B * p.Hkv * groups);
+    const int tile = n_pos_tiles - 1 - tg.rank;  // late tiles carry more separators: start them first
     const int i0 = tile * TP;
-    int y = blockIdx.y;
+    int y = tg.group;
     const int hg = y % groups;
     const int kv = (y / groups) % p.Hkv;
     const int b = y / (groups * p.Hkv);
@@ -107,86 +129,228 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[db][i] = 0.f;
 
-    u32x4 kpre[LOADS], vpre[LOADS];
-    int lo_pre[LOADS], hi_pre[LOADS];
-    auto prefetch = [&](int t) {
+    // ---- tile loads (see the forward kernel: same scheme, other LDS layouts)
+    const int my_pc = lane % CH, my_sub = lane / CH;
+    uint32_t kgo[LOADS];  // byte offset of this lane's 16-byte piece inside a K or V row
+    int rrow[LOADS];
 #pragma unroll
-        for (int u = 0; u < LOADS; ++u) {
-            int c = tid + u * NT;
-            int r = c / CH, ch = c % CH;
-            int j = stream_key(st, t * kBN + r, p, idx, prefix, lo_pre[u], hi_pre[u]);
-            kpre[u] = *reinterpret_cast<const u32x4 *>(Kh + (long)j * D + ch * 8);
-            vpre[u] = *reinterpret_cast<const u32x4 *>(Vh + (long)j * D + ch * 8);
+    for (int u = 0; u < LOADS; ++u) {
+        rrow[u] = (LOADS * wave + u) * RPL + my_sub;
+        kgo[u] = swz_chunk<kSwzBoth, D>(my_pc, rrow[u]) * 16;
+    }
+    const char *Kb = reinterpret_cast<const char *>(Kh), *Vb = reinterpret_cast<const char *>(Vh);
+    auto tile_class = [&](int t) {
+        const int k0 = t * kBN;
+        return (k0 + kBN <= st.n_dense) ? 0 : (k0 >= st.n_dense ? 1 : 2);
+    };
+    const int m_part = lane / MR, m_row = wave * MR + lane % MR;  // lanes 0 .. 3*MR-1 are used
+    auto issue_meta = [&](int t) __attribute__((always_inline)) {
+        const int k = t * kBN + m_row;
+        const int e = min(max(st.sep_lo - st.n_init + k, 0), p.cap - 1);
+        const int j = min(max(st.bs - st.n_dense + k, 0), p.L - 1);
+        const int32_t *src = m_part == 0 ? idx + e : prefix + j + (m_part - 1);
+        if (lane < 3 * MR) dma_to_lds_4_addr(src, lds_addr(&meta_s[t % MST][wave][0]));
+    };
+    int jrow[LOADS], rawi[LOADS], raw0[LOADS], raw1[LOADS];
+    auto read_entries = [&](int t) __attribute__((always_inline)) {
+        const int *mt = &meta_s[t % MST][wave][0];
+        static_for<LOADS>([&](auto U) {
+            constexpr int u = U;
+            rawi[u] = mt[u * RPL + my_sub];
+            raw0[u] = mt[MR + u * RPL + my_sub];
+            raw1[u] = mt[2 * MR + u * RPL + my_sub];
+        });
+    };
+    auto prepare_row = [&](int t, auto U) __attribute__((always_inline)) {
+        constexpr int u = decltype(U)::value;
+        const int ms_ = t % MKS;
+        const int r = rrow[u];
+        const int k = t * kBN + r;
+        // the clamp keeps a stale list tail (caller broke sep_count <= cap) from faulting
+        const int jl = min(max(rawi[u], 0), p.L - 1);
+        if (tile_class(t) == 0) {
+            jrow[u] = k < st.n_init ? k : jl;
+        } else {
+            const bool init = k < st.n_init, dense = k < st.n_dense, pad = k >= st.n_total;
+            const int jb = st.bs + (k - st.n_dense);
+            const bool always = dense | (jb < p.a) | (raw1[u] != raw0[u]);
+            int j = init ? k : (dense ? jl : jb);
+            j = pad ? 0 : j;
+            const int lo = pad ? kIntMax : j;
+            int hi = always ? kIntMax : jb + p.n - 1;
+            hi = pad ? -1 : hi;
+            if (my_pc == 0) {
+                lo_s[ms_][r] = lo;
+                hi_s[ms_][r] = hi;
+            }
+            jrow[u] = j;
         }
     };
-    prefetch(0);
+    auto issue_row = [&](int t, auto U) __attribute__((always_inline)) {
+        constexpr int u = decltype(U)::value;
+        const uint32_t kst = lds_addr(&Ks[t % KST][0]), vst = lds_addr(&Vs[t % VST][0]);
+        const uint32_t wave_off = (uint32_t)((LOADS * wave + u) * RPL * D * 2);
+        const uint32_t row_off = (uint32_t)jrow[u] * (uint32_t)(D * 2);
+        dma_to_lds_16(Kb, row_off + kgo[u], kst + wave_off);
+        dma_to_lds_16(Vb, row_off + kgo[u], vst + wave_off);
+    };
+    // a tile step issues [1 entry load][2*LOADS row loads], in this order; loads complete in order
+    auto entries_landed = [&]() __attribute__((always_inline)) {
+        if constexpr (LOADS == 1)
+            asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    };
+    auto wait_older_loads = [&]() __attribute__((always_inline)) {
+        static_assert(LOADS == 1 || LOADS == 2, "wait counts are written for 1 or 2 loads per tensor");
+        if constexpr (LOADS == 1)
+            asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+    };
+    auto wg_barrier = [&]() __attribute__((always_inline)) {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
 
-    for (int t = 0; t < n_tiles; ++t) {
-        __syncthreads();
+    // per-lane byte offsets of the operand fragments inside a tile
+    const int a_row = pi_row(qi);
+    const uint32_t ks_base = lds_addr(&Ks[0][0]), vs_base = lds_addr(&Vs[0][0]);
+    // Row-major fragments: the XOR permutation acts on the 16-byte chunk index 2*ks + hh, and the
+    // k-step only enters through bits 1..3 of it, so fragment ks sits at (fragment 0) ^ (32 * ks):
+    // one register instead of KSTEPS.  (Tile bases are multiples of 1 KB, so the XOR commutes with
+    // adding the base.)  K and V tiles share one layout and therefore these offsets.
+    const uint32_t koff0 = lds_off_a<kSwzBoth, D>(a_row, hh);
+    uint32_t ktr0[DB], ktr1[DB];
 #pragma unroll
-        for (int u = 0; u < LOADS; ++u) {
-            int c = tid + u * NT;
-            int r = c / CH, ch = c % CH;
-            *reinterpret_cast<u32x4 *>(Ks + r * KS + ch * 8) = kpre[u];
-            *reinterpret_cast<u32x4 *>(Vs + r * KS + ch * 8) = vpre[u];
-            if (ch == 0) {
-                lo_s[r] = lo_pre[u];
-                hi_s[r] = hi_pre[u];
-            }
-        }
-        __syncthreads();
-        if (t + 1 < n_tiles) prefetch(t + 1);
-
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            int mode = block_mode(st, t * kBN + kb * 32, pw, p.n);
-            if (mode == 0) continue;
-            f32x16 sacc, pacc;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) sacc[i] = pacc[i] = 0.f;
-            int row = kb * 32 + pi_row(qi);
-#pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks) {
-                sacc = mfma_bf16(lds_read_a(Ks, row, KS, ks * 16 + 8 * hh), qreg[ks], sacc);
-                pacc = mfma_bf16(lds_read_a(Vs, row, KS, ks * 16 + 8 * hh), doreg[ks], pacc);
-            }
-            if (mode == 1) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    float pr = __builtin_amdgcn_exp2f(sacc[i] * sl2 - lse2);
-                    sacc[i] = pr * (pacc[i] - Di);
-                }
-            } else {
-#pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    int base = kb * 32 + 16 * half + 8 * hh;
-                    int4 lo0 = *reinterpret_cast<const int4 *>(lo_s + base);
-                    int4 lo1 = *reinterpret_cast<const int4 *>(lo_s + base + 4);
-                    int4 hi0 = *reinterpret_cast<const int4 *>(hi_s + base);
-                    int4 hi1 = *reinterpret_cast<const int4 *>(hi_s + base + 4);
-                    int los[8] = {lo0.x, lo0.y, lo0.z, lo0.w, lo1.x, lo1.y, lo1.z, lo1.w};
-                    int his[8] = {hi0.x, hi0.y, hi0.z, hi0.w, hi1.x, hi1.y, hi1.z, hi1.w};
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) {
-                        int i = 8 * half + k;
-                        bool vis = (los[k] <= iq) & (iq <= his[k]);
-                        float pr = __builtin_amdgcn_exp2f(sacc[i] * sl2 - lse2);
-                        sacc[i] = vis ? pr * (pacc[i] - Di) : 0.f;
-                    }
-                }
-            }
-            // dQ^T += K^T dS^T
-#pragma unroll
-            for (int stp = 0; stp < 2; ++stp) {
-                bf16x8 dsb = pack_bf16x8(sacc, 8 * stp);
-#pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    bf16x8 kt = lds_read_a_tr(Ks, kb * 32 + stp * 16, KS, db * 32, lane);
-                    acc[db] = mfma_bf16(kt, dsb, acc[db]);
-                }
-            }
-        }
+    for (int db = 0; db < DB; ++db) {
+        ktr0[db] = lds_off_a_tr<kSwzBoth, D>(db * 32, lane);
+        ktr1[db] = lds_off_a_tr_second<kSwzBoth, D>(db * 32, lane);
     }
+    // for d = 128 the second transposed read is the first with chunk bit 0 flipped, four rows on
+    auto tr_second = [&](uint32_t first, int db) __attribute__((always_inline)) {
+        if constexpr (D == 128)
+            return (first ^ 16u) + 4u * D * 2u;
+        else
+            return first - ktr0[db] + ktr1[db];
+    };
+
+    // ---- one block of 32 keys: tile X, block HB
+    constexpr int LA = 4;
+    constexpr int NS1 = 2 * KSTEPS, NS2 = 2 * DB;  // matrix instructions: scores, then the dQ update
+    auto block_step = [&](int X, auto HB_, auto LD_) __attribute__((always_inline)) {
+        constexpr int HB = decltype(HB_)::value;
+        constexpr bool DO_LD = decltype(LD_)::value != 0;
+        const uint32_t kst = ks_base + (X % KST) * (TILE * 2) + HB * 32 * D * 2;
+        const uint32_t vst = vs_base + (X % VST) * (TILE * 2) + HB * 32 * D * 2;
+        f32x16 sacc, pacc;
+        bf16x8 frag[LA];
+        auto request1 = [&](auto S) __attribute__((always_inline)) {
+            constexpr int s = decltype(S)::value;
+            if constexpr (s < NS1) {
+                constexpr int ks = s / 2;
+                frag[s % LA] = lds_read_b128_at(((s % 2 == 0 ? kst : vst) + koff0) ^ (32u * ks));
+            }
+        };
+        static_for<LA>([&](auto S) { request1(S); });
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<NS1>([&](auto S) {
+            constexpr int s = decltype(S)::value, ks = s / 2;
+            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            if constexpr (s % 2 == 0)
+                sacc = mfma_bf16(frag[s % LA], qreg[ks], ks == 0 ? zero : sacc);
+            else
+                pacc = mfma_bf16(frag[s % LA], doreg[ks], ks == 0 ? zero : pacc);
+            request1(IntC<s + LA>{});
+            // the load path of tile X+2 rides along with the first block of the tile
+            if constexpr (DO_LD) {
+                if constexpr (s == 0) {
+                    entries_landed();
+                    read_entries(X + 2);
+                } else if constexpr (s == NS1 / 4) {
+                    prepare_row(X + 2, IntC<0>{});
+                } else if constexpr (s == NS1 / 4 + 1 && LOADS == 2) {
+                    prepare_row(X + 2, IntC<LOADS - 1>{});
+                } else if constexpr (s == NS1 / 2) {
+                    issue_meta(X + 3);
+                } else if constexpr (s == NS1 / 2 + NS1 / 8) {
+                    issue_row(X + 2, IntC<0>{});
+                } else if constexpr (s == NS1 / 2 + NS1 / 4 && LOADS == 2) {
+                    issue_row(X + 2, IntC<LOADS - 1>{});
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        // transposed K fragments of the first half of the dQ update are requested before the dS
+        // arithmetic, those of the second half while the first half multiplies
+        bf16x8 tfr[DB];
+#pragma unroll
+        for (int db = 0; db < DB; ++db) tfr[db] = lds_read_tr_at2(kst + ktr0[db], tr_second(kst + ktr0[db], db));
+        // dS = P (dP - D), zero where masked
+        if (block_mode(st, X * kBN + HB * 32, pw, p.n) != 1) {
+            const int ms_ = X % MKS;
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const int base = HB * 32 + 16 * half + 8 * hh;
+                const int4 lo0 = *reinterpret_cast<const int4 *>(&lo_s[ms_][base]);
+                const int4 lo1 = *reinterpret_cast<const int4 *>(&lo_s[ms_][base + 4]);
+                const int4 hi0 = *reinterpret_cast<const int4 *>(&hi_s[ms_][base]);
+                const int4 hi1 = *reinterpret_cast<const int4 *>(&hi_s[ms_][base + 4]);
+                const int los[8] = {lo0.x, lo0.y, lo0.z, lo0.w, lo1.x, lo1.y, lo1.z, lo1.w};
+                const int his[8] = {hi0.x, hi0.y, hi0.z, hi0.w, hi1.x, hi1.y, hi1.z, hi1.w};
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const bool vis = (los[k] <= iq) & (iq <= his[k]);
+                    sacc[8 * half + k] = vis ? sacc[8 * half + k] : -INFINITY;
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float pr = __builtin_amdgcn_exp2f(fmaf(sacc[i], sl2, -lse2));
+            sacc[i] = pr * (pacc[i] - Di);
+        }
+        const bf16x8 dsb0 = pack_bf16x8(sacc, 0), dsb1 = pack_bf16x8(sacc, 8);
+        // dQ^T += K^T dS^T
+        bf16x8 tfr2[DB];
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            acc[db] = mfma_bf16(tfr[db], dsb0, acc[db]);
+            tfr2[db] = lds_read_tr_at2(kst + ktr0[db] + 16 * D * 2, tr_second(kst + ktr0[db], db) + 16 * D * 2);
+        }
+#pragma unroll
+        for (int db = 0; db < DB; ++db) acc[db] = mfma_bf16(tfr2[db], dsb1, acc[db]);
+    };
+
+    // ---- prologue: index entries of tiles 0..2, then tiles 0 and 1 on their way into LDS
+    issue_meta(0);
+    issue_meta(1);
+    issue_meta(2);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    read_entries(0);
+    static_for<LOADS>([&](auto U) { prepare_row(0, U); });
+    static_for<LOADS>([&](auto U) { issue_row(0, U); });
+    read_entries(1);
+    static_for<LOADS>([&](auto U) { prepare_row(1, U); });
+    static_for<LOADS>([&](auto U) { issue_row(1, U); });
+    entries_landed();  // tile 0 has landed when at most the row loads of tile 1 are in flight
+    wg_barrier();
+
+    // Tile step X reads K_X (row-major and transposed) and V_X and requests tile X+2, whose stages
+    // held tile X-1: last read in step X-1, which every wave has left when it passes the barrier.
+    const IntC<1> yes;
+    const IntC<0> no;
+    for (int X = 0; X < n_tiles; ++X) {
+        if (X > 0) {
+            wait_older_loads();  // this wave's loads of tile X: everything older than step X-1's requests
+            wg_barrier();
+        }
+        block_step(X, IntC<0>{}, yes);
+        block_step(X, IntC<1>{}, no);
+    }
+    // the loads of the tiles past the end must have landed before the LDS is handed on
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     if (iq < p.L) {
         uint16_t *dst = dQ + qrow_id * D;
@@ -201,16 +365,11 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(
     }
 }
 
-#ifndef SEPATTN_DQ_WAVES
-#define SEPATTN_DQ_WAVES 8
-#endif
-
 template <int D>
 int launch_bwd(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
                const uint16_t *O, const float *LSE, const uint16_t *dO, const int32_t *sep_idx,
                const int32_t *sep_prefix, uint16_t *dQ, uint16_t *dK, uint16_t *dV, void *ws,
                hipStream_t st) {
-    constexpr int NW = SEPATTN_DQ_WAVES;
     const BwdWorkspace w = bwd_workspace(p);
     char *base = static_cast<char *>(ws);
     float *Dws = reinterpret_cast<float *>(base);
@@ -220,16 +379,18 @@ int launch_bwd(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
 
     int G = p.Hq / p.Hkv;
     int GP = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
-    int TP = 32 * NW / GP;
-    dim3 grid((p.L + TP - 1) / TP, p.B * p.Hkv * (G / GP)), block(NW * 64);
+    int TP = 32 * 8 / GP;
+    const long n_wg = (long)((p.L + TP - 1) / TP) * p.B * p.Hkv * (G / GP);
+    if (n_wg > 0x7FFFFFFFL) return SEPATTN_ERR_SHAPE;
+    dim3 grid((unsigned)n_wg), block(512);
     {
     ProfScope prof(SEPATTN_K_BWD_DQ, st);
     if (GP == 4)
-        hipLaunchKernelGGL((dq_kernel<D, NW, 4>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, dQ, Dws, Lws);
+        hipLaunchKernelGGL((dq_kernel<D, 4>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, dQ, Dws, Lws);
     else if (GP == 2)
-        hipLaunchKernelGGL((dq_kernel<D, NW, 2>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, dQ, Dws, Lws);
+        hipLaunchKernelGGL((dq_kernel<D, 2>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, dQ, Dws, Lws);
     else
-        hipLaunchKernelGGL((dq_kernel<D, NW, 1>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, dQ, Dws, Lws);
+        hipLaunchKernelGGL((dq_kernel<D, 1>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, dQ, Dws, Lws);
     }
     if (hipGetLastError() != hipSuccess) return SEPATTN_ERR_HIP;
     return launch_dkv_bf16(p, Q, K, V, Lws, dO, Dws, sep_idx, sep_prefix, dK, dV, farK, farV, st);

@@ -188,6 +188,17 @@ __device__ inline bf16x8 lds_read_tr_at(uint32_t addr, uint32_t second) {
     x.s[1] = hi;
     return x.v;
 }
+__device__ inline bf16x8 lds_read_tr_at2(uint32_t addr0, uint32_t addr1) {
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)addr0);
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)addr1);
+    union {
+        s16x4 s[2];
+        bf16x8 v;
+    } x;
+    x.s[0] = lo;
+    x.s[1] = hi;
+    return x.v;
+}
 #pragma clang diagnostic pop
 // byte offset of the 16-byte row-major A fragment (row, logical chunk) in a swizzled unpadded tile
 template <int MODE, int D>
@@ -204,6 +215,15 @@ __device__ inline uint32_t lds_off_a_tr(int col0, int lane) {
     return (uint32_t)(r * D + swz_chunk<MODE, D>(c >> 3, r) * 8 + (c & 4)) * 2u;
 }
 
+// the same for the second transposed read (row r + 4), for layouts in which it is not simply
+// 4 rows further on (kSwzBoth)
+template <int MODE, int D>
+__device__ inline uint32_t lds_off_a_tr_second(int col0, int lane) {
+    int p = lane & 15, g = lane >> 4;
+    int r = 8 * (g >> 1) + (p >> 2) + 4;
+    int c = col0 + 16 * (g & 1) + 4 * (p & 3);
+    return (uint32_t)(r * D + swz_chunk<MODE, D>(c >> 3, r) * 8 + (c & 4)) * 2u;
+}
 // 16-byte read of a row-major A operand from LDS
 __device__ inline bf16x8 lds_read_a(const uint16_t *tile, int row, int stride, int col) {
     return *reinterpret_cast<const bf16x8 *>(tile + row * stride + col);

@@ -38,9 +38,9 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
 # The figures and the commands are in profiles/; None = not measured for the current kernels.
 CALIB_BYTES = 256 << 20
 MEASURED_TRAFFIC_BYTES = {
-    "forward": None,
-    "bwd_dq": None,
-    "bwd_dkv": None,
+    "forward": 176.1e6,   # read 108.0 MB + written 68.2 MB   (algorithmic: 168.8 MB)
+    "bwd_dq": 313.6e6,    # read 244.4 MB + written 69.2 MB
+    "bwd_dkv": 497.0e6,   # read 407.9 MB + written 89.0 MB
 }
 
 

@@ -342,18 +342,30 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
         return;
 #endif
         if constexpr (c == 0) {
+#ifndef SEPATTN_X_NOLD_ENT
             entries_landed();
             read_entries(T);
+#endif
         } else if constexpr (c == 2) {
+#ifndef SEPATTN_X_NOLD_PREP
             prepare_row(T, IntC<0>{});
+#endif
         } else if constexpr (c == 4 && LOADS == 2) {
+#ifndef SEPATTN_X_NOLD_PREP
             prepare_row(T, IntC<LOADS - 1>{});
+#endif
         } else if constexpr (c == 6) {
+#ifndef SEPATTN_X_NOLD_META
             issue_meta(T + 1);
+#endif
         } else if constexpr (c == 8) {
+#ifndef SEPATTN_X_NOLD_ROWS
             issue_row(T, IntC<0>{});
+#endif
         } else if constexpr (c == 10 && LOADS == 2) {
+#ifndef SEPATTN_X_NOLD_ROWS
             issue_row(T, IntC<LOADS - 1>{});
+#endif
         }
     };
 

@@ -5,18 +5,12 @@
 //   dV_j = sum_i P_ij dO_i   (dK, dV summed over the query heads of the KV head).
 //
 // Three launches, no floating-point atomics (results are bit-reproducible):
-//  1. dq_kernel: one workgroup per query tile, same dense key stream as the forward
-//     [initial | separators older than the window | band].  Also writes D_i for the other two.
-//  2. dkv_kernel<far>: the visible pairs split into band pairs (i-j < n) and far pairs (i-j >= n,
-//     j an initial token or a separator).  Far pairs are handled on the COMPACTED list of such keys
-//     (128 consecutive list entries per workgroup, gathered K/V rows) against a chunk of the query
-//     range; every (list tile, query chunk) unit writes an fp32 partial dK/dV to the workspace.
-//  3. dkv_kernel<band>: one workgroup per 128 consecutive keys against the queries j <= i < j+n.
-//     Its epilogue adds, in fixed chunk order, the far partials of the keys that have them, then
-//     rounds once to bf16.  One workgroup owns each key row: no atomics needed.
-// In the dK/dV kernels the wave's 32 keys are the B operands (kept in registers for the whole
-// unit) and query tiles (Q, dO, LSE, D) stream through LDS; the four query heads of a GQA group are
-// just four times as many query tiles.
+//  1. dq_kernel (this file): one workgroup per query tile, same dense key stream as the forward
+//     [initial | separators older than the window | band].  Also writes D_i and LSE_i*log2(e).
+//  2. dkv_kernel (bwd_dkv_bf16.hip): the visible pairs split into band pairs (i-j < n) and far
+//     pairs (i-j >= n, j an initial token or a separator); far units work on the COMPACTED list of
+//     such keys and write fp32 partials, band units finish the keys that are not on that list.
+//  3. dkv_combine_kernel: adds, in fixed order, the partials of every far-list key and rounds once.
 #include "bwd_common.h"
 #include "mfma_common.h"
 #include "key_stream.h"

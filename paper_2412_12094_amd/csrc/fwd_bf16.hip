@@ -10,19 +10,16 @@
 // tokens / separators) and are gathered through the compacted separator index list; only band keys
 // need the per-element test  j <= i and (i-j < n or j is an initial token or a separator).
 //
-// Schedule: the two waves that share a SIMD (w and w+4) run half a tile apart ("ping-pong").  Time is
-// cut into half-phases separated by workgroup barriers; in every half-phase one wave of each SIMD is
-// in its MFMA phase  [O^T += V^T P^T of tile t-1, then S^T = K Q^T of tile t]  while the other is in
-// its VALU phase  [mask + online softmax of its tile, global loads of coming tiles].  The matrix
-// pipe and the vector ALU of a SIMD are thus busy at the same time without any instruction-level
-// interleaving inside a wave.  K tiles live in 3 LDS stages, V tiles and the per-key visibility
-// ranges in 4; tiles are filled by direct global->LDS loads (global_load_lds_dwordx4, no staging
-// registers) issued about two tiles ahead, unpadded with XOR-swizzled 16-byte chunks (see
-// mfma_common.h).  V^T operands are read with ds_read_b64_tr_b16.  A wave
-// skips 32-key blocks that lie entirely in its future and drops the mask test on blocks every one
-// of its rows sees in full.  The running maximum is only raised when it grows by more than 2^8 (all
-// terms carry the same stale maximum, so the result is unchanged), which removes almost every
-// rescale of the output accumulators.
+// Schedule: every wave runs the same software pipeline over blocks of 32 keys; the score block of
+// the next block, the output update of the previous one and the softmax of the current one are
+// interleaved instruction by instruction (the matrix instructions execute while the vector
+// instructions issued after them run), one workgroup barrier per tile.  K tiles live in 3 LDS stages,
+// V tiles and the per-key visibility ranges in 4; tiles are filled by direct global->LDS loads
+// (global_load_lds_dwordx4, no staging registers) issued two tiles ahead, unpadded with XOR-swizzled
+// 16-byte chunks (see mfma_common.h).  V^T operands are read with ds_read_b64_tr_b16.  A wave drops
+// the mask test on blocks every one of its rows sees in full.  The running maximum is only raised
+// when it grows by more than 2^8 (all terms carry the same stale maximum, so the result is
+// unchanged), which removes almost every rescale of the output accumulators.
 #include "common.h"
 #include "mfma_common.h"
 #include "key_stream.h"

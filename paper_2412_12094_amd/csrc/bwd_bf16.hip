@@ -95,6 +95,7 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
     const uint16_t *Vh = V + ((long)b * p.Hkv + kv) * (long)p.L * D;
     const Stream st = make_stream(p, prefix, i0, TP);
     const int n_tiles = (st.n_total + kBN - 1) / kBN;
+    const FullBlocks fullb = full_blocks(st, pw, p.n);
 
     const long qrow_id = ((long)b * p.Hq + head) * p.L + min(iq, p.L - 1);
     bf16x8 qreg[KSTEPS], doreg[KSTEPS];
@@ -282,7 +283,7 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
 #pragma unroll
         for (int db = 0; db < DB; ++db) tfr[db] = lds_read_tr_at2(kst + ktr0[db], tr_second(kst + ktr0[db], db));
         // dS = P (dP - D), zero where masked
-        if (block_mode(st, X * kBN + HB * 32, pw, p.n) != 1) {
+        if (!block_is_full(fullb, X * kBN + HB * 32)) {
             const int ms_ = X % MKS;
 #pragma unroll
             for (int half = 0; half < 2; ++half) {

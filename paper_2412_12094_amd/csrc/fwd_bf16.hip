@@ -67,10 +67,16 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     __shared__ __attribute__((aligned(16))) int lo_s[VST][kBN];
     __shared__ __attribute__((aligned(16))) int hi_s[VST][kBN];
 
+#ifdef SEPATTN_X_TIMING
+    const unsigned long long w_start = wall_clock64();
+#endif
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps branches scalar
     const int grp = wave >> 2;                                  // waves w and w+4 share a SIMD
     const int qi = lane & 31, hh = lane >> 5;
+#ifdef SEPATTN_X_HALFWAVES
+    if (wave >= 4) return;  // timing experiment: one wave per SIMD
+#endif
     const int G = p.Hq / p.Hkv, groups = G / GP;
     const int n_pos_tiles = (p.L + TP - 1) / TP;
     const TileGroup tg = xcd_tile_group(blockIdx.x, n_pos_tiles, p.B * p.Hkv * groups);
@@ -91,6 +97,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
 
     const Stream st = make_stream(p, prefix, i0, TP);
     const int n_tiles = (st.n_total + kBN - 1) / kBN;
+    const FullBlocks fullb = full_blocks(st, pw, p.n);
 
     // this wave's queries as B operands
     bf16x8 qreg[KSTEPS];
@@ -272,7 +279,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
         return;
 #endif
         if constexpr (c == 0) {
-            sm.masked = block_mode(st, tile * kBN + kb * 32, pw, p.n) != 1;
+            sm.masked = !block_is_full(fullb, tile * kBN + kb * 32);
 #ifdef SEPATTN_X_SM_NOBR
             sm.masked = false;
 #endif
@@ -462,6 +469,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
 
 #ifdef SEPATTN_X_TIMING
     tlast = clock64();
+    const unsigned long long w_loop0 = wall_clock64();
 #endif
     const IntC<1> yes;
     const IntC<0> no;
@@ -472,6 +480,12 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     half_step(0, second_block, yes, no, yes, no, s_b, p_b, s_a, p_a, 0, 0);
     for (int X = 1; X < n_tiles; ++X) {
         publish();
+#ifdef SEPATTN_X_PRIO
+        if ((X ^ (wave >> 2)) & 1) __builtin_amdgcn_s_setprio(SEPATTN_X_PRIO); else __builtin_amdgcn_s_setprio(0);
+#endif
+#ifdef SEPATTN_X_PRIO_FIXED
+        if (wave >> 2) __builtin_amdgcn_s_setprio(SEPATTN_X_PRIO_FIXED);
+#endif
         half_step(X, first_block, yes, yes, yes, yes, s_a, p_a, s_b, p_b, X - 1, 1);
         TICK(1)
         half_step(X, second_block, yes, yes, yes, no, s_b, p_b, s_a, p_a, X, 0);
@@ -484,7 +498,11 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     // workgroup ends and its LDS is handed to the next one
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #ifdef SEPATTN_X_TIMING
+    const unsigned long long w_loop1 = wall_clock64();
     if (lane == 0 && blockIdx.x < 2048) {
+        tacc[3] = w_loop0 - w_start;
+        tacc[6] = w_loop1 - w_loop0;
+        tacc[7] = w_start;
         tacc[5] = n_tiles;
         for (int k = 0; k < 8; ++k) g_dbg[((long)blockIdx.x * 8 + wave) * 8 + k] = tacc[k];
     }

@@ -90,4 +90,23 @@ __device__ inline int block_mode(const Stream &st, int k0, int pw, int n) {
     return 2;
 }
 
+// The same decision for "every pair of the block is visible" (mode 1), reduced to three comparisons
+// against thresholds that are computed once per wave: a block of 32 stream elements starting at k0
+// needs no mask test iff it lies in the dense part (k0 <= dense_last) or is a band block whose keys
+// are inside every row's window and not in any row's future (band_first <= k0 <= band_last).
+struct FullBlocks {
+    int dense_last, band_first, band_last;
+};
+__device__ inline FullBlocks full_blocks(const Stream &st, int pw, int n) {
+    FullBlocks f;
+    const int pmax = pw + 31;
+    f.dense_last = st.n_dense - 32;
+    f.band_first = max(st.n_dense, st.n_dense + (pmax - n + 1) - st.bs);  // jmin + n - 1 >= pmax
+    f.band_last = min(st.n_dense + (pw - 31) - st.bs, st.n_total - 32);   // jmax <= pw, no padding
+    return f;
+}
+__device__ inline bool block_is_full(const FullBlocks &f, int k0) {
+    return (k0 <= f.dense_last) | ((k0 >= f.band_first) & (k0 <= f.band_last));
+}
+
 }  // namespace sepattn

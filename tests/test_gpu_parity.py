@@ -301,6 +301,8 @@ def random_sizes(rng, S, a, s, wcap, w):
     (2, 4, 4, 64, 2, 10, 8, 41),
     (4, 6, 3, 128, 0, 33, 16, 100),
     (1, 8, 1, 64, 4, 300, 100, 1500),
+    (2, 32, 1, 128, 4, 500, 64, 900),   # a full 32-head group, several slices per cache
+    (1, 64, 1, 128, 2, 40, 16, 120),    # 64 heads per KV head: wider than one matrix-instruction operand
 ])
 def test_decode_matches_oracle(sp, dtype, S, Hq, Hkv, d, a, s, w, c):
     cfg = wl.CacheConfig("t", S, Hq, Hkv, d, a, s, w, c, 0.1, dtype, seed=77 + c)
@@ -327,6 +329,29 @@ def test_decode_empty_sequence_and_single_entry(sp):
     o, l = host(out), host(lse)
     assert np.all(o[0] == 0) and np.all(np.isneginf(l[0]))
     assert np.array_equal(o[1], np.repeat(data["Vc"][1, :, 10], 2, axis=0))  # the only entry: window slot 0
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_decode_ignores_slots_beyond_the_sizes(sp, dtype):
+    """Slots past Size_* hold unspecified data (here NaN): they must not reach the result."""
+    S, Hq, Hkv, d, a, s, w, c = 3, 8, 2, 128, 4, 90, 20, 300
+    cfg = wl.CacheConfig("t", S, Hq, Hkv, d, a, s, w, c, 0.1, dtype, seed=11)
+    sizes = np.array([[4, 90, 100, 20], [3, 17, 0, 5], [4, 33, 41, 20]], dtype=np.int32)
+    data = wl.make_cache(cfg, sizes)
+    Kc, Vc = data["Kc"].copy(), data["Vc"].copy()
+    for q in range(S):
+        ni, ns, npast, nl = sizes[q]
+        for arr in (Kc, Vc):
+            arr[q, :, ni:a] = np.nan
+            arr[q, :, a + ns:a + s] = np.nan
+            arr[q, :, a + s + npast + nl:] = np.nan
+    scale = 1.0 / math.sqrt(d)
+    out, lse = sp.sepattn_decode(dev(data["q"], dtype), dev(Kc, dtype), dev(Vc, dtype), dev(sizes), a, s, w, scale)
+    torch.cuda.synchronize()
+    ref, lref = oracle.decode(data["q"], data["Kc"], data["Vc"], sizes, a, s, scale)
+    assert np.isfinite(host(out)).all()
+    assert np.abs(host(out) - ref).max() <= TOL[dtype]
+    assert np.abs(host(lse) - lref).max() <= LSE_TOL[dtype]
 
 
 def test_decode_config5_full_size(sp):

@@ -72,6 +72,20 @@ int check_kv(const sepkv_params *p) {
 
 }  // namespace
 
+namespace sepattn {
+int compute_units() {
+    static int cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+}  // namespace sepattn
+
 extern "C" {
 
 const char *sepattn_status_string(int status) {

@@ -15,6 +15,9 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? SEPATTN_OK
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// number of compute units of the current device (queried once per device; 256 if the query fails)
+int compute_units();
+
 // Measurement hook: brackets launches of the selected kernel with HIP events (see sepattn.h).
 void profile_mark(int kernel, hipStream_t st, bool stop);
 struct ProfScope {

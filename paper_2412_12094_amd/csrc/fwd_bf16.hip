@@ -50,7 +50,7 @@ template <int D, int GP>
 __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     sepattn_params p, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
     const uint16_t *__restrict__ V, const int32_t *__restrict__ sep_idx,
-    const int32_t *__restrict__ sep_prefix, uint16_t *__restrict__ O, float *__restrict__ LSE) {
+    const int32_t *__restrict__ sep_prefix, uint16_t *__restrict__ O, float *__restrict__ LSE, int wpg) {
     constexpr int NW = 8;
     constexpr int TP = 32 * NW / GP;  // query positions per workgroup
     constexpr int CH = D / 8;         // 16-byte chunks per row
@@ -77,48 +77,39 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
 #ifdef SEPATTN_X_HALFWAVES
     if (wave >= 4) return;  // timing experiment: one wave per SIMD
 #endif
+    // A workgroup is persistent: it belongs to one (batch, KV head, head group) and walks through
+    // several query tiles of it ("segments"), `wpg` workgroups per group sharing the tiles in zig-zag
+    // order (round r: rank r*wpg + j for even r, r*wpg + wpg-1-j for odd r; rank 0 = the last tile,
+    // the one with the longest key stream), so that with an even spread of separators every
+    // workgroup gets about the same number of stream tiles.  Launch gaps, the tail of a grid of
+    // unequal workgroups and most of the per-tile start-up cost are paid once per workgroup.
     const int G = p.Hq / p.Hkv, groups = G / GP;
     const int n_pos_tiles = (p.L + TP - 1) / TP;
-    const TileGroup tg = xcd_tile_group(blockIdx.x, n_pos_tiles, p.B * p.Hkv * groups);
-    const int tile = n_pos_tiles - 1 - tg.rank;  // late tiles carry more separators: start them first
-    const int i0 = tile * TP;
+    const TileGroup tg = xcd_tile_group(blockIdx.x, wpg, p.B * p.Hkv * groups);
     int y = tg.group;
     const int hg = y % groups;
     const int kv = (y / groups) % p.Hkv;
     const int b = y / (groups * p.Hkv);
     const int head = kv * G + hg * GP + (wave % GP);
-    const int pw = i0 + 32 * (wave / GP);  // first position of this wave
-    const int iq = pw + qi;                // this lane's query position
 
     const int32_t *prefix = sep_prefix + (long)b * (p.L + 1);
     const int32_t *idx = sep_idx + (long)b * p.cap;
     const uint16_t *Kh = K + ((long)b * p.Hkv + kv) * (long)p.L * D;
     const uint16_t *Vh = V + ((long)b * p.Hkv + kv) * (long)p.L * D;
 
-    const Stream st = make_stream(p, prefix, i0, TP);
-    const int n_tiles = (st.n_total + kBN - 1) / kBN;
-    const FullBlocks fullb = full_blocks(st, pw, p.n);
-
-    // this wave's queries as B operands
-    bf16x8 qreg[KSTEPS];
-    {
-        const uint16_t *qrow = Q + (((long)b * p.Hq + head) * p.L + min(iq, p.L - 1)) * D;
-#pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks)
-            qreg[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(qrow + ks * 16 + 8 * hh));
-    }
+    // state of the current segment (the lambdas below refer to it)
+    int i0 = 0, pw = 0, iq = 0, n_tiles = 0;
+    Stream st = {};
+    FullBlocks fullb = {};
+    bf16x8 qreg[KSTEPS];  // this wave's queries as B operands
     const float sl2 = p.scale * kLog2e_f;
 #ifdef SEPATTN_X_TIMING
     unsigned long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tlast = clock64();
 #endif
 
     f32x16 oacc[DB];
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;  // m_run in the log2 domain (scores times scale*log2e)
-    float alpha_pending = 1.f;             // rescale of oacc decided in a VALU phase, applied in the next MFMA phase
+    float alpha_pending = 1.f;             // rescale of oacc decided by a softmax, applied before the next output update
 
     // ---- tile loads: wave w fills rows (LOADS*w + u)*RPL .. +RPL-1 of a tile with one wave-wide
     // direct global->LDS load per tensor; a lane owns physical chunk lane%CH of its row.  Everything
@@ -452,6 +443,29 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
         TICK(4)
     };
 
+    for (int round = 0;; ++round) {
+    const int rank = round * wpg + ((round & 1) ? wpg - 1 - tg.rank : tg.rank);
+    if (rank >= n_pos_tiles) break;
+    i0 = (n_pos_tiles - 1 - rank) * TP;
+    pw = i0 + 32 * (wave / GP);  // first position of this wave
+    iq = pw + qi;                // this lane's query position
+    st = make_stream(p, prefix, i0, TP);
+    n_tiles = (st.n_total + kBN - 1) / kBN;
+    fullb = full_blocks(st, pw, p.n);
+    {
+        const uint16_t *qrow = Q + (((long)b * p.Hq + head) * p.L + min(iq, p.L - 1)) * D;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks)
+            qreg[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(qrow + ks * 16 + 8 * hh));
+    }
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
+    m_run = -INFINITY;
+    l_run = 0.f;
+    alpha_pending = 1.f;
+
     // ---- prologue: index entries of tiles 0..2, then tiles 0 and 1 on their way into LDS
     issue_meta(0);
     issue_meta(1);
@@ -530,6 +544,10 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
             }
         if (hh == 0) LSE[orow] = (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2_f;
     }
+    // every wave has left the last tile step (and its loads have landed) before the next segment
+    // starts to refill the LDS stages
+    wg_barrier();
+    }  // segments
 }
 
 template <int D>
@@ -539,14 +557,21 @@ int launch_fwd(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
     int G = p.Hq / p.Hkv;
     int GP = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
     int TP = 32 * 8 / GP;
-    dim3 grid(((p.L + TP - 1) / TP) * p.B * p.Hkv * (G / GP)), block(512);
+    const int n_pos_tiles = (p.L + TP - 1) / TP;
+    const long n_groups = (long)p.B * p.Hkv * (G / GP);
+    // persistent workgroups: one per compute unit (the kernel's LDS footprint allows no more), spread
+    // evenly over the groups; never more than a group has tiles
+    int wpg = (int)(compute_units() / n_groups);
+    wpg = wpg < 1 ? 1 : (wpg > n_pos_tiles ? n_pos_tiles : wpg);
+    if (n_groups * wpg > 0x7FFFFFFFL) return SEPATTN_ERR_SHAPE;
+    dim3 grid((unsigned)(n_groups * wpg)), block(512);
     ProfScope prof(SEPATTN_K_FORWARD, st);
     if (GP == 4)
-        hipLaunchKernelGGL((fwd_bf16_kernel<D, 4>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, O, LSE);
+        hipLaunchKernelGGL((fwd_bf16_kernel<D, 4>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, O, LSE, wpg);
     else if (GP == 2)
-        hipLaunchKernelGGL((fwd_bf16_kernel<D, 2>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, O, LSE);
+        hipLaunchKernelGGL((fwd_bf16_kernel<D, 2>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, O, LSE, wpg);
     else
-        hipLaunchKernelGGL((fwd_bf16_kernel<D, 1>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, O, LSE);
+        hipLaunchKernelGGL((fwd_bf16_kernel<D, 1>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, O, LSE, wpg);
     return launch_status();
 }
 

@@ -128,35 +128,36 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
         vgo[u] = swz_chunk<kSwzTr, D>(my_pc, rrow[u]) * 16;
     }
     const char *Kb = reinterpret_cast<const char *>(Kh), *Vb = reinterpret_cast<const char *>(Vh);
-    auto tile_class = [&](int t) {
+    auto tile_class = [&](const Stream &ss, int t) {
         const int k0 = t * kBN;
-        return (k0 + kBN <= st.n_dense) ? 0 : (k0 >= st.n_dense ? 1 : 2);
+        return (k0 + kBN <= ss.n_dense) ? 0 : (k0 >= ss.n_dense ? 1 : 2);
     };
     // Index stage, one tile ahead of the rows: the list entry (dense part) and the two prefix counts
     // (band part) of each of the MR rows this wave fills, fetched by 3*MR lanes with one 4-byte
-    // global->LDS load into the wave's own slot of a small ring; the wave reads them back in its
-    // next VALU phase.  All vector-memory traffic of the loop is thus global->LDS, issued through
-    // inline assembly and waited for with explicit counts.
+    // global->LDS load into the wave's own slot of a small ring; the wave reads them back one tile
+    // step later.  All vector-memory traffic of the loop is thus global->LDS, issued through inline
+    // assembly and waited for with explicit counts.
+    // A tile is named by the stream of its segment (ss), its number in that stream (t) and its
+    // number in the concatenation of all segments of this workgroup (g), which selects the LDS stage.
     constexpr int MR = LOADS * RPL;  // rows per wave and tile
     constexpr int MST = 4;           // ring stages
     __shared__ __attribute__((aligned(128))) int meta_s[MST][NW][32];
     const int m_part = lane / MR, m_row = wave * MR + lane % MR;  // lanes 0 .. 3*MR-1 are used
-    auto issue_meta = [&](int t) __attribute__((always_inline)) {
+    auto issue_meta = [&](const Stream &ss, int t, int g) __attribute__((always_inline)) {
         const int k = t * kBN + m_row;
-        const int e = min(max(st.sep_lo - st.n_init + k, 0), p.cap - 1);
-        const int j = min(max(st.bs - st.n_dense + k, 0), p.L - 1);
+        const int e = min(max(ss.sep_lo - ss.n_init + k, 0), p.cap - 1);
+        const int j = min(max(ss.bs - ss.n_dense + k, 0), p.L - 1);
         const int32_t *src = m_part == 0 ? idx + e : prefix + j + (m_part - 1);
-        if (lane < 3 * MR) dma_to_lds_4_addr(src, lds_addr(&meta_s[t % MST][wave][0]));
+        if (lane < 3 * MR) dma_to_lds_4_addr(src, lds_addr(&meta_s[g % MST][wave][0]));
     };
-    // Rows of tile t in two steps, so that the index entries of the NEXT tile can be requested in
+    // Rows of a tile in two steps, so that the index entries of the NEXT tile can be requested in
     // between: vector-memory results return in issue order, and with the order
-    //   [entries of t+1] [rows of t]   the wait for the entries does not wait for the rows.
-    // Tiles past the end of the stream are "loaded" too (row 0, never visible): a loop body without
-    // alternatives keeps the count of outstanding loads exact, and the LDS stage such a tile lands in
-    // is free by the same argument as for a real tile.
+    //   [entries of the next tile] [rows of this tile]   the wait for the entries does not wait for
+    // the rows.  Past the last segment the stream is empty: its tiles are "loaded" too (row 0, never
+    // visible), which keeps the count of outstanding loads exact in a loop body without alternatives.
     int jrow[LOADS], rawi[LOADS], raw0[LOADS], raw1[LOADS];
-    auto read_entries = [&](int t) __attribute__((always_inline)) {
-        const int *mt = &meta_s[t % MST][wave][0];
+    auto read_entries = [&](int g) __attribute__((always_inline)) {
+        const int *mt = &meta_s[g % MST][wave][0];
         static_for<LOADS>([&](auto U) {
             constexpr int u = U;
             rawi[u] = mt[u * RPL + my_sub];
@@ -164,18 +165,18 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
             raw1[u] = mt[2 * MR + u * RPL + my_sub];
         });
     };
-    auto prepare_row = [&](int t, auto U) __attribute__((always_inline)) {
+    auto prepare_row = [&](const Stream &ss, int t, int g, auto U) __attribute__((always_inline)) {
         constexpr int u = decltype(U)::value;
-        const int vs_ = t % VST;
+        const int vs_ = g % VST;
         const int r = rrow[u];
         const int k = t * kBN + r;
         // the clamp keeps a stale list tail (caller broke sep_count <= cap) from faulting
         const int jl = min(max(rawi[u], 0), p.L - 1);
-        if (tile_class(t) == 0) {
-            jrow[u] = k < st.n_init ? k : jl;
+        if (tile_class(ss, t) == 0) {
+            jrow[u] = k < ss.n_init ? k : jl;
         } else {
-            const bool init = k < st.n_init, dense = k < st.n_dense, pad = k >= st.n_total;
-            const int jb = st.bs + (k - st.n_dense);
+            const bool init = k < ss.n_init, dense = k < ss.n_dense, pad = k >= ss.n_total;
+            const int jb = ss.bs + (k - ss.n_dense);
             const bool always = dense | (jb < p.a) | (raw1[u] != raw0[u]);
             int j = init ? k : (dense ? jl : jb);
             j = pad ? 0 : j;
@@ -189,19 +190,54 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
             jrow[u] = j;
         }
     };
-    auto issue_row = [&](int t, auto U) __attribute__((always_inline)) {
+    auto issue_row = [&](int g, auto U) __attribute__((always_inline)) {
         constexpr int u = decltype(U)::value;
-        const uint32_t kst = lds_addr(&Ks[t % KST][0]), vst = lds_addr(&Vs[t % VST][0]);
+        const uint32_t kst = lds_addr(&Ks[g % KST][0]), vst = lds_addr(&Vs[g % VST][0]);
         const uint32_t wave_off = (uint32_t)((LOADS * wave + u) * RPL * D * 2);  // bytes: 1 KB per wave-wide load
         const uint32_t row_off = (uint32_t)jrow[u] * (uint32_t)(D * 2);
         dma_to_lds_16(Kb, row_off + kgo[u], kst + wave_off);
         dma_to_lds_16(Vb, row_off + vgo[u], vst + wave_off);
     };
-    auto prepare_rows = [&](int t) __attribute__((always_inline)) {
-        static_for<LOADS>([&](auto U) { prepare_row(t, U); });
+
+    // ---- segments of this workgroup and the load cursor.  The tiles of all segments form ONE stream
+    // of loads: the cursor (segment lcur, tile l_t, global number l_g) always points at the next tile
+    // whose rows are to be requested, two tiles ahead of the tile being multiplied, also across
+    // segment borders, so that only the first segment of a workgroup pays the start-up latencies.
+    struct Seg {
+        Stream st;
+        int n_tiles, i0;
     };
-    auto issue_rows = [&](int t) __attribute__((always_inline)) {
-        static_for<LOADS>([&](auto U) { issue_row(t, U); });
+    auto open_segment = [&](int round) {
+        Seg g;
+        const int rank = round * wpg + ((round & 1) ? wpg - 1 - tg.rank : tg.rank);
+        if (rank >= n_pos_tiles) {  // no more work: an empty stream of padding tiles
+            g.st = Stream{0, 0, 0, 0, 0};
+            g.n_tiles = kIntMax;
+            g.i0 = -1;
+        } else {
+            g.i0 = (n_pos_tiles - 1 - rank) * TP;
+            g.st = make_stream(p, prefix, g.i0, TP);
+            g.n_tiles = (g.st.n_total + kBN - 1) / kBN;
+        }
+        return g;
+    };
+    Seg lcur = open_segment(0), lnext = open_segment(1);
+    int l_round = 0, l_t = 0, l_g = 0;
+    auto advance_cursor = [&]() __attribute__((always_inline)) {
+        ++l_g;
+        if (++l_t == lcur.n_tiles) {
+            lcur = lnext;
+            ++l_round;
+            l_t = 0;
+            lnext = open_segment(l_round + 1);
+        }
+    };
+    // index entries of the tile after the cursor
+    auto issue_meta_after_cursor = [&]() __attribute__((always_inline)) {
+        if (l_t + 1 < lcur.n_tiles)
+            issue_meta(lcur.st, l_t + 1, l_g + 1);
+        else
+            issue_meta(lnext.st, 0, l_g + 1);
     };
     // An MFMA phase issues [1 entry load][2*LOADS row loads], in this order; loads complete in order.
     //   entries_landed:    at most the row loads of the previous phase are still in flight
@@ -262,7 +298,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
         float m_loc, neg_m, psum;
         bool masked;
     } sm;
-    auto softmax_chunk = [&](auto C, f32x16 &s, bf16x8 (&pb)[2], int tile, int kb) __attribute__((always_inline)) {
+    auto softmax_chunk = [&](auto C, f32x16 &s, bf16x8 (&pb)[2], int tile, int gtile, int kb) __attribute__((always_inline)) {
         constexpr int c = decltype(C)::value;
 #ifdef SEPATTN_X_NOSM
         if constexpr (c == 13) pb[0] = qreg[0];
@@ -275,7 +311,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
             sm.masked = false;
 #endif
             if (sm.masked) {
-                const int vs_ = tile % VST;
+                const int vs_ = gtile % VST;
 #pragma unroll
                 for (int half = 0; half < 2; ++half) {
                     const int base = kb * 32 + 16 * half + 8 * hh;
@@ -330,43 +366,34 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
             l_run += sm.psum;
         }
     };
-    // one piece of the load path of tile T (rows) and T+1 (index entries)
-    auto load_chunk = [&](auto C, int T) __attribute__((always_inline)) {
+    // one piece of the load path: rows of the tile at the cursor, index entries of the tile after it
+    auto load_chunk = [&](auto C) __attribute__((always_inline)) {
         constexpr int c = decltype(C)::value;
 #ifdef SEPATTN_X_NOLD
         return;
 #endif
         if constexpr (c == 0) {
-#ifndef SEPATTN_X_NOLD_ENT
             entries_landed();
-            read_entries(T);
-#endif
+            read_entries(l_g);
         } else if constexpr (c == 2) {
-#ifndef SEPATTN_X_NOLD_PREP
-            prepare_row(T, IntC<0>{});
-#endif
+            prepare_row(lcur.st, l_t, l_g, IntC<0>{});
         } else if constexpr (c == 4 && LOADS == 2) {
-#ifndef SEPATTN_X_NOLD_PREP
-            prepare_row(T, IntC<LOADS - 1>{});
-#endif
+            prepare_row(lcur.st, l_t, l_g, IntC<LOADS - 1>{});
         } else if constexpr (c == 6) {
-#ifndef SEPATTN_X_NOLD_META
-            issue_meta(T + 1);
-#endif
+            issue_meta_after_cursor();
         } else if constexpr (c == 8) {
-#ifndef SEPATTN_X_NOLD_ROWS
-            issue_row(T, IntC<0>{});
-#endif
+            issue_row(l_g, IntC<0>{});
         } else if constexpr (c == 10 && LOADS == 2) {
-#ifndef SEPATTN_X_NOLD_ROWS
-            issue_row(T, IntC<LOADS - 1>{});
-#endif
+            issue_row(l_g, IntC<LOADS - 1>{});
+        } else if constexpr (c == 12) {
+            advance_cursor();
         }
     };
 
     // one half of a tile step.  HB: which block of the tile (0 or 1).  DO_QK: S(2X+HB) of tile X into
     // s_new; DO_PV: O^T += V_{X-1}[32 HB ..]^T p_old^T; DO_SM: softmax of the block whose scores are
     // s_old (tile sm_tile, block sm_kb) into p_new; DO_LD: the load path of tile X+2 rides along.
+    int gbase = 0;  // global number of tile 0 of the segment being multiplied
     auto half_step = [&](int X, auto HB_, auto DO_QK_, auto DO_PV_, auto DO_SM_, auto DO_LD_, f32x16 &s_new,
                          const bf16x8 (&p_old)[2], f32x16 &s_old, bf16x8 (&p_new)[2], int sm_tile,
                          int sm_kb) __attribute__((always_inline)) {
@@ -382,8 +409,8 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
                 for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha_pending;
             alpha_pending = 1.f;
         }
-        const uint32_t vst = vs_base + ((X + VST - 1) % VST) * (TILE * 2) + HB * 32 * D * 2;
-        const uint32_t kst = ks_base + (X % KST) * (TILE * 2) + HB * 32 * D * 2;
+        const uint32_t vst = vs_base + ((gbase + X + VST - 1) % VST) * (TILE * 2) + HB * 32 * D * 2;
+        const uint32_t kst = ks_base + ((gbase + X) % KST) * (TILE * 2) + HB * 32 * D * 2;
         uint32_t va_[DB], ka_[KSTEPS];
 #pragma unroll
         for (int db = 0; db < DB; ++db) va_[db] = vst + voff[db];
@@ -426,8 +453,8 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
             static_for<CPS>([&](auto J) {
                 constexpr int c = s_ * CPS + decltype(J)::value;
                 if constexpr (c < 16) {
-                    if constexpr (DO_SM) softmax_chunk(IntC<c>{}, s_old, p_new, sm_tile, sm_kb);
-                    if constexpr (DO_LD) load_chunk(IntC<c>{}, X + 2);
+                    if constexpr (DO_SM) softmax_chunk(IntC<c>{}, s_old, p_new, sm_tile, gbase + sm_tile, sm_kb);
+                    if constexpr (DO_LD) load_chunk(IntC<c>{});
                 }
             });
             __builtin_amdgcn_sched_barrier(0);
@@ -443,21 +470,41 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
         TICK(4)
     };
 
-    for (int round = 0;; ++round) {
-    const int rank = round * wpg + ((round & 1) ? wpg - 1 - tg.rank : tg.rank);
-    if (rank >= n_pos_tiles) break;
-    i0 = (n_pos_tiles - 1 - rank) * TP;
-    pw = i0 + 32 * (wave / GP);  // first position of this wave
-    iq = pw + qi;                // this lane's query position
-    st = make_stream(p, prefix, i0, TP);
-    n_tiles = (st.n_total + kBN - 1) / kBN;
-    fullb = full_blocks(st, pw, p.n);
-    {
-        const uint16_t *qrow = Q + (((long)b * p.Hq + head) * p.L + min(iq, p.L - 1)) * D;
+    // ---- start-up, once per workgroup: the first two tiles of the concatenated stream on their way
+    // into LDS, the index entries of the third requested (three dependent round trips)
+    issue_meta(lcur.st, 0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int rep = 0; rep < 2; ++rep) {
+        read_entries(l_g);
+        static_for<LOADS>([&](auto U) { prepare_row(lcur.st, l_t, l_g, U); });
+        issue_meta_after_cursor();
+        static_for<LOADS>([&](auto U) { issue_row(l_g, U); });
+        advance_cursor();
+        entries_landed();  // the entries just requested (the rows after them may be in flight)
+    }
+    wg_barrier();  // tile 0 is in LDS (its rows were the first loads)
+
+    const IntC<1> yes;
+    const IntC<0> no;
+    const IntC<0> first_block;
+    const IntC<1> second_block;
+    Seg cseg = open_segment(0), cnext = open_segment(1);
+    auto load_queries = [&](int seg_i0) __attribute__((always_inline)) {
+        const int row = min(seg_i0 + 32 * (wave / GP) + qi, p.L - 1);
+        const uint16_t *qrow = Q + (((long)b * p.Hq + head) * p.L + row) * D;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks)
             qreg[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(qrow + ks * 16 + 8 * hh));
-    }
+    };
+    load_queries(cseg.i0);
+    for (int round = 0; cseg.i0 >= 0; ++round) {
+    i0 = cseg.i0;
+    pw = i0 + 32 * (wave / GP);  // first position of this wave
+    iq = pw + qi;                // this lane's query position
+    st = cseg.st;
+    n_tiles = cseg.n_tiles;
+    fullb = full_blocks(st, pw, p.n);
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -466,51 +513,25 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     l_run = 0.f;
     alpha_pending = 1.f;
 
-    // ---- prologue: index entries of tiles 0..2, then tiles 0 and 1 on their way into LDS
-    issue_meta(0);
-    issue_meta(1);
-    issue_meta(2);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    read_entries(0);
-    prepare_rows(0);
-    issue_rows(0);
-    read_entries(1);
-    prepare_rows(1);
-    issue_rows(1);
-    // tile 0 has landed when at most the row loads of tile 1 are in flight
-    entries_landed();
-    wg_barrier();
-
-#ifdef SEPATTN_X_TIMING
-    tlast = clock64();
-    const unsigned long long w_loop0 = wall_clock64();
-#endif
-    const IntC<1> yes;
-    const IntC<0> no;
-    const IntC<0> first_block;
-    const IntC<1> second_block;
-    // step 0: no output update yet, no softmax in the first half
+    // step 0: no output update yet, no softmax in the first half.  Tile 0 of the segment has been
+    // published already: by the start-up barrier, or by the barrier of the previous segment's last
+    // step (its rows were requested two load steps earlier, and each wave waits for everything but
+    // its newest load step before a barrier).
     half_step(0, first_block, yes, no, no, yes, s_a, p_a, s_b, p_b, 0, 0);
     half_step(0, second_block, yes, no, yes, no, s_b, p_b, s_a, p_a, 0, 0);
     for (int X = 1; X < n_tiles; ++X) {
         publish();
-#ifdef SEPATTN_X_PRIO
-        if ((X ^ (wave >> 2)) & 1) __builtin_amdgcn_s_setprio(SEPATTN_X_PRIO); else __builtin_amdgcn_s_setprio(0);
-#endif
-#ifdef SEPATTN_X_PRIO_FIXED
-        if (wave >> 2) __builtin_amdgcn_s_setprio(SEPATTN_X_PRIO_FIXED);
-#endif
         half_step(X, first_block, yes, yes, yes, yes, s_a, p_a, s_b, p_b, X - 1, 1);
         TICK(1)
         half_step(X, second_block, yes, yes, yes, no, s_b, p_b, s_a, p_a, X, 0);
     }
-    // last step: output updates of the last tile, softmax of its second block
+    // last step: output updates of the last tile, softmax of its second block; the queries of the
+    // next segment are fetched meanwhile (the registers are free: no score block in this step)
     publish();
+    if (cnext.i0 >= 0) load_queries(cnext.i0);
     half_step(n_tiles, first_block, no, yes, yes, no, s_a, p_a, s_b, p_b, n_tiles - 1, 1);
     half_step(n_tiles, second_block, no, yes, no, no, s_b, p_b, s_a, p_a, n_tiles, 0);
-    // the loads of the tiles past the end are still in flight: they must have landed before the
-    // workgroup ends and its LDS is handed to the next one
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    gbase += n_tiles;
 #ifdef SEPATTN_X_TIMING
     const unsigned long long w_loop1 = wall_clock64();
     if (lane == 0 && blockIdx.x < 2048) {
@@ -544,10 +565,12 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
             }
         if (hh == 0) LSE[orow] = (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2_f;
     }
-    // every wave has left the last tile step (and its loads have landed) before the next segment
-    // starts to refill the LDS stages
-    wg_barrier();
+    cseg = cnext;
+    cnext = open_segment(round + 2);
     }  // segments
+    // the loads of the padding tiles past the last segment are still in flight: they must have
+    // landed before the workgroup ends and its LDS is handed on
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
 template <int D>

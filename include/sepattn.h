@@ -89,7 +89,7 @@ typedef struct {
     int B;       /* sequences                                                                  */
     int Hq;      /* query heads                                                                */
     int Hkv;     /* key/value heads; Hq % Hkv == 0; query head h reads KV head h / (Hq/Hkv)     */
-    int L;       /* sequence length (the paper's m)                                            */
+    int L;       /* sequence length (the paper's m); L * d * 4 < 2^32, else SEPATTN_ERR_SHAPE   */
     int d;       /* head dimension d_k = d_v: 64 or 128                                        */
     int a;       /* number of initial tokens kept, a >= 0                                      */
     int n;       /* number of neighbouring tokens kept, the token itself included, n >= 1      */

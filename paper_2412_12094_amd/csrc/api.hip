@@ -46,6 +46,8 @@ int check_attn(const sepattn_params *p) {
     // index arithmetic inside the kernels uses 32-bit positions and 64-bit offsets
     if ((long)p->B * p->Hq * p->L > (1L << 40)) return SEPATTN_ERR_SHAPE;
     if ((long)p->B * p->Hq > 65535L) return SEPATTN_ERR_SHAPE;  // second grid dimension
+    // rows inside one head are addressed as (uniform base of the head) + 32-bit byte offset
+    if ((long)p->L * p->d * 4 > 0xFFFFFFFFL) return SEPATTN_ERR_SHAPE;
     return SEPATTN_OK;
 }
 

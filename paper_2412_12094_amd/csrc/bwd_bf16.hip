@@ -5,7 +5,7 @@
 //   dV_j = sum_i P_ij dO_i   (dK, dV summed over the query heads of the KV head).
 //
 // Three launches, no floating-point atomics (results are bit-reproducible):
-//  1. dq_kernel (this file): one workgroup per query tile, same dense key stream as the forward
+//  1. dq_kernel (this file): persistent workgroups over the query tiles, same dense key stream as the forward
 //     [initial | separators older than the window | band].  Also writes D_i and LSE_i*log2(e).
 //  2. dkv_kernel (bwd_dkv_bf16.hip): the visible pairs split into band pairs (i-j < n) and far
 //     pairs (i-j >= n, j an initial token or a separator); far units work on the COMPACTED list of
@@ -53,7 +53,7 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
     const uint16_t *__restrict__ V, const uint16_t *__restrict__ O, const float *__restrict__ LSE,
     const uint16_t *__restrict__ dO, const int32_t *__restrict__ sep_idx,
     const int32_t *__restrict__ sep_prefix, uint16_t *__restrict__ dQ, float *__restrict__ Dws,
-    float *__restrict__ Lws) {
+    float *__restrict__ Lws, int wpg) {
     constexpr int NW = 8;
     constexpr int TP = 32 * NW / GP;
     constexpr int CH = D / 8;
@@ -76,53 +76,30 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int qi = lane & 31, hh = lane >> 5;
+    // Persistent workgroups as in the forward kernel: a workgroup belongs to one (batch, KV head, head
+    // group) and walks through several query tiles of it ("segments") in zig-zag order, `wpg`
+    // workgroups per group; rank 0 is the last tile, the one with the longest key stream.
     const int G = p.Hq / p.Hkv, groups = G / GP;
     const int n_pos_tiles = (p.L + TP - 1) / TP;
-    const TileGroup tg = xcd_tile_group(blockIdx.x, n_pos_tiles, p.B * p.Hkv * groups);
-    const int tile = n_pos_tiles - 1 - tg.rank;  // late tiles carry more separators: start them first
-    const int i0 = tile * TP;
+    const TileGroup tg = xcd_tile_group(blockIdx.x, wpg, p.B * p.Hkv * groups);
     int y = tg.group;
     const int hg = y % groups;
     const int kv = (y / groups) % p.Hkv;
     const int b = y / (groups * p.Hkv);
     const int head = kv * G + hg * GP + (wave % GP);
-    const int pw = i0 + 32 * (wave / GP);
-    const int iq = pw + qi;
 
     const int32_t *prefix = sep_prefix + (long)b * (p.L + 1);
     const int32_t *idx = sep_idx + (long)b * p.cap;
     const uint16_t *Kh = K + ((long)b * p.Hkv + kv) * (long)p.L * D;
     const uint16_t *Vh = V + ((long)b * p.Hkv + kv) * (long)p.L * D;
-    const Stream st = make_stream(p, prefix, i0, TP);
-    const int n_tiles = (st.n_total + kBN - 1) / kBN;
-    const FullBlocks fullb = full_blocks(st, pw, p.n);
 
-    const long qrow_id = ((long)b * p.Hq + head) * p.L + min(iq, p.L - 1);
+    // state of the segment being multiplied (the lambdas below refer to it)
+    int iq = 0;
+    FullBlocks fullb = {};
     bf16x8 qreg[KSTEPS], doreg[KSTEPS];
-    float Di;
-    {
-        const uint16_t *qrow = Q + qrow_id * D, *dorow = dO + qrow_id * D, *orow = O + qrow_id * D;
-        float part = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) {
-            u32x4 dq4 = *reinterpret_cast<const u32x4 *>(dorow + ks * 16 + 8 * hh);
-            u32x4 o4 = *reinterpret_cast<const u32x4 *>(orow + ks * 16 + 8 * hh);
-            qreg[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(qrow + ks * 16 + 8 * hh));
-            doreg[ks] = as_bf16x8(dq4);
-            part += bf16_dot8(dq4, o4);
-        }
-        Di = pair_sum(part);
-        if (hh == 0 && iq < p.L) Dws[qrow_id] = Di;
-    }
+    float Di = 0.f, lse2 = 0.f;
     const float sl2 = p.scale * kLog2e_f;
-    const float lse2 = LSE[qrow_id] * kLog2e_f;
-    if (hh == 0 && iq < p.L) Lws[qrow_id] = lse2;  // the dK/dV kernels work in the log2 domain too
-
     f32x16 acc[DB];
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[db][i] = 0.f;
 
     // ---- tile loads (see the forward kernel: same scheme, other LDS layouts)
     const int my_pc = lane % CH, my_sub = lane / CH;
@@ -134,21 +111,23 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
         kgo[u] = swz_chunk<kSwzBoth, D>(my_pc, rrow[u]) * 16;
     }
     const char *Kb = reinterpret_cast<const char *>(Kh), *Vb = reinterpret_cast<const char *>(Vh);
-    auto tile_class = [&](int t) {
+    auto tile_class = [&](const Stream &ss, int t) {
         const int k0 = t * kBN;
-        return (k0 + kBN <= st.n_dense) ? 0 : (k0 >= st.n_dense ? 1 : 2);
+        return (k0 + kBN <= ss.n_dense) ? 0 : (k0 >= ss.n_dense ? 1 : 2);
     };
+    // A tile is named by the stream of its segment (ss), its number in that stream (t) and its
+    // number in the concatenation of all segments of this workgroup (g), which selects the LDS stage.
     const int m_part = lane / MR, m_row = wave * MR + lane % MR;  // lanes 0 .. 3*MR-1 are used
-    auto issue_meta = [&](int t) __attribute__((always_inline)) {
+    auto issue_meta = [&](const Stream &ss, int t, int g) __attribute__((always_inline)) {
         const int k = t * kBN + m_row;
-        const int e = min(max(st.sep_lo - st.n_init + k, 0), p.cap - 1);
-        const int j = min(max(st.bs - st.n_dense + k, 0), p.L - 1);
+        const int e = min(max(ss.sep_lo - ss.n_init + k, 0), p.cap - 1);
+        const int j = min(max(ss.bs - ss.n_dense + k, 0), p.L - 1);
         const int32_t *src = m_part == 0 ? idx + e : prefix + j + (m_part - 1);
-        if (lane < 3 * MR) dma_to_lds_4_addr(src, lds_addr(&meta_s[t % MST][wave][0]));
+        if (lane < 3 * MR) dma_to_lds_4_addr(src, lds_addr(&meta_s[g % MST][wave][0]));
     };
     int jrow[LOADS], rawi[LOADS], raw0[LOADS], raw1[LOADS];
-    auto read_entries = [&](int t) __attribute__((always_inline)) {
-        const int *mt = &meta_s[t % MST][wave][0];
+    auto read_entries = [&](int g) __attribute__((always_inline)) {
+        const int *mt = &meta_s[g % MST][wave][0];
         static_for<LOADS>([&](auto U) {
             constexpr int u = U;
             rawi[u] = mt[u * RPL + my_sub];
@@ -156,18 +135,18 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
             raw1[u] = mt[2 * MR + u * RPL + my_sub];
         });
     };
-    auto prepare_row = [&](int t, auto U) __attribute__((always_inline)) {
+    auto prepare_row = [&](const Stream &ss, int t, int g, auto U) __attribute__((always_inline)) {
         constexpr int u = decltype(U)::value;
-        const int ms_ = t % MKS;
+        const int ms_ = g % MKS;
         const int r = rrow[u];
         const int k = t * kBN + r;
         // the clamp keeps a stale list tail (caller broke sep_count <= cap) from faulting
         const int jl = min(max(rawi[u], 0), p.L - 1);
-        if (tile_class(t) == 0) {
-            jrow[u] = k < st.n_init ? k : jl;
+        if (tile_class(ss, t) == 0) {
+            jrow[u] = k < ss.n_init ? k : jl;
         } else {
-            const bool init = k < st.n_init, dense = k < st.n_dense, pad = k >= st.n_total;
-            const int jb = st.bs + (k - st.n_dense);
+            const bool init = k < ss.n_init, dense = k < ss.n_dense, pad = k >= ss.n_total;
+            const int jb = ss.bs + (k - ss.n_dense);
             const bool always = dense | (jb < p.a) | (raw1[u] != raw0[u]);
             int j = init ? k : (dense ? jl : jb);
             j = pad ? 0 : j;
@@ -181,13 +160,54 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
             jrow[u] = j;
         }
     };
-    auto issue_row = [&](int t, auto U) __attribute__((always_inline)) {
+    auto issue_row = [&](int g, auto U) __attribute__((always_inline)) {
         constexpr int u = decltype(U)::value;
-        const uint32_t kst = lds_addr(&Ks[t % KST][0]), vst = lds_addr(&Vs[t % VST][0]);
+        const uint32_t kst = lds_addr(&Ks[g % KST][0]), vst = lds_addr(&Vs[g % VST][0]);
         const uint32_t wave_off = (uint32_t)((LOADS * wave + u) * RPL * D * 2);
         const uint32_t row_off = (uint32_t)jrow[u] * (uint32_t)(D * 2);
         dma_to_lds_16(Kb, row_off + kgo[u], kst + wave_off);
         dma_to_lds_16(Vb, row_off + kgo[u], vst + wave_off);
+    };
+
+    // ---- segments of this workgroup and the load cursor: the tiles of all segments form one stream
+    // of loads; the cursor (segment lcur, tile l_t, global number l_g) points at the next tile whose
+    // rows are to be requested, two tiles ahead of the tile being multiplied, also across segment
+    // borders.  Past the last segment the stream is empty: its tiles are "loaded" too (row 0, never
+    // visible), which keeps the count of outstanding loads exact.
+    struct Seg {
+        Stream st;
+        int n_tiles, i0;
+    };
+    auto open_segment = [&](int round) {
+        Seg g;
+        const int rank = round * wpg + ((round & 1) ? wpg - 1 - tg.rank : tg.rank);
+        if (rank >= n_pos_tiles) {
+            g.st = Stream{0, 0, 0, 0, 0};
+            g.n_tiles = kIntMax;
+            g.i0 = -1;
+        } else {
+            g.i0 = (n_pos_tiles - 1 - rank) * TP;
+            g.st = make_stream(p, prefix, g.i0, TP);
+            g.n_tiles = (g.st.n_total + kBN - 1) / kBN;
+        }
+        return g;
+    };
+    Seg lcur = open_segment(0), lnext = open_segment(1);
+    int l_round = 0, l_t = 0, l_g = 0;
+    auto advance_cursor = [&]() __attribute__((always_inline)) {
+        ++l_g;
+        if (++l_t == lcur.n_tiles) {
+            lcur = lnext;
+            ++l_round;
+            l_t = 0;
+            lnext = open_segment(l_round + 1);
+        }
+    };
+    auto issue_meta_after_cursor = [&]() __attribute__((always_inline)) {
+        if (l_t + 1 < lcur.n_tiles)
+            issue_meta(lcur.st, l_t + 1, l_g + 1);
+        else
+            issue_meta(lnext.st, 0, l_g + 1);
     };
     // a tile step issues [1 entry load][2*LOADS row loads], in this order; loads complete in order
     auto entries_landed = [&]() __attribute__((always_inline)) {
@@ -231,14 +251,15 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
             return first - ktr0[db] + ktr1[db];
     };
 
-    // ---- one block of 32 keys: tile X, block HB
+    // ---- one block of 32 keys: tile X of the current segment (global number gbase + X), block HB
+    int gbase = 0;
     constexpr int LA = 4;
     constexpr int NS1 = 2 * KSTEPS, NS2 = 2 * DB;  // matrix instructions: scores, then the dQ update
     auto block_step = [&](int X, auto HB_, auto LD_) __attribute__((always_inline)) {
         constexpr int HB = decltype(HB_)::value;
         constexpr bool DO_LD = decltype(LD_)::value != 0;
-        const uint32_t kst = ks_base + (X % KST) * (TILE * 2) + HB * 32 * D * 2;
-        const uint32_t vst = vs_base + (X % VST) * (TILE * 2) + HB * 32 * D * 2;
+        const uint32_t kst = ks_base + ((gbase + X) % KST) * (TILE * 2) + HB * 32 * D * 2;
+        const uint32_t vst = vs_base + ((gbase + X) % VST) * (TILE * 2) + HB * 32 * D * 2;
         f32x16 sacc, pacc;
         bf16x8 frag[LA];
         auto request1 = [&](auto S) __attribute__((always_inline)) {
@@ -258,21 +279,24 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
             else
                 pacc = mfma_bf16(frag[s % LA], doreg[ks], ks == 0 ? zero : pacc);
             request1(IntC<s + LA>{});
-            // the load path of tile X+2 rides along with the first block of the tile
+            // the load path of the tile at the cursor (two tiles ahead) rides along with the first
+            // block of the tile
             if constexpr (DO_LD) {
                 if constexpr (s == 0) {
                     entries_landed();
-                    read_entries(X + 2);
+                    read_entries(l_g);
                 } else if constexpr (s == NS1 / 4) {
-                    prepare_row(X + 2, IntC<0>{});
+                    prepare_row(lcur.st, l_t, l_g, IntC<0>{});
                 } else if constexpr (s == NS1 / 4 + 1 && LOADS == 2) {
-                    prepare_row(X + 2, IntC<LOADS - 1>{});
+                    prepare_row(lcur.st, l_t, l_g, IntC<LOADS - 1>{});
                 } else if constexpr (s == NS1 / 2) {
-                    issue_meta(X + 3);
+                    issue_meta_after_cursor();
                 } else if constexpr (s == NS1 / 2 + NS1 / 8) {
-                    issue_row(X + 2, IntC<0>{});
+                    issue_row(l_g, IntC<0>{});
                 } else if constexpr (s == NS1 / 2 + NS1 / 4 && LOADS == 2) {
-                    issue_row(X + 2, IntC<LOADS - 1>{});
+                    issue_row(l_g, IntC<LOADS - 1>{});
+                } else if constexpr (s == NS1 - 1) {
+                    advance_cursor();
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -284,7 +308,7 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
         for (int db = 0; db < DB; ++db) tfr[db] = lds_read_tr_at2(kst + ktr0[db], tr_second(kst + ktr0[db], db));
         // dS = P (dP - D), zero where masked
         if (!block_is_full(fullb, X * kBN + HB * 32)) {
-            const int ms_ = X % MKS;
+            const int ms_ = (gbase + X) % MKS;
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
                 const int base = HB * 32 + 16 * half + 8 * hh;
@@ -318,46 +342,87 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
         for (int db = 0; db < DB; ++db) acc[db] = mfma_bf16(tfr2[db], dsb1, acc[db]);
     };
 
-    // ---- prologue: index entries of tiles 0..2, then tiles 0 and 1 on their way into LDS
-    issue_meta(0);
-    issue_meta(1);
-    issue_meta(2);
+    // ---- start-up, once per workgroup: the first two tiles of the concatenated stream on their way
+    // into LDS, the index entries of the third requested
+    issue_meta(lcur.st, 0, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    read_entries(0);
-    static_for<LOADS>([&](auto U) { prepare_row(0, U); });
-    static_for<LOADS>([&](auto U) { issue_row(0, U); });
-    read_entries(1);
-    static_for<LOADS>([&](auto U) { prepare_row(1, U); });
-    static_for<LOADS>([&](auto U) { issue_row(1, U); });
-    entries_landed();  // tile 0 has landed when at most the row loads of tile 1 are in flight
-    wg_barrier();
+#pragma unroll
+    for (int rep = 0; rep < 2; ++rep) {
+        read_entries(l_g);
+        static_for<LOADS>([&](auto U) { prepare_row(lcur.st, l_t, l_g, U); });
+        issue_meta_after_cursor();
+        static_for<LOADS>([&](auto U) { issue_row(l_g, U); });
+        advance_cursor();
+        entries_landed();  // the entries just requested (the rows after them may be in flight)
+    }
 
-    // Tile step X reads K_X (row-major and transposed) and V_X and requests tile X+2, whose stages
-    // held tile X-1: last read in step X-1, which every wave has left when it passes the barrier.
     const IntC<1> yes;
     const IntC<0> no;
-    for (int X = 0; X < n_tiles; ++X) {
-        if (X > 0) {
-            wait_older_loads();  // this wave's loads of tile X: everything older than step X-1's requests
-            wg_barrier();
+    Seg cseg = open_segment(0);
+    for (int round = 0; cseg.i0 >= 0; ++round) {
+        const int pw = cseg.i0 + 32 * (wave / GP);
+        iq = pw + qi;
+        fullb = full_blocks(cseg.st, pw, p.n);
+        // rows of this wave's head: (uniform base) + 32-bit byte offset of the lane's piece
+        const long head_row0 = ((long)b * p.Hq + head) * p.L;
+        {
+            const uint32_t voff = (uint32_t)min(iq, p.L - 1) * (uint32_t)(D * 2) + 16u * hh;
+            const char *qb = reinterpret_cast<const char *>(Q + head_row0 * D);
+            const char *dob = reinterpret_cast<const char *>(dO + head_row0 * D);
+            const char *ob = reinterpret_cast<const char *>(O + head_row0 * D);
+            float part = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) {
+                u32x4 dq4 = *reinterpret_cast<const u32x4 *>(dob + (voff + 32u * ks));
+                u32x4 o4 = *reinterpret_cast<const u32x4 *>(ob + (voff + 32u * ks));
+                qreg[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(qb + (voff + 32u * ks)));
+                doreg[ks] = as_bf16x8(dq4);
+                part += bf16_dot8(dq4, o4);
+            }
+            Di = pair_sum(part);
+            const uint32_t soff = (uint32_t)min(iq, p.L - 1) * 4u;
+            lse2 = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(LSE + head_row0) + soff) * kLog2e_f;
+            if (hh == 0 && iq < p.L) {
+                *reinterpret_cast<float *>(reinterpret_cast<char *>(Dws + head_row0) + soff) = Di;
+                // the dK/dV kernels work in the log2 domain too
+                *reinterpret_cast<float *>(reinterpret_cast<char *>(Lws + head_row0) + soff) = lse2;
+            }
         }
-        block_step(X, IntC<0>{}, yes);
-        block_step(X, IntC<1>{}, no);
-    }
-    // the loads of the tiles past the end must have landed before the LDS is handed on
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-
-    if (iq < p.L) {
-        uint16_t *dst = dQ + qrow_id * D;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                uint2 v = pack_bf16x4(acc[db][4 * i4] * p.scale, acc[db][4 * i4 + 1] * p.scale,
-                                      acc[db][4 * i4 + 2] * p.scale, acc[db][4 * i4 + 3] * p.scale);
-                *reinterpret_cast<uint2 *>(dst + db * 32 + 8 * i4 + 4 * hh) = v;
-            }
+            for (int i = 0; i < 16; ++i) acc[db][i] = 0.f;
+
+        // Tile step X reads K and V of tile gbase+X (row-major and transposed) and requests the tile
+        // two further on, whose stages held tile gbase+X-1: last read in the previous step, which
+        // every wave has left when it passes the barrier.  The barrier publishes tile gbase+X: each
+        // wave has waited for everything older than the previous step's requests.
+        const int n_tiles = cseg.n_tiles;
+        for (int X = 0; X < n_tiles; ++X) {
+            wait_older_loads();
+            wg_barrier();
+            block_step(X, IntC<0>{}, yes);
+            block_step(X, IntC<1>{}, no);
+        }
+        gbase += n_tiles;
+
+        if (iq < p.L) {
+            char *dqb = reinterpret_cast<char *>(dQ + head_row0 * D);
+            const uint32_t voff = (uint32_t)iq * (uint32_t)(D * 2) + 8u * hh;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    uint2 v = pack_bf16x4(acc[db][4 * i4] * p.scale, acc[db][4 * i4 + 1] * p.scale,
+                                          acc[db][4 * i4 + 2] * p.scale, acc[db][4 * i4 + 3] * p.scale);
+                    *reinterpret_cast<uint2 *>(dqb + (voff + 64u * db + 16u * i4)) = v;
+                }
+        }
+        cseg = open_segment(round + 1);
     }
+    // the loads of the padding tiles past the last segment must have landed before the workgroup
+    // ends and its LDS is handed on
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
 template <int D>
@@ -375,17 +440,21 @@ int launch_bwd(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
     int G = p.Hq / p.Hkv;
     int GP = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
     int TP = 32 * 8 / GP;
-    const long n_wg = (long)((p.L + TP - 1) / TP) * p.B * p.Hkv * (G / GP);
-    if (n_wg > 0x7FFFFFFFL) return SEPATTN_ERR_SHAPE;
-    dim3 grid((unsigned)n_wg), block(512);
+    const int n_pos_tiles = (p.L + TP - 1) / TP;
+    const long n_groups = (long)p.B * p.Hkv * (G / GP);
+    // persistent workgroups: one per compute unit, spread evenly over the groups
+    int wpg = (int)(compute_units() / n_groups);
+    wpg = wpg < 1 ? 1 : (wpg > n_pos_tiles ? n_pos_tiles : wpg);
+    if (n_groups * wpg > 0x7FFFFFFFL) return SEPATTN_ERR_SHAPE;
+    dim3 grid((unsigned)(n_groups * wpg)), block(512);
     {
     ProfScope prof(SEPATTN_K_BWD_DQ, st);
     if (GP == 4)
-        hipLaunchKernelGGL((dq_kernel<D, 4>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, dQ, Dws, Lws);
+        hipLaunchKernelGGL((dq_kernel<D, 4>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, dQ, Dws, Lws, wpg);
     else if (GP == 2)
-        hipLaunchKernelGGL((dq_kernel<D, 2>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, dQ, Dws, Lws);
+        hipLaunchKernelGGL((dq_kernel<D, 2>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, dQ, Dws, Lws, wpg);
     else
-        hipLaunchKernelGGL((dq_kernel<D, 1>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, dQ, Dws, Lws);
+        hipLaunchKernelGGL((dq_kernel<D, 1>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, dQ, Dws, Lws, wpg);
     }
     if (hipGetLastError() != hipSuccess) return SEPATTN_ERR_HIP;
     return launch_dkv_bf16(p, Q, K, V, Lws, dO, Dws, sep_idx, sep_prefix, dK, dV, farK, farV, st);

@@ -28,15 +28,6 @@
 #include "bwd_common.h"
 #include "mfma_common.h"
 
-// Ablation switches for tuning (SEPATTN_X_*): never defined in the product build.
-#ifdef SEPATTN_X_NOLDSOP
-#define RD_ROW(T, row, chunk) breg[(chunk) >> 1]
-#define RD_TR(T, r0, c0) breg[((c0) >> 5) & (KSTEPS - 1)]
-#else
-#define RD_ROW(T, row, chunk) lds_read_a_swz<kSwzBoth, D>(T, row, chunk)
-#define RD_TR(T, r0, c0) lds_read_a_tr_swz<kSwzBoth, D>(T, r0, c0, lane)
-#endif
-
 #ifdef SEPATTN_X_TIMING
 __device__ unsigned long long g_dbg_dkv[4 * 16384];
 extern "C" int sepattn_debug_read_dkv(unsigned long long *host, int n) {
@@ -107,6 +98,21 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
     const int my_pc = lane % CH, my_sub = lane / CH;
     // loads this wave issues per tile: the first two waves also fetch LSE*log2e and D
     const bool extra_load = wave < 2;
+    // Per-lane byte offsets of the operand fragments inside a tile, computed once.  The first
+    // contraction reads rows of T1 (Q for the P-wave, dO for the dS-wave), the second reads the other
+    // tensor (T2) transposed.  Row-major fragments: the XOR permutation acts on the 16-byte chunk
+    // index 2*ks + hh and the k-step only enters through bits 1..3 of it, so fragment ks sits at
+    // (fragment 0) ^ (32 * ks); tile and block bases are multiples of 1 KB, so the XOR commutes with
+    // adding them.
+    const uint32_t q_base = lds_addr(&Qs[0][0]), do_base = lds_addr(&dOs[0][0]);
+    const uint32_t t1_base = (role == 0 ? q_base : do_base) + lds_off_a<kSwzBoth, D>(a_row, hh);
+    const uint32_t t2_base = role == 0 ? do_base : q_base;
+    uint32_t ktr0[DB], ktr1[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+        ktr0[db] = t2_base + lds_off_a_tr<kSwzBoth, D>(db * 32, lane);
+        ktr1[db] = t2_base + lds_off_a_tr_second<kSwzBoth, D>(db * 32, lane);
+    }
 
     // one unit per workgroup: a (list tile, query chunk) pair in the far pass, a key tile in the band pass
     if (FAR && unit >= ((fl.NF + kBK - 1) / kBK) * fg.NCH) return;
@@ -224,63 +230,69 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
         // ---- per-block pieces.  Block gb = 2*tile + half covers 32 query rows starting at r0.
         struct Blk {
             int buf, qb, r0;
-            bool full;  // every (query, key) pair of the block is visible: no mask test needed
+            uint32_t off;  // byte offset of the block's first row from the start of the ring
+            bool full;     // every (query, key) pair of the block is visible: no mask test needed
         };
         int blk_qt = 0;  // query tile (within its head) of the block handed out next
         auto next_block = [&](int gb) {
             Blk k;
             k.qb = gb & 1;
             k.buf = (gb >> 1) % NBUF;
+            k.off = (uint32_t)k.buf * (TILE * 2) + (uint32_t)k.qb * (32 * D * 2);
             k.r0 = q_lo + blk_qt * kBQ + 32 * k.qb;
             const int r1 = k.r0 + 31;
             k.full = (k.r0 >= lo_max) && (r1 <= hi_min);
             if (k.qb == 1 && ++blk_qt == n_qt) blk_qt = 0;
             return k;
         };
-        // first contraction reads rows of T1, second reads the other tensor (T2) transposed
-        auto read_rows = [&](const Blk &k, bf16x8 (&afr)[KSTEPS]) {
-            const uint16_t *T1 = role == 0 ? Qs[k.buf] : dOs[k.buf];
-            const int row = k.qb * 32 + a_row;
-#pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks) afr[ks] = RD_ROW(T1, row, 2 * ks + hh);
+        // fragment reads by precomputed address: one vector instruction per read forms the address
+        auto rd_row = [&](uint32_t rbase, int ks) __attribute__((always_inline)) {
+            return lds_read_b128_at(rbase ^ (32u * ks));
         };
-        auto read_transposed = [&](const Blk &k, bf16x8 (&tfr)[2][DB]) {
-            const uint16_t *T2 = role == 0 ? dOs[k.buf] : Qs[k.buf];
+        // rows 16*stp .. +15 of the block, columns 32*db .. +31, transposed.  For d = 128 the second
+        // 64-bit read is the first with chunk bit 0 flipped, four rows on.
+        auto rd_tr = [&](uint32_t boff, int stp, int db) __attribute__((always_inline)) {
+            const uint32_t first = boff + ktr0[db];
+            const uint32_t second = D == 128 ? (first ^ 16u) + 4u * D * 2u : boff + ktr1[db];
+            return lds_read_tr_at2(first + stp * 16 * D * 2, second + stp * 16 * D * 2);
+        };
+        auto read_rows = [&](const Blk &k, bf16x8 (&afr)[KSTEPS]) __attribute__((always_inline)) {
+            const uint32_t rbase = t1_base + k.off;
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) afr[ks] = rd_row(rbase, ks);
+        };
+        auto read_transposed = [&](const Blk &k, bf16x8 (&tfr)[2][DB]) __attribute__((always_inline)) {
 #pragma unroll
             for (int stp = 0; stp < 2; ++stp)
 #pragma unroll
-                for (int db = 0; db < DB; ++db)
-                    tfr[stp][db] = RD_TR(T2, k.qb * 32 + stp * 16, db * 32);
+                for (int db = 0; db < DB; ++db) tfr[stp][db] = rd_tr(k.off, stp, db);
         };
         // The two contractions of one pipeline step, with the LDS reads of the later one placed
         // between the MFMA groups of the earlier one: a fragment is requested four MFMAs (128 cycles)
         // before its use, and at most 32 fragment registers are live.  The scheduling fences keep the
         // compiler from hoisting all reads to the top (which would spill).
-        auto zero = [&](f32x16 &x) {
+        auto zero = [&](f32x16 &x) __attribute__((always_inline)) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) x[i] = 0.f;
         };
         // acc += T2^T(cur) x_b(cur), then x = T1(nxt) B        (P-wave order)
-        auto gemm2_then_gemm1 = [&](const Blk &cur, const bf16x8 (&xb)[2], const Blk &nxt, f32x16 &x) {
-            const uint16_t *T2 = role == 0 ? dOs[cur.buf] : Qs[cur.buf];
-            const uint16_t *T1 = role == 0 ? Qs[nxt.buf] : dOs[nxt.buf];
-            const int row = nxt.qb * 32 + a_row;
+        auto gemm2_then_gemm1 = [&](const Blk &cur, const bf16x8 (&xb)[2], const Blk &nxt, f32x16 &x) __attribute__((always_inline)) {
+            const uint32_t rbase = t1_base + nxt.off;
             bf16x8 t0[DB], t1[DB], a0[KSTEPS / 2], a1[KSTEPS / 2];
 #pragma unroll
-            for (int db = 0; db < DB; ++db) t0[db] = RD_TR(T2, cur.qb * 32, db * 32);
+            for (int db = 0; db < DB; ++db) t0[db] = rd_tr(cur.off, 0, db);
 #pragma unroll
-            for (int db = 0; db < DB; ++db) t1[db] = RD_TR(T2, cur.qb * 32 + 16, db * 32);
+            for (int db = 0; db < DB; ++db) t1[db] = rd_tr(cur.off, 1, db);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int db = 0; db < DB; ++db) acc[db] = mfma_bf16(t0[db], xb[0], acc[db]);
 #pragma unroll
-            for (int ks = 0; ks < KSTEPS / 2; ++ks) a0[ks] = RD_ROW(T1, row, 2 * ks + hh);
+            for (int ks = 0; ks < KSTEPS / 2; ++ks) a0[ks] = rd_row(rbase, ks);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int db = 0; db < DB; ++db) acc[db] = mfma_bf16(t1[db], xb[1], acc[db]);
 #pragma unroll
-            for (int ks = 0; ks < KSTEPS / 2; ++ks)
-                a1[ks] = RD_ROW(T1, row, 2 * (ks + KSTEPS / 2) + hh);
+            for (int ks = 0; ks < KSTEPS / 2; ++ks) a1[ks] = rd_row(rbase, ks + KSTEPS / 2);
             __builtin_amdgcn_sched_barrier(0);
             zero(x);
 #pragma unroll
@@ -291,19 +303,18 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
         };
         // xn = T1(nxt) B (fragments a0, a1 already requested), then acc += T2^T(cur) x_b(cur)   (dS-wave order)
         auto gemm1_then_gemm2 = [&](const Blk &nxt, const bf16x8 (&a0)[KSTEPS / 2], const bf16x8 (&a1)[KSTEPS / 2],
-                                    f32x16 &xn, const Blk &cur, const bf16x8 (&xb)[2]) {
-            const uint16_t *T2 = role == 0 ? dOs[cur.buf] : Qs[cur.buf];
+                                    f32x16 &xn, const Blk &cur, const bf16x8 (&xb)[2]) __attribute__((always_inline)) {
             bf16x8 t0[DB], t1[DB];
             zero(xn);
 #pragma unroll
             for (int ks = 0; ks < KSTEPS / 2; ++ks) xn = mfma_bf16(a0[ks], breg[ks], xn);
 #pragma unroll
-            for (int db = 0; db < DB; ++db) t0[db] = RD_TR(T2, cur.qb * 32, db * 32);
+            for (int db = 0; db < DB; ++db) t0[db] = rd_tr(cur.off, 0, db);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int ks = 0; ks < KSTEPS / 2; ++ks) xn = mfma_bf16(a1[ks], breg[ks + KSTEPS / 2], xn);
 #pragma unroll
-            for (int db = 0; db < DB; ++db) t1[db] = RD_TR(T2, cur.qb * 32 + 16, db * 32);
+            for (int db = 0; db < DB; ++db) t1[db] = rd_tr(cur.off, 1, db);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int db = 0; db < DB; ++db) acc[db] = mfma_bf16(t0[db], xb[0], acc[db]);
@@ -311,13 +322,12 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
             for (int db = 0; db < DB; ++db) acc[db] = mfma_bf16(t1[db], xb[1], acc[db]);
             __builtin_amdgcn_sched_barrier(0);
         };
-        auto read_rows_halves = [&](const Blk &k, bf16x8 (&a0)[KSTEPS / 2], bf16x8 (&a1)[KSTEPS / 2]) {
-            const uint16_t *T1 = role == 0 ? Qs[k.buf] : dOs[k.buf];
-            const int row = k.qb * 32 + a_row;
+        auto read_rows_halves = [&](const Blk &k, bf16x8 (&a0)[KSTEPS / 2], bf16x8 (&a1)[KSTEPS / 2]) __attribute__((always_inline)) {
+            const uint32_t rbase = t1_base + k.off;
 #pragma unroll
             for (int ks = 0; ks < KSTEPS / 2; ++ks) {
-                a0[ks] = RD_ROW(T1, row, 2 * ks + hh);
-                a1[ks] = RD_ROW(T1, row, 2 * (ks + KSTEPS / 2) + hh);
+                a0[ks] = rd_row(rbase, ks);
+                a1[ks] = rd_row(rbase, ks + KSTEPS / 2);
             }
         };
         auto gemm1 = [&](const bf16x8 (&afr)[KSTEPS], f32x16 &x) {

@@ -38,9 +38,9 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
 # The figures and the commands are in profiles/; None = not measured for the current kernels.
 CALIB_BYTES = 256 << 20
 MEASURED_TRAFFIC_BYTES = {
-    "forward": 176.1e6,   # read 108.0 MB + written 68.2 MB   (algorithmic: 168.8 MB)
-    "bwd_dq": 313.6e6,    # read 244.4 MB + written 69.2 MB
-    "bwd_dkv": 497.0e6,   # read 407.9 MB + written 89.0 MB
+    "forward": 176.9e6,   # read 108.7 MB + written 68.2 MB   (algorithmic: 168.8 MB)
+    "bwd_dq": 321.0e6,    # read 247.8 MB + written 73.2 MB
+    "bwd_dkv": 502.1e6,   # read 411.3 MB + written 90.8 MB
 }
 
 
@@ -65,8 +65,11 @@ def count_far_pairs(flags_row: np.ndarray, a: int, n: int) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--ramp-seconds", type=float, default=1.0,
+                    help="untimed sustained load before the warm-up steps: the shader clock needs some tenths "
+                         "of a second of load to reach its steady state")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     args = ap.parse_args()
@@ -112,6 +115,7 @@ def main() -> int:
         sp.sepattn_forward(Q, K, V, idx, cnt, pre, c.a, c.n, c.scale, out=(O, LSE), ws=fws)
         sp.sepattn_backward(Q, K, V, O, LSE, dO, idx, cnt, pre, c.a, c.n, c.scale, out=(dQ, dK, dV), ws=bws)
 
+    ramp_until(torch, step, args.ramp_seconds)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -127,11 +131,11 @@ def main() -> int:
     train_kernels = ["mark", "compact_count", "compact_write", "forward", "bwd_dq", "bwd_dkv", "bwd_combine"]
     per_kernel_us = {}
     for name in train_kernels:
-        sp.sepattn_profile_begin(sp.KERNEL_IDS[name], 5)
-        for _ in range(5):
+        sp.sepattn_profile_begin(sp.KERNEL_IDS[name], 20)
+        for _ in range(20):
             step()
         torch.cuda.synchronize()
-        ms = sp.sepattn_profile_end(5)
+        ms = sp.sepattn_profile_end(20)
         per_kernel_us[name] = 1e3 * float(np.median(ms))
     dominant = max(per_kernel_us, key=per_kernel_us.get)
 
@@ -172,6 +176,7 @@ def main() -> int:
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "clock_ramp_s": args.ramp_seconds,
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True,
         "scaling": "weak",
@@ -188,14 +193,23 @@ def main() -> int:
     }
 
     if not args.no_decode:
-        out["decode"] = bench_decode(torch, sp, wl)
+        out["decode"] = bench_decode(torch, sp, wl, args.ramp_seconds)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, inp, flags, c, p_vis)
     print(json.dumps(out))
     return 0
 
 
-def bench_decode(torch, sp, wl):
+def ramp_until(torch, step, seconds):
+    """Untimed sustained load: the step, over and over, for the given wall-clock time."""
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(20):
+            step()
+        torch.cuda.synchronize()
+
+
+def bench_decode(torch, sp, wl, ramp_seconds):
     """Config 5: one decode step over 32 x 8 x 3332-entry caches; eviction of a full past window."""
     c = wl.CONFIGS["cfg5"]
     data = wl.make_cache(c)
@@ -207,7 +221,13 @@ def bench_decode(torch, sp, wl):
     ws = torch.empty(1 << 24, dtype=torch.uint8, device=q.device)
     # two further caches so that consecutive steps do not find their K/V in the 256 MB last-level cache
     caches = [(Kc, Vc)] + [(torch.randn_like(Kc), torch.randn_like(Vc)) for _ in range(2)]
-    steps, warm = 60, 9
+    steps, warm = 300, 9
+
+    def decode_round():
+        for k_, v_ in caches:
+            sp.sepattn_decode(q, k_, v_, sizes, c.a, c.s, c.w, c.scale, out=(out, lse), ws=ws)
+
+    ramp_until(torch, decode_round, ramp_seconds)
     for i in range(warm):
         k_, v_ = caches[i % 3]
         sp.sepattn_decode(q, k_, v_, sizes, c.a, c.s, c.w, c.scale, out=(out, lse), ws=ws)

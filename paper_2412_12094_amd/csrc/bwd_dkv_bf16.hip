@@ -30,6 +30,10 @@
 
 #ifdef SEPATTN_X_TIMING
 __device__ unsigned long long g_dbg_dkv[4 * 16384];
+__device__ unsigned long long g_dbg_dkv_w[16384 * 8 * 4];  // per unit and wave: loop, wait, barrier cycles, blocks
+extern "C" int sepattn_debug_read_dkv_w(unsigned long long *host, int n) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg_dkv_w), sizeof(unsigned long long) * n);
+}
 extern "C" int sepattn_debug_read_dkv(unsigned long long *host, int n) {
     return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg_dkv), sizeof(unsigned long long) * n);
 }
@@ -393,11 +397,25 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
         };
         // barrier after the first contraction (and publication of P) of block gb; the barrier of a
         // tile's second block also publishes the next tile: every wave has waited for its own share
+#ifdef SEPATTN_X_TIMING
+        unsigned long long tw_acc = 0, tb_acc = 0;
+#endif
         auto block_barrier = [&](int gb) {
+#ifdef SEPATTN_X_TIMING
+            const unsigned long long tt0 = clock64();
+#endif
             if (gb & 1) wait_all_but_newest_tile(iss_tt > (gb >> 1) + 2);  // tile (gb>>1)+2 is in flight
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#ifdef SEPATTN_X_TIMING
+            const unsigned long long tt1 = clock64();
+#endif
 #ifndef SEPATTN_X_NOBAR
             __builtin_amdgcn_s_barrier();
+#endif
+#ifdef SEPATTN_X_TIMING
+            const unsigned long long tt2 = clock64();
+            tw_acc += tt1 - tt0;
+            tb_acc += tt2 - tt1;
 #endif
             // after the first barrier of tile tt nobody reads tile tt-1 any more: refill its buffer
             if (!(gb & 1) && iss_tt < n_tiles) issue_tile();
@@ -464,6 +482,14 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
             pipeline(IntC<1>{});
 #ifdef SEPATTN_X_TIMING
         const unsigned long long c_loop1 = clock64();
+        if (lane == 0 && unit < 1024 && bkv < 8) {
+            const int dslot = (FAR ? 0 : 8192) + bkv * 1024 + unit;
+            unsigned long long *w = &g_dbg_dkv_w[(dslot * 8 + wave) * 4];
+            w[0] = c_loop1 - c_loop0;
+            w[1] = tw_acc;
+            w[2] = tb_acc;
+            w[3] = n_blocks;
+        }
         if (tid == 0) {
             const int dslot = (FAR ? 0 : 8192) + bkv * 1024 + unit;
             if (unit < 1024 && bkv < 8) {

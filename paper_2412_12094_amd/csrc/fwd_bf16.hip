@@ -535,10 +535,9 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
 #ifdef SEPATTN_X_TIMING
     const unsigned long long w_loop1 = wall_clock64();
     if (lane == 0 && blockIdx.x < 2048) {
-        tacc[3] = w_loop0 - w_start;
-        tacc[6] = w_loop1 - w_loop0;
+        tacc[6] = w_loop1 - w_start;  // wall clock since the workgroup started, at the end of this segment
         tacc[7] = w_start;
-        tacc[5] = n_tiles;
+        tacc[5] += n_tiles;
         for (int k = 0; k < 8; ++k) g_dbg[((long)blockIdx.x * 8 + wave) * 8 + k] = tacc[k];
     }
 #endif

@@ -436,6 +436,7 @@ int launch_bwd(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
     float *Lws = reinterpret_cast<float *>(base + w.d_bytes);
     float *farK = reinterpret_cast<float *>(base + 2 * w.d_bytes);
     float *farV = reinterpret_cast<float *>(base + 2 * w.d_bytes + w.far_bytes);
+    int32_t *piece_tab = reinterpret_cast<int32_t *>(base + 2 * w.d_bytes + 2 * w.far_bytes);
 
     int G = p.Hq / p.Hkv;
     int GP = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
@@ -457,7 +458,7 @@ int launch_bwd(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
         hipLaunchKernelGGL((dq_kernel<D, 1>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, dQ, Dws, Lws, wpg);
     }
     if (hipGetLastError() != hipSuccess) return SEPATTN_ERR_HIP;
-    return launch_dkv_bf16(p, Q, K, V, Lws, dO, Dws, sep_idx, sep_prefix, dK, dV, farK, farV, st);
+    return launch_dkv_bf16(p, Q, K, V, Lws, dO, Dws, sep_idx, sep_prefix, dK, dV, farK, farV, piece_tab, st);
 }
 
 }  // namespace

@@ -3,16 +3,21 @@
 //   P_ij = exp(scale <Q_i, K_j> - LSE_i),  summed over the query heads of the KV head.
 //
 // The visible pairs split into band pairs (i-j < n) and far pairs (i-j >= n, j an initial token or a
-// separator, Sec. 3.1).  One launch of dkv_kernel runs two kinds of units:
-//   far unit:  far pairs on the COMPACTED list of such keys (128 consecutive list entries, gathered
-//              K/V rows) against one chunk of the query range; writes an fp32 partial dK/dV per
-//              (list tile, query chunk) to the workspace.
-//   band unit: 128 consecutive keys against the queries j <= i < j+n.  Keys that are not on the far
-//              list are finished here (rounded once to bf16); for the others the band unit writes one
-//              more fp32 partial.
+// separator, Sec. 3.1).  dkv_kernel runs persistent workgroups, `wpg` per (batch, KV head), each of
+// which works through
+//   its far pieces: far pairs on the COMPACTED list of such keys.  For list tile ft (128 consecutive
+//              list entries, gathered K/V rows) the work is the sequence of items (query tile of 64
+//              rows, query head) from the first query that sees the tile's first key to the end of
+//              the sequence; the items of all list tiles, concatenated, are cut into wpg equal
+//              slices, and the part of a workgroup's slice inside one list tile is a piece.  A piece
+//              writes an fp32 partial dK/dV of the tile's rows to the workspace (slot w + ft).
+//   its band units: 128 consecutive keys against the queries j <= i < j+n (units w, w+wpg, ...).
+//              Keys that are not on the far list are finished here (rounded once to bf16); for the
+//              others the band unit writes one more fp32 partial.
 // dkv_combine_kernel then adds, in fixed order, the partials of every far-list key and rounds once to
-// bf16.  One workgroup owns each partial row: no atomics, results are bit-reproducible.  Far units
-// come first in the grid (they are the longer ones) and band units fill the CUs as those drain.
+// bf16.  One workgroup owns each partial row: no atomics, results are bit-reproducible.  Every
+// workgroup gets the same amount of far work and (up to one) the same number of band units, so the
+// compute units finish together.
 // A workgroup is 8 waves = 4 key blocks of 32 keys x 2 roles.  The two waves of a key block split
 // the four contractions so that each keeps only one operand matrix and one accumulator resident:
 //   P-wave :  S = Q K^T   -> P = exp2(.)      -> dV^T += dO^T P     (holds K rows, dV^T)
@@ -58,7 +63,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
     const uint16_t *__restrict__ V, const float *__restrict__ LSE2, const uint16_t *__restrict__ dO,
     const float *__restrict__ Dws, const int32_t *__restrict__ sep_idx,
     const int32_t *__restrict__ sep_prefix, uint16_t *__restrict__ dK, uint16_t *__restrict__ dV,
-    float *__restrict__ farK, float *__restrict__ farV, int n_far_head, int n_band) {
+    float *__restrict__ farK, float *__restrict__ farV, int32_t *__restrict__ piece_tab, int wpg, int n_band) {
     constexpr int NW = 2 * kDkvWaves;        // waves per workgroup
     constexpr int CH = D / 8;                // 16-byte chunks per row
     constexpr int RPL = 64 / CH;             // rows covered by one wave-wide 1 KB load
@@ -81,22 +86,16 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
     const int kbw = wave % kDkvWaves;   // key block of the wave
     const int kj = lane & 31, hh = lane >> 5;
     const int G = p.Hq / p.Hkv;
-    // 1-D grid, slot-major: consecutive workgroups are the same slot of consecutive (batch, KV head)
-    // pairs, so far units (the long ones) are dispatched before band units, and with 8 KV heads each
-    // head's K, V, Q, dO rows stay in the L2 of one XCD.  The far units a list of up to L/8 entries
-    // needs come first; the remaining far slots (nearly always empty) come after the band units so
-    // that their workgroups do not queue in front of real work.
+    // 1-D grid: consecutive workgroups belong to consecutive (batch, KV head) pairs, so with 8 KV heads
+    // each head's K, V, Q, dO rows stay in the L2 of one XCD.
     const int n_bkv = p.B * p.Hkv;
-    const int bkv = blockIdx.x % n_bkv, slot = blockIdx.x / n_bkv;
+    const int bkv = blockIdx.x % n_bkv, w_id = blockIdx.x / n_bkv;
     const int kv = bkv % p.Hkv, b = bkv / p.Hkv;
-    // slot order: [likely far units | band units | far units only a very long list has]
-    const bool FAR = slot < n_far_head || slot >= n_far_head + n_band;
-    const int unit = FAR ? (slot < n_far_head ? slot : slot - n_band) : slot - n_far_head;  // far unit or key tile
     const int32_t *prefix = sep_prefix + (long)b * (p.L + 1);
     const int32_t *idx = sep_idx + (long)b * p.cap;
     const long kvrow0 = ((long)b * p.Hkv + kv) * (long)p.L;
     const float sl2 = p.scale * kLog2e_f;
-    const FarGeom fg = far_geom(p);
+    const FarGeom fg = far_geom(p, wpg);
     const FarList fl = far_list(p, prefix);
     const int a_row = pi_row(kj);
     const int my_pc = lane % CH, my_sub = lane / CH;
@@ -118,27 +117,101 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
         ktr1[db] = t2_base + lds_off_a_tr_second<kSwzBoth, D>(db * 32, lane);
     }
 
-    // one unit per workgroup: a (list tile, query chunk) pair in the far pass, a key tile in the band pass
-    if (FAR && unit >= ((fl.NF + kBK - 1) / kBK) * fg.NCH) return;
+    // ---- the far work of this (batch, KV head) and this workgroup's slice [s0, s1) of it.
+    // Lane t of a group of 64 list tiles describes tile t: first query row and number of items.
+    const int NFT = (fl.NF + kBK - 1) / kBK;
+    auto tile_items = [&](int t, int &fq) __attribute__((always_inline)) {
+        fq = p.L;
+        if (t < NFT) fq = align_down32(far_pos(fl, t * kBK, idx, p.L) + p.n);
+        return fq < p.L ? G * ((p.L - fq + kBQ - 1) / kBQ) : 0;
+    };
+    auto inclusive_scan = [&](int v) __attribute__((always_inline)) {
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int u = __shfl_up(v, off);
+            if (lane >= off) v += u;
+        }
+        return v;
+    };
+    long far_total = 0;
+    for (int base = 0; base < NFT; base += 64) {
+        int fq;
+        far_total += __builtin_amdgcn_readfirstlane(__shfl(inclusive_scan(tile_items(base + lane, fq)), 63));
+    }
+    // no more slices than items, so that no slice is empty: the pieces of a list tile then belong to
+    // consecutive workgroups, which is what the combine kernel relies on
+    const long wfar = far_total < wpg ? (far_total > 0 ? far_total : 1) : wpg;
+    const long s0 = w_id < wfar ? w_id * far_total / wfar : far_total;
+    const long s1 = w_id < wfar ? (w_id + 1) * far_total / wfar : far_total;
+
+    // iteration state over the pieces: first the far pieces of the slice (list tiles in groups of 64,
+    // `pend` = tiles of the current group that overlap the slice and are still to be visited), then
+    // the band units
+    int it_phase = 0, grp_next = 0, grp_base = 0, band_u = w_id;
+    long cum_next = 0, grp_cum = 0;
+    int g_fq = 0, g_nq = 0, g_excl = 0;
+    unsigned long long pend = 0;
 #ifdef SEPATTN_X_TIMING
-    const unsigned long long t_begin = wall_clock64(), c_begin = clock64();
-    __shared__ unsigned simd_map;
-    if (tid == 0) simd_map = 0;
-    __syncthreads();
-    if (lane == 0) atomicOr(&simd_map, ((__builtin_amdgcn_s_getreg((4 << 0) | (4 << 6) | (1 << 11))) & 3u) << (4 * wave));
-    __syncthreads();
+    const unsigned long long t_begin = wall_clock64();
+    unsigned long long tw_acc = 0, tb_acc = 0, tl_acc = 0, nblk_acc = 0;
 #endif
-    {
-        // ---- this wave's 32 keys and the query range of the unit
-        int j, lo, hi, q_lo, q_hi, fidx = 0, chunk = 0;
+    for (;;) {
+        bool FAR = false, have = false;
+        int ft = 0, fq0 = 0, item0 = 0, n_items = 0, unit = 0, n_qt = 1;
+        while (!have) {
+            if (it_phase == 0) {
+                if (pend == 0) {
+                    if (grp_next >= NFT || cum_next >= s1) {
+                        it_phase = 1;
+                        continue;
+                    }
+                    grp_base = grp_next;
+                    grp_cum = cum_next;
+                    g_nq = tile_items(grp_base + lane, g_fq);
+                    const int inc = inclusive_scan(g_nq);
+                    g_excl = inc - g_nq;
+                    pend = __ballot(g_nq > 0 && grp_cum + inc > s0 && grp_cum + g_excl < s1);
+                    cum_next = grp_cum + __builtin_amdgcn_readfirstlane(__shfl(inc, 63));
+                    grp_next = grp_base + 64;
+                    continue;
+                }
+                const int l = __ffsll(pend) - 1;
+                pend &= pend - 1;
+                const long first = grp_cum + __builtin_amdgcn_readfirstlane(__shfl(g_excl, l));
+                const int nq = __builtin_amdgcn_readfirstlane(__shfl(g_nq, l));
+                const long lo_i = s0 > first ? s0 : first, hi_i = s1 < first + nq ? s1 : first + nq;
+                ft = grp_base + l;
+                fq0 = __builtin_amdgcn_readfirstlane(__shfl(g_fq, l));
+                item0 = (int)(lo_i - first);
+                n_items = (int)(hi_i - lo_i);
+                n_qt = nq / G;
+                // the combine kernel finds the pieces of a list tile through its first and last workgroup
+                if (tid == 0) {
+                    int32_t *tab = piece_tab + ((long)bkv * fg.NFTcap + ft) * 2;
+                    if (item0 == 0) tab[0] = w_id;
+                    if (item0 + n_items == nq) tab[1] = w_id;
+                }
+                FAR = true;
+                have = true;
+            } else {
+                if (band_u >= n_band) break;
+                unit = band_u;
+                band_u += wpg;
+                have = true;
+            }
+        }
+        if (!have) break;
+        // the previous piece's last LDS reads are done in every wave before its buffers are refilled
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+
+        // ---- this wave's 32 keys and the query range of the piece.  Item i of the piece is query tile
+        // i % n_qt (64 rows from q_lo on) of query head i / n_qt.
+        int j, lo, hi, q_lo, q_hi, fidx = 0;
         bool valid;
         if (FAR) {
-            int ft = unit / fg.NCH;
-            chunk = unit % fg.NCH;
-            int pos_first = far_pos(fl, ft * kBK, idx, p.L);
-            q_lo = max(chunk * fg.CQ, align_down32(pos_first + p.n));
-            q_hi = min(p.L, (chunk + 1) * fg.CQ);
-            if (q_lo >= q_hi) return;
+            q_lo = fq0;
+            q_hi = p.L;
             fidx = ft * kBK + 32 * kbw + kj;
             valid = fidx < fl.NF;
             j = valid ? far_pos(fl, fidx, idx, p.L) : 0;
@@ -153,6 +226,9 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
             lo = j;
             hi = min(j + p.n - 1, p.L - 1);
             if (!valid) j = 0;
+            item0 = 0;
+            n_qt = (q_hi - q_lo + kBQ - 1) / kBQ;
+            n_items = G * n_qt;
         }
         if (!valid) {
             lo = kIntMax;
@@ -177,8 +253,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[db][i] = 0.f;
 
-        const int n_qt = (q_hi - q_lo + kBQ - 1) / kBQ;
-        const int n_tiles = G * n_qt;
+        const int n_tiles = n_items;
         const int n_blocks = 2 * n_tiles;
 
         // tile tt -> LDS buffer tt%3: wave w fills rows (LOADS*w + u)*RPL .. +RPL-1 with one wave-wide
@@ -186,7 +261,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
         // logical chunk the permutation maps there.  Rows past the sequence end are clamped (they are
         // masked by the [lo, hi] test: hi <= L-1).  Tiles are issued in order; (iss_g, iss_qt) is the
         // (head, query tile) of the next one.
-        int iss_tt = 0, iss_g = 0, iss_qt = 0;
+        int iss_tt = 0, iss_g = item0 / n_qt, iss_qt = item0 % n_qt;
         auto issue_tile = [&]() {
             const int buf = iss_tt % NBUF;
             const long hrow0 = ((long)b * p.Hq + kv * G + iss_g) * (long)p.L;
@@ -237,7 +312,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
             uint32_t off;  // byte offset of the block's first row from the start of the ring
             bool full;     // every (query, key) pair of the block is visible: no mask test needed
         };
-        int blk_qt = 0;  // query tile (within its head) of the block handed out next
+        int blk_qt = item0 % n_qt;  // query tile (within its head) of the block handed out next
         auto next_block = [&](int gb) {
             Blk k;
             k.qb = gb & 1;
@@ -397,9 +472,6 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
         };
         // barrier after the first contraction (and publication of P) of block gb; the barrier of a
         // tile's second block also publishes the next tile: every wave has waited for its own share
-#ifdef SEPATTN_X_TIMING
-        unsigned long long tw_acc = 0, tb_acc = 0;
-#endif
         auto block_barrier = [&](int gb) {
 #ifdef SEPATTN_X_TIMING
             const unsigned long long tt0 = clock64();
@@ -481,43 +553,28 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
         else
             pipeline(IntC<1>{});
 #ifdef SEPATTN_X_TIMING
-        const unsigned long long c_loop1 = clock64();
-        if (lane == 0 && unit < 1024 && bkv < 8) {
-            const int dslot = (FAR ? 0 : 8192) + bkv * 1024 + unit;
-            unsigned long long *w = &g_dbg_dkv_w[(dslot * 8 + wave) * 4];
-            w[0] = c_loop1 - c_loop0;
-            w[1] = tw_acc;
-            w[2] = tb_acc;
-            w[3] = n_blocks;
-        }
-        if (tid == 0) {
-            const int dslot = (FAR ? 0 : 8192) + bkv * 1024 + unit;
-            if (unit < 1024 && bkv < 8) {
-                g_dbg_dkv[4 * dslot + 0] = t_begin;
-                g_dbg_dkv[4 * dslot + 2] = ((c_loop0 - c_begin) << 32) | (c_loop1 - c_loop0);
-                g_dbg_dkv[4 * dslot + 3] = ((unsigned long long)n_blocks << 32) | simd_map;
-            }
-        }
+        tl_acc += clock64() - c_loop0;
+        nblk_acc += n_blocks;
 #endif
 
-        // ---- epilogue: the P-wave owns dV, the dS-wave owns dK (times scale).  A far unit writes the
-        // partial of its chunk; a band unit finishes keys that are not on the far list and writes the
-        // band partial (slot NCH) of those that are.
+        // ---- epilogue: the P-wave owns dV, the dS-wave owns dK (times scale).  A far piece writes its
+        // partial (slot w + ft, row = entry within the list tile); a band unit finishes keys that are
+        // not on the far list and writes the band partial (one row per list entry, after the slots)
+        // of those that are.
         const float oscale = role == 0 ? 1.f : p.scale;
         float *farX = role == 0 ? farV : farK;
-        int slot_c = chunk, slot_f = fidx;
+        long part_row = (long)(w_id + ft) * kBK + 32 * kbw + kj;
         bool to_partial = FAR;
         if (!FAR && valid) {
             const int f = far_index(fl, prefix, j);
             if (f >= 0 && far_first_query(fl, f, idx, p) < p.L) {
                 to_partial = true;
-                slot_c = fg.NCH;
-                slot_f = f;
+                part_row = (long)fg.NP * kBK + f;
             }
         }
         if (valid) {
             if (to_partial) {
-                const long prow = ((((long)b * p.Hkv + kv) * (fg.NCH + 1) + slot_c) * fg.NFcap + slot_f) * D;
+                const long prow = ((long)bkv * fg.rows + part_row) * D;
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -540,53 +597,74 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
                     }
             }
         }
+    }  // pieces
 #ifdef SEPATTN_X_TIMING
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        if (tid == 0 && unit < 1024 && bkv < 8) {
-            const int dslot = (FAR ? 0 : 8192) + bkv * 1024 + unit;
-            g_dbg_dkv[4 * dslot + 1] = wall_clock64();
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (lane == 0 && blockIdx.x < 4096) {
+        unsigned long long *w = &g_dbg_dkv_w[((long)blockIdx.x * 8 + wave) * 4];
+        w[0] = tl_acc;
+        w[1] = tw_acc;
+        w[2] = tb_acc;
+        w[3] = nblk_acc;
+        if (wave == 0) {
+            g_dbg_dkv[4 * blockIdx.x + 0] = t_begin;
+            g_dbg_dkv[4 * blockIdx.x + 1] = wall_clock64();
+            g_dbg_dkv[4 * blockIdx.x + 3] = nblk_acc;
         }
-#endif
     }
+#endif
 }
 
-// Sum of the partials of every far-list key (its far chunks in ascending order, then the band
-// partial), rounded once to bf16.  One thread per (key, 4 consecutive columns).
+// Sum of the partials of every far-list key (the far pieces of its list tile in ascending workgroup
+// order, then the band partial), rounded once to bf16.  One thread per (key, 4 consecutive columns).
 template <int D>
 __global__ __launch_bounds__(256) void dkv_combine_kernel(sepattn_params p, const int32_t *__restrict__ sep_idx,
                                                           const int32_t *__restrict__ sep_prefix,
                                                           uint16_t *__restrict__ dK, uint16_t *__restrict__ dV,
                                                           const float *__restrict__ farK,
-                                                          const float *__restrict__ farV) {
+                                                          const float *__restrict__ farV,
+                                                          const int32_t *__restrict__ piece_tab, int wpg) {
     constexpr int TPR = D / 4;  // threads per row
     const int bkv = blockIdx.y, kv = bkv % p.Hkv, b = bkv / p.Hkv;
     const int32_t *prefix = sep_prefix + (long)b * (p.L + 1);
     const int32_t *idx = sep_idx + (long)b * p.cap;
-    const FarGeom fg = far_geom(p);
+    const FarGeom fg = far_geom(p, wpg);
     const FarList fl = far_list(p, prefix);
     const int f = (blockIdx.x * 256 + threadIdx.x) / TPR, col = ((blockIdx.x * 256 + threadIdx.x) % TPR) * 4;
     if (f >= fl.NF) return;
     const int A = far_first_query(fl, f, idx, p);
     if (A >= p.L) return;  // no far pair: the band unit has written this row
     const int j = far_pos(fl, f, idx, p.L);
-    const long base = ((long)b * p.Hkv + kv) * (fg.NCH + 1);
-    // fixed trip count with clamped slots: all loads are issued before the first sum needs one
-    const int c0 = A / fg.CQ;
-    float4 pk[kFarChunks + 1], pv[kFarChunks + 1];
-#pragma unroll
-    for (int c = 0; c <= kFarChunks; ++c) {
-        const int cc = min(max(c, c0), fg.NCH);
-        const long prow = ((base + cc) * fg.NFcap + f) * D + col;
-        pk[c] = *reinterpret_cast<const float4 *>(farK + prow);
-        pv[c] = *reinterpret_cast<const float4 *>(farV + prow);
-    }
+    const int ft = f / kBK;
+    const int32_t *tab = piece_tab + ((long)bkv * fg.NFTcap + ft) * 2;
+    // the clamps keep a table that the far pass did not write (it always does) from faulting
+    const int w0 = min(max(tab[0], 0), wpg - 1), w1 = min(max(tab[1], w0), wpg - 1);
+    const long base = (long)bkv * fg.rows;
     float4 sk = {0.f, 0.f, 0.f, 0.f}, sv = {0.f, 0.f, 0.f, 0.f};
+    // four pieces at a time (clamped slots), so that their loads are in flight together
+    for (int w = w0; w <= w1; w += 4) {
+        float4 pk[4], pv[4];
 #pragma unroll
-    for (int c = 0; c <= kFarChunks; ++c) {
-        if (c >= c0 && c <= fg.NCH) {
-            sk.x += pk[c].x, sk.y += pk[c].y, sk.z += pk[c].z, sk.w += pk[c].w;
-            sv.x += pv[c].x, sv.y += pv[c].y, sv.z += pv[c].z, sv.w += pv[c].w;
+        for (int c = 0; c < 4; ++c) {
+            const int ww = min(w + c, w1);
+            const long prow = (base + (long)(ww + ft) * kBK + (f - ft * kBK)) * D + col;
+            pk[c] = *reinterpret_cast<const float4 *>(farK + prow);
+            pv[c] = *reinterpret_cast<const float4 *>(farV + prow);
         }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (w + c <= w1) {
+                sk.x += pk[c].x, sk.y += pk[c].y, sk.z += pk[c].z, sk.w += pk[c].w;
+                sv.x += pv[c].x, sv.y += pv[c].y, sv.z += pv[c].z, sv.w += pv[c].w;
+            }
+        }
+    }
+    {
+        const long prow = (base + (long)fg.NP * kBK + f) * D + col;
+        const float4 bk = *reinterpret_cast<const float4 *>(farK + prow);
+        const float4 bv = *reinterpret_cast<const float4 *>(farV + prow);
+        sk.x += bk.x, sk.y += bk.y, sk.z += bk.z, sk.w += bk.w;
+        sv.x += bv.x, sv.y += bv.y, sv.z += bv.z, sv.w += bv.w;
     }
     const long orow = (((long)b * p.Hkv + kv) * (long)p.L + j) * D + col;
     *reinterpret_cast<uint2 *>(dK + orow) = pack_bf16x4(sk.x, sk.y, sk.z, sk.w);
@@ -597,25 +675,22 @@ template <int D>
 int launch_dkv(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
                const float *lse2, const uint16_t *dO, const float *Dws, const int32_t *sep_idx,
                const int32_t *sep_prefix, uint16_t *dK, uint16_t *dV, float *farK, float *farV,
-               hipStream_t st) {
-    const FarGeom fg = far_geom(p);
-    // far units the list could have at full capacity (most exit at once: the list is far shorter),
-    // then one band unit per 128 keys
-    const long far_grid = (long)(fg.NFcap / kBK) * fg.NCH, band_grid = (p.L + kBK - 1) / kBK;
-    long far_head = (long)((p.a + p.L / 8 + kBK - 1) / kBK) * fg.NCH;
-    if (far_head > far_grid) far_head = far_grid;
-    const long total = (far_grid + band_grid) * p.B * p.Hkv;
+               int32_t *piece_tab, hipStream_t st) {
+    const int wpg = dkv_workgroups_per_head(p);
+    const FarGeom fg = far_geom(p, wpg);
+    const long band_grid = (p.L + kBK - 1) / kBK;
+    const long total = (long)wpg * p.B * p.Hkv;
     if (total > 0x7FFFFFFFL) return SEPATTN_ERR_SHAPE;
     {
         ProfScope prof(SEPATTN_K_BWD_DKV, st);
         hipLaunchKernelGGL((dkv_kernel<D>), dim3((unsigned)total), dim3(kDkvThreads), 0, st, p, Q, K, V, lse2, dO, Dws,
-                           sep_idx, sep_prefix, dK, dV, farK, farV, (int)far_head, (int)band_grid);
+                           sep_idx, sep_prefix, dK, dV, farK, farV, piece_tab, wpg, (int)band_grid);
     }
     if (hipGetLastError() != hipSuccess) return SEPATTN_ERR_HIP;
     ProfScope prof(SEPATTN_K_BWD_COMBINE, st);
     const int rows_per_block = 256 / (D / 4);
     hipLaunchKernelGGL((dkv_combine_kernel<D>), dim3((fg.NFcap + rows_per_block - 1) / rows_per_block, p.B * p.Hkv),
-                       dim3(256), 0, st, p, sep_idx, sep_prefix, dK, dV, farK, farV);
+                       dim3(256), 0, st, p, sep_idx, sep_prefix, dK, dV, farK, farV, piece_tab, wpg);
     return launch_status();
 }
 
@@ -624,9 +699,9 @@ int launch_dkv(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
 int launch_dkv_bf16(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
                     const float *lse2, const uint16_t *dO, const float *Dws, const int32_t *sep_idx,
                     const int32_t *sep_prefix, uint16_t *dK, uint16_t *dV, float *farK, float *farV,
-                    hipStream_t st) {
-    if (p.d == 64) return launch_dkv<64>(p, Q, K, V, lse2, dO, Dws, sep_idx, sep_prefix, dK, dV, farK, farV, st);
-    return launch_dkv<128>(p, Q, K, V, lse2, dO, Dws, sep_idx, sep_prefix, dK, dV, farK, farV, st);
+                    int32_t *piece_tab, hipStream_t st) {
+    if (p.d == 64) return launch_dkv<64>(p, Q, K, V, lse2, dO, Dws, sep_idx, sep_prefix, dK, dV, farK, farV, piece_tab, st);
+    return launch_dkv<128>(p, Q, K, V, lse2, dO, Dws, sep_idx, sep_prefix, dK, dV, farK, farV, piece_tab, st);
 }
 
 }  // namespace sepattn

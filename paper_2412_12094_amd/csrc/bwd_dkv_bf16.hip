@@ -71,14 +71,14 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
     constexpr int KSTEPS = D / 16;
     constexpr int DB = D / 32;
     constexpr int TILE = kBQ * D;
-    constexpr int NBUF = 3;
+    constexpr int NBUF = 4;
     static_assert(LOADS >= 1 && LOADS * RPL * NW == kBQ, "tile must divide among the waves");
 
     __shared__ __attribute__((aligned(1024))) uint16_t Qs[NBUF][TILE];
     __shared__ __attribute__((aligned(1024))) uint16_t dOs[NBUF][TILE];
     __shared__ __attribute__((aligned(256))) float lse_s[NBUF][kBQ];
     __shared__ __attribute__((aligned(256))) float d_s[NBUF][kBQ];
-    __shared__ __attribute__((aligned(1024))) float Pex[kDkvWaves][2][4][64 * 4];  // [key block][qb][reg/4][lane*4]
+    __shared__ __attribute__((aligned(1024))) uint16_t Pex[kDkvWaves][2][2][64 * 8];  // [key block][step parity][k-half][lane*8], bf16
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -253,10 +253,29 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[db][i] = 0.f;
 
+        // The piece as a sequence of steps; in every step a wave works on one block of 32 query rows.
+        // Far piece: block s of its tiles in step s.  Band unit: a key block of 32 keys needs only NBK
+        // of the nbh blocks of a head (the queries j <= i < j+n of its keys), key block kb the blocks
+        // kb .. kb+NBK-1; all waves walk through a head's blocks together, but the last ov = nbh-NBK
+        // steps of a head are merged with the first ov steps of the next head: in merged step b the
+        // key blocks kb > b finish the old head (block NBK+b, which the others cannot see) while the
+        // key blocks kb <= b start the new one (block b, which the others cannot see either: its
+        // queries come before their keys).  A head then costs NBK steps instead of nbh.
         const int n_tiles = n_items;
-        const int n_blocks = 2 * n_tiles;
+        const int nbh = FAR ? 2 * n_tiles : 2 * n_qt;            // blocks per "head" (a far piece is one run)
+        const int NBK = (p.n + 30) / 32 + 1;
+        // steps from one head's start to the next's: at least NBK; at most kDkvWaves-1 merged steps;
+        // and more than half a head, so that a head's tail only overlaps the head that follows it and
+        // the ring of NBUF tiles always holds what two consecutive steps need
+        int st_P = NBK > nbh / 2 + 1 ? NBK : nbh / 2 + 1;
+        st_P = st_P > nbh - (kDkvWaves - 1) ? st_P : nbh - (kDkvWaves - 1);
+        if (FAR || st_P > nbh) st_P = nbh;
+        const int st_ov = nbh - st_P;                            // 0 .. kDkvWaves-1
+        const int st_G = FAR ? 1 : G;
+        const int n_blocks = (st_G - 1) * st_P + nbh;            // steps of the piece
+        const int tiles_per_head = FAR ? 0 : n_qt;
 
-        // tile tt -> LDS buffer tt%3: wave w fills rows (LOADS*w + u)*RPL .. +RPL-1 with one wave-wide
+        // tile tt -> LDS buffer tt%4: wave w fills rows (LOADS*w + u)*RPL .. +RPL-1 with one wave-wide
         // direct load per tensor; a lane owns physical chunk lane%CH of its row and fetches the
         // logical chunk the permutation maps there.  Rows past the sequence end are clamped (they are
         // masked by the [lo, hi] test: hi <= L-1).  Tiles are issued in order; (iss_g, iss_qt) is the
@@ -287,41 +306,98 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
                 ++iss_g;
             }
         };
-        // wait until at most the loads of one tile (the newest) are still in flight; they complete
-        // in the order they were issued
-        auto wait_all_but_newest_tile = [&](bool newest_issued) {
-            if (!newest_issued) {
+        // wait until at most the loads of the n_out newest tiles are still in flight (loads complete in
+        // the order they were issued; a wave issues 2*LOADS loads per tile, the first two waves one more)
+        static_assert(LOADS == 1 || LOADS == 2, "wait counts below are written for 1 or 2 loads per tensor");
+        auto wait_tiles = [&](int n_out) __attribute__((always_inline)) {
+            constexpr int LW = 2 * LOADS;
+            if (n_out <= 0) {
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            } else if (extra_load) {
-                if constexpr (LOADS == 1)
-                    asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
-                else
-                    asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+            } else if (n_out == 1) {
+                if (extra_load) {
+                    if constexpr (LW == 2) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+                    else asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+                } else {
+                    if constexpr (LW == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+                    else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+                }
+            } else if (n_out == 2) {
+                if (extra_load) {
+                    if constexpr (LW == 2) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+                    else asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+                } else {
+                    if constexpr (LW == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+                    else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+                }
             } else {
-                if constexpr (LOADS == 1)
-                    asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-                else
-                    asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+                if (extra_load) {
+                    if constexpr (LW == 2) asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
+                    else asm volatile("s_waitcnt vmcnt(15)" ::: "memory");
+                } else {
+                    if constexpr (LW == 2) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+                    else asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+                }
             }
         };
-        static_assert(LOADS == 1 || LOADS == 2, "wait counts above are written for 1 or 2 loads per tensor");
 
-        // ---- per-block pieces.  Block gb = 2*tile + half covers 32 query rows starting at r0.
+        // ---- per-step pieces.  (st_g, st_b) is the step handed out last: head st_g (the one that was
+        // started last), block st_b of it; the block a wave works on in that step follows from the
+        // merging rule above.  Tiles are numbered in load order (head-major).
         struct Blk {
-            int buf, qb, r0;
+            int buf, qb, r0, ps;
             uint32_t off;  // byte offset of the block's first row from the start of the ring
             bool full;     // every (query, key) pair of the block is visible: no mask test needed
         };
-        int blk_qt = item0 % n_qt;  // query tile (within its head) of the block handed out next
-        auto next_block = [&](int gb) {
+        int st_g = 0, st_b = -1, st_n = -1;  // st_n: number of the step handed out last
+        int st_base = 0;                     // st_g * tiles_per_head
+        int blk_qt = item0 % n_qt;           // far piece: query tile (within its head) of the next block
+        // lowest and highest tile any wave works on in step (head g, block b); base = g * tiles_per_head
+        auto step_tiles = [&](int g, int b, int base, int &lo_t, int &hi_t) __attribute__((always_inline)) {
+            const int own = base + (b >> 1);
+            lo_t = hi_t = own;
+            if (g > 0 && b < st_ov) {
+                const int old = base - tiles_per_head + ((b + st_P) >> 1);
+                lo_t = old;
+                if (g == st_G) hi_t = old;
+            }
+        };
+        int lo_cur = 0, hi_cur = 0, hi_next = 0;  // tiles of the step handed out last; highest of the one after
+        int hi_landed = 0;                        // highest tile this wave has waited for
+        auto next_block = [&]() __attribute__((always_inline)) {
+            ++st_n;
+            if (++st_b == st_P) {
+                st_b = 0;
+                ++st_g;
+                st_base += tiles_per_head;
+            }
             Blk k;
-            k.qb = gb & 1;
-            k.buf = (gb >> 1) % NBUF;
+            int tile_lin;
+            if (FAR) {
+                k.qb = st_b & 1;
+                tile_lin = st_b >> 1;
+                k.r0 = q_lo + blk_qt * kBQ + 32 * k.qb;
+                if (k.qb == 1 && ++blk_qt == n_qt) blk_qt = 0;
+                lo_cur = hi_cur = tile_lin;
+                hi_next = (st_b + 1) >> 1;
+            } else {
+                const bool prev = st_g > 0 && st_b < st_ov && (kbw > st_b || st_g == st_G);
+                const int blk = prev ? st_b + st_P : st_b;
+                k.qb = blk & 1;
+                tile_lin = (prev ? st_base - tiles_per_head : st_base) + (blk >> 1);
+                k.r0 = q_lo + 32 * blk;
+                step_tiles(st_g, st_b, st_base, lo_cur, hi_cur);
+                int lo_unused;
+                if (st_b + 1 == st_P)
+                    step_tiles(st_g + 1, 0, st_base + tiles_per_head, lo_unused, hi_next);
+                else
+                    step_tiles(st_g, st_b + 1, st_base, lo_unused, hi_next);
+            }
+            if (st_n + 1 >= n_blocks) hi_next = n_tiles - 1;
+            k.ps = st_n & 1;
+            k.buf = tile_lin % NBUF;
             k.off = (uint32_t)k.buf * (TILE * 2) + (uint32_t)k.qb * (32 * D * 2);
-            k.r0 = q_lo + blk_qt * kBQ + 32 * k.qb;
             const int r1 = k.r0 + 31;
             k.full = (k.r0 >= lo_max) && (r1 <= hi_min);
-            if (k.qb == 1 && ++blk_qt == n_qt) blk_qt = 0;
             return k;
         };
         // fragment reads by precomputed address: one vector instruction per read forms the address
@@ -432,11 +508,9 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
                 rv[8 * half + 4] = l1.x, rv[8 * half + 5] = l1.y, rv[8 * half + 6] = l1.z, rv[8 * half + 7] = l1.w;
             }
         };
-        // P-wave: P = exp2(S*scale*log2e - LSE*log2e), zero where masked; handed to the dS-wave
-        auto softmax_and_publish = [&](const Blk &k, f32x16 &x) {
-#ifdef SEPATTN_X_NOSM
-            return;
-#endif
+        // P-wave: P = exp2(S*scale*log2e - LSE*log2e), zero where masked, rounded to bf16 (the form its
+        // own second contraction needs) and handed to the dS-wave in that form
+        auto softmax_and_publish = [&](const Blk &k, f32x16 &x, bf16x8 (&xb)[2]) __attribute__((always_inline)) {
             float ls[16];
             read_rowvals(k, ls);
 #pragma unroll
@@ -448,82 +522,80 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
                     x[i] = (lo <= iqr && iqr <= hi) ? x[i] : 0.f;
                 }
             }
-            float *pex = &Pex[kbw][k.qb][0][lane * 4];
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                f32x4 v4 = {x[4 * g4], x[4 * g4 + 1], x[4 * g4 + 2], x[4 * g4 + 3]};
-                *reinterpret_cast<f32x4 *>(pex + g4 * 256) = v4;
-            }
+            xb[0] = pack_bf16x8(x, 0);
+            xb[1] = pack_bf16x8(x, 8);
+            *reinterpret_cast<bf16x8 *>(&Pex[kbw][k.ps][0][lane * 8]) = xb[0];
+            *reinterpret_cast<bf16x8 *>(&Pex[kbw][k.ps][1][lane * 8]) = xb[1];
         };
         // dS-wave: dS = P (dP - D)
-        auto fetch_p_and_form_ds = [&](const Blk &k, f32x16 &x) {
-#ifdef SEPATTN_X_NOSM
-            return;
-#endif
+        auto fetch_p_and_form_ds = [&](const Blk &k, f32x16 &x) __attribute__((always_inline)) {
             float dd[16];
             read_rowvals(k, dd);
-            const float *pex = &Pex[kbw][k.qb][0][lane * 4];
 #pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                const f32x4 p4 = *reinterpret_cast<const f32x4 *>(pex + g4 * 256);
+            for (int h = 0; h < 2; ++h) {
+                const u32x4 pw = *reinterpret_cast<const u32x4 *>(&Pex[kbw][k.ps][h][lane * 8]);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) x[4 * g4 + e] = p4[e] * (x[4 * g4 + e] - dd[4 * g4 + e]);
+                for (int e = 0; e < 4; ++e) {
+                    const float p_lo = __uint_as_float(pw[e] << 16), p_hi = __uint_as_float(pw[e] & 0xFFFF0000u);
+                    x[8 * h + 2 * e] = p_lo * (x[8 * h + 2 * e] - dd[8 * h + 2 * e]);
+                    x[8 * h + 2 * e + 1] = p_hi * (x[8 * h + 2 * e + 1] - dd[8 * h + 2 * e + 1]);
+                }
             }
         };
-        // barrier after the first contraction (and publication of P) of block gb; the barrier of a
-        // tile's second block also publishes the next tile: every wave has waited for its own share
-        auto block_barrier = [&](int gb) {
+        // Barrier after the first contraction (and publication of P) of the step handed out last.  The
+        // interval after it reads the blocks of that step (second contraction) and of the next one
+        // (first contraction): every wave first waits for its share of the tiles the next step needs,
+        // and after the barrier the buffers of the tiles below the lowest one still in use are refilled.
+        auto block_barrier = [&]() __attribute__((always_inline)) {
 #ifdef SEPATTN_X_TIMING
             const unsigned long long tt0 = clock64();
 #endif
-            if (gb & 1) wait_all_but_newest_tile(iss_tt > (gb >> 1) + 2);  // tile (gb>>1)+2 is in flight
+            if (hi_next != hi_landed) {
+                wait_tiles(iss_tt - 1 - hi_next);
+                hi_landed = hi_next;
+            }
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #ifdef SEPATTN_X_TIMING
             const unsigned long long tt1 = clock64();
 #endif
-#ifndef SEPATTN_X_NOBAR
             __builtin_amdgcn_s_barrier();
-#endif
 #ifdef SEPATTN_X_TIMING
             const unsigned long long tt2 = clock64();
             tw_acc += tt1 - tt0;
             tb_acc += tt2 - tt1;
 #endif
-            // after the first barrier of tile tt nobody reads tile tt-1 any more: refill its buffer
-            if (!(gb & 1) && iss_tt < n_tiles) issue_tile();
+            while (iss_tt < n_tiles && iss_tt - NBUF < lo_cur) issue_tile();
         };
 
-        issue_tile();
-        if (n_tiles > 1) issue_tile();
-        wait_all_but_newest_tile(n_tiles > 1);
+        // start-up: the ring is filled, step 0 needs tile 0 only
+        while (iss_tt < n_tiles && iss_tt < NBUF) issue_tile();
+        wait_tiles(iss_tt - 1);
         __builtin_amdgcn_s_barrier();
 
-        // ---- software pipeline over blocks.  Between the barriers of blocks gb and gb+1 a wave runs
-        // the second contraction of block gb and the first of block gb+1, with the LDS operands of
-        // both requested up front; the P-wave puts its softmax arithmetic last (it overlaps the other
-        // wave's MFMAs on the same SIMD), the dS-wave puts its arithmetic first.
-        // Every wave runs every block of the unit, also blocks in which its keys see no query (their
-        // P is zero through the mask): the waves meet at a barrier per block anyway, and a loop body
-        // without per-block alternatives keeps the accumulators in place.
+        // ---- software pipeline over the steps.  Between the barriers of steps s and s+1 a wave runs
+        // the second contraction of its block of step s and the first of its block of step s+1, with
+        // the LDS operands of both requested up front; the P-wave puts its softmax arithmetic last (it
+        // overlaps the other wave's MFMAs on the same SIMD), the dS-wave puts its arithmetic first.
+        // A wave also runs the blocks of a far piece or of its head in which its keys see no query
+        // (their P is zero through the mask): the waves meet at a barrier per step anyway, and a loop
+        // body without alternatives keeps the accumulators in place.
         auto pipeline = [&](auto ROLE) {
             constexpr int R = ROLE;
             f32x16 x;
-            Blk cur = next_block(0);
+            bf16x8 xb[2];
+            Blk cur = next_block();
             {
                 bf16x8 afr[KSTEPS];
                 read_rows(cur, afr);
                 gemm1(afr, x);
-                if constexpr (R == 0) softmax_and_publish(cur, x);
+                if constexpr (R == 0) softmax_and_publish(cur, x, xb);
             }
-            block_barrier(0);
+            block_barrier();
             for (int gb = 0; gb + 1 < n_blocks; ++gb) {
-                const Blk nxt = next_block(gb + 1);
-                bf16x8 xb[2];
+                const Blk nxt = next_block();
                 if constexpr (R == 0) {
-                    xb[0] = pack_bf16x8(x, 0);
-                    xb[1] = pack_bf16x8(x, 8);
                     gemm2_then_gemm1(cur, xb, nxt, x);
-                    softmax_and_publish(nxt, x);
+                    softmax_and_publish(nxt, x, xb);
                 } else {
                     bf16x8 a0[KSTEPS / 2], a1[KSTEPS / 2];
                     read_rows_halves(nxt, a0, a1);  // in flight during the dS arithmetic
@@ -533,15 +605,17 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
                     __builtin_amdgcn_sched_barrier(0);
                     gemm1_then_gemm2(nxt, a0, a1, x, cur, xb);
                 }
-                block_barrier(gb + 1);
+                block_barrier();
                 cur = nxt;
             }
             {
-                bf16x8 tfr[2][DB], xb[2];
+                bf16x8 tfr[2][DB];
                 read_transposed(cur, tfr);
-                if constexpr (R == 1) fetch_p_and_form_ds(cur, x);
-                xb[0] = pack_bf16x8(x, 0);
-                xb[1] = pack_bf16x8(x, 8);
+                if constexpr (R == 1) {
+                    fetch_p_and_form_ds(cur, x);
+                    xb[0] = pack_bf16x8(x, 0);
+                    xb[1] = pack_bf16x8(x, 8);
+                }
                 gemm2(tfr, xb);
             }
         };

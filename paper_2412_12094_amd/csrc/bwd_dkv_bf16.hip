@@ -340,64 +340,61 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
             }
         };
 
-        // ---- per-step pieces.  (st_g, st_b) is the step handed out last: head st_g (the one that was
-        // started last), block st_b of it; the block a wave works on in that step follows from the
-        // merging rule above.  Tiles are numbered in load order (head-major).
+        // ---- per-step pieces.  What a wave needs to know about a step (the LDS offset of its block, the
+        // block's first query row, whether the block needs the mask test, which tiles the step and its
+        // successor touch) is computed for 64 steps at a time, one step per lane, and fetched with
+        // three v_readlane per step: scalar bookkeeping inside the loop costs issue slots that the
+        // matrix instructions need.  Tiles are numbered in load order (head-major).
         struct Blk {
-            int buf, qb, r0, ps;
-            uint32_t off;  // byte offset of the block's first row from the start of the ring
-            bool full;     // every (query, key) pair of the block is visible: no mask test needed
+            int r0, ps, rv;  // first query row; parity of the step (P exchange slot); float offset of the row values
+            uint32_t off;    // byte offset of the block's first row from the start of the ring
+            bool full;       // every (query, key) pair of the block is visible: no mask test needed
         };
-        int st_g = 0, st_b = -1, st_n = -1;  // st_n: number of the step handed out last
-        int st_base = 0;                     // st_g * tiles_per_head
-        int blk_qt = item0 % n_qt;           // far piece: query tile (within its head) of the next block
-        // lowest and highest tile any wave works on in step (head g, block b); base = g * tiles_per_head
-        auto step_tiles = [&](int g, int b, int base, int &lo_t, int &hi_t) __attribute__((always_inline)) {
-            const int own = base + (b >> 1);
-            lo_t = hi_t = own;
-            if (g > 0 && b < st_ov) {
-                const int old = base - tiles_per_head + ((b + st_P) >> 1);
-                lo_t = old;
-                if (g == st_G) hi_t = old;
-            }
+        const int q0_tile = item0 % n_qt;
+        // step s: the tile and block this wave (key block kbw) works on, lowest / highest tile of any wave
+        auto step_of = [&](int s, int &tile, int &blk, int &lo_t, int &hi_t) __attribute__((always_inline)) {
+            const int g = s / st_P, b = s - g * st_P;
+            const int base_t = g * tiles_per_head;
+            const bool mg = g > 0 && b < st_ov;
+            const int own = base_t + (b >> 1), old = base_t - tiles_per_head + ((b + st_P) >> 1);
+            const bool prev = mg && (kbw > b || g == st_G);
+            tile = prev ? old : own;
+            blk = prev ? b + st_P : b;
+            lo_t = mg ? old : own;
+            hi_t = (mg && g == st_G) ? old : own;
         };
-        int lo_cur = 0, hi_cur = 0, hi_next = 0;  // tiles of the step handed out last; highest of the one after
+        uint32_t sch_off = 0;
+        int sch_r0 = 0, sch_t = 0;
+        auto fill_schedule = [&](int first) __attribute__((always_inline)) {
+            const int sidx = first + lane;
+            int tile, blk, lo_t, hi_t, tile_n, blk_n, lo_n, hi_n;
+            step_of(sidx, tile, blk, lo_t, hi_t);
+            step_of(sidx + 1, tile_n, blk_n, lo_n, hi_n);
+            if (sidx + 1 >= n_blocks) hi_n = n_tiles - 1;
+            const int buf = tile % NBUF, qb = blk & 1;
+            const int r0 = q_lo + ((q0_tile + (blk >> 1)) % n_qt) * kBQ + 32 * qb;
+            const bool full = (r0 >= lo_max) && (r0 + 31 <= hi_min);
+            sch_off = (uint32_t)buf * (TILE * 2) + (uint32_t)qb * (32 * D * 2);
+            sch_r0 = r0 | (buf << 2) | (qb << 1) | (full ? 1 : 0);  // r0 is a multiple of 32
+            sch_t = (lo_t << 2) | max(0, min(hi_n - lo_t, 3));
+        };
+        int st_n = -1;                            // number of the step handed out last
+        int lo_cur = 0, hi_next = 0;              // lowest tile of that step; highest tile of the step after it
         int hi_landed = 0;                        // highest tile this wave has waited for
         auto next_block = [&]() __attribute__((always_inline)) {
             ++st_n;
-            if (++st_b == st_P) {
-                st_b = 0;
-                ++st_g;
-                st_base += tiles_per_head;
-            }
+            const int l = st_n & 63;
+            if (l == 0) fill_schedule(st_n);
             Blk k;
-            int tile_lin;
-            if (FAR) {
-                k.qb = st_b & 1;
-                tile_lin = st_b >> 1;
-                k.r0 = q_lo + blk_qt * kBQ + 32 * k.qb;
-                if (k.qb == 1 && ++blk_qt == n_qt) blk_qt = 0;
-                lo_cur = hi_cur = tile_lin;
-                hi_next = (st_b + 1) >> 1;
-            } else {
-                const bool prev = st_g > 0 && st_b < st_ov && (kbw > st_b || st_g == st_G);
-                const int blk = prev ? st_b + st_P : st_b;
-                k.qb = blk & 1;
-                tile_lin = (prev ? st_base - tiles_per_head : st_base) + (blk >> 1);
-                k.r0 = q_lo + 32 * blk;
-                step_tiles(st_g, st_b, st_base, lo_cur, hi_cur);
-                int lo_unused;
-                if (st_b + 1 == st_P)
-                    step_tiles(st_g + 1, 0, st_base + tiles_per_head, lo_unused, hi_next);
-                else
-                    step_tiles(st_g, st_b + 1, st_base, lo_unused, hi_next);
-            }
-            if (st_n + 1 >= n_blocks) hi_next = n_tiles - 1;
+            k.off = __builtin_amdgcn_readlane(sch_off, l);
+            const int r0p = __builtin_amdgcn_readlane(sch_r0, l);
+            const int tp = __builtin_amdgcn_readlane(sch_t, l);
+            k.r0 = r0p & ~31;
+            k.full = r0p & 1;
+            k.rv = ((r0p >> 2) & 3) * kBQ + ((r0p >> 1) & 1) * 32;
             k.ps = st_n & 1;
-            k.buf = tile_lin % NBUF;
-            k.off = (uint32_t)k.buf * (TILE * 2) + (uint32_t)k.qb * (32 * D * 2);
-            const int r1 = k.r0 + 31;
-            k.full = (k.r0 >= lo_max) && (r1 <= hi_min);
+            lo_cur = tp >> 2;
+            hi_next = lo_cur + (tp & 3);
             return k;
         };
         // fragment reads by precomputed address: one vector instruction per read forms the address
@@ -498,10 +495,10 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
         };
         // the sixteen per-row values (LSE*log2e or D) of the block's rows held by this lane
         auto read_rowvals = [&](const Blk &k, float (&rv)[16]) {
-            const float *rowval = role == 0 ? lse_s[k.buf] : d_s[k.buf];
+            const float *rowval = (role == 0 ? &lse_s[0][0] : &d_s[0][0]) + k.rv;
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
-                const int base = k.qb * 32 + 16 * half + 8 * hh;
+                const int base = 16 * half + 8 * hh;
                 const float4 l0 = *reinterpret_cast<const float4 *>(rowval + base);
                 const float4 l1 = *reinterpret_cast<const float4 *>(rowval + base + 4);
                 rv[8 * half + 0] = l0.x, rv[8 * half + 1] = l0.y, rv[8 * half + 2] = l0.z, rv[8 * half + 3] = l0.w;

@@ -61,7 +61,9 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
     constexpr int LOADS = kBN / (RPL * NW);
     constexpr int KSTEPS = D / 16;
     constexpr int DB = D / 32;
-    constexpr int KST = 3, VST = 3, MKS = 3;  // LDS stages of K, of V, and of the visibility ranges
+    // LDS stages of K, of V, and of the visibility ranges: powers of two, so that a stage number is
+    // a mask of the tile number (the kernels spend their time issuing instructions, scalar ones too)
+    constexpr int KST = 4, VST = 4, MKS = 4;
     constexpr int TILE = kBN * D;
     static_assert(LOADS >= 1 && LOADS * RPL * NW == kBN, "tile must divide among the waves");
 
@@ -123,11 +125,11 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
         const int e = min(max(ss.sep_lo - ss.n_init + k, 0), p.cap - 1);
         const int j = min(max(ss.bs - ss.n_dense + k, 0), p.L - 1);
         const int32_t *src = m_part == 0 ? idx + e : prefix + j + (m_part - 1);
-        if (lane < 3 * MR) dma_to_lds_4_addr(src, lds_addr(&meta_s[g % MST][wave][0]));
+        if (lane < 3 * MR) dma_to_lds_4_addr(src, lds_addr(&meta_s[(unsigned)g % MST][wave][0]));
     };
     int jrow[LOADS], rawi[LOADS], raw0[LOADS], raw1[LOADS];
     auto read_entries = [&](int g) __attribute__((always_inline)) {
-        const int *mt = &meta_s[g % MST][wave][0];
+        const int *mt = &meta_s[(unsigned)g % MST][wave][0];
         static_for<LOADS>([&](auto U) {
             constexpr int u = U;
             rawi[u] = mt[u * RPL + my_sub];
@@ -137,7 +139,7 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
     };
     auto prepare_row = [&](const Stream &ss, int t, int g, auto U) __attribute__((always_inline)) {
         constexpr int u = decltype(U)::value;
-        const int ms_ = g % MKS;
+        const int ms_ = (unsigned)g % MKS;
         const int r = rrow[u];
         const int k = t * kBN + r;
         // the clamp keeps a stale list tail (caller broke sep_count <= cap) from faulting
@@ -162,7 +164,7 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
     };
     auto issue_row = [&](int g, auto U) __attribute__((always_inline)) {
         constexpr int u = decltype(U)::value;
-        const uint32_t kst = lds_addr(&Ks[g % KST][0]), vst = lds_addr(&Vs[g % VST][0]);
+        const uint32_t kst = lds_addr(&Ks[(unsigned)g % KST][0]), vst = lds_addr(&Vs[(unsigned)g % VST][0]);
         const uint32_t wave_off = (uint32_t)((LOADS * wave + u) * RPL * D * 2);
         const uint32_t row_off = (uint32_t)jrow[u] * (uint32_t)(D * 2);
         dma_to_lds_16(Kb, row_off + kgo[u], kst + wave_off);
@@ -258,8 +260,8 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
     auto block_step = [&](int X, auto HB_, auto LD_) __attribute__((always_inline)) {
         constexpr int HB = decltype(HB_)::value;
         constexpr bool DO_LD = decltype(LD_)::value != 0;
-        const uint32_t kst = ks_base + ((gbase + X) % KST) * (TILE * 2) + HB * 32 * D * 2;
-        const uint32_t vst = vs_base + ((gbase + X) % VST) * (TILE * 2) + HB * 32 * D * 2;
+        const uint32_t kst = ks_base + ((unsigned)(gbase + X) % KST) * (TILE * 2) + HB * 32 * D * 2;
+        const uint32_t vst = vs_base + ((unsigned)(gbase + X) % VST) * (TILE * 2) + HB * 32 * D * 2;
         f32x16 sacc, pacc;
         bf16x8 frag[LA];
         auto request1 = [&](auto S) __attribute__((always_inline)) {
@@ -308,7 +310,7 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
         for (int db = 0; db < DB; ++db) tfr[db] = lds_read_tr_at2(kst + ktr0[db], tr_second(kst + ktr0[db], db));
         // dS = P (dP - D), zero where masked
         if (!block_is_full(fullb, X * kBN + HB * 32)) {
-            const int ms_ = (gbase + X) % MKS;
+            const int ms_ = (unsigned)(gbase + X) % MKS;
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
                 const int base = HB * 32 + 16 * half + 8 * hh;

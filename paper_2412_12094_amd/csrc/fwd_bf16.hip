@@ -58,7 +58,9 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     constexpr int LOADS = kBN / (RPL * NW);  // wave-wide loads per wave per tensor per tile
     constexpr int KSTEPS = D / 16;
     constexpr int DB = D / 32;
-    constexpr int KST = 3, VST = 4;  // LDS stages of K, and of V and the visibility ranges
+    // LDS stages of K, and of V and the visibility ranges: powers of two, so that a stage number is a
+    // mask of the tile number (the kernel spends its time issuing instructions, scalar ones too)
+    constexpr int KST = 4, VST = 4;
     constexpr int TILE = kBN * D;    // elements per LDS tile (unpadded, XOR-swizzled chunks)
     static_assert(LOADS >= 1 && LOADS * RPL * NW == kBN, "tile must divide among the waves");
 
@@ -148,7 +150,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
         const int e = min(max(ss.sep_lo - ss.n_init + k, 0), p.cap - 1);
         const int j = min(max(ss.bs - ss.n_dense + k, 0), p.L - 1);
         const int32_t *src = m_part == 0 ? idx + e : prefix + j + (m_part - 1);
-        if (lane < 3 * MR) dma_to_lds_4_addr(src, lds_addr(&meta_s[g % MST][wave][0]));
+        if (lane < 3 * MR) dma_to_lds_4_addr(src, lds_addr(&meta_s[(unsigned)g % MST][wave][0]));
     };
     // Rows of a tile in two steps, so that the index entries of the NEXT tile can be requested in
     // between: vector-memory results return in issue order, and with the order
@@ -157,7 +159,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     // visible), which keeps the count of outstanding loads exact in a loop body without alternatives.
     int jrow[LOADS], rawi[LOADS], raw0[LOADS], raw1[LOADS];
     auto read_entries = [&](int g) __attribute__((always_inline)) {
-        const int *mt = &meta_s[g % MST][wave][0];
+        const int *mt = &meta_s[(unsigned)g % MST][wave][0];
         static_for<LOADS>([&](auto U) {
             constexpr int u = U;
             rawi[u] = mt[u * RPL + my_sub];
@@ -167,7 +169,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     };
     auto prepare_row = [&](const Stream &ss, int t, int g, auto U) __attribute__((always_inline)) {
         constexpr int u = decltype(U)::value;
-        const int vs_ = g % VST;
+        const int vs_ = (unsigned)g % VST;
         const int r = rrow[u];
         const int k = t * kBN + r;
         // the clamp keeps a stale list tail (caller broke sep_count <= cap) from faulting
@@ -192,7 +194,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     };
     auto issue_row = [&](int g, auto U) __attribute__((always_inline)) {
         constexpr int u = decltype(U)::value;
-        const uint32_t kst = lds_addr(&Ks[g % KST][0]), vst = lds_addr(&Vs[g % VST][0]);
+        const uint32_t kst = lds_addr(&Ks[(unsigned)g % KST][0]), vst = lds_addr(&Vs[(unsigned)g % VST][0]);
         const uint32_t wave_off = (uint32_t)((LOADS * wave + u) * RPL * D * 2);  // bytes: 1 KB per wave-wide load
         const uint32_t row_off = (uint32_t)jrow[u] * (uint32_t)(D * 2);
         dma_to_lds_16(Kb, row_off + kgo[u], kst + wave_off);
@@ -311,7 +313,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
             sm.masked = false;
 #endif
             if (sm.masked) {
-                const int vs_ = gtile % VST;
+                const int vs_ = (unsigned)gtile % VST;
 #pragma unroll
                 for (int half = 0; half < 2; ++half) {
                     const int base = kb * 32 + 16 * half + 8 * hh;
@@ -409,8 +411,8 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
                 for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha_pending;
             alpha_pending = 1.f;
         }
-        const uint32_t vst = vs_base + ((gbase + X + VST - 1) % VST) * (TILE * 2) + HB * 32 * D * 2;
-        const uint32_t kst = ks_base + ((gbase + X) % KST) * (TILE * 2) + HB * 32 * D * 2;
+        const uint32_t vst = vs_base + ((unsigned)(gbase + X + VST - 1) % VST) * (TILE * 2) + HB * 32 * D * 2;
+        const uint32_t kst = ks_base + ((unsigned)(gbase + X) % KST) * (TILE * 2) + HB * 32 * D * 2;
         uint32_t va_[DB], ka_[KSTEPS];
 #pragma unroll
         for (int db = 0; db < DB; ++db) va_[db] = vst + voff[db];

@@ -6,7 +6,7 @@
 //
 // Three launches, no floating-point atomics (results are bit-reproducible):
 //  1. dq_kernel (this file): persistent workgroups over the query tiles, same dense key stream as the forward
-//     [initial | separators older than the window | band].  Also writes D_i and LSE_i*log2(e).
+//     [initial | separators older than the window | band].  Also writes -D_i and LSE_i*log2(e).
 //  2. dkv_kernel (bwd_dkv_bf16.hip): the visible pairs split into band pairs (i-j < n) and far
 //     pairs (i-j >= n, j an initial token or a separator); far units work on the COMPACTED list of
 //     such keys and write fp32 partials, band units finish the keys that are not on that list.
@@ -385,7 +385,8 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
             const uint32_t soff = (uint32_t)min(iq, p.L - 1) * 4u;
             lse2 = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(LSE + head_row0) + soff) * kLog2e_f;
             if (hh == 0 && iq < p.L) {
-                *reinterpret_cast<float *>(reinterpret_cast<char *>(Dws + head_row0) + soff) = Di;
+                // stored negated: the dK/dV kernel starts its dP accumulator from -D
+                *reinterpret_cast<float *>(reinterpret_cast<char *>(Dws + head_row0) + soff) = -Di;
                 // the dK/dV kernels work in the log2 domain too
                 *reinterpret_cast<float *>(reinterpret_cast<char *>(Lws + head_row0) + soff) = lse2;
             }

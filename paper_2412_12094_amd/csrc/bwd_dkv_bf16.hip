@@ -453,11 +453,11 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
             for (int ks = 0; ks < KSTEPS / 2; ++ks) x = mfma_bf16(a1[ks], breg[ks + KSTEPS / 2], x);
             __builtin_amdgcn_sched_barrier(0);
         };
-        // xn = T1(nxt) B (fragments a0, a1 already requested), then acc += T2^T(cur) x_b(cur)   (dS-wave order)
+        // xn += T1(nxt) B (fragments a0, a1 already requested; xn comes in holding -D of the block's rows,
+        // so that it leaves as dP - D), then acc += T2^T(cur) x_b(cur)   (dS-wave order)
         auto gemm1_then_gemm2 = [&](const Blk &nxt, const bf16x8 (&a0)[KSTEPS / 2], const bf16x8 (&a1)[KSTEPS / 2],
                                     f32x16 &xn, const Blk &cur, const bf16x8 (&xb)[2]) __attribute__((always_inline)) {
             bf16x8 t0[DB], t1[DB];
-            zero(xn);
 #pragma unroll
             for (int ks = 0; ks < KSTEPS / 2; ++ks) xn = mfma_bf16(a0[ks], breg[ks], xn);
 #pragma unroll
@@ -482,8 +482,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
                 a1[ks] = rd_row(rbase, ks + KSTEPS / 2);
             }
         };
-        auto gemm1 = [&](const bf16x8 (&afr)[KSTEPS], f32x16 &x) {
-            zero(x);
+        auto gemm1 = [&](const bf16x8 (&afr)[KSTEPS], f32x16 &x) {  // x += T1 B
 #pragma unroll
             for (int ks = 0; ks < KSTEPS; ++ks) x = mfma_bf16(afr[ks], breg[ks], x);
         };
@@ -494,7 +493,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
                 for (int db = 0; db < DB; ++db) acc[db] = mfma_bf16(tfr[stp][db], xb[stp], acc[db]);
         };
         // the sixteen per-row values (LSE*log2e or D) of the block's rows held by this lane
-        auto read_rowvals = [&](const Blk &k, float (&rv)[16]) {
+        auto read_rowvals = [&](const Blk &k, f32x16 &rv) __attribute__((always_inline)) {
             const float *rowval = (role == 0 ? &lse_s[0][0] : &d_s[0][0]) + k.rv;
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
@@ -508,7 +507,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
         // P-wave: P = exp2(S*scale*log2e - LSE*log2e), zero where masked, rounded to bf16 (the form its
         // own second contraction needs) and handed to the dS-wave in that form
         auto softmax_and_publish = [&](const Blk &k, f32x16 &x, bf16x8 (&xb)[2]) __attribute__((always_inline)) {
-            float ls[16];
+            f32x16 ls;
             read_rowvals(k, ls);
 #pragma unroll
             for (int i = 0; i < 16; ++i) x[i] = __builtin_amdgcn_exp2f(fmaf(x[i], sl2, -ls[i]));
@@ -524,20 +523,22 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
             *reinterpret_cast<bf16x8 *>(&Pex[kbw][k.ps][0][lane * 8]) = xb[0];
             *reinterpret_cast<bf16x8 *>(&Pex[kbw][k.ps][1][lane * 8]) = xb[1];
         };
-        // dS-wave: dS = P (dP - D)
-        auto fetch_p_and_form_ds = [&](const Blk &k, f32x16 &x) __attribute__((always_inline)) {
-            float dd[16];
-            read_rowvals(k, dd);
+        // dS-wave: dS = P (dP - D); x holds dP - D (the accumulator started from -D), the result is
+        // rounded to bf16 in the form the second contraction needs
+        auto fetch_p_and_form_ds = [&](const Blk &k, const f32x16 &x, bf16x8 (&xb)[2]) __attribute__((always_inline)) {
+            f32x16 ds;
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 const u32x4 pw = *reinterpret_cast<const u32x4 *>(&Pex[kbw][k.ps][h][lane * 8]);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const float p_lo = __uint_as_float(pw[e] << 16), p_hi = __uint_as_float(pw[e] & 0xFFFF0000u);
-                    x[8 * h + 2 * e] = p_lo * (x[8 * h + 2 * e] - dd[8 * h + 2 * e]);
-                    x[8 * h + 2 * e + 1] = p_hi * (x[8 * h + 2 * e + 1] - dd[8 * h + 2 * e + 1]);
+                    ds[8 * h + 2 * e] = p_lo * x[8 * h + 2 * e];
+                    ds[8 * h + 2 * e + 1] = p_hi * x[8 * h + 2 * e + 1];
                 }
             }
+            xb[0] = pack_bf16x8(ds, 0);
+            xb[1] = pack_bf16x8(ds, 8);
         };
         // Barrier after the first contraction (and publication of P) of the step handed out last.  The
         // interval after it reads the blocks of that step (second contraction) and of the next one
@@ -578,41 +579,56 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
         // body without alternatives keeps the accumulators in place.
         auto pipeline = [&](auto ROLE) {
             constexpr int R = ROLE;
-            f32x16 x;
+            f32x16 x, y;  // P-wave: scores (x only); dS-wave: dP - D of the current and of the next block, in turn
             bf16x8 xb[2];
             Blk cur = next_block();
             {
                 bf16x8 afr[KSTEPS];
                 read_rows(cur, afr);
+                if constexpr (R == 0)
+                    zero(x);
+                else
+                    read_rowvals(cur, x);
                 gemm1(afr, x);
                 if constexpr (R == 0) softmax_and_publish(cur, x, xb);
             }
             block_barrier();
-            for (int gb = 0; gb + 1 < n_blocks; ++gb) {
+            // one step of the dS-wave: xc holds dP - D of block cur, xn receives that of block nxt
+            auto ds_step = [&](f32x16 &xc, f32x16 &xn) __attribute__((always_inline)) {
                 const Blk nxt = next_block();
-                if constexpr (R == 0) {
-                    gemm2_then_gemm1(cur, xb, nxt, x);
-                    softmax_and_publish(nxt, x, xb);
-                } else {
-                    bf16x8 a0[KSTEPS / 2], a1[KSTEPS / 2];
-                    read_rows_halves(nxt, a0, a1);  // in flight during the dS arithmetic
-                    fetch_p_and_form_ds(cur, x);
-                    xb[0] = pack_bf16x8(x, 0);
-                    xb[1] = pack_bf16x8(x, 8);
-                    __builtin_amdgcn_sched_barrier(0);
-                    gemm1_then_gemm2(nxt, a0, a1, x, cur, xb);
-                }
+                bf16x8 a0[KSTEPS / 2], a1[KSTEPS / 2];
+                read_rows_halves(nxt, a0, a1);  // in flight during the dS arithmetic
+                read_rowvals(nxt, xn);
+                fetch_p_and_form_ds(cur, xc, xb);
+                __builtin_amdgcn_sched_barrier(0);
+                gemm1_then_gemm2(nxt, a0, a1, xn, cur, xb);
                 block_barrier();
                 cur = nxt;
+            };
+            if constexpr (R == 0) {
+                for (int gb = 0; gb + 1 < n_blocks; ++gb) {
+                    const Blk nxt = next_block();
+                    gemm2_then_gemm1(cur, xb, nxt, x);
+                    softmax_and_publish(nxt, x, xb);
+                    block_barrier();
+                    cur = nxt;
+                }
+            } else {
+                // two steps per trip, so that the two accumulators swap roles without copies
+                int gb = 0;
+                for (; gb + 2 < n_blocks; gb += 2) {
+                    ds_step(x, y);
+                    ds_step(y, x);
+                }
+                if (gb + 1 < n_blocks) {
+                    ds_step(x, y);
+                    x = y;
+                }
             }
             {
                 bf16x8 tfr[2][DB];
                 read_transposed(cur, tfr);
-                if constexpr (R == 1) {
-                    fetch_p_and_form_ds(cur, x);
-                    xb[0] = pack_bf16x8(x, 0);
-                    xb[1] = pack_bf16x8(x, 8);
-                }
+                if constexpr (R == 1) fetch_p_and_form_ds(cur, x, xb);
                 gemm2(tfr, xb);
             }
         };

@@ -99,8 +99,6 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
     const FarList fl = far_list(p, prefix);
     const int a_row = pi_row(kj);
     const int my_pc = lane % CH, my_sub = lane / CH;
-    // loads this wave issues per tile: the first two waves also fetch LSE*log2e and D
-    const bool extra_load = wave < 2;
     // Per-lane byte offsets of the operand fragments inside a tile, computed once.  The first
     // contraction reads rows of T1 (Q for the P-wave, dO for the dS-wave), the second reads the other
     // tensor (T2) transposed.  Row-major fragments: the XOR permutation acts on the 16-byte chunk
@@ -298,8 +296,15 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
                 dma_to_lds_16(Q + hrow0 * D, off, lds_addr(&Qs[buf][wave_off]));
                 dma_to_lds_16(dO + hrow0 * D, off, lds_addr(&dOs[buf][wave_off]));
             });
-            if (wave == 0) dma_to_lds_4(LSE2 + hrow0, (uint32_t)min(qbase + lane, p.L - 1) * 4u, lds_addr(&lse_s[buf][0]));
-            if (wave == 1) dma_to_lds_4(Dws + hrow0, (uint32_t)min(qbase + lane, p.L - 1) * 4u, lds_addr(&d_s[buf][0]));
+            // the 64 + 64 row values (LSE*log2e, -D): sixteen per wave, so that every wave issues the same
+            // number of loads per tile
+            {
+                static_assert(NW == 8 && kBQ == 64, "the row values are dealt to eight waves");
+                const int part = wave & 3;
+                const float *src = (wave < 4 ? LSE2 : Dws) + hrow0;
+                float *dst = wave < 4 ? &lse_s[buf][16 * part] : &d_s[buf][16 * part];
+                if (lane < 16) dma_to_lds_4(src, (uint32_t)min(qbase + 16 * part + lane, p.L - 1) * 4u, lds_addr(dst));
+            }
             ++iss_tt;
             if (++iss_qt == n_qt) {
                 iss_qt = 0;
@@ -307,36 +312,21 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
             }
         };
         // wait until at most the loads of the n_out newest tiles are still in flight (loads complete in
-        // the order they were issued; a wave issues 2*LOADS loads per tile, the first two waves one more)
+        // the order they were issued; every wave issues 2*LOADS + 1 loads per tile)
         static_assert(LOADS == 1 || LOADS == 2, "wait counts below are written for 1 or 2 loads per tensor");
         auto wait_tiles = [&](int n_out) __attribute__((always_inline)) {
-            constexpr int LW = 2 * LOADS;
+            constexpr int LW = 2 * LOADS + 1;
             if (n_out <= 0) {
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             } else if (n_out == 1) {
-                if (extra_load) {
-                    if constexpr (LW == 2) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
-                    else asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
-                } else {
-                    if constexpr (LW == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-                    else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-                }
+                if constexpr (LW == 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
             } else if (n_out == 2) {
-                if (extra_load) {
-                    if constexpr (LW == 2) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-                    else asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
-                } else {
-                    if constexpr (LW == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-                    else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-                }
+                if constexpr (LW == 3) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
             } else {
-                if (extra_load) {
-                    if constexpr (LW == 2) asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
-                    else asm volatile("s_waitcnt vmcnt(15)" ::: "memory");
-                } else {
-                    if constexpr (LW == 2) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-                    else asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
-                }
+                if constexpr (LW == 3) asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(15)" ::: "memory");
             }
         };
 

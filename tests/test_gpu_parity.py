@@ -179,6 +179,8 @@ def check_backward(sp, B, Hq, Hkv, L, d, a, n, p, dtype, seed, qkv_scale=1.0):
     (2, 3, 3, 65, 64, 2, 7, 0.3),
     (1, 8, 1, 130, 64, 1, 9, 0.15),
     (1, 1, 1, 1, 64, 4, 64, 0.0),
+    (1, 4, 1, 900, 64, 2, 33, 0.1),        # GQA 4:1, window of two blocks: band units of several heads, short heads
+    (2, 16, 2, 520, 128, 4, 200, 0.1),     # GQA 8:1, band units cut off by the sequence end
 ])
 def test_backward_matches_oracle(sp, dtype, B, Hq, Hkv, L, d, a, n, p):
     check_backward(sp, B, Hq, Hkv, L, d, a, n, p, dtype, seed=2000 + L + n)

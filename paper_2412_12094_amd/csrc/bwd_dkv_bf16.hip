@@ -283,9 +283,6 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
             const int buf = iss_tt % NBUF;
             const long hrow0 = ((long)b * p.Hq + kv * G + iss_g) * (long)p.L;
             const int qbase = q_lo + iss_qt * kBQ;
-#ifdef SEPATTN_X_NOISSUE
-            if (iss_tt < 2)
-#endif
             static_for<LOADS>([&](auto U) {
                 constexpr int u = U;
                 const int r = (LOADS * wave + u) * RPL + my_sub;

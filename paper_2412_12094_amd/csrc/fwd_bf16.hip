@@ -76,9 +76,6 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps branches scalar
     const int grp = wave >> 2;                                  // waves w and w+4 share a SIMD
     const int qi = lane & 31, hh = lane >> 5;
-#ifdef SEPATTN_X_HALFWAVES
-    if (wave >= 4) return;  // timing experiment: one wave per SIMD
-#endif
     // A workgroup is persistent: it belongs to one (batch, KV head, head group) and walks through
     // several query tiles of it ("segments"), `wpg` workgroups per group sharing the tiles in zig-zag
     // order (round r: rank r*wpg + j for even r, r*wpg + wpg-1-j for odd r; rank 0 = the last tile,
@@ -302,16 +299,8 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     } sm;
     auto softmax_chunk = [&](auto C, f32x16 &s, bf16x8 (&pb)[2], int tile, int gtile, int kb) __attribute__((always_inline)) {
         constexpr int c = decltype(C)::value;
-#ifdef SEPATTN_X_NOSM
-        if constexpr (c == 13) pb[0] = qreg[0];
-        if constexpr (c == 14) pb[1] = qreg[1];
-        return;
-#endif
         if constexpr (c == 0) {
             sm.masked = !block_is_full(fullb, tile * kBN + kb * 32);
-#ifdef SEPATTN_X_SM_NOBR
-            sm.masked = false;
-#endif
             if (sm.masked) {
                 const int vs_ = (unsigned)gtile % VST;
 #pragma unroll
@@ -336,12 +325,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
         } else if constexpr (c == 4) {
             const float m_new = fmaxf(m_run, pair_max(sm.m_loc * sl2));
             const bool grow = m_new > m_run + kRescaleThreshold;
-#ifdef SEPATTN_X_SM_NOBR
-            m_run = fmaxf(m_run, m_new);
-            if (false) {
-#else
             if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
-#endif
                 const float alpha = grow ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.f;
                 m_run = grow ? m_new : m_run;
                 l_run *= alpha;
@@ -354,11 +338,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
             // the transcendental unit have arrived
             if constexpr (c < 13) {
 #pragma unroll
-#ifdef SEPATTN_X_SM_NOEXP
-                for (int i = 2 * (c - 5); i < 2 * (c - 5) + 2; ++i) s[i] = fmaf(s[i], sl2, sm.neg_m) * 0.001f;
-#else
                 for (int i = 2 * (c - 5); i < 2 * (c - 5) + 2; ++i) s[i] = __builtin_amdgcn_exp2f(fmaf(s[i], sl2, sm.neg_m));
-#endif
             }
             if constexpr (c > 5) sm.psum += s[2 * (c - 6)] + s[2 * (c - 6) + 1];
             if constexpr (c == 13) pb[0] = pack_bf16x8(s, 0);
@@ -371,9 +351,6 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     // one piece of the load path: rows of the tile at the cursor, index entries of the tile after it
     auto load_chunk = [&](auto C) __attribute__((always_inline)) {
         constexpr int c = decltype(C)::value;
-#ifdef SEPATTN_X_NOLD
-        return;
-#endif
         if constexpr (c == 0) {
             entries_landed();
             read_entries(l_g);
@@ -421,10 +398,6 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
         bf16x8 frag[LA];
         auto request = [&](auto S) __attribute__((always_inline)) {
             constexpr int s = decltype(S)::value;
-#ifdef SEPATTN_X_NOLDS
-            if constexpr (s < NS) frag[s % LA] = qreg[s % KSTEPS];
-            return;
-#endif
             if constexpr (s < N1) {
                 frag[s % LA] = lds_read_b128_at(ka_[s]);
             } else if constexpr (s < NS) {

@@ -96,17 +96,7 @@ __device__ inline int swz_chunk(int chunk, int row) {
     return MODE == kSwzRow ? (chunk ^ ((row >> 1) & 7)) : (chunk ^ (((row >> 1) & 1) << 2));
 }
 
-__device__ inline void load_to_lds_16(const void *gsrc, void *lds_wave_base) {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
-                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
-}
-// the 4-byte form: lane l's dword lands at (wave-uniform base) + 4*l
-__device__ inline void load_to_lds_4(const void *gsrc, void *lds_wave_base) {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
-                                     (__attribute__((address_space(3))) void *)lds_wave_base, 4, 0, 0);
-}
-
-// The same loads through inline assembly.  For the builtin forms the compiler knows that LDS is
+// Direct global->LDS loads, through inline assembly.  For the builtin forms the compiler knows that LDS is
 // written asynchronously, and since it cannot tell which LDS bytes a later ds_read touches it makes
 // every LDS read wait for ALL outstanding loads (vmcnt(0)), which serialises a prefetch pipeline.
 // These forms are opaque to it: the kernels that use them wait explicitly (s_waitcnt vmcnt(n), loads
@@ -144,8 +134,8 @@ __device__ inline bf16x8 lds_read_a_swz(const uint16_t *tile, int row, int chunk
     return *reinterpret_cast<const bf16x8 *>(tile + row * D + swz_chunk<MODE, D>(chunk, row) * 8);
 }
 
-// transposed A operand from a swizzled unpadded tile (see lds_read_a_tr): rows row0 + 8*hh .. +7,
-// columns col0 + l%32
+// transposed A operand from a swizzled unpadded tile: element (m, k) = tile[row0 + k][col0 + m],
+// m = l%32, the k-slots of lane half hh are rows row0 + 8*hh .. +7.  Two 64-bit transposed reads.
 template <int MODE, int D>
 __device__ inline bf16x8 lds_read_a_tr_swz(const uint16_t *tile, int row0, int col0, int lane) {
     int p = lane & 15, g = lane >> 4;
@@ -224,30 +214,6 @@ __device__ inline uint32_t lds_off_a_tr_second(int col0, int lane) {
     int c = col0 + 16 * (g & 1) + 4 * (p & 3);
     return (uint32_t)(r * D + swz_chunk<MODE, D>(c >> 3, r) * 8 + (c & 4)) * 2u;
 }
-// 16-byte read of a row-major A operand from LDS
-__device__ inline bf16x8 lds_read_a(const uint16_t *tile, int row, int stride, int col) {
-    return *reinterpret_cast<const bf16x8 *>(tile + row * stride + col);
-}
-
-// transposed A operand: element (m, k) = tile[row0 + k][col0 + m], m = l%32, k-slots of lane half
-// hh are rows row0 + 8*hh .. +7.  Two 64-bit transposed reads.
-__device__ inline bf16x8 lds_read_a_tr(const uint16_t *tile, int row0, int stride, int col0, int lane) {
-    int p = lane & 15, g = lane >> 4;
-    int r = row0 + 8 * (g >> 1) + (p >> 2);
-    int c = col0 + 16 * (g & 1) + 4 * (p & 3);
-    const uint16_t *a0 = tile + r * stride + c;
-    const uint16_t *a1 = a0 + 4 * stride;
-    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)a0);
-    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)a1);
-    union {
-        s16x4 s[2];
-        bf16x8 v;
-    } x;
-    x.s[0] = lo;
-    x.s[1] = hi;
-    return x.v;
-}
-
 // combine a per-lane value with the other half of the lane pair (l, l^32)
 __device__ inline float pair_max(float x) {
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);

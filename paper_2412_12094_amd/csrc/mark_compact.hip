@@ -47,6 +47,7 @@ int launch_mark(const int32_t *token_ids, long n_tokens, const SepIdSet &set, ui
 
 // ---- compaction --------------------------------------------------------------------------------
 constexpr int kCompactThreads = 256;
+constexpr int kCompactSingleLaunch = 32768;  // longest sequence compacted with one launch
 constexpr int kCompactIters = kCompactChunk / kCompactThreads;  // 8 ballots per wave per chunk
 constexpr int kCompactWaves = kCompactThreads / kWave;
 
@@ -85,12 +86,35 @@ __global__ __launch_bounds__(kCompactThreads) void compact_write_kernel(
     int base = chunk * kCompactChunk;
     int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
 
-    // separators in earlier chunks of this sequence
-    if (wave == 0) {
+    // separators in earlier chunks of this sequence: from the counts of pass 1, or (short sequences,
+    // single launch) counted here from the flags themselves
+    if (chunk_counts != nullptr) {
+        if (wave == 0) {
+            int s = 0;
+            for (int c = lane; c < chunk; c += kWave) s += chunk_counts[(long)b * n_chunks + c];
+            for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+            if (lane == 0) base_s = s;
+        }
+    } else {
+        __shared__ int early[kCompactWaves];
         int s = 0;
-        for (int c = lane; c < chunk; c += kWave) s += chunk_counts[(long)b * n_chunks + c];
+        if ((reinterpret_cast<uintptr_t>(row) & 3u) == 0) {  // base is a multiple of 4
+            for (int j = threadIdx.x * 4; j < base; j += kCompactThreads * 4) {
+                const uint32_t w = *reinterpret_cast<const uint32_t *>(row + j);
+                // one bit per non-zero byte
+                s += __popc((((w & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | w) & 0x80808080u);
+            }
+        } else {
+            for (int j = threadIdx.x; j < base; j += kCompactThreads) s += row[j] != 0;
+        }
         for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
-        if (lane == 0) base_s = s;
+        if (lane == 0) early[wave] = s;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int t = 0;
+            for (int w2 = 0; w2 < kCompactWaves; ++w2) t += early[w2];
+            base_s = t;
+        }
     }
     unsigned long long lt_mask = (1ull << lane) - 1ull;
     bool flag[kCompactIters];
@@ -134,15 +158,19 @@ int launch_compact(const uint8_t *is_sep, int B, int L, int32_t *sep_idx, int ca
                    int32_t *sep_count, int32_t *sep_prefix, int32_t *chunk_counts, hipStream_t st) {
     int n_chunks = (L + kCompactChunk - 1) / kCompactChunk;
     dim3 grid(n_chunks, B);
-    {
+    // Up to kCompactSingleLaunch positions a workgroup counts the separators in front of its chunk
+    // itself (at most that many flag bytes, read once more): one launch instead of two, which matters
+    // because at these sizes the kernels last no longer than their launch.
+    const bool single = L <= kCompactSingleLaunch;
+    if (!single) {
         ProfScope prof(SEPATTN_K_COMPACT_COUNT, st);
         hipLaunchKernelGGL(compact_count_kernel, grid, dim3(kCompactThreads), 0, st, is_sep, L, n_chunks,
                            chunk_counts);
+        if (hipGetLastError() != hipSuccess) return SEPATTN_ERR_HIP;
     }
-    if (hipGetLastError() != hipSuccess) return SEPATTN_ERR_HIP;
     ProfScope prof(SEPATTN_K_COMPACT_WRITE, st);
     hipLaunchKernelGGL(compact_write_kernel, grid, dim3(kCompactThreads), 0, st, is_sep, L, n_chunks,
-                       chunk_counts, sep_idx, cap, sep_count, sep_prefix);
+                       single ? nullptr : chunk_counts, sep_idx, cap, sep_count, sep_prefix);
     return launch_status();
 }
 

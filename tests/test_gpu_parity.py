@@ -269,6 +269,32 @@ def test_config3_backward_one_kv_group_at_full_size(sp):
     assert_close(host(dV[:, kv:kv + 1]), rV, "bf16", "dV")
 
 
+def test_config4_backward_agrees_with_the_fp32_kernels(sp):
+    """64K context is out of the dense oracle's reach for the backward.  The fp32 kernels (parity-
+    tested against the oracle at the sizes above) run the same bf16-rounded inputs here; the bf16 MFMA
+    path must agree with them within the bf16 bound, and be bit-reproducible.  A consistency check of
+    the long-context code paths (dozens of list tiles, hundreds of stream tiles per workgroup), not a
+    parity claim of its own."""
+    c = wl.CONFIGS["cfg4"]
+    inp = wl.config_inputs(c)
+    is_sep, idx, cnt, pre = gpu_index(sp, inp["token_ids"])
+    q, k, v = (dev(inp[x], "bf16") for x in ("Q", "K", "V"))
+    g = torch.Generator(device="cuda").manual_seed(5)
+    do = torch.randn(q.shape, device="cuda", generator=g).to(torch.bfloat16)
+    O, LSE = sp.sepattn_forward(q, k, v, idx, cnt, pre, c.a, c.n, c.scale)
+    got = sp.sepattn_backward(q, k, v, O, LSE, do, idx, cnt, pre, c.a, c.n, c.scale)
+    again = sp.sepattn_backward(q, k, v, O, LSE, do, idx, cnt, pre, c.a, c.n, c.scale)
+    qf, kf, vf, dof = q.float(), k.float(), v.float(), do.float()
+    Of, LSEf = sp.sepattn_forward(qf, kf, vf, idx, cnt, pre, c.a, c.n, c.scale)
+    ref = sp.sepattn_backward(qf, kf, vf, Of, LSEf, dof, idx, cnt, pre, c.a, c.n, c.scale)
+    torch.cuda.synchronize()
+    for a, b, r, name in zip(got, again, ref, ("dQ", "dK", "dV")):
+        assert torch.equal(a, b), name
+        err = (a.float() - r).abs()
+        bound = TOL["bf16"] + r.abs() * 2.0 ** -8
+        assert bool((err <= bound).all()), (name, float((err - bound).max()))
+
+
 def test_forward_backward_are_bit_reproducible(sp):
     tok, Q, K, V, dO = make_case(1, 8, 2, 1500, 128, 0.08, "bf16", 3)
     is_sep, idx, cnt, pre = gpu_index(sp, tok)

@@ -55,14 +55,18 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     constexpr int TP = 32 * NW / GP;  // query positions per workgroup
     constexpr int CH = D / 8;         // 16-byte chunks per row
     constexpr int RPL = 64 / CH;      // rows covered by one wave-wide 1 KB load
-    constexpr int LOADS = kBN / (RPL * NW);  // wave-wide loads per wave per tensor per tile
+    // The tile loads are issued by the first NLW waves only.  Waves w and w+4 share a SIMD and the
+    // arbiter serves the older one (w) first: it reaches every barrier long before its partner, so
+    // the load path costs nothing there, while on the younger wave it would lengthen the critical path.
+    constexpr int NLW = 4;
+    constexpr int LOADS = kBN / (RPL * NLW);  // wave-wide loads per loading wave per tensor per tile
     constexpr int KSTEPS = D / 16;
     constexpr int DB = D / 32;
     // LDS stages of K, and of V and the visibility ranges: powers of two, so that a stage number is a
     // mask of the tile number (the kernel spends its time issuing instructions, scalar ones too)
     constexpr int KST = 4, VST = 4;
     constexpr int TILE = kBN * D;    // elements per LDS tile (unpadded, XOR-swizzled chunks)
-    static_assert(LOADS >= 1 && LOADS * RPL * NW == kBN, "tile must divide among the waves");
+    static_assert(LOADS >= 1 && LOADS * RPL * NLW == kBN, "tile must divide among the loading waves");
 
     __shared__ __attribute__((aligned(1024))) uint16_t Ks[KST][TILE];
     __shared__ __attribute__((aligned(1024))) uint16_t Vs[VST][TILE];
@@ -140,14 +144,15 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     // number in the concatenation of all segments of this workgroup (g), which selects the LDS stage.
     constexpr int MR = LOADS * RPL;  // rows per wave and tile
     constexpr int MST = 4;           // ring stages
-    __shared__ __attribute__((aligned(128))) int meta_s[MST][NW][32];
+    __shared__ __attribute__((aligned(256))) int meta_s[MST][NLW][64];  // 3 * MR <= 48 entries per wave and stage
+    const bool loader = wave < NLW;
     const int m_part = lane / MR, m_row = wave * MR + lane % MR;  // lanes 0 .. 3*MR-1 are used
     auto issue_meta = [&](const Stream &ss, int t, int g) __attribute__((always_inline)) {
         const int k = t * kBN + m_row;
         const int e = min(max(ss.sep_lo - ss.n_init + k, 0), p.cap - 1);
         const int j = min(max(ss.bs - ss.n_dense + k, 0), p.L - 1);
         const int32_t *src = m_part == 0 ? idx + e : prefix + j + (m_part - 1);
-        if (lane < 3 * MR) dma_to_lds_4_addr(src, lds_addr(&meta_s[(unsigned)g % MST][wave][0]));
+        if (lane < 3 * MR) dma_to_lds_4_addr(src, lds_addr(&meta_s[(unsigned)g % MST][wave % NLW][0]));
     };
     // Rows of a tile in two steps, so that the index entries of the NEXT tile can be requested in
     // between: vector-memory results return in issue order, and with the order
@@ -156,7 +161,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     // visible), which keeps the count of outstanding loads exact in a loop body without alternatives.
     int jrow[LOADS], rawi[LOADS], raw0[LOADS], raw1[LOADS];
     auto read_entries = [&](int g) __attribute__((always_inline)) {
-        const int *mt = &meta_s[(unsigned)g % MST][wave][0];
+        const int *mt = &meta_s[(unsigned)g % MST][wave % NLW][0];
         static_for<LOADS>([&](auto U) {
             constexpr int u = U;
             rawi[u] = mt[u * RPL + my_sub];
@@ -241,19 +246,19 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     // An MFMA phase issues [1 entry load][2*LOADS row loads], in this order; loads complete in order.
     //   entries_landed:    at most the row loads of the previous phase are still in flight
     //   wait_older_loads:  everything older than this phase's loads has landed
-    auto entries_landed = [&]() __attribute__((always_inline)) {
-        if constexpr (LOADS == 1)
-            asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-        else
-            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    auto wait_vmcnt = [&](auto N) __attribute__((always_inline)) {
+        constexpr int n = decltype(N)::value;
+        static_assert(n == 2 || n == 3 || n == 4 || n == 5 || n == 8 || n == 9, "add the count");
+        if constexpr (n == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+        if constexpr (n == 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+        if constexpr (n == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        if constexpr (n == 5) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+        if constexpr (n == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        if constexpr (n == 9) asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
     };
-    auto wait_older_loads = [&]() __attribute__((always_inline)) {
-        static_assert(LOADS == 1 || LOADS == 2, "wait counts are written for 1 or 2 loads per tensor");
-        if constexpr (LOADS == 1)
-            asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
-        else
-            asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
-    };
+    auto entries_landed = [&]() __attribute__((always_inline)) { wait_vmcnt(IntC<2 * LOADS>{}); };
+    // (a wave that loads nothing has nothing in flight: the wait falls through)
+    auto wait_older_loads = [&]() __attribute__((always_inline)) { wait_vmcnt(IntC<1 + 2 * LOADS>{}); };
 
     const int a_row = pi_row(qi);
 
@@ -351,19 +356,19 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     // one piece of the load path: rows of the tile at the cursor, index entries of the tile after it
     auto load_chunk = [&](auto C) __attribute__((always_inline)) {
         constexpr int c = decltype(C)::value;
+        constexpr int PSTEP = LOADS <= 2 ? 2 : 1, PREP0 = LOADS <= 2 ? 2 : 1;  // chunks of the row preparation
+        constexpr int ISTEP = LOADS <= 2 ? 2 : 1;                             // chunks 8.. of the row loads
+        static_assert(PREP0 + (LOADS - 1) * PSTEP < 6 && 8 + (LOADS - 1) * ISTEP < 12, "chunks overlap");
+        if (!loader) return;
         if constexpr (c == 0) {
             entries_landed();
             read_entries(l_g);
-        } else if constexpr (c == 2) {
-            prepare_row(lcur.st, l_t, l_g, IntC<0>{});
-        } else if constexpr (c == 4 && LOADS == 2) {
-            prepare_row(lcur.st, l_t, l_g, IntC<LOADS - 1>{});
+        } else if constexpr (c >= PREP0 && c < 6 && (c - PREP0) % PSTEP == 0 && (c - PREP0) / PSTEP < LOADS) {
+            prepare_row(lcur.st, l_t, l_g, IntC<(c - PREP0) / PSTEP>{});
         } else if constexpr (c == 6) {
             issue_meta_after_cursor();
-        } else if constexpr (c == 8) {
-            issue_row(l_g, IntC<0>{});
-        } else if constexpr (c == 10 && LOADS == 2) {
-            issue_row(l_g, IntC<LOADS - 1>{});
+        } else if constexpr (c >= 8 && c < 12 && (c - 8) % ISTEP == 0 && (c - 8) / ISTEP < LOADS) {
+            issue_row(l_g, IntC<(c - 8) / ISTEP>{});
         } else if constexpr (c == 12) {
             advance_cursor();
         }
@@ -447,16 +452,18 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
 
     // ---- start-up, once per workgroup: the first two tiles of the concatenated stream on their way
     // into LDS, the index entries of the third requested (three dependent round trips)
-    issue_meta(lcur.st, 0, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (loader) {
+        issue_meta(lcur.st, 0, 0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
-    for (int rep = 0; rep < 2; ++rep) {
-        read_entries(l_g);
-        static_for<LOADS>([&](auto U) { prepare_row(lcur.st, l_t, l_g, U); });
-        issue_meta_after_cursor();
-        static_for<LOADS>([&](auto U) { issue_row(l_g, U); });
-        advance_cursor();
-        entries_landed();  // the entries just requested (the rows after them may be in flight)
+        for (int rep = 0; rep < 2; ++rep) {
+            read_entries(l_g);
+            static_for<LOADS>([&](auto U) { prepare_row(lcur.st, l_t, l_g, U); });
+            issue_meta_after_cursor();
+            static_for<LOADS>([&](auto U) { issue_row(l_g, U); });
+            advance_cursor();
+            entries_landed();  // the entries just requested (the rows after them may be in flight)
+        }
     }
     wg_barrier();  // tile 0 is in LDS (its rows were the first loads)
 

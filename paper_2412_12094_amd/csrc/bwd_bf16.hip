@@ -58,14 +58,17 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
     constexpr int TP = 32 * NW / GP;
     constexpr int CH = D / 8;
     constexpr int RPL = 64 / CH;
-    constexpr int LOADS = kBN / (RPL * NW);
+    // the tile loads are issued by the first NLW waves only: of the two waves that share a SIMD the
+    // older one (w < 4) is served first and reaches every barrier long before its partner
+    constexpr int NLW = 4;
+    constexpr int LOADS = kBN / (RPL * NLW);
     constexpr int KSTEPS = D / 16;
     constexpr int DB = D / 32;
     // LDS stages of K, of V, and of the visibility ranges: powers of two, so that a stage number is
     // a mask of the tile number (the kernels spend their time issuing instructions, scalar ones too)
     constexpr int KST = 4, VST = 4, MKS = 4;
     constexpr int TILE = kBN * D;
-    static_assert(LOADS >= 1 && LOADS * RPL * NW == kBN, "tile must divide among the waves");
+    static_assert(LOADS >= 1 && LOADS * RPL * NLW == kBN, "tile must divide among the loading waves");
 
     __shared__ __attribute__((aligned(1024))) uint16_t Ks[KST][TILE];
     __shared__ __attribute__((aligned(1024))) uint16_t Vs[VST][TILE];
@@ -73,10 +76,11 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
     __shared__ __attribute__((aligned(16))) int hi_s[MKS][kBN];
     constexpr int MR = LOADS * RPL;  // rows per wave and tile
     constexpr int MST = 4;           // ring stages of the index entries
-    __shared__ __attribute__((aligned(128))) int meta_s[MST][NW][32];
+    __shared__ __attribute__((aligned(256))) int meta_s[MST][NLW][64];  // 3 * MR <= 48 entries per wave and stage
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool loader = wave < NLW;
     const int qi = lane & 31, hh = lane >> 5;
     // Persistent workgroups as in the forward kernel: a workgroup belongs to one (batch, KV head, head
     // group) and walks through several query tiles of it ("segments") in zig-zag order, `wpg`
@@ -105,13 +109,7 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
 
     // ---- tile loads (see the forward kernel: same scheme, other LDS layouts)
     const int my_pc = lane % CH, my_sub = lane / CH;
-    uint32_t kgo[LOADS];  // byte offset of this lane's 16-byte piece inside a K or V row
-    int rrow[LOADS];
-#pragma unroll
-    for (int u = 0; u < LOADS; ++u) {
-        rrow[u] = (LOADS * wave + u) * RPL + my_sub;
-        kgo[u] = swz_chunk<kSwzBoth, D>(my_pc, rrow[u]) * 16;
-    }
+    const int row0 = LOADS * wave * RPL + my_sub;  // first of the rows of a tile this lane helps to fill (+ u * RPL)
     const char *Kb = reinterpret_cast<const char *>(Kh), *Vb = reinterpret_cast<const char *>(Vh);
     auto tile_class = [&](const Stream &ss, int t) {
         const int k0 = t * kBN;
@@ -125,31 +123,26 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
         const int e = min(max(ss.sep_lo - ss.n_init + k, 0), p.cap - 1);
         const int j = min(max(ss.bs - ss.n_dense + k, 0), p.L - 1);
         const int32_t *src = m_part == 0 ? idx + e : prefix + j + (m_part - 1);
-        if (lane < 3 * MR) dma_to_lds_4_addr(src, lds_addr(&meta_s[(unsigned)g % MST][wave][0]));
+        if (lane < 3 * MR) dma_to_lds_4_addr(src, lds_addr(&meta_s[(unsigned)g % MST][wave % NLW][0]));
     };
-    int jrow[LOADS], rawi[LOADS], raw0[LOADS], raw1[LOADS];
-    auto read_entries = [&](int g) __attribute__((always_inline)) {
-        const int *mt = &meta_s[(unsigned)g % MST][wave][0];
-        static_for<LOADS>([&](auto U) {
-            constexpr int u = U;
-            rawi[u] = mt[u * RPL + my_sub];
-            raw0[u] = mt[MR + u * RPL + my_sub];
-            raw1[u] = mt[2 * MR + u * RPL + my_sub];
-        });
-    };
-    auto prepare_row = [&](const Stream &ss, int t, int g, auto U) __attribute__((always_inline)) {
+    // One row of the tile at a time (the loading waves have time to spare, registers are scarce): read
+    // the row's index entries, work out its key position and visibility range, request the row.
+    auto load_row = [&](const Stream &ss, int t, int g, auto U) __attribute__((always_inline)) {
         constexpr int u = decltype(U)::value;
+        const int *mt = &meta_s[(unsigned)g % MST][wave % NLW][0];
+        const int rawi = mt[u * RPL + my_sub], raw0 = mt[MR + u * RPL + my_sub], raw1 = mt[2 * MR + u * RPL + my_sub];
         const int ms_ = (unsigned)g % MKS;
-        const int r = rrow[u];
+        const int r = row0 + u * RPL;
         const int k = t * kBN + r;
         // the clamp keeps a stale list tail (caller broke sep_count <= cap) from faulting
-        const int jl = min(max(rawi[u], 0), p.L - 1);
+        const int jl = min(max(rawi, 0), p.L - 1);
+        int jrow;
         if (tile_class(ss, t) == 0) {
-            jrow[u] = k < ss.n_init ? k : jl;
+            jrow = k < ss.n_init ? k : jl;
         } else {
             const bool init = k < ss.n_init, dense = k < ss.n_dense, pad = k >= ss.n_total;
             const int jb = ss.bs + (k - ss.n_dense);
-            const bool always = dense | (jb < p.a) | (raw1[u] != raw0[u]);
+            const bool always = dense | (jb < p.a) | (raw1 != raw0);
             int j = init ? k : (dense ? jl : jb);
             j = pad ? 0 : j;
             const int lo = pad ? kIntMax : j;
@@ -159,16 +152,13 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
                 lo_s[ms_][r] = lo;
                 hi_s[ms_][r] = hi;
             }
-            jrow[u] = j;
+            jrow = j;
         }
-    };
-    auto issue_row = [&](int g, auto U) __attribute__((always_inline)) {
-        constexpr int u = decltype(U)::value;
         const uint32_t kst = lds_addr(&Ks[(unsigned)g % KST][0]), vst = lds_addr(&Vs[(unsigned)g % VST][0]);
         const uint32_t wave_off = (uint32_t)((LOADS * wave + u) * RPL * D * 2);
-        const uint32_t row_off = (uint32_t)jrow[u] * (uint32_t)(D * 2);
-        dma_to_lds_16(Kb, row_off + kgo[u], kst + wave_off);
-        dma_to_lds_16(Vb, row_off + kgo[u], vst + wave_off);
+        const uint32_t off = (uint32_t)jrow * (uint32_t)(D * 2) + swz_chunk<kSwzBoth, D>(my_pc, r) * 16;
+        dma_to_lds_16(Kb, off, kst + wave_off);
+        dma_to_lds_16(Vb, off, vst + wave_off);
     };
 
     // ---- segments of this workgroup and the load cursor: the tiles of all segments form one stream
@@ -212,19 +202,19 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
             issue_meta(lnext.st, 0, l_g + 1);
     };
     // a tile step issues [1 entry load][2*LOADS row loads], in this order; loads complete in order
-    auto entries_landed = [&]() __attribute__((always_inline)) {
-        if constexpr (LOADS == 1)
-            asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-        else
-            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    auto wait_vmcnt = [&](auto N) __attribute__((always_inline)) {
+        constexpr int n = decltype(N)::value;
+        static_assert(n == 2 || n == 3 || n == 4 || n == 5 || n == 8 || n == 9, "add the count");
+        if constexpr (n == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+        if constexpr (n == 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+        if constexpr (n == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        if constexpr (n == 5) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+        if constexpr (n == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        if constexpr (n == 9) asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
     };
-    auto wait_older_loads = [&]() __attribute__((always_inline)) {
-        static_assert(LOADS == 1 || LOADS == 2, "wait counts are written for 1 or 2 loads per tensor");
-        if constexpr (LOADS == 1)
-            asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
-        else
-            asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
-    };
+    auto entries_landed = [&]() __attribute__((always_inline)) { wait_vmcnt(IntC<2 * LOADS>{}); };
+    // (a wave that loads nothing has nothing in flight: the wait falls through)
+    auto wait_older_loads = [&]() __attribute__((always_inline)) { wait_vmcnt(IntC<1 + 2 * LOADS>{}); };
     auto wg_barrier = [&]() __attribute__((always_inline)) {
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
@@ -284,21 +274,17 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
             // the load path of the tile at the cursor (two tiles ahead) rides along with the first
             // block of the tile
             if constexpr (DO_LD) {
-                if constexpr (s == 0) {
-                    entries_landed();
-                    read_entries(l_g);
-                } else if constexpr (s == NS1 / 4) {
-                    prepare_row(lcur.st, l_t, l_g, IntC<0>{});
-                } else if constexpr (s == NS1 / 4 + 1 && LOADS == 2) {
-                    prepare_row(lcur.st, l_t, l_g, IntC<LOADS - 1>{});
-                } else if constexpr (s == NS1 / 2) {
-                    issue_meta_after_cursor();
-                } else if constexpr (s == NS1 / 2 + NS1 / 8) {
-                    issue_row(l_g, IntC<0>{});
-                } else if constexpr (s == NS1 / 2 + NS1 / 4 && LOADS == 2) {
-                    issue_row(l_g, IntC<LOADS - 1>{});
-                } else if constexpr (s == NS1 - 1) {
-                    advance_cursor();
+                static_assert(NS1 / 4 + 2 * (LOADS - 1) < NS1 - 1, "the row slots must come before the cursor moves");
+                // order of the requests: [entries of the tile after the cursor] [rows of the tile at it]
+                if (loader) {
+                    if constexpr (s == 0) {
+                        entries_landed();
+                        issue_meta_after_cursor();
+                    } else if constexpr (s >= NS1 / 4 && (s - NS1 / 4) % 2 == 0 && (s - NS1 / 4) / 2 < LOADS) {
+                        load_row(lcur.st, l_t, l_g, IntC<(s - NS1 / 4) / 2>{});
+                    } else if constexpr (s == NS1 - 1) {
+                        advance_cursor();
+                    }
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -346,16 +332,16 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
 
     // ---- start-up, once per workgroup: the first two tiles of the concatenated stream on their way
     // into LDS, the index entries of the third requested
-    issue_meta(lcur.st, 0, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (loader) {
+        issue_meta(lcur.st, 0, 0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
-    for (int rep = 0; rep < 2; ++rep) {
-        read_entries(l_g);
-        static_for<LOADS>([&](auto U) { prepare_row(lcur.st, l_t, l_g, U); });
-        issue_meta_after_cursor();
-        static_for<LOADS>([&](auto U) { issue_row(l_g, U); });
-        advance_cursor();
-        entries_landed();  // the entries just requested (the rows after them may be in flight)
+        for (int rep = 0; rep < 2; ++rep) {
+            issue_meta_after_cursor();
+            static_for<LOADS>([&](auto U) { load_row(lcur.st, l_t, l_g, U); });
+            advance_cursor();
+            entries_landed();  // the entries just requested (the rows after them may be in flight)
+        }
     }
 
     const IntC<1> yes;

@@ -13,7 +13,7 @@ printed as ONE JSON line together with
                     dense bf16 MFMA peak,
   - "cpu_baseline": the CPU oracle timed on this host on a bounded sample of the same workload,
   - "decode":       the streaming-decode workload (32 sequences x 3332 cache entries) as achieved
-                    HBM GB/s, and the cache eviction step.
+                    HBM GB/s, the cache eviction step, and the hand-over from an 8K prompt to the cache.
 Only one GPU is used; `--gpus N` with N > 1 exits with a message.
 """
 from __future__ import annotations
@@ -273,6 +273,28 @@ def bench_decode(torch, sp, wl, ramp_seconds):
     res["evict"] = {"us": round(float(np.median(times[2:])), 2), "kept_rows_per_head": kept,
                     "moved_bytes": int(moved_rows * row * 2 * 2 * c.Hkv),
                     "gbs": round(moved_rows * row * 2 * 2 * c.Hkv / float(np.median(times[2:])) / 1e3, 1)}
+    # hand-over from an 8K prompt to the cache (initial tokens, separators older than the window, window)
+    Lp = 8192
+    tokp = torch.from_numpy(wl.make_token_ids(c.S, Lp, 0.08, 4242)).cuda()
+    sep_p = sp.sepattn_mark_separators(tokp, wl.SEPARATOR_IDS.tolist())
+    idx_p, cnt_p, pre_p = sp.sepattn_compact_indices(sep_p)
+    Kp = torch.randn((c.S, c.Hkv, Lp, c.d), device=q.device, dtype=torch.bfloat16)
+    Vp = torch.randn_like(Kp)
+    nw = c.window_capacity
+    outs = (torch.zeros_like(Kc), torch.zeros_like(Vc), flags.clone(), sz.clone())
+    ftimes = []
+    for i in range(12):
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        sp.sepkv_fill_from_prefill(Kp, Vp, sep_p, idx_p, pre_p, c.Hq, c.a, c.s, c.w, c.c, nw, out=outs)
+        e1.record()
+        torch.cuda.synchronize()
+        ftimes.append(e0.elapsed_time(e1) * 1e3)
+    rows = int(outs[3].sum().item())
+    res["fill_from_prefill"] = {"prompt_len": Lp, "us": round(float(np.median(ftimes[2:])), 2),
+                                "rows_per_head": rows, "moved_bytes": int(rows * row * 2 * 2 * c.Hkv),
+                                "gbs": round(rows * row * 2 * 2 * c.Hkv / float(np.median(ftimes[2:])) / 1e3, 1)}
     return res
 
 

@@ -187,6 +187,30 @@ size_t sepkv_evict_workspace_bytes(const sepkv_params *p);
 int sepkv_evict_window(const sepkv_params *p, void *Kc, void *Vc, uint8_t *win_is_sep,
                        int32_t *sizes, void *ws, size_t ws_bytes, void *stream);
 
+/* Hand-over from prefill to the cache (Sec. 3.2 "Generation": only the KV of initial, separator and
+ * neighbouring tokens is kept; Sec. 3.3 for the block layout): after L prompt tokens the cache of
+ * each sequence receives
+ *     Initial Cache    positions 0 .. min(a, L) - 1
+ *     Separator Cache  the newest (at most s) separators among the positions [min(a, L), L - nw),
+ *                      oldest first; older ones are dropped, as the compression step would drop them
+ *     window           the last nw positions, oldest first; the newest min(w, nw) are the Local Window
+ * i.e. the state the append / compression policy reaches after L tokens when its window then holds
+ * nw entries (the caller knows nw: the policy's n after L tokens).  Rows are copied bit-exactly.
+ *   L            prompt length;  nw  window entries, 0 <= nw <= min(c - a - s, L - min(a, L))
+ *   K, V         DEVICE dtype [S, Hkv, L, d]     the prefill's keys and values
+ *   is_sep       DEVICE uint8 [S, L]             as from sepattn_mark_separators
+ *   sep_idx      DEVICE int32 [S, cap], sep_prefix DEVICE int32 [S, L+1]: as from
+ *                sepattn_compact_indices (cap >= the number of separators, else the newest listed ones)
+ *   Kc, Vc       DEVICE dtype [S, Hkv, c, d]     out; slots beyond the new sizes are left untouched
+ *   win_is_sep   DEVICE uint8 [S, c-a-s]         out: separator flag of each window entry
+ *   sizes        DEVICE int32 [S, 4]             out: (min(a, L), kept separators, nw - Size_local_w, Size_local_w)
+ * Errors: SEPATTN_ERR_PARAM if nw is out of range.
+ */
+int sepkv_fill_from_prefill(const sepkv_params *p, int L, int nw, const void *K, const void *V,
+                            const uint8_t *is_sep, const int32_t *sep_idx, int cap,
+                            const int32_t *sep_prefix, void *Kc, void *Vc, uint8_t *win_is_sep,
+                            int32_t *sizes, void *stream);
+
 /* ------------------------------------------------------------------------------------------
  * Measurement hooks (not part of the method; the only process-wide state the library keeps).
  * Between sepattn_profile_begin and sepattn_profile_end every launch of the selected kernel is
@@ -211,7 +235,8 @@ typedef enum {
     SEPATTN_K_DECODE_MERGE = 8,
     SEPATTN_K_EVICT_PLAN = 9,
     SEPATTN_K_EVICT_MOVE = 10,
-    SEPATTN_K_COUNT = 11
+    SEPATTN_K_CACHE_FILL = 11,
+    SEPATTN_K_COUNT = 12
 } sepattn_kernel_id;
 const char *sepattn_kernel_name(int kernel);
 int sepattn_profile_begin(int kernel, int max_records);

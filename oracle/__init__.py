@@ -180,3 +180,39 @@ def evict_window(Kc: np.ndarray, Vc: np.ndarray, win_is_sep: np.ndarray, sizes: 
     if rc != 0:
         raise ValueError(f"oracle_evict_window failed with code {rc}")
     return Kc, Vc, fl, sz
+
+
+def fill_from_prefill(K: np.ndarray, V: np.ndarray, is_sep: np.ndarray, a: int, s: int, w: int, c: int,
+                      nw: int):
+    """Hand-over from prefill to the four-block cache (Sec. 3.2 "Generation", Sec. 3.3): keep the
+    initial tokens, the newest (at most s) separators older than the window, and the last nw tokens.
+
+    K, V: [S,Hkv,L,d] of any fixed-width dtype; is_sep: [S,L].  Returns (Kc, Vc, win_is_sep, sizes,
+    valid) with Kc, Vc [S,Hkv,c,d] (zero where no row was placed), win_is_sep uint8 [S,c-a-s],
+    sizes int32 [S,4] and valid bool [S,c]: the slots that hold a row.
+    """
+    S, Hkv, L, d = K.shape
+    wcap = c - a - s
+    assert 0 <= nw <= min(wcap, L - min(a, L))
+    Kc = np.zeros((S, Hkv, c, d), dtype=K.dtype)
+    Vc = np.zeros((S, Hkv, c, d), dtype=V.dtype)
+    flags = np.zeros((S, wcap), dtype=np.uint8)
+    sizes = np.zeros((S, 4), dtype=np.int32)
+    valid = np.zeros((S, c), dtype=bool)
+    for q in range(S):
+        n_init = min(a, L)
+        wstart = L - nw
+        old_seps = [j for j in range(n_init, wstart) if is_sep[q, j]]
+        kept = old_seps[len(old_seps) - min(s, len(old_seps)):]
+        placed = [(t, t) for t in range(n_init)]
+        placed += [(a + k, j) for k, j in enumerate(kept)]
+        placed += [(a + s + u, wstart + u) for u in range(nw)]
+        for slot, j in placed:
+            Kc[q, :, slot] = K[q, :, j]
+            Vc[q, :, slot] = V[q, :, j]
+            valid[q, slot] = True
+        for u in range(nw):
+            flags[q, u] = 1 if is_sep[q, wstart + u] else 0
+        wl = min(w, nw)
+        sizes[q] = (n_init, len(kept), nw - wl, wl)
+    return Kc, Vc, flags, sizes, valid

@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     sepattn_backward_workspace_bytes,
     sepattn_decode,
     sepkv_evict_window,
+    sepkv_fill_from_prefill,
     KERNEL_IDS,
     sepattn_kernel_name,
     sepattn_profile_begin,

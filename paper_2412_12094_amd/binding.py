@@ -33,6 +33,7 @@ EXPORTS = (
     "sepattn_decode",
     "sepkv_evict_workspace_bytes",
     "sepkv_evict_window",
+    "sepkv_fill_from_prefill",
     "sepattn_kernel_name",
     "sepattn_profile_begin",
     "sepattn_profile_end",
@@ -97,6 +98,8 @@ def load(path: Optional[str] = None):
     lib.sepkv_evict_workspace_bytes.argtypes = [kp]
     lib.sepkv_evict_window.restype = ci
     lib.sepkv_evict_window.argtypes = [kp] + [vp] * 5 + [sz, vp]
+    lib.sepkv_fill_from_prefill.restype = ci
+    lib.sepkv_fill_from_prefill.argtypes = [kp, ci, ci, vp, vp, vp, vp, ci, vp, vp, vp, vp, vp, vp]
     lib.sepattn_kernel_name.restype = ctypes.c_char_p
     lib.sepattn_kernel_name.argtypes = [ci]
     lib.sepattn_profile_begin.restype = ci
@@ -113,7 +116,8 @@ def status_string(status: int) -> str:
 
 
 KERNEL_IDS = {"mark": 0, "compact_count": 1, "compact_write": 2, "forward": 3, "bwd_dq": 4, "bwd_dkv": 5,
-              "bwd_combine": 6, "decode_split": 7, "decode_merge": 8, "evict_plan": 9, "evict_move": 10}
+              "bwd_combine": 6, "decode_split": 7, "decode_merge": 8, "evict_plan": 9, "evict_move": 10,
+              "cache_fill": 11}
 
 
 def sepattn_kernel_name(kernel: int) -> str:
@@ -302,3 +306,25 @@ def sepkv_evict_window(Kc, Vc, win_is_sep, sizes, Hq: int, a: int, s: int, w: in
     _check("sepkv_evict_window",
            lib.sepkv_evict_window(ctypes.byref(p), _ptr(Kc), _ptr(Vc), _ptr(win_is_sep), _ptr(sizes), _ptr(ws),
                                   ws.numel(), _stream(Kc)))
+
+
+def sepkv_fill_from_prefill(K, V, is_sep, sep_idx, sep_prefix, Hq: int, a: int, s: int, w: int, c: int, nw: int,
+                            out=None):
+    """Prefill K, V [S,Hkv,L,d] -> (Kc, Vc [S,Hkv,c,d], win_is_sep uint8 [S,c-a-s], sizes int32 [S,4]).
+    Freshly allocated outputs are zero-filled (the call leaves slots beyond the sizes untouched)."""
+    _dev(K, V, is_sep, sep_idx, sep_prefix)
+    S, Hkv, L, d = K.shape
+    p = SepkvParams(S, int(Hq), Hkv, d, int(a), int(s), int(w), int(c), 1.0, _dtype_code(K))
+    if out is None:
+        Kc = torch.zeros((S, Hkv, c, d), dtype=K.dtype, device=K.device)
+        Vc = torch.zeros_like(Kc)
+        flags = torch.zeros((S, c - a - s), dtype=torch.uint8, device=K.device)
+        sizes = torch.zeros((S, 4), dtype=torch.int32, device=K.device)
+    else:
+        Kc, Vc, flags, sizes = out
+        _dev(Kc, Vc, flags, sizes)
+    _check("sepkv_fill_from_prefill",
+           load().sepkv_fill_from_prefill(ctypes.byref(p), int(L), int(nw), _ptr(K), _ptr(V), _ptr(is_sep),
+                                          _ptr(sep_idx), int(sep_idx.shape[1]), _ptr(sep_prefix), _ptr(Kc), _ptr(Vc),
+                                          _ptr(flags), _ptr(sizes), _stream(K)))
+    return Kc, Vc, flags, sizes

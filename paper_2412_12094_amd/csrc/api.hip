@@ -109,7 +109,7 @@ const char *sepattn_kernel_name(int kernel) {
                                                  "fwd_bf16_kernel", "dq_kernel", "dkv_kernel",
                                                  "dkv_combine_kernel", "decode_split_kernel",
                                                  "decode_merge_kernel", "evict_plan_kernel",
-                                                 "evict_move_kernel"};
+                                                 "evict_move_kernel", "cache_fill_kernel"};
     return (kernel >= 0 && kernel < SEPATTN_K_COUNT) ? names[kernel] : "unknown";
 }
 
@@ -266,6 +266,21 @@ int sepkv_evict_window(const sepkv_params *p, void *Kc, void *Vc, uint8_t *win_i
     if (!aligned(Kc, 16) || !aligned(Vc, 16)) return SEPATTN_ERR_PARAM;
     if (!ws || ws_bytes < evict_workspace(*p) || !aligned(ws, 256)) return SEPATTN_ERR_WORKSPACE;
     return launch_evict(*p, Kc, Vc, win_is_sep, sizes, ws, static_cast<hipStream_t>(stream));
+}
+
+int sepkv_fill_from_prefill(const sepkv_params *p, int L, int nw, const void *K, const void *V,
+                            const uint8_t *is_sep, const int32_t *sep_idx, int cap, const int32_t *sep_prefix,
+                            void *Kc, void *Vc, uint8_t *win_is_sep, int32_t *sizes, void *stream) {
+    int rc = check_kv(p);
+    if (rc != SEPATTN_OK) return rc;
+    if (!K || !V || !is_sep || !sep_idx || !sep_prefix || !Kc || !Vc || !win_is_sep || !sizes) return SEPATTN_ERR_NULL;
+    if (L <= 0 || (long)p->S * p->Hkv * L > (1L << 40)) return SEPATTN_ERR_SHAPE;
+    if (cap < 1) return SEPATTN_ERR_CAPACITY;
+    const int n_init = p->a < L ? p->a : L;
+    if (nw < 0 || nw > p->c - p->a - p->s || nw > L - n_init) return SEPATTN_ERR_PARAM;
+    if (!aligned(K, 16) || !aligned(V, 16) || !aligned(Kc, 16) || !aligned(Vc, 16)) return SEPATTN_ERR_PARAM;
+    return launch_cache_fill(*p, L, nw, K, V, is_sep, sep_idx, cap, sep_prefix, Kc, Vc, win_is_sep, sizes,
+                             static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

@@ -65,5 +65,8 @@ int launch_decode(const sepkv_params &p, const void *q, const void *Kc, const vo
 size_t evict_workspace(const sepkv_params &p);
 int launch_evict(const sepkv_params &p, void *Kc, void *Vc, uint8_t *win_is_sep, int32_t *sizes,
                  void *ws, hipStream_t st);
+int launch_cache_fill(const sepkv_params &p, int L, int nw, const void *K, const void *V, const uint8_t *is_sep,
+                      const int32_t *sep_idx, int cap, const int32_t *sep_prefix, void *Kc, void *Vc,
+                      uint8_t *win_is_sep, int32_t *sizes, hipStream_t st);
 
 }  // namespace sepattn

@@ -471,6 +471,83 @@ def test_evict_config5_then_decode(sp):
 
 
 # ----------------------------------------------------------------------------------------------
+# hand-over from prefill to the cache
+# ----------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("S,Hkv,L,d,a,s,w,c,nw,p", [
+    (2, 2, 300, 128, 4, 40, 16, 4 + 40 + 90, 70, 0.2),     # more old separators than the cache holds: newest s
+    (3, 1, 200, 64, 3, 100, 8, 3 + 100 + 40, 40, 0.1),     # every separator fits
+    (1, 2, 50, 128, 4, 10, 4, 4 + 10 + 30, 0, 0.3),        # empty window
+    (2, 1, 3, 64, 4, 10, 4, 4 + 10 + 30, 0, 0.5),          # prompt shorter than the Initial Cache
+    (1, 3, 130, 128, 0, 5, 2, 0 + 5 + 129 + 1, 129, 0.0),  # a = 0, no separators, window of almost everything
+    (1, 1, 700, 128, 4, 64, 32, 4 + 64 + 300, 300, 1.0),   # every token a separator
+])
+def test_fill_from_prefill_matches_oracle_bit_exact(sp, dtype, S, Hkv, L, d, a, s, w, c, nw, p):
+    rng = np.random.default_rng(L + nw)
+    tok = wl.make_token_ids(S, L, p, 50 + L)
+    flags = oracle.mark_separators(tok, wl.SEPARATOR_IDS)
+    K = rng.standard_normal((S, Hkv, L, d)).astype(np.float32)
+    V = rng.standard_normal((S, Hkv, L, d)).astype(np.float32)
+    if dtype == "bf16":
+        Kb, Vb = bits(K), bits(V)  # raw bf16 bit patterns: the copy must be bit-exact
+        Kd, Vd = dev(Kb.view(np.int16)).view(torch.bfloat16), dev(Vb.view(np.int16)).view(torch.bfloat16)
+        raw = lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)
+    else:
+        Kb, Vb = K, V
+        Kd, Vd = dev(K), dev(V)
+        raw = lambda t: t.cpu().numpy()
+    rK, rV, rF, rS, valid = oracle.fill_from_prefill(Kb, Vb, flags, a, s, w, c, nw)
+    is_sep, idx, cnt, pre = gpu_index(sp, tok)
+    # pre-filled outputs: slots that receive no row must stay as they are
+    Kc = torch.full((S, Hkv, c, d), 7.0, dtype=Kd.dtype, device="cuda")
+    Vc = torch.full((S, Hkv, c, d), -3.0, dtype=Kd.dtype, device="cuda")
+    Fd = torch.full((S, c - a - s), 9, dtype=torch.uint8, device="cuda")
+    Sd = torch.zeros((S, 4), dtype=torch.int32, device="cuda")
+    K0, V0 = raw(Kc).copy(), raw(Vc).copy()
+    sp.sepkv_fill_from_prefill(Kd, Vd, is_sep, idx, pre, Hkv, a, s, w, c, nw, out=(Kc, Vc, Fd, Sd))
+    torch.cuda.synchronize()
+    assert np.array_equal(host(Sd), rS)
+    gK, gV, gF = raw(Kc), raw(Vc), host(Fd)
+    for q in range(S):
+        m = valid[q]
+        assert np.array_equal(gK[q][:, m], rK[q][:, m]) and np.array_equal(gV[q][:, m], rV[q][:, m])
+        assert np.array_equal(gK[q][:, ~m], K0[q][:, ~m]) and np.array_equal(gV[q][:, ~m], V0[q][:, ~m])
+        assert np.array_equal(gF[q, :nw], rF[q, :nw]) and (gF[q, nw:] == 9).all()
+
+
+def test_prefill_then_fill_then_decode_reproduces_the_last_row(sp):
+    """End to end on the GPU: forward over the prompt, hand-over with nw = n, decode with the last
+    query: the result is the forward's last row (Sec. 3.2 "Generation")."""
+    B, Hq, Hkv, L, d, a, n, p = 2, 8, 2, 1500, 128, 4, 256, 0.08
+    tok, Q, K, V, _ = make_case(B, Hq, Hkv, L, d, p, "bf16", 77)
+    is_sep, idx, cnt, pre = gpu_index(sp, tok)
+    q, k, v = (dev(x, "bf16") for x in (Q, K, V))
+    scale = 1.0 / math.sqrt(d)
+    O, LSE = sp.sepattn_forward(q, k, v, idx, cnt, pre, a, n, scale)
+    s_cap, w = 256, 64
+    c = a + s_cap + 400
+    Kc, Vc, Fd, Sd = sp.sepkv_fill_from_prefill(k, v, is_sep, idx, pre, Hq, a, s_cap, w, c, n)
+    assert int(cnt.max()) <= s_cap  # every separator fits, so nothing the last row sees is dropped
+    out, lse = sp.sepattn_decode(q[:, :, L - 1].contiguous(), Kc, Vc, Sd, a, s_cap, w, scale)
+    torch.cuda.synchronize()
+    assert np.abs(host(out) - host(O[:, :, L - 1])).max() <= 2e-2
+    assert np.abs(host(lse) - host(LSE[:, :, L - 1])).max() <= 2e-3
+
+
+def test_fill_from_prefill_rejects_a_window_that_does_not_fit(sp):
+    S, Hkv, L, d = 1, 1, 40, 64
+    tok = wl.make_token_ids(S, L, 0.1, 3)
+    is_sep, idx, cnt, pre = gpu_index(sp, tok)
+    K = torch.zeros((S, Hkv, L, d), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(sp.SepattnError) as e:
+        sp.sepkv_fill_from_prefill(K, K, is_sep, idx, pre, 1, 4, 10, 4, 4 + 10 + 20, 21)  # nw > c-a-s
+    assert e.value.status == 3
+    with pytest.raises(sp.SepattnError) as e:
+        sp.sepkv_fill_from_prefill(K, K, is_sep, idx, pre, 1, 4, 10, 4, 4 + 10 + 60, 37)  # nw > L-a
+    assert e.value.status == 3
+
+
+# ----------------------------------------------------------------------------------------------
 # error paths through the ABI (nothing is launched)
 # ----------------------------------------------------------------------------------------------
 def test_bad_arguments_are_rejected(sp):

@@ -389,6 +389,50 @@ def test_decode_equals_prefill_row_under_fundamental_design_cache():
         assert np.allclose(lse[0], LSE[0, :, i], atol=1e-12)
 
 
+def test_fill_from_prefill_reproduces_the_last_prefill_row():
+    """Sec. 3.2 "Generation": the cache handed over after L tokens, with nw = n and room for every
+    separator, holds exactly what row L-1 of the prefill sees, so decoding Q_{L-1} over it gives
+    that row.  Pins the hand-over against the forward and the decode together."""
+    B, Hq, Hkv, L, d, a, n = 2, 4, 2, 83, 8, 3, 11
+    is_sep = _flags(B, L, 0.2, 5)
+    Q, K, V = _rand((B, Hq, L, d), 1), _rand((B, Hkv, L, d), 2), _rand((B, Hkv, L, d), 3)
+    O, LSE = oracle.forward(Q, K, V, is_sep, a, n, 0.35)
+    s_cap, w = 60, 4
+    c = a + s_cap + 16
+    Kc, Vc, flags, sizes, valid = oracle.fill_from_prefill(K, V, is_sep, a, s_cap, w, c, n)
+    out, lse = oracle.decode(Q[:, :, L - 1], Kc, Vc, sizes, a, s_cap, 0.35)
+    assert np.allclose(out, O[:, :, L - 1], atol=1e-12)
+    assert np.allclose(lse, LSE[:, :, L - 1], atol=1e-12)
+    assert np.array_equal(flags[:, :n], is_sep[:, L - n:])
+    assert (sizes[:, 2] + sizes[:, 3] == n).all() and (sizes[:, 3] == w).all()
+    assert (valid.sum(1) == sizes.sum(1)).all()
+
+
+def test_fill_from_prefill_agrees_with_the_streaming_policy():
+    """The hand-over must land in the state the token-by-token policy of Sec. 3.3 reaches: with nw =
+    the policy's n after L tokens, the separator count equals the simulator's Size_sep, the rows of
+    the Separator Cache are the newest separators older than the window (oldest first), and a
+    too-small Separator Cache keeps the newest s of them."""
+    a, s, w, c = 2, 6, 5, 24
+    L = 150
+    is_sep = _flags(1, L, 0.25, 9)
+    sim = cache_sim.simulate(is_sep[0], a, s, w, c)
+    K = np.arange(L, dtype=np.float64).reshape(1, 1, L, 1) + 0.5  # a row is its position + 0.5
+    for m in (1, 2, 7, 23, 24, 60, 149):
+        Lm = m + 1
+        nw = int(sim["n"][m])
+        Kc, Vc, flags, sizes, valid = oracle.fill_from_prefill(K[:, :, :Lm], K[:, :, :Lm], is_sep[:, :Lm], a, s, w, c, nw)
+        assert sizes[0, 0] == min(a, Lm)
+        assert sizes[0, 2] + sizes[0, 3] == nw
+        assert sizes[0, 1] == sim["size_sep"][m], (m, sizes[0], sim["size_sep"][m])
+        assert sizes.sum() == sim["size_run"][m]
+        kept = (Kc[0, 0, a:a + sizes[0, 1], 0] - 0.5).astype(int)
+        want = [j for j in range(min(a, Lm), Lm - nw) if is_sep[0, j]][-s:] if s else []
+        assert list(kept) == want[len(want) - sizes[0, 1]:]
+        win = (Kc[0, 0, a + s:a + s + nw, 0] - 0.5).astype(int)
+        assert list(win) == list(range(Lm - nw, Lm))
+
+
 def test_decode_zero_query_probe_counts_entries():
     S, Hq, Hkv, d, a, s, c = 3, 2, 1, 4, 2, 5, 16
     Kc, Vc = _rand((S, Hkv, c, d), 1), _rand((S, Hkv, c, d), 2)

@@ -216,3 +216,93 @@ def fill_from_prefill(K: np.ndarray, V: np.ndarray, is_sep: np.ndarray, a: int, 
         wl = min(w, nw)
         sizes[q] = (n_init, len(kept), nw - wl, wl)
     return Kc, Vc, flags, sizes, valid
+
+
+def rope_rotate(x: np.ndarray, pos, base: float) -> np.ndarray:
+    """Rotary position encoding of x [..., d] at position(s) `pos` (broadcast over x's leading axes).
+
+    Sec. 3.3 "Positional Encoding" fixes which positions are used (those within the cache); the
+    rotation itself is the one of the Llama / Pythia backbones the paper evaluates (Sec. 4.1): dimension
+    i < d/2 is paired with i + d/2 and the pair is turned by pos * base**(-2i/d).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    d = x.shape[-1]
+    h = d // 2
+    theta = np.float64(base) ** (-2.0 * np.arange(h, dtype=np.float64) / d)
+    ang = np.asarray(pos, dtype=np.float64)[..., None] * theta
+    co, si = np.cos(ang), np.sin(ang)
+    x1, x2 = x[..., :h], x[..., h:]
+    return np.concatenate([x1 * co - x2 * si, x2 * co + x1 * si], axis=-1)
+
+
+def cache_slots(sizes_row: np.ndarray, a: int, s: int) -> np.ndarray:
+    """Slots of the valid entries of one sequence, oldest first: Initial Cache, Separator Cache,
+    Past Window Cache, Local Window Cache (Sec. 3.3)."""
+    n_init, n_sep, n_past, n_loc = (int(v) for v in sizes_row)
+    return np.concatenate([np.arange(n_init), a + np.arange(n_sep), a + s + np.arange(n_past + n_loc)]).astype(np.int64)
+
+
+def decode_rope(q: np.ndarray, Kc: np.ndarray, Vc: np.ndarray, sizes: np.ndarray, a: int, s: int,
+                scale: float, base: float):
+    """Single-query attention over the cache with positions taken *within the cache* (Sec. 3.3
+    "Positional Encoding"; Sec. 4.6, the ablation of the positional shifting): the valid entries, oldest
+    first, are at positions 0 .. nv-1 and the query (the newest entry's token) at nv-1.  q and the
+    cached keys are stored without position encoding.  Returns (out [S,Hq,d], lse [S,Hq]) in fp64.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    Kc = np.asarray(Kc, dtype=np.float64)
+    Vc = np.asarray(Vc, dtype=np.float64)
+    S, Hq, d = q.shape
+    Hkv = Kc.shape[1]
+    G = Hq // Hkv
+    out = np.zeros((S, Hq, d))
+    lse = np.full((S, Hq), -np.inf)
+    for sq in range(S):
+        slots = cache_slots(sizes[sq], a, s)
+        nv = len(slots)
+        if nv == 0:
+            continue
+        for h in range(Hq):
+            kv = h // G
+            Kr = rope_rotate(Kc[sq, kv, slots], np.arange(nv), base)
+            qr = rope_rotate(q[sq, h], nv - 1, base)
+            sc = scale * (Kr @ qr)
+            m = sc.max()
+            p = np.exp(sc - m)
+            lse[sq, h] = m + np.log(p.sum())
+            out[sq, h] = (p / p.sum()) @ Vc[sq, kv, slots]
+    return out, lse
+
+
+def append_token(Kc: np.ndarray, Vc: np.ndarray, win_is_sep: np.ndarray, sizes: np.ndarray,
+                 k_new: np.ndarray, v_new: np.ndarray, is_sep_new: np.ndarray, a: int, s: int, w: int):
+    """One new token per sequence enters the cache (Sec. 3.3 "Framework"): the Initial Cache takes the
+    first a tokens; later tokens enter the Local Window Cache, whose oldest entry passes to the Past
+    Window Cache once it holds more than w.  A sequence whose window region [a+s, c) is full is left
+    as it is (the compression step has to run first).  Works on copies; k_new, v_new: [S,Hkv,d].
+    """
+    Kc = np.array(Kc, copy=True)
+    Vc = np.array(Vc, copy=True)
+    fl = np.array(win_is_sep, dtype=np.uint8, copy=True)
+    sz = np.array(sizes, dtype=np.int32, copy=True)
+    S, _, c, _ = Kc.shape
+    wcap = c - a - s
+    for sq in range(S):
+        n_init, n_sep, n_past, n_loc = (int(v) for v in sz[sq])
+        if n_init < a:
+            Kc[sq, :, n_init] = k_new[sq]
+            Vc[sq, :, n_init] = v_new[sq]
+            sz[sq, 0] = n_init + 1
+            continue
+        u = n_past + n_loc
+        if u >= wcap:
+            continue
+        Kc[sq, :, a + s + u] = k_new[sq]
+        Vc[sq, :, a + s + u] = v_new[sq]
+        fl[sq, u] = 1 if is_sep_new[sq] else 0
+        n_loc += 1
+        if n_loc > w:
+            n_loc -= 1
+            n_past += 1
+        sz[sq, 2], sz[sq, 3] = n_past, n_loc
+    return Kc, Vc, fl, sz

@@ -444,6 +444,132 @@ def test_decode_zero_query_probe_counts_entries():
 
 
 # ----------------------------------------------------------------------------------------------
+# positions within the cache (Sec. 3.3 "Positional Encoding") and the append step
+# ----------------------------------------------------------------------------------------------
+def test_rope_rotation_worked_examples():
+    """Pairing (i, i + d/2), direction and frequencies: unit vectors turn by pos * base**(-2i/d)."""
+    for pos in (0, 1, 7, 1000):
+        assert np.allclose(oracle.rope_rotate(np.array([1.0, 0.0]), pos, 123.0), [math.cos(pos), math.sin(pos)], atol=1e-12)
+        assert np.allclose(oracle.rope_rotate(np.array([0.0, 1.0]), pos, 123.0), [-math.sin(pos), math.cos(pos)], atol=1e-12)
+        # d = 4, base = 100: the second pair (dimensions 1 and 3) turns by 0.1 per position
+        got = oracle.rope_rotate(np.array([0.0, 2.0, 0.0, 0.0]), pos, 100.0)
+        assert np.allclose(got, [0.0, 2 * math.cos(0.1 * pos), 0.0, 2 * math.sin(0.1 * pos)], atol=1e-12)
+    # d = 8, base = 10000: angles 1, 0.1, 0.01, 0.001 per position
+    x = np.zeros(8)
+    x[3] = 1.0
+    assert np.allclose(oracle.rope_rotate(x, 500, 10000.0)[[3, 7]], [math.cos(0.5), math.sin(0.5)], atol=1e-12)
+    # a rotation: lengths are kept, positions broadcast over rows
+    X = _rand((5, 16), 3)
+    assert np.allclose(np.linalg.norm(oracle.rope_rotate(X, np.arange(5), 10000.0), axis=1), np.linalg.norm(X, axis=1), atol=1e-12)
+
+
+def test_decode_rope_matches_the_relative_position_form():
+    """With rotary encoding a score depends on the distance only: in complex form, pairing dimension
+    i with i + d/2, score = Re sum_i q_i conj(k_i) exp(1j (m - p) theta_i).  The query sits at the
+    newest entry's position m = nv - 1 and entry e (oldest first) at p = e."""
+    S, Hq, Hkv, d, a, s, c = 3, 4, 2, 8, 2, 5, 20
+    base, scale = 50.0, 0.3
+    Kc, Vc, q = _rand((S, Hkv, c, d), 1), _rand((S, Hkv, c, d), 2), _rand((S, Hq, d), 3)
+    sizes = np.array([[2, 5, 4, 5], [1, 0, 0, 1], [2, 3, 0, 9]], dtype=np.int32)
+    out, lse = oracle.decode_rope(q, Kc, Vc, sizes, a, s, scale, base)
+    h = d // 2
+    theta = np.array([base ** (-i / h) for i in range(h)])
+    for sq in range(S):
+        slots = list(range(sizes[sq, 0])) + [a + k for k in range(sizes[sq, 1])] + [a + s + u for u in range(sizes[sq, 2] + sizes[sq, 3])]
+        nv = len(slots)
+        for hq in range(Hq):
+            kv = hq // (Hq // Hkv)
+            zq = q[sq, hq, :h] + 1j * q[sq, hq, h:]
+            sc = np.empty(nv)
+            for e, sl in enumerate(slots):
+                zk = Kc[sq, kv, sl, :h] + 1j * Kc[sq, kv, sl, h:]
+                sc[e] = scale * np.real(np.sum(zq * np.conj(zk) * np.exp(1j * (nv - 1 - e) * theta)))
+            pr = np.exp(sc - sc.max())
+            assert np.allclose(out[sq, hq], (pr / pr.sum()) @ Vc[sq, kv, slots], atol=1e-12)
+            assert np.isclose(lse[sq, hq], sc.max() + np.log(pr.sum()), atol=1e-12)
+
+
+def test_decode_rope_special_cases():
+    S, Hq, Hkv, d, a, s, c = 2, 2, 1, 8, 2, 4, 16
+    Kc, Vc, q = _rand((S, Hkv, c, d), 4), _rand((S, Hkv, c, d), 5), _rand((S, Hq, d), 6)
+    sizes = np.array([[2, 3, 2, 4], [2, 4, 0, 6]], dtype=np.int32)
+    # (i) frequencies that vanish (huge base) leave only pair 0 turning; without that pair in the query
+    #     the encoding drops out and the plain decode must come back
+    q0 = q.copy()
+    q0[..., 0] = 0.0
+    q0[..., d // 2] = 0.0
+    out, lse = oracle.decode_rope(q0, Kc, Vc, sizes, a, s, 0.4, 1e300)
+    out_plain, lse_plain = oracle.decode(q0, Kc, Vc, sizes, a, s, 0.4)
+    assert np.allclose(out, out_plain, atol=1e-12) and np.allclose(lse, lse_plain, atol=1e-12)
+    # (ii) one entry: position 0 for key and query, no rotation at all
+    one = np.array([[1, 0, 0, 0], [1, 0, 0, 0]], dtype=np.int32)
+    out, lse = oracle.decode_rope(q, Kc, Vc, one, a, s, 0.4, 10000.0)
+    assert np.allclose(out, np.repeat(Vc[:, :, 0], Hq, axis=1), atol=1e-12)
+    assert np.allclose(lse, 0.4 * np.einsum("shd,sd->sh", q, Kc[:, 0, 0]), atol=1e-12)
+    # (iii) positions are those within the cache, not slots: the same entries in the same order, split
+    #      differently among the blocks, give the same result
+    sizes_a = np.array([[2, 3, 0, 4]], dtype=np.int32)
+    sizes_b = np.array([[2, 0, 0, 7]], dtype=np.int32)
+    Kb, Vb = np.zeros_like(Kc[:1]), np.zeros_like(Vc[:1])
+    src = [0, 1, a, a + 1, a + 2, a + s, a + s + 1, a + s + 2, a + s + 3]
+    dst = [0, 1] + [a + s + u for u in range(7)]
+    Kb[0, :, dst], Vb[0, :, dst] = Kc[0, :, src], Vc[0, :, src]
+    oa, la = oracle.decode_rope(q[:1], Kc[:1], Vc[:1], sizes_a, a, s, 0.4, 10000.0)
+    ob, lb = oracle.decode_rope(q[:1], Kb, Vb, sizes_b, a, s, 0.4, 10000.0)
+    assert np.allclose(oa, ob, atol=1e-12) and np.allclose(la, lb, atol=1e-12)
+    # (iv) an empty cache
+    out, lse = oracle.decode_rope(q, Kc, Vc, np.zeros((S, 4), dtype=np.int32), a, s, 0.4, 10000.0)
+    assert (out == 0).all() and np.isneginf(lse).all()
+
+
+def _stream(is_sep, K, a, s, w, c, upto):
+    """Tokens 0 .. upto-1 enter one by one; the compression step runs whenever the window region is full."""
+    S, Hkv, L, d = K.shape
+    Kc, Vc = np.zeros((S, Hkv, c, d)), np.zeros((S, Hkv, c, d))
+    fl, sz = np.zeros((S, c - a - s), dtype=np.uint8), np.zeros((S, 4), dtype=np.int32)
+    hist = []
+    for m in range(upto):
+        Kc, Vc, fl, sz = oracle.append_token(Kc, Vc, fl, sz, K[:, :, m], -K[:, :, m], is_sep[:, m], a, s, w)
+        if sz[0, 2] + sz[0, 3] == c - a - s:
+            Kc, Vc, fl, sz = oracle.evict_window(Kc, Vc, fl, sz, a, s)
+        hist.append(sz[0].copy())
+    return Kc, Vc, fl, sz, hist
+
+
+def test_append_and_compress_reach_the_handover_state():
+    """Sec. 3.2 / 3.3: streaming the tokens in one by one must leave the cache the hand-over from a
+    prefill of the same tokens builds (same rows in the same slots, same flags and sizes)."""
+    a, s, w, c, L = 2, 5, 4, 19, 90
+    is_sep = _flags(1, L, 0.3, 11)
+    K = _rand((1, 2, L, 3), 12)
+    for upto in (1, 2, 3, 9, 14, 15, 40, 90):
+        Kc, Vc, fl, sz, _ = _stream(is_sep, K, a, s, w, c, upto)
+        nw = int(sz[0, 2] + sz[0, 3])
+        Kf, Vf, ff, sf, valid = oracle.fill_from_prefill(K[:, :, :upto], -K[:, :, :upto], is_sep[:, :upto], a, s, w, c, nw)
+        assert np.array_equal(sz, sf), (upto, sz, sf)
+        assert np.array_equal(fl[:, :nw], ff[:, :nw])
+        assert np.array_equal(Kc[0][:, valid[0]], Kf[0][:, valid[0]]) and np.array_equal(Vc[0][:, valid[0]], Vf[0][:, valid[0]])
+
+
+def test_append_follows_the_size_state_machine():
+    """Without a Separator Cache (s = 0) "window region full" and "Size_run = c" are the same event, so
+    the sizes must follow the simulator of Sec. 3.3 token by token; the Local Window never exceeds w."""
+    a, s, w, c, L = 3, 0, 4, 13, 60
+    is_sep = _flags(1, L, 0.3, 13)
+    K = _rand((1, 1, L, 2), 14)
+    sim = cache_sim.simulate(is_sep[0], a, s, w, c)
+    _, _, _, _, hist = _stream(is_sep, K, a, s, w, c, L)
+    for m, h in enumerate(hist):
+        assert h[0] == min(a, m + 1) and h[3] <= w
+        assert h[2] + h[3] == sim["n"][m] and h.sum() == sim["size_run"][m]
+    # a full window region refuses the token
+    Kc, Vc = np.zeros((1, 1, 8, 2)), np.zeros((1, 1, 8, 2))
+    sz = np.array([[1, 2, 2, 3]], dtype=np.int32)
+    K2, V2, f2, s2 = oracle.append_token(Kc, Vc, np.zeros((1, 5), dtype=np.uint8), sz, np.ones((1, 1, 2)), np.ones((1, 1, 2)), np.array([1]), 1, 2, 3)
+    assert np.array_equal(s2, sz) and (K2 == 0).all()
+
+
+# ----------------------------------------------------------------------------------------------
 # eviction and the cache-size state machine
 # ----------------------------------------------------------------------------------------------
 def test_evict_postconditions_and_rows_bit_exact():

@@ -169,6 +169,40 @@ int sepattn_decode(const sepkv_params *p, const void *q, const void *Kc, const v
                    const int32_t *sizes, void *out, float *lse, void *ws, size_t ws_bytes,
                    void *stream);
 
+/* Decode with positions within the cache (Sec. 3.3 "Positional Encoding"; Sec. 4.6, the ablation
+ * of the positional shifting): q and the cached keys are stored WITHOUT position encoding; the
+ * valid entries of a sequence, oldest first (Initial, Separator, Past Window, Local Window Cache),
+ * are at positions 0 .. nv-1 and the query, the newest entry's token, at nv-1.  Keys and query are
+ * turned by the rotary encoding of the backbones the paper evaluates (dimension i < d/2 pairs with
+ * i + d/2; the pair at position t is rotated by t * base^(-2i/d)) inside the kernel, so entries
+ * that move or drop out of the cache never have to be re-encoded in memory.
+ *   sepkv_rope_table: fills  table  DEVICE fp32 [n_pos, 2, d/2]  (16-byte aligned; cos, then sin, of
+ *       position * base^(-2i/d); computed in double, rounded to fp32); d is 64 or 128, base > 1.
+ *       Build it once per (d, base); the caller owns it.
+ *   sepattn_decode_rope: as sepattn_decode, plus  rope_table  from sepkv_rope_table with
+ *       n_pos >= c (SEPATTN_ERR_SHAPE otherwise).  The table must be complete before the call
+ *       runs (same stream, or synchronised).
+ */
+int sepkv_rope_table(int n_pos, int d, double base, float *table, void *stream);
+int sepattn_decode_rope(const sepkv_params *p, const void *q, const void *Kc, const void *Vc,
+                        const int32_t *sizes, const float *rope_table, int n_pos, void *out,
+                        float *lse, void *ws, size_t ws_bytes, void *stream);
+
+/* A new token enters the cache of every sequence (Sec. 3.3 "Framework"): the first a tokens of a
+ * sequence go to the Initial Cache; a later token is written behind the newest window entry and
+ * joins the Local Window Cache, and once that holds more than w its oldest entry passes to the
+ * Past Window Cache.  A sequence whose window region is full (Size_past_w + Size_local_w = c-a-s)
+ * is left unchanged: run sepkv_evict_window first (its sizes tell: they did not change).
+ *   k_new, v_new  DEVICE dtype [S, Hkv, d]      the token's key and value (copied bit-exactly)
+ *   is_sep_new    DEVICE uint8 [S]              whether the token is a separator
+ *   Kc, Vc        DEVICE dtype [S, Hkv, c, d]   in/out
+ *   win_is_sep    DEVICE uint8 [S, c-a-s]       in/out
+ *   sizes         DEVICE int32 [S, 4]           in/out
+ */
+int sepkv_append(const sepkv_params *p, const void *k_new, const void *v_new,
+                 const uint8_t *is_sep_new, void *Kc, void *Vc, uint8_t *win_is_sep,
+                 int32_t *sizes, void *stream);
+
 /* Compression step (Sec. 3.3; caption of the streaming-design figure): the separators of the Past
  * Window Cache are appended to the Separator Cache, its other entries are dropped, and the Local
  * Window becomes the whole window.  If the Separator Cache would exceed s, its oldest entries are
@@ -236,7 +270,9 @@ typedef enum {
     SEPATTN_K_EVICT_PLAN = 9,
     SEPATTN_K_EVICT_MOVE = 10,
     SEPATTN_K_CACHE_FILL = 11,
-    SEPATTN_K_COUNT = 12
+    SEPATTN_K_ROPE_TABLE = 12,
+    SEPATTN_K_CACHE_APPEND = 13,
+    SEPATTN_K_COUNT = 14
 } sepattn_kernel_id;
 const char *sepattn_kernel_name(int kernel);
 int sepattn_profile_begin(int kernel, int max_records);

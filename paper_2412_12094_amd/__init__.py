@@ -21,6 +21,9 @@ from .binding import (  # noqa: F401
     sepattn_decode,
     sepkv_evict_window,
     sepkv_fill_from_prefill,
+    sepkv_rope_table,
+    sepattn_decode_rope,
+    sepkv_append,
     KERNEL_IDS,
     sepattn_kernel_name,
     sepattn_profile_begin,

@@ -34,6 +34,9 @@ EXPORTS = (
     "sepkv_evict_workspace_bytes",
     "sepkv_evict_window",
     "sepkv_fill_from_prefill",
+    "sepkv_rope_table",
+    "sepattn_decode_rope",
+    "sepkv_append",
     "sepattn_kernel_name",
     "sepattn_profile_begin",
     "sepattn_profile_end",
@@ -100,6 +103,12 @@ def load(path: Optional[str] = None):
     lib.sepkv_evict_window.argtypes = [kp] + [vp] * 5 + [sz, vp]
     lib.sepkv_fill_from_prefill.restype = ci
     lib.sepkv_fill_from_prefill.argtypes = [kp, ci, ci, vp, vp, vp, vp, ci, vp, vp, vp, vp, vp, vp]
+    lib.sepkv_rope_table.restype = ci
+    lib.sepkv_rope_table.argtypes = [ci, ci, ctypes.c_double, vp, vp]
+    lib.sepattn_decode_rope.restype = ci
+    lib.sepattn_decode_rope.argtypes = [kp, vp, vp, vp, vp, vp, ci, vp, vp, vp, sz, vp]
+    lib.sepkv_append.restype = ci
+    lib.sepkv_append.argtypes = [kp] + [vp] * 8
     lib.sepattn_kernel_name.restype = ctypes.c_char_p
     lib.sepattn_kernel_name.argtypes = [ci]
     lib.sepattn_profile_begin.restype = ci
@@ -117,7 +126,7 @@ def status_string(status: int) -> str:
 
 KERNEL_IDS = {"mark": 0, "compact_count": 1, "compact_write": 2, "forward": 3, "bwd_dq": 4, "bwd_dkv": 5,
               "bwd_combine": 6, "decode_split": 7, "decode_merge": 8, "evict_plan": 9, "evict_move": 10,
-              "cache_fill": 11}
+              "cache_fill": 11, "rope_table": 12, "cache_append": 13}
 
 
 def sepattn_kernel_name(kernel: int) -> str:
@@ -292,6 +301,49 @@ def sepattn_decode(q, Kc, Vc, sizes, a: int, s: int, w: int, scale: float,
            lib.sepattn_decode(ctypes.byref(p), _ptr(q), _ptr(Kc), _ptr(Vc), _ptr(sizes), _ptr(o), _ptr(lse),
                               _ptr(ws), ws.numel(), _stream(q)))
     return o, lse
+
+
+def sepkv_rope_table(n_pos: int, d: int, base: float, device, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """-> fp32 [n_pos, 2, d/2]: cos, then sin, of position * base^(-2i/d)."""
+    if out is None:
+        out = torch.empty((int(n_pos), 2, int(d) // 2), dtype=torch.float32, device=device)
+    _dev(out)
+    _check("sepkv_rope_table", load().sepkv_rope_table(int(n_pos), int(d), float(base), _ptr(out), _stream(out)))
+    return out
+
+
+def sepattn_decode_rope(q, Kc, Vc, sizes, rope_table, a: int, s: int, w: int, scale: float,
+                        out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None, ws: Optional[torch.Tensor] = None):
+    """As sepattn_decode, with q and the cached keys stored without position encoding and turned by
+    their positions within the cache inside the kernel; rope_table from sepkv_rope_table."""
+    _dev(q, Kc, Vc, sizes, rope_table)
+    assert sizes.dtype == torch.int32 and rope_table.dtype == torch.float32
+    assert rope_table.dim() == 3 and rope_table.shape[1] == 2 and rope_table.shape[2] * 2 == q.shape[2]
+    p = _kv_params(q, Kc, a, s, w, scale)
+    lib = load()
+    if out is None:
+        o = torch.empty_like(q)
+        lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
+    else:
+        o, lse = out
+    if ws is None:
+        ws = _ws(lib.sepattn_decode_workspace_bytes(ctypes.byref(p)), q.device)
+    _check("sepattn_decode_rope",
+           lib.sepattn_decode_rope(ctypes.byref(p), _ptr(q), _ptr(Kc), _ptr(Vc), _ptr(sizes), _ptr(rope_table),
+                                   int(rope_table.shape[0]), _ptr(o), _ptr(lse), _ptr(ws), ws.numel(), _stream(q)))
+    return o, lse
+
+
+def sepkv_append(k_new, v_new, is_sep_new, Kc, Vc, win_is_sep, sizes, Hq: int, a: int, s: int, w: int) -> None:
+    """In place: k_new, v_new [S,Hkv,d] and is_sep_new uint8 [S] enter Kc, Vc [S,Hkv,c,d], win_is_sep, sizes."""
+    _dev(k_new, v_new, is_sep_new, Kc, Vc, win_is_sep, sizes)
+    assert sizes.dtype == torch.int32 and is_sep_new.dtype == torch.uint8 and win_is_sep.dtype == torch.uint8
+    S, Hkv, c, d = Kc.shape
+    assert tuple(k_new.shape) == (S, Hkv, d) and tuple(v_new.shape) == (S, Hkv, d) and k_new.dtype == Kc.dtype
+    p = SepkvParams(S, int(Hq), Hkv, d, int(a), int(s), int(w), c, 1.0, _dtype_code(Kc))
+    _check("sepkv_append",
+           load().sepkv_append(ctypes.byref(p), _ptr(k_new), _ptr(v_new), _ptr(is_sep_new), _ptr(Kc), _ptr(Vc),
+                               _ptr(win_is_sep), _ptr(sizes), _stream(Kc)))
 
 
 def sepkv_evict_window(Kc, Vc, win_is_sep, sizes, Hq: int, a: int, s: int, w: int,

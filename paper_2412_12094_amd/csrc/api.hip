@@ -109,7 +109,8 @@ const char *sepattn_kernel_name(int kernel) {
                                                  "fwd_bf16_kernel", "dq_kernel", "dkv_kernel",
                                                  "dkv_combine_kernel", "decode_split_kernel",
                                                  "decode_merge_kernel", "evict_plan_kernel",
-                                                 "evict_move_kernel", "cache_fill_kernel"};
+                                                 "evict_move_kernel", "cache_fill_kernel", "rope_table_kernel",
+                                                 "cache_append_kernel"};
     return (kernel >= 0 && kernel < SEPATTN_K_COUNT) ? names[kernel] : "unknown";
 }
 
@@ -250,7 +251,39 @@ int sepattn_decode(const sepkv_params *p, const void *q, const void *Kc, const v
     if (!q || !Kc || !Vc || !sizes || !out) return SEPATTN_ERR_NULL;
     if (!aligned(q, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(out, 16)) return SEPATTN_ERR_PARAM;
     if (!ws || ws_bytes < decode_workspace(*p) || !aligned(ws, 256)) return SEPATTN_ERR_WORKSPACE;
-    return launch_decode(*p, q, Kc, Vc, sizes, out, lse, ws, static_cast<hipStream_t>(stream));
+    return launch_decode(*p, q, Kc, Vc, sizes, nullptr, 0, out, lse, ws, static_cast<hipStream_t>(stream));
+}
+
+int sepkv_rope_table(int n_pos, int d, double base, float *table, void *stream) {
+    if (!table) return SEPATTN_ERR_NULL;
+    if (n_pos < 1 || n_pos > (1 << 28)) return SEPATTN_ERR_SHAPE;
+    if (d != 64 && d != 128) return SEPATTN_ERR_DTYPE;
+    if (!(base > 1.0) || base > 1e30) return SEPATTN_ERR_PARAM;
+    if (!aligned(table, 16)) return SEPATTN_ERR_PARAM;
+    return launch_rope_table(n_pos, d, base, table, static_cast<hipStream_t>(stream));
+}
+
+int sepattn_decode_rope(const sepkv_params *p, const void *q, const void *Kc, const void *Vc,
+                        const int32_t *sizes, const float *rope_table, int n_pos, void *out, float *lse,
+                        void *ws, size_t ws_bytes, void *stream) {
+    int rc = check_kv(p);
+    if (rc != SEPATTN_OK) return rc;
+    if (!q || !Kc || !Vc || !sizes || !out || !rope_table) return SEPATTN_ERR_NULL;
+    if (n_pos < p->c) return SEPATTN_ERR_SHAPE;  // a row for every position a full cache can hold
+    if (!aligned(q, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(out, 16) || !aligned(rope_table, 16))
+        return SEPATTN_ERR_PARAM;
+    if (!ws || ws_bytes < decode_workspace(*p) || !aligned(ws, 256)) return SEPATTN_ERR_WORKSPACE;
+    return launch_decode(*p, q, Kc, Vc, sizes, rope_table, n_pos, out, lse, ws, static_cast<hipStream_t>(stream));
+}
+
+int sepkv_append(const sepkv_params *p, const void *k_new, const void *v_new, const uint8_t *is_sep_new,
+                 void *Kc, void *Vc, uint8_t *win_is_sep, int32_t *sizes, void *stream) {
+    int rc = check_kv(p);
+    if (rc != SEPATTN_OK) return rc;
+    if (!k_new || !v_new || !is_sep_new || !Kc || !Vc || !win_is_sep || !sizes) return SEPATTN_ERR_NULL;
+    if (!aligned(k_new, 16) || !aligned(v_new, 16) || !aligned(Kc, 16) || !aligned(Vc, 16)) return SEPATTN_ERR_PARAM;
+    return launch_cache_append(*p, k_new, v_new, is_sep_new, Kc, Vc, win_is_sep, sizes,
+                               static_cast<hipStream_t>(stream));
 }
 
 size_t sepkv_evict_workspace_bytes(const sepkv_params *p) {

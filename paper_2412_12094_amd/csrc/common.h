@@ -60,8 +60,13 @@ int launch_backward_bf16(const sepattn_params &p, const void *Q, const void *K, 
 
 // ---- streaming cache ---------------------------------------------------------------------------
 size_t decode_workspace(const sepkv_params &p);
+// rope: table of cos / sin by position [n_pos][2][d/2] (keys stored without position encoding), or nullptr
 int launch_decode(const sepkv_params &p, const void *q, const void *Kc, const void *Vc,
-                  const int32_t *sizes, void *out, float *lse, void *ws, hipStream_t st);
+                  const int32_t *sizes, const float *rope, int n_pos, void *out, float *lse, void *ws,
+                  hipStream_t st);
+int launch_rope_table(int n_pos, int d, double base, float *table, hipStream_t st);
+int launch_cache_append(const sepkv_params &p, const void *k_new, const void *v_new, const uint8_t *is_sep_new,
+                        void *Kc, void *Vc, uint8_t *win_is_sep, int32_t *sizes, hipStream_t st);
 size_t evict_workspace(const sepkv_params &p);
 int launch_evict(const sepkv_params &p, void *Kc, void *Vc, uint8_t *win_is_sep, int32_t *sizes,
                  void *ws, hipStream_t st);

@@ -10,6 +10,11 @@
 //     with DPP adds, and each lane group keeps its own online-softmax state;
 //   - partial (max, sum, unnormalised output) triples are merged through LDS, written to the
 //     workspace, and a second tiny kernel merges the `nsplit` slices.
+// With ROPE (positions within the cache, Sec. 3.3 "Positional Encoding") the keys are stored without
+// position encoding; a rotary score depends on the distance between query and key only, so instead
+// of turning the key row the kernel turns the query by that distance: the lane that holds
+// dimensions of the first half uses q_x cos - q_y sin, the one with the second half q_y cos + q_x sin
+// (cos / sin of distance * frequency from the caller's table).
 #include "common.h"
 #include "decode_common.h"
 
@@ -61,10 +66,11 @@ struct Partial {
     static constexpr int kFloats = D + 2;
 };
 
-template <typename T, int D, int GT>
+template <typename T, int D, int GT, bool ROPE>
 __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(
     sepkv_params p, int nsplit, const T *__restrict__ q, const T *__restrict__ Kc,
-    const T *__restrict__ Vc, const int32_t *__restrict__ sizes, float *__restrict__ part) {
+    const T *__restrict__ Vc, const int32_t *__restrict__ sizes, const float *__restrict__ rope, int n_pos,
+    float *__restrict__ part) {
     constexpr int LPR = D / 8;         // lanes per cache row
     constexpr int RPW = kWave / LPR;   // rows per wave load
     constexpr int NSLOT = kDecodeWaves * RPW;
@@ -100,6 +106,17 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(
         load8<T>(q + ((long)sq * p.Hq + h0 + g) * D + c * 8, qv[g]);
         for (int t = 0; t < 8; ++t) qv[g][t] *= p.scale * kLog2e;
     }
+    // the other member of each rotary pair (dimension i <-> i + D/2), signed: -q_y for a lane of the
+    // first half, +q_x for one of the second half
+    float qo[ROPE ? GT : 1][8];
+    const int f0 = (c % (LPR / 2)) * 8;  // first of this lane's eight frequencies
+    if constexpr (ROPE) {
+        const float sgn = (c >= LPR / 2) ? p.scale * kLog2e : -p.scale * kLog2e;
+        for (int g = 0; g < GT; ++g) {
+            load8<T>(q + ((long)sq * p.Hq + h0 + g) * D + ((c + LPR / 2) % LPR) * 8, qo[g]);
+            for (int t = 0; t < 8; ++t) qo[g][t] *= sgn;
+        }
+    }
     float m[GT], l[GT], acc[GT][8];
     for (int g = 0; g < GT; ++g) {
         m[g] = -INFINITY;
@@ -119,15 +136,35 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(
             load8<T>(Vh + (long)sl * D + c * 8, vr[u]);
         }
         float sc[GT][kRowsUnroll];
-#pragma unroll
-        for (int g = 0; g < GT; ++g) {
+        if constexpr (ROPE) {
 #pragma unroll
             for (int u = 0; u < kRowsUnroll; ++u) {
-                float s = 0.f;
+                // entry e sits at position e, the query at nv - 1
+                const int dist = ok[u] ? (nv - 1) - (eb + u * NSLOT) : 0;
+                const float *row = rope + (long)min(dist, n_pos - 1) * D + f0;
+                float co[8], si[8];
+                load8<float>(row, co);
+                load8<float>(row + D / 2, si);
 #pragma unroll
-                for (int t = 0; t < 8; ++t) s = fmaf(qv[g][t], kr[u][t], s);
-                s = row_sum<LPR>(s);
-                sc[g][u] = ok[u] ? s : -INFINITY;
+                for (int g = 0; g < GT; ++g) {
+                    float s = 0.f;
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) s = fmaf(fmaf(qv[g][t], co[t], qo[g][t] * si[t]), kr[u][t], s);
+                    s = row_sum<LPR>(s);
+                    sc[g][u] = ok[u] ? s : -INFINITY;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int g = 0; g < GT; ++g) {
+#pragma unroll
+                for (int u = 0; u < kRowsUnroll; ++u) {
+                    float s = 0.f;
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) s = fmaf(qv[g][t], kr[u][t], s);
+                    s = row_sum<LPR>(s);
+                    sc[g][u] = ok[u] ? s : -INFINITY;
+                }
             }
         }
 #pragma unroll
@@ -222,19 +259,19 @@ int pick_nsplit(const sepkv_params &p) {
     return (int)(ns < 1 ? 1 : (ns > 64 ? 64 : ns));
 }
 
-template <typename T, int D>
+template <typename T, int D, bool ROPE>
 int launch_decode_t(const sepkv_params &p, const T *q, const T *Kc, const T *Vc, const int32_t *sizes,
-                    T *out, float *lse, float *part, hipStream_t st) {
+                    const float *rope, int n_pos, T *out, float *lse, float *part, hipStream_t st) {
     int G = p.Hq / p.Hkv, GT = pick_gt(G), nsplit = pick_nsplit(p);
     dim3 grid(nsplit, p.S * p.Hkv * (G / GT)), block(kDecodeThreads);
     {
     ProfScope prof(SEPATTN_K_DECODE_SPLIT, st);
     if (GT == 4)
-        hipLaunchKernelGGL((decode_split_kernel<T, D, 4>), grid, block, 0, st, p, nsplit, q, Kc, Vc, sizes, part);
+        hipLaunchKernelGGL((decode_split_kernel<T, D, 4, ROPE>), grid, block, 0, st, p, nsplit, q, Kc, Vc, sizes, rope, n_pos, part);
     else if (GT == 2)
-        hipLaunchKernelGGL((decode_split_kernel<T, D, 2>), grid, block, 0, st, p, nsplit, q, Kc, Vc, sizes, part);
+        hipLaunchKernelGGL((decode_split_kernel<T, D, 2, ROPE>), grid, block, 0, st, p, nsplit, q, Kc, Vc, sizes, rope, n_pos, part);
     else
-        hipLaunchKernelGGL((decode_split_kernel<T, D, 1>), grid, block, 0, st, p, nsplit, q, Kc, Vc, sizes, part);
+        hipLaunchKernelGGL((decode_split_kernel<T, D, 1, ROPE>), grid, block, 0, st, p, nsplit, q, Kc, Vc, sizes, rope, n_pos, part);
     }
     if (hipGetLastError() != hipSuccess) return SEPATTN_ERR_HIP;
     ProfScope prof(SEPATTN_K_DECODE_MERGE, st);
@@ -249,13 +286,24 @@ size_t decode_workspace(const sepkv_params &p) {
     return align_up((size_t)p.S * p.Hq * nsplit * (p.d + 2) * sizeof(float), 256);
 }
 
+template <typename T>
+int launch_decode_valu(const sepkv_params &p, const void *q, const void *Kc, const void *Vc, const int32_t *sizes,
+                       const float *rope, int n_pos, void *out, float *lse, float *part, hipStream_t st) {
+    const T *q_ = (const T *)q, *K_ = (const T *)Kc, *V_ = (const T *)Vc;
+    if (p.d == 64 && rope) return launch_decode_t<T, 64, true>(p, q_, K_, V_, sizes, rope, n_pos, (T *)out, lse, part, st);
+    if (p.d == 64) return launch_decode_t<T, 64, false>(p, q_, K_, V_, sizes, rope, n_pos, (T *)out, lse, part, st);
+    if (rope) return launch_decode_t<T, 128, true>(p, q_, K_, V_, sizes, rope, n_pos, (T *)out, lse, part, st);
+    return launch_decode_t<T, 128, false>(p, q_, K_, V_, sizes, rope, n_pos, (T *)out, lse, part, st);
+}
+
 int launch_decode(const sepkv_params &p, const void *q, const void *Kc, const void *Vc,
-                  const int32_t *sizes, void *out, float *lse, void *ws, hipStream_t st) {
+                  const int32_t *sizes, const float *rope, int n_pos, void *out, float *lse, void *ws,
+                  hipStream_t st) {
     float *part = static_cast<float *>(ws);
     if (decode_mfma_applicable(p)) {
         using T = uint16_t;
         const int nsplit = decode_mfma_nsplit(p);
-        int rc = launch_decode_mfma(p, nsplit, (const T *)q, (const T *)Kc, (const T *)Vc, sizes, (T *)out, lse, part, st);
+        int rc = launch_decode_mfma(p, nsplit, (const T *)q, (const T *)Kc, (const T *)Vc, sizes, rope, n_pos, (T *)out, lse, part, st);
         if (rc != SEPATTN_OK || nsplit == 1) return rc;
         ProfScope prof(SEPATTN_K_DECODE_MERGE, st);
         if (p.d == 64)
@@ -264,16 +312,8 @@ int launch_decode(const sepkv_params &p, const void *q, const void *Kc, const vo
             hipLaunchKernelGGL((decode_merge_kernel<T, 128>), dim3(p.S * p.Hq), dim3(128), 0, st, nsplit, part, (T *)out, lse);
         return launch_status();
     }
-    if (p.dtype == SEPATTN_BF16) {
-        using T = uint16_t;
-        if (p.d == 64)
-            return launch_decode_t<T, 64>(p, (const T *)q, (const T *)Kc, (const T *)Vc, sizes, (T *)out, lse, part, st);
-        return launch_decode_t<T, 128>(p, (const T *)q, (const T *)Kc, (const T *)Vc, sizes, (T *)out, lse, part, st);
-    }
-    using T = float;
-    if (p.d == 64)
-        return launch_decode_t<T, 64>(p, (const T *)q, (const T *)Kc, (const T *)Vc, sizes, (T *)out, lse, part, st);
-    return launch_decode_t<T, 128>(p, (const T *)q, (const T *)Kc, (const T *)Vc, sizes, (T *)out, lse, part, st);
+    if (p.dtype == SEPATTN_BF16) return launch_decode_valu<uint16_t>(p, q, Kc, Vc, sizes, rope, n_pos, out, lse, part, st);
+    return launch_decode_valu<float>(p, q, Kc, Vc, sizes, rope, n_pos, out, lse, part, st);
 }
 
 }  // namespace sepattn

@@ -21,7 +21,9 @@ __device__ inline uint16_t decode_f32_to_bf16(float f) {
 
 bool decode_mfma_applicable(const sepkv_params &p);
 int decode_mfma_nsplit(const sepkv_params &p);
+// rope: table of cos / sin by position [n_pos][2][d/2], or nullptr for keys that carry their encoding
 int launch_decode_mfma(const sepkv_params &p, int nsplit, const uint16_t *q, const uint16_t *Kc, const uint16_t *Vc,
-                       const int32_t *sizes, uint16_t *out, float *lse, float *part, hipStream_t st);
+                       const int32_t *sizes, const float *rope, int n_pos, uint16_t *out, float *lse, float *part,
+                       hipStream_t st);
 
 }  // namespace sepattn

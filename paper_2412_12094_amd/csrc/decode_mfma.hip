@@ -19,6 +19,15 @@
 //   - online softmax per lane pair as in the training forward; the four waves' (max, sum, output)
 //     states are merged through LDS at the end.  With nsplit == 1 the workgroup writes the final
 //     output, else a partial record that decode_merge_kernel combines.
+//
+// Positions within the cache (Sec. 3.3 "Positional Encoding", Sec. 4.6): with ROPE the cache holds
+// keys without position encoding and the kernel turns every key row by its position among the valid
+// entries (oldest = 0) and the query by the newest entry's position, on the way from LDS to the
+// matrix cores.  A lane always reads the same row of a block and the same 2 x 8-element pieces of
+// it, and dimension i pairs with i + D/2, i.e. with the same element of another piece the lane
+// holds, so the rotation needs no exchange between lanes: a lane keeps cos / sin of its row's
+// position for its D/4 frequencies in registers (read once from the caller's table) and advances
+// them from one of its blocks to the next (128 positions on) with the angle-sum formulas.
 #include "common.h"
 #include "mfma_common.h"
 #include "decode_common.h"
@@ -42,15 +51,20 @@ constexpr int kDmThreads = 64 * kDmWaves;
 constexpr int kDmRows = 32;  // cache rows per stage
 constexpr int kDmStages = 2;
 
-template <int D>
+__device__ inline f32x8 widen(bf16x8 v) { return __builtin_convertvector(v, f32x8); }
+__device__ inline bf16x8 narrow(f32x8 v) { return __builtin_convertvector(v, bf16x8); }  // round to nearest even
+
+// rope: [n_pos][2][D/2] fp32, cos then sin of position * base^(-2i/D); only read with ROPE
+template <int D, bool ROPE>
 __global__ __launch_bounds__(kDmThreads, 1) void decode_mfma_kernel(
     sepkv_params p, int G, const uint16_t *__restrict__ q, const uint16_t *__restrict__ Kc,
-    const uint16_t *__restrict__ Vc, const int32_t *__restrict__ sizes, float *__restrict__ part,
-    uint16_t *__restrict__ out, float *__restrict__ lse) {
+    const uint16_t *__restrict__ Vc, const int32_t *__restrict__ sizes, const float *__restrict__ rope, int n_pos,
+    float *__restrict__ part, uint16_t *__restrict__ out, float *__restrict__ lse) {
     constexpr int CH = D / 8;          // 16-byte chunks per row
     constexpr int RPL = 64 / CH;       // rows covered by one wave-wide 1 KB load
     constexpr int NLD = kDmRows / RPL; // wave-wide loads per tensor per stage
     constexpr int KSTEPS = D / 16;
+    constexpr int KS2 = KSTEPS / 2;    // a lane's piece ks (dimensions 16 ks + 8 hh ..) pairs with piece ks + KS2
     constexpr int DB = D / 32;
     constexpr int TILE = kDmRows * D;  // elements per stage and tensor
     constexpr int PF = D + 2;          // partial record: max (log2 domain), sum, D unnormalised outputs
@@ -135,6 +149,33 @@ __global__ __launch_bounds__(kDmThreads, 1) void decode_mfma_kernel(
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) qreg[ks] = as_bf16x8(col < G ? qraw[ks] : u32x4{0u, 0u, 0u, 0u});
 
+    // cos / sin of a table row for this lane's frequencies 16 ks + 8 hh + (0..7), ks < KS2
+    f32x8 rc[KS2], rs[KS2];  // of this lane's row in its next block
+    f32x8 tc[KS2], ts[KS2];  // of the distance between two of its blocks
+    auto table_row = [&](int pos, f32x8(&co)[KS2], f32x8(&si)[KS2]) {
+        const float *row = rope + (long)min(max(pos, 0), n_pos - 1) * D + 8 * hh;
+#pragma unroll
+        for (int ks = 0; ks < KS2; ++ks) {
+            const f32x4 c0 = *reinterpret_cast<const f32x4 *>(row + 16 * ks), c1 = *reinterpret_cast<const f32x4 *>(row + 16 * ks + 4);
+            const f32x4 s0 = *reinterpret_cast<const f32x4 *>(row + D / 2 + 16 * ks), s1 = *reinterpret_cast<const f32x4 *>(row + D / 2 + 16 * ks + 4);
+            co[ks] = f32x8{c0[0], c0[1], c0[2], c0[3], c1[0], c1[1], c1[2], c1[3]};
+            si[ks] = f32x8{s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
+        }
+    };
+    // (x, y) -> (x cos - y sin, y cos + x sin) on a pair of pieces
+    auto turn = [&](bf16x8 &lo, bf16x8 &hi, const f32x8 &co, const f32x8 &si) {
+        const f32x8 x = widen(lo), y = widen(hi);
+        lo = narrow(x * co - y * si);
+        hi = narrow(y * co + x * si);
+    };
+    if constexpr (ROPE) {
+        table_row(nv - 1, rc, rs);  // the query is the newest entry's token
+#pragma unroll
+        for (int ks = 0; ks < KS2; ++ks) turn(qreg[ks], qreg[ks + KS2], rc[ks], rs[ks]);
+        table_row(e0 + wave * kDmRows + a_row, rc, rs);
+        table_row(kDmWaves * kDmRows, tc, ts);
+    }
+
     for (int k = 0; k < n_my; ++k) {
         wait_older_stage(k + 1 < n_my);
 #ifdef SEPATTN_X_TIMING
@@ -153,6 +194,10 @@ __global__ __launch_bounds__(kDmThreads, 1) void decode_mfma_kernel(
             bf16x8 ka[KSTEPS];
 #pragma unroll
             for (int ks = 0; ks < KSTEPS; ++ks) ka[ks] = lds_read_a_swz<kSwzRow, D>(Kst, a_row, 2 * ks + hh);
+            if constexpr (ROPE) {
+#pragma unroll
+                for (int ks = 0; ks < KS2; ++ks) turn(ka[ks], ka[ks + KS2], rc[ks], rs[ks]);
+            }
 #pragma unroll
             for (int ks = 0; ks < KSTEPS; ++ks) sacc = mfma_bf16(ka[ks], qreg[ks], sacc);
         }
@@ -168,6 +213,15 @@ __global__ __launch_bounds__(kDmThreads, 1) void decode_mfma_kernel(
         // cycles of a block
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         if (k + kDmStages < n_my) issue_stage(k + kDmStages);
+        if constexpr (ROPE) {
+            // the lane's row of its next block lies kDmWaves * kDmRows positions further on
+#pragma unroll
+            for (int ks = 0; ks < KS2; ++ks) {
+                const f32x8 c_old = rc[ks];
+                rc[ks] = c_old * tc[ks] - rs[ks] * ts[ks];
+                rs[ks] = rs[ks] * tc[ks] + c_old * ts[ks];
+            }
+        }
 
         if (n_valid < kDmRows) {
 #pragma unroll
@@ -277,15 +331,20 @@ int decode_mfma_nsplit(const sepkv_params &p) {
 }
 
 int launch_decode_mfma(const sepkv_params &p, int nsplit, const uint16_t *q, const uint16_t *Kc, const uint16_t *Vc,
-                       const int32_t *sizes, uint16_t *out, float *lse, float *part, hipStream_t st) {
+                       const int32_t *sizes, const float *rope, int n_pos, uint16_t *out, float *lse, float *part,
+                       hipStream_t st) {
     if (p.Hkv > 65535 || p.S > 65535) return SEPATTN_ERR_SHAPE;
-    const dim3 grid(nsplit, p.Hkv, p.S);
+    const dim3 grid(nsplit, p.Hkv, p.S), block(kDmThreads);
     const int G = p.Hq / p.Hkv;
     ProfScope prof(SEPATTN_K_DECODE_SPLIT, st);
-    if (p.d == 64)
-        hipLaunchKernelGGL((decode_mfma_kernel<64>), grid, dim3(kDmThreads), 0, st, p, G, q, Kc, Vc, sizes, part, out, lse);
+    if (p.d == 64 && rope)
+        hipLaunchKernelGGL((decode_mfma_kernel<64, true>), grid, block, 0, st, p, G, q, Kc, Vc, sizes, rope, n_pos, part, out, lse);
+    else if (p.d == 64)
+        hipLaunchKernelGGL((decode_mfma_kernel<64, false>), grid, block, 0, st, p, G, q, Kc, Vc, sizes, rope, n_pos, part, out, lse);
+    else if (rope)
+        hipLaunchKernelGGL((decode_mfma_kernel<128, true>), grid, block, 0, st, p, G, q, Kc, Vc, sizes, rope, n_pos, part, out, lse);
     else
-        hipLaunchKernelGGL((decode_mfma_kernel<128>), grid, dim3(kDmThreads), 0, st, p, G, q, Kc, Vc, sizes, part, out, lse);
+        hipLaunchKernelGGL((decode_mfma_kernel<128, false>), grid, block, 0, st, p, G, q, Kc, Vc, sizes, rope, n_pos, part, out, lse);
     return launch_status();
 }
 

@@ -548,6 +548,189 @@ def test_fill_from_prefill_rejects_a_window_that_does_not_fit(sp):
 
 
 # ----------------------------------------------------------------------------------------------
+# positions within the cache (rotary encoding applied inside the decode) and the append step
+# ----------------------------------------------------------------------------------------------
+# A bf16 score here carries two more roundings than the plain decode: the turned key row and the
+# turned query go to the matrix cores in bf16 (relative step 2^-9 per element).  For unit-normal
+# q, k and scale = 1/sqrt(d) that is a random score error of about 2^-9 * 0.58 * sqrt(2) ~ 1.6e-3
+# (one sigma), which the log-sum-exp of a cache with few entries inherits in full: 1e-2 is six sigma.
+ROPE_LSE_TOL = {"bf16": 1e-2, "fp32": 1e-4}
+
+
+@pytest.mark.parametrize("d,base,n_pos", [(128, 10000.0, 700), (64, 500000.0, 4100), (128, 500000.0, 33)])
+def test_rope_table_matches_the_closed_form(sp, d, base, n_pos):
+    tab = host(sp.sepkv_rope_table(n_pos, d, base, "cuda"))
+    torch.cuda.synchronize()
+    x = np.concatenate([np.ones(d // 2), np.zeros(d // 2)])  # turned by pos: (cos, sin) of every frequency
+    ref = oracle.rope_rotate(np.tile(x, (n_pos, 1)), np.arange(n_pos), base)
+    assert tab.shape == (n_pos, 2, d // 2)
+    assert np.abs(tab.reshape(n_pos, d) - ref).max() <= 1.2e-7  # fp32 rounding of values in [-1, 1]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("S,Hq,Hkv,d,a,s,w,c,base", [
+    (3, 8, 2, 128, 4, 64, 32, 200, 10000.0),
+    (2, 4, 4, 64, 2, 10, 8, 41, 10000.0),
+    (4, 6, 3, 128, 0, 33, 16, 100, 500000.0),
+    (1, 8, 1, 64, 4, 300, 100, 1500, 500000.0),
+    (2, 32, 1, 128, 4, 500, 64, 900, 10000.0),    # a full 32-head group, several slices per cache
+    (1, 64, 1, 128, 2, 40, 16, 120, 10000.0),     # 64 heads per KV head: the vector-ALU kernel
+    (2, 8, 2, 128, 4, 1000, 256, 3000, 500000.0), # many blocks per wave: the angle recurrence runs long
+])
+def test_decode_rope_matches_oracle(sp, dtype, S, Hq, Hkv, d, a, s, w, c, base):
+    cfg = wl.CacheConfig("t", S, Hq, Hkv, d, a, s, w, c, 0.1, dtype, seed=177 + c)
+    rng = np.random.default_rng(c)
+    sizes = random_sizes(rng, S, a, s, c - a - s, w)
+    sizes[0] = [a, s, c - a - s - w, w]  # one completely full cache
+    data = wl.make_cache(cfg, sizes)
+    scale = 1.0 / math.sqrt(d)
+    table = sp.sepkv_rope_table(c, d, base, "cuda")
+    out, lse = sp.sepattn_decode_rope(dev(data["q"], dtype), dev(data["Kc"], dtype), dev(data["Vc"], dtype),
+                                      dev(sizes), table, a, s, w, scale)
+    torch.cuda.synchronize()
+    ref, lref = oracle.decode_rope(data["q"], data["Kc"], data["Vc"], sizes, a, s, scale, base)
+    assert np.abs(host(out) - ref).max() <= TOL[dtype]
+    assert np.abs(host(lse) - lref).max() <= ROPE_LSE_TOL[dtype]
+    # the encoding matters at these sizes: the plain decode is far from this result
+    plain, _ = oracle.decode(data["q"], data["Kc"], data["Vc"], sizes, a, s, scale)
+    assert np.abs(plain - ref).max() > 0.05
+
+
+def test_decode_rope_empty_sequence_single_entry_and_stale_slots(sp):
+    S, Hq, Hkv, d, a, s, w, c = 3, 4, 2, 128, 2, 8, 4, 30
+    cfg = wl.CacheConfig("t", S, Hq, Hkv, d, a, s, w, c, 0.1, "bf16", seed=5)
+    sizes = np.array([[0, 0, 0, 0], [0, 0, 0, 1], [1, 3, 5, 4]], dtype=np.int32)
+    data = wl.make_cache(cfg, sizes)
+    Kc, Vc = data["Kc"].copy(), data["Vc"].copy()
+    for arr in (Kc, Vc):  # slots beyond the sizes hold unspecified data
+        arr[2, :, 1:a] = np.nan
+        arr[2, :, a + 3:a + s] = np.nan
+        arr[2, :, a + s + 9:] = np.nan
+    table = sp.sepkv_rope_table(c, d, 10000.0, "cuda")
+    out, lse = sp.sepattn_decode_rope(dev(data["q"], "bf16"), dev(Kc, "bf16"), dev(Vc, "bf16"), dev(sizes), table,
+                                      a, s, w, 0.1)
+    torch.cuda.synchronize()
+    o, l = host(out), host(lse)
+    assert np.all(o[0] == 0) and np.all(np.isneginf(l[0]))
+    assert np.array_equal(o[1], np.repeat(data["Vc"][1, :, a + s], 2, axis=0))  # the only entry: window slot 0
+    ref, lref = oracle.decode_rope(data["q"][2:], data["Kc"][2:], data["Vc"][2:], sizes[2:], a, s, 0.1, 10000.0)
+    assert np.abs(o[2:] - ref).max() <= 2e-2 and np.abs(l[2:] - lref).max() <= 1e-2
+
+
+def test_decode_rope_config5_full_size(sp):
+    c = wl.CONFIGS["cfg5"]
+    data = wl.make_cache(c)
+    table = sp.sepkv_rope_table(c.c, c.d, 500000.0, "cuda")
+    out, lse = sp.sepattn_decode_rope(dev(data["q"], "bf16"), dev(data["Kc"], "bf16"), dev(data["Vc"], "bf16"),
+                                      dev(data["sizes"]), table, c.a, c.s, c.w, c.scale)
+    torch.cuda.synchronize()
+    ref, lref = oracle.decode_rope(data["q"], data["Kc"], data["Vc"], data["sizes"], c.a, c.s, c.scale, 500000.0)
+    assert np.abs(host(out) - ref).max() <= 2e-2
+    assert np.abs(host(lse) - lref).max() <= 1e-2
+
+
+def test_decode_rope_rejects_a_short_table(sp):
+    cfg = wl.CacheConfig("t", 1, 2, 1, 64, 2, 8, 4, 30, 0.1, "bf16", seed=5)
+    data = wl.make_cache(cfg)
+    table = sp.sepkv_rope_table(29, 64, 10000.0, "cuda")
+    with pytest.raises(sp.SepattnError) as e:
+        sp.sepattn_decode_rope(dev(data["q"], "bf16"), dev(data["Kc"], "bf16"), dev(data["Vc"], "bf16"),
+                               dev(data["sizes"]), table, 2, 8, 4, 0.1)
+    assert e.value.status == 2
+    with pytest.raises(sp.SepattnError) as e:
+        sp.sepkv_rope_table(16, 64, 1.0, "cuda")  # base must exceed 1
+    assert e.value.status == 3
+
+
+def as_dev_bits(x_u16):
+    return dev(x_u16.view(np.int16)).view(torch.bfloat16)
+
+
+def from_dev_bits(t):
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_append_matches_oracle_bit_exact(sp, d):
+    S, Hq, Hkv, a, s, w = 6, 8, 2, 4, 12, 8
+    c = a + s + 30
+    cfg = wl.CacheConfig("t", S, Hq, Hkv, d, a, s, w, c, 0.3, "bf16", seed=23)
+    sizes = np.array([[0, 0, 0, 0],      # first token of a sequence
+                      [3, 0, 0, 0],      # last initial slot
+                      [4, 0, 0, 0],      # first window entry
+                      [4, 5, 0, 8],      # Local Window full: its oldest entry passes to the Past Window
+                      [4, 12, 21, 8],    # one free window slot
+                      [4, 7, 22, 8]],    # window region full: refused
+                     dtype=np.int32)
+    data = wl.make_cache(cfg, sizes)
+    Kb, Vb = bits(data["Kc"]), bits(data["Vc"])
+    rng = np.random.default_rng(3)
+    kn = rng.integers(0, 2 ** 16, size=(S, Hkv, d)).astype(np.uint16)
+    vn = rng.integers(0, 2 ** 16, size=(S, Hkv, d)).astype(np.uint16)
+    sep_new = np.array([1, 0, 1, 1, 0, 1], dtype=np.uint8)
+    rK, rV, rF, rS = oracle.append_token(Kb, Vb, data["win_is_sep"], sizes, kn, vn, sep_new, a, s, w)
+    Kd, Vd, Fd, Sd = as_dev_bits(Kb), as_dev_bits(Vb), dev(data["win_is_sep"]), dev(sizes)
+    sp.sepkv_append(as_dev_bits(kn), as_dev_bits(vn), dev(sep_new), Kd, Vd, Fd, Sd, Hq, a, s, w)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(Sd), rS)
+    assert np.array_equal(host(Fd), rF)
+    assert np.array_equal(from_dev_bits(Kd), rK) and np.array_equal(from_dev_bits(Vd), rV)
+    assert np.array_equal(rS[5], sizes[5]) and rS[3, 2] == 1 and rS[3, 3] == 8
+
+
+def test_streaming_fill_append_compress_decode_rope(sp):
+    """The generation loop on the GPU against the same chain in the oracle: hand-over from a prompt,
+    then tokens enter one by one, the compression step runs whenever the window region is full, and
+    every few tokens the newest token's query is decoded with positions within the cache."""
+    S, Hq, Hkv, d, a, s, w = 2, 8, 2, 128, 4, 24, 16
+    c = a + s + 48
+    L0, steps, base = 200, 90, 10000.0
+    tok = wl.make_token_ids(S, L0 + steps, 0.15, 31)
+    Q, K, V = wl.make_qkv(S, Hq, Hkv, L0 + steps, d, 1.0, 31, "bf16")
+    flags_all = oracle.mark_separators(tok, wl.SEPARATOR_IDS)
+    Kb, Vb = bits(K), bits(V)
+    to_f = lambda u: (u.astype(np.uint32) << 16).view(np.float32)
+    scale = 1.0 / math.sqrt(d)
+    # oracle state
+    nw0 = 20
+    rK, rV, rF, rS, _ = oracle.fill_from_prefill(Kb[:, :, :L0], Vb[:, :, :L0], flags_all[:, :L0], a, s, w, c, nw0)
+    # GPU state
+    is_sep, idx, cnt, pre = gpu_index(sp, tok[:, :L0])
+    Kd, Vd, Fd, Sd = sp.sepkv_fill_from_prefill(as_dev_bits(np.ascontiguousarray(Kb[:, :, :L0])),
+                                                as_dev_bits(np.ascontiguousarray(Vb[:, :, :L0])), is_sep, idx, pre,
+                                                Hq, a, s, w, c, nw0)
+    table = sp.sepkv_rope_table(c, d, base, "cuda")
+    qd = dev(Q, "bf16")
+    n_compress = 0
+    for t in range(L0, L0 + steps):
+        kn, vn = np.ascontiguousarray(Kb[:, :, t]), np.ascontiguousarray(Vb[:, :, t])
+        fn = np.ascontiguousarray(flags_all[:, t]).astype(np.uint8)
+        rK, rV, rF, rS = oracle.append_token(rK, rV, rF, rS, kn, vn, fn, a, s, w)
+        sp.sepkv_append(as_dev_bits(kn), as_dev_bits(vn), dev(fn), Kd, Vd, Fd, Sd, Hq, a, s, w)
+        if (t - L0) % 7 == 0 or t == L0 + steps - 1:
+            out, lse = sp.sepattn_decode_rope(qd[:, :, t].contiguous(), Kd, Vd, Sd, table, a, s, w, scale)
+            torch.cuda.synchronize()
+            assert np.array_equal(host(Sd), rS), t
+            ref, lref = oracle.decode_rope(Q[:, :, t], to_f(rK), to_f(rV), rS, a, s, scale, base)
+            assert np.abs(host(out) - ref).max() <= 2e-2, t
+            assert np.abs(host(lse) - lref).max() <= 1e-2, t
+        if rS[0, 2] + rS[0, 3] == c - a - s:  # both sequences advance in step
+            rK, rV, rF, rS = oracle.evict_window(rK, rV, rF, rS, a, s)
+            sp.sepkv_evict_window(Kd, Vd, Fd, Sd, Hq, a, s, w)
+            n_compress += 1
+    torch.cuda.synchronize()
+    assert n_compress >= 2
+    assert np.array_equal(host(Sd), rS)
+    for q in range(S):
+        ni, ns, npast, nl = rS[q]
+        for g, r in ((from_dev_bits(Kd), rK), (from_dev_bits(Vd), rV)):
+            assert np.array_equal(g[q, :, :ni], r[q, :, :ni])
+            assert np.array_equal(g[q, :, a:a + ns], r[q, :, a:a + ns])
+            assert np.array_equal(g[q, :, a + s:a + s + npast + nl], r[q, :, a + s:a + s + npast + nl])
+        assert np.array_equal(host(Fd)[q, :npast + nl], rF[q, :npast + nl])
+
+
+# ----------------------------------------------------------------------------------------------
 # error paths through the ABI (nothing is launched)
 # ----------------------------------------------------------------------------------------------
 def test_bad_arguments_are_rejected(sp):

@@ -13,7 +13,8 @@ printed as ONE JSON line together with
                     dense bf16 MFMA peak,
   - "cpu_baseline": the CPU oracle timed on this host on a bounded sample of the same workload,
   - "decode":       the streaming-decode workload (32 sequences x 3332 cache entries) as achieved
-                    HBM GB/s, the cache eviction step, and the hand-over from an 8K prompt to the cache.
+                    HBM GB/s (also with positions within the cache applied in the kernel), the append and
+                    eviction steps, and the hand-over from an 8K prompt to the cache.
 Only one GPU is used; `--gpus N` with N > 1 exits with a message.
 """
 from __future__ import annotations
@@ -249,6 +250,33 @@ def bench_decode(torch, sp, wl, ramp_seconds):
            "kv_bytes_per_step": int(kv_bytes),
            "gbs_step": round(kv_bytes / us_step / 1e3, 1), "gbs_kernel": round(kv_bytes / k_us / 1e3, 1),
            "frac_hbm_peak_kernel": round(kv_bytes / k_us / 1e3 / PEAK_HBM_GBS, 4)}
+    # the same step with positions within the cache: keys stored without position encoding, turned in the kernel
+    table = sp.sepkv_rope_table(c.c, c.d, 500000.0, q.device)
+    for i in range(60):
+        k_, v_ = caches[i % 3]
+        sp.sepattn_decode_rope(q, k_, v_, sizes, table, c.a, c.s, c.w, c.scale, out=(out, lse), ws=ws)
+    torch.cuda.synchronize()
+    sp.sepattn_profile_begin(sp.KERNEL_IDS["decode_split"], steps)
+    for i in range(steps):
+        k_, v_ = caches[i % 3]
+        sp.sepattn_decode_rope(q, k_, v_, sizes, table, c.a, c.s, c.w, c.scale, out=(out, lse), ws=ws)
+    torch.cuda.synchronize()
+    r_us = 1e3 * float(np.mean(sp.sepattn_profile_end(steps)))
+    res["rope"] = {"split_kernel_us": round(r_us, 2), "gbs_kernel": round(kv_bytes / r_us / 1e3, 1),
+                   "frac_hbm_peak_kernel": round(kv_bytes / r_us / 1e3 / PEAK_HBM_GBS, 4)}
+    # one token enters every cache (the window region has room: sizes restored every time)
+    k_new, v_new = torch.randn((c.S, c.Hkv, c.d), device=q.device, dtype=torch.bfloat16), torch.randn(
+        (c.S, c.Hkv, c.d), device=q.device, dtype=torch.bfloat16)
+    sep_new = torch.zeros((c.S,), dtype=torch.uint8, device=q.device)
+    sz_room = sizes.clone()
+    sz_room[:, 2] -= 1
+    sz_a, fl_a = sz_room.clone(), torch.from_numpy(data["win_is_sep"]).cuda()
+    sp.sepattn_profile_begin(sp.KERNEL_IDS["cache_append"], 50)
+    for i in range(50):
+        sz_a.copy_(sz_room)
+        sp.sepkv_append(k_new, v_new, sep_new, Kc, Vc, fl_a, sz_a, c.Hq, c.a, c.s, c.w)
+    torch.cuda.synchronize()
+    res["append_us"] = round(1e3 * float(np.median(sp.sepattn_profile_end(50)[5:])), 2)
     # eviction: restore the sizes / flags every time (in place otherwise empties the past window)
     flags0 = torch.from_numpy(data["win_is_sep"]).cuda()
     sizes0 = sizes.clone()

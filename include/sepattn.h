@@ -64,6 +64,15 @@ const char *sepattn_status_string(int status);
 int sepattn_mark_separators(const int32_t *token_ids, int B, int L, const int32_t *sep_ids,
                             int n_sep, uint8_t *is_sep, void *stream);
 
+/* Fixed-interval variant (the appendix "Fixed-Interval Variant", FixLLM): instead of the separators,
+ * one token in every `delta` is attended to between the initial and the neighbouring tokens.  Writes
+ * is_sep[b, j] = (j % delta == phase); everything downstream (compaction, forward, backward, the
+ * cache calls) takes this bitmap in place of the separator flags.
+ *   delta >= 1, 0 <= phase < delta (SEPATTN_ERR_PARAM otherwise)
+ *   is_sep     DEVICE uint8 [B, L]  out, 4-byte aligned
+ */
+int sepattn_mark_interval(int B, int L, int delta, int phase, uint8_t *is_sep, void *stream);
+
 /* ------------------------------------------------------------------------------------------
  * Separator compaction: the index form of the separator part of mask M (Eq. 2), shared by all
  * layers and heads of a batch.
@@ -272,7 +281,8 @@ typedef enum {
     SEPATTN_K_CACHE_FILL = 11,
     SEPATTN_K_ROPE_TABLE = 12,
     SEPATTN_K_CACHE_APPEND = 13,
-    SEPATTN_K_COUNT = 14
+    SEPATTN_K_MARK_INTERVAL = 14,
+    SEPATTN_K_COUNT = 15
 } sepattn_kernel_id;
 const char *sepattn_kernel_name(int kernel);
 int sepattn_profile_begin(int kernel, int max_records);

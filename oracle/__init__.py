@@ -70,6 +70,13 @@ def mark_separators(token_ids: np.ndarray, sep_ids: np.ndarray) -> np.ndarray:
     return out
 
 
+def mark_interval(B: int, L: int, delta: int, phase: int) -> np.ndarray:
+    """Markers of the fixed-interval variant (appendix "Fixed-Interval Variant"): one token in every
+    `delta` takes the separators' place: position j iff j % delta == phase.  uint8 [B, L]."""
+    row = np.array([1 if j % delta == phase else 0 for j in range(L)], dtype=np.uint8)
+    return np.tile(row, (B, 1))
+
+
 def compact_indices(is_sep: np.ndarray, cap: Optional[int] = None
                     ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     """(sep_idx [B,cap] padded with -1, sep_count [B], sep_prefix [B,L+1])."""

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     load,
     status_string,
     sepattn_mark_separators,
+    sepattn_mark_interval,
     sepattn_compact_indices,
     sepattn_forward,
     sepattn_backward,

@@ -23,6 +23,7 @@ SEPATTN_FP32 = 1
 EXPORTS = (
     "sepattn_status_string",
     "sepattn_mark_separators",
+    "sepattn_mark_interval",
     "sepattn_compact_workspace_bytes",
     "sepattn_compact_indices",
     "sepattn_forward_workspace_bytes",
@@ -79,6 +80,8 @@ def load(path: Optional[str] = None):
     lib.sepattn_status_string.argtypes = [ci]
     lib.sepattn_mark_separators.restype = ci
     lib.sepattn_mark_separators.argtypes = [vp, ci, ci, vp, ci, vp, vp]
+    lib.sepattn_mark_interval.restype = ci
+    lib.sepattn_mark_interval.argtypes = [ci, ci, ci, ci, vp, vp]
     lib.sepattn_compact_workspace_bytes.restype = sz
     lib.sepattn_compact_workspace_bytes.argtypes = [ci, ci]
     lib.sepattn_compact_indices.restype = ci
@@ -126,7 +129,8 @@ def status_string(status: int) -> str:
 
 KERNEL_IDS = {"mark": 0, "compact_count": 1, "compact_write": 2, "forward": 3, "bwd_dq": 4, "bwd_dkv": 5,
               "bwd_combine": 6, "decode_split": 7, "decode_merge": 8, "evict_plan": 9, "evict_move": 10,
-              "cache_fill": 11, "rope_table": 12, "cache_append": 13}
+              "cache_fill": 11, "rope_table": 12, "cache_append": 13,
+              "mark_interval": 14}
 
 
 def sepattn_kernel_name(kernel: int) -> str:
@@ -193,6 +197,16 @@ def sepattn_mark_separators(token_ids: torch.Tensor, sep_ids, out: Optional[torc
     _check("sepattn_mark_separators",
            load().sepattn_mark_separators(_ptr(token_ids), B, L, ctypes.cast(ids, ctypes.c_void_p),
                                           len(sep_ids), _ptr(out), _stream(token_ids)))
+    return out
+
+
+def sepattn_mark_interval(B: int, L: int, delta: int, phase: int, device, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """-> is_sep uint8 [B,L] with is_sep[b, j] = (j % delta == phase): the fixed-interval variant's markers."""
+    if out is None:
+        out = torch.empty((int(B), int(L)), dtype=torch.uint8, device=device)
+    _dev(out)
+    _check("sepattn_mark_interval",
+           load().sepattn_mark_interval(int(B), int(L), int(delta), int(phase), _ptr(out), _stream(out)))
     return out
 
 

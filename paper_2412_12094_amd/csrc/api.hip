@@ -110,7 +110,7 @@ const char *sepattn_kernel_name(int kernel) {
                                                  "dkv_combine_kernel", "decode_split_kernel",
                                                  "decode_merge_kernel", "evict_plan_kernel",
                                                  "evict_move_kernel", "cache_fill_kernel", "rope_table_kernel",
-                                                 "cache_append_kernel"};
+                                                 "cache_append_kernel", "mark_interval_kernel"};
     return (kernel >= 0 && kernel < SEPATTN_K_COUNT) ? names[kernel] : "unknown";
 }
 
@@ -168,6 +168,14 @@ int sepattn_mark_separators(const int32_t *token_ids, int B, int L, const int32_
     set.n = n_sep;
     for (int k = 0; k < SEPATTN_MAX_SEP_IDS; ++k) set.ids[k] = k < n_sep ? sep_ids[k] : sep_ids[0];
     return launch_mark(token_ids, (long)B * L, set, is_sep, static_cast<hipStream_t>(stream));
+}
+
+int sepattn_mark_interval(int B, int L, int delta, int phase, uint8_t *is_sep, void *stream) {
+    if (!is_sep) return SEPATTN_ERR_NULL;
+    if (B <= 0 || L <= 0) return SEPATTN_ERR_SHAPE;
+    if (delta < 1 || phase < 0 || phase >= delta) return SEPATTN_ERR_PARAM;
+    if (!aligned(is_sep, 4)) return SEPATTN_ERR_PARAM;
+    return launch_mark_interval(B, L, delta, phase, is_sep, static_cast<hipStream_t>(stream));
 }
 
 size_t sepattn_compact_workspace_bytes(int B, int L) {

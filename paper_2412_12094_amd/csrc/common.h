@@ -34,6 +34,7 @@ struct SepIdSet {
 };
 int launch_mark(const int32_t *token_ids, long n_tokens, const SepIdSet &set, uint8_t *is_sep,
                 hipStream_t st);
+int launch_mark_interval(int B, int L, int delta, int phase, uint8_t *is_sep, hipStream_t st);
 constexpr int kCompactChunk = 2048;  // tokens per workgroup of the compaction kernels
 int launch_compact(const uint8_t *is_sep, int B, int L, int32_t *sep_idx, int cap,
                    int32_t *sep_count, int32_t *sep_prefix, int32_t *chunk_counts, hipStream_t st);

@@ -45,6 +45,39 @@ int launch_mark(const int32_t *token_ids, long n_tokens, const SepIdSet &set, ui
     return launch_status();
 }
 
+// Fixed-interval variant ("FixLLM", the appendix on the fixed-interval variant): one token in every
+// `delta` is marked instead of the separators: position j of every sequence iff j % delta == phase.
+__global__ __launch_bounds__(256) void mark_interval_kernel(int L, long n, int delta, int phase,
+                                                            uint8_t *__restrict__ out) {
+    const long t4 = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (t4 >= n) return;
+    int r = (int)((t4 % L) % delta);  // residue of the first of this thread's four positions
+    int j = (int)(t4 % L);
+    unsigned f[4];
+    for (int k = 0; k < 4; ++k) {
+        f[k] = (r == phase);
+        ++j;
+        r = (r + 1 == delta) ? 0 : r + 1;
+        if (j == L) {  // next sequence
+            j = 0;
+            r = 0;
+        }
+    }
+    if (t4 + 4 <= n) {
+        *reinterpret_cast<uint32_t *>(out + t4) = f[0] | (f[1] << 8) | (f[2] << 16) | (f[3] << 24);
+    } else {
+        for (int k = 0; t4 + k < n; ++k) out[t4 + k] = (uint8_t)f[k];
+    }
+}
+
+int launch_mark_interval(int B, int L, int delta, int phase, uint8_t *is_sep, hipStream_t st) {
+    const long n = (long)B * L, threads = (n + 3) / 4;
+    const unsigned blocks = (unsigned)((threads + 255) / 256);
+    ProfScope prof(SEPATTN_K_MARK_INTERVAL, st);
+    hipLaunchKernelGGL(mark_interval_kernel, dim3(blocks), dim3(256), 0, st, L, n, delta, phase, is_sep);
+    return launch_status();
+}
+
 // ---- compaction --------------------------------------------------------------------------------
 constexpr int kCompactThreads = 256;
 constexpr int kCompactSingleLaunch = 32768;  // longest sequence compacted with one launch

@@ -106,6 +106,38 @@ def test_mark_with_one_and_with_64_ids(sp):
 # ----------------------------------------------------------------------------------------------
 # forward / backward
 # ----------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("B,L,delta,phase", [(1, 1, 1, 0), (3, 63, 4, 1), (2, 2047, 5, 4), (5, 333, 16, 0),
+                                             (1, 8192, 5, 2), (2, 100, 200, 150)])
+def test_mark_interval_bit_exact(sp, B, L, delta, phase):
+    got = host(sp.sepattn_mark_interval(B, L, delta, phase, "cuda"))
+    torch.cuda.synchronize()
+    assert np.array_equal(got, oracle.mark_interval(B, L, delta, phase))
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("delta", [4, 5])
+def test_fixed_interval_variant_forward_backward(sp, dtype, delta):
+    """The fixed-interval variant (one token in every delta in place of the separators; three initial
+    tokens and n = 256 as in its table) through compaction, forward and backward."""
+    B, Hq, Hkv, L, d, a, n = 1, 4, 2, 1500, 128, 3, 256
+    _, Q, K, V, dO = make_case(B, Hq, Hkv, L, d, 0.0, dtype, 5)
+    is_sep = sp.sepattn_mark_interval(B, L, delta, 0, "cuda")
+    idx, cnt, pre = sp.sepattn_compact_indices(is_sep)
+    flags = oracle.mark_interval(B, L, delta, 0)
+    assert int(cnt[0]) == flags.sum()
+    scale = 1.0 / math.sqrt(d)
+    q, k, v, do = (dev(x, dtype) for x in (Q, K, V, dO))
+    O, LSE = sp.sepattn_forward(q, k, v, idx, cnt, pre, a, n, scale)
+    dQ, dK, dV = sp.sepattn_backward(q, k, v, O, LSE, do, idx, cnt, pre, a, n, scale)
+    torch.cuda.synchronize()
+    rO, rL = oracle.forward(Q, K, V, flags, a, n, scale)
+    rdQ, rdK, rdV = oracle.backward(Q, K, V, dO, flags, a, n, scale)
+    assert_close(host(O), rO, dtype, "O")
+    assert np.abs(host(LSE) - rL).max() <= LSE_TOL[dtype]
+    for g, r, nm in ((dQ, rdQ, "dQ"), (dK, rdK, "dK"), (dV, rdV, "dV")):
+        assert_close(host(g), r, dtype, nm)
+
+
 def run_forward(sp, tok, Q, K, V, a, n, scale, dtype):
     is_sep, idx, cnt, pre = gpu_index(sp, tok)
     O, LSE = sp.sepattn_forward(dev(Q, dtype), dev(K, dtype), dev(V, dtype), idx, cnt, pre, a, n, scale)

@@ -443,6 +443,21 @@ def test_decode_zero_query_probe_counts_entries():
     assert np.allclose(out[2, 0], Vc[2, 0, slots].mean(0), atol=1e-12)
 
 
+def test_mark_interval_worked_example_and_mask():
+    """Fixed-interval variant: with delta = 4, phase = 1 the markers of 10 positions are 1, 5, 9; a row
+    of the mask then sees the initial tokens, the marked positions and its neighbours, nothing else."""
+    m = oracle.mark_interval(2, 10, 4, 1)
+    assert m.dtype == np.uint8 and m.tolist() == [[0, 1, 0, 0, 0, 1, 0, 0, 0, 1]] * 2
+    for L, delta, phase in ((37, 5, 0), (64, 8, 7), (5, 9, 3), (16, 1, 0)):
+        f = oracle.mark_interval(1, L, delta, phase)[0]
+        assert f.sum() == len(range(phase, L, delta)) and all(f[j] for j in range(phase, L, delta))
+    L, a, n, delta = 40, 2, 4, 8
+    M = oracle.mask(oracle.mark_interval(1, L, delta, 3)[0], a, n)
+    for i in range(L):
+        want = {j for j in range(i + 1) if j < a or j % delta == 3 or i - j < n}
+        assert set(np.nonzero(M[i])[0]) == want
+
+
 # ----------------------------------------------------------------------------------------------
 # positions within the cache (Sec. 3.3 "Positional Encoding") and the append step
 # ----------------------------------------------------------------------------------------------

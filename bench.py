@@ -39,8 +39,8 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
 # The figures and the commands are in profiles/; None = not measured for the current kernels.
 CALIB_BYTES = 256 << 20
 MEASURED_TRAFFIC_BYTES = {
-    "forward": 177.1e6,   # read 108.9 MB + written 68.2 MB   (algorithmic: 168.8 MB)
-    "bwd_dq": 321.1e6,    # read 247.8 MB + written 73.3 MB
+    "forward": 176.6e6,   # read 108.5 MB + written 68.2 MB   (algorithmic: 168.8 MB)
+    "bwd_dq": 324.1e6,    # read 248.0 MB + written 76.1 MB
     "bwd_dkv": 547.6e6,   # read 473.3 MB + written 74.3 MB
 }
 
@@ -298,9 +298,15 @@ def bench_decode(torch, sp, wl, ramp_seconds):
     # rows the method must move: kept past-window rows, plus (separator cache full) the surviving
     # separator rows shifted down and the local window slid to the front; read + write, K and V
     moved_rows = kept + int((c.s * c.S) - kept) + c.w * c.S
-    res["evict"] = {"us": round(float(np.median(times[2:])), 2), "kept_rows_per_head": kept,
+    res["evict"] = {"us": round(float(np.median(times[2:])), 2), "kept_past_window_rows_all_sequences": kept, "moved_rows_per_sequence_and_head": c.s + c.w,
                     "moved_bytes": int(moved_rows * row * 2 * 2 * c.Hkv),
                     "gbs": round(moved_rows * row * 2 * 2 * c.Hkv / float(np.median(times[2:])) / 1e3, 1)}
+    # a generation step = append + decode; the compression step amortised at cfg5's stated cadence (every 256
+    # tokens) and at the cadence the paper's trigger gives for these sizes (every c-a-s-w = 1024 tokens)
+    tok_us = us_step + res["append_us"]
+    res["generation_us_per_token"] = {"append_plus_decode": round(tok_us, 2),
+                                      "with_evict_every_256": round(tok_us + res["evict"]["us"] / 256, 2),
+                                      "with_evict_every_1024": round(tok_us + res["evict"]["us"] / 1024, 2)}
     # hand-over from an 8K prompt to the cache (initial tokens, separators older than the window, window)
     Lp = 8192
     tokp = torch.from_numpy(wl.make_token_ids(c.S, Lp, 0.08, 4242)).cuda()

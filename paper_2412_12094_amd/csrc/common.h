@@ -15,6 +15,17 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? SEPATTN_OK
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// 16-byte loads and stores with the non-temporal hint, for rows that are touched once
+typedef unsigned int nt_u32x4 __attribute__((ext_vector_type(4)));
+__device__ inline uint4 nt_load(const uint4 *p) {
+    const nt_u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const nt_u32x4 *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ inline void nt_store(uint4 v, uint4 *p) {
+    const nt_u32x4 t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<nt_u32x4 *>(p));
+}
+
 // number of compute units of the current device (queried once per device; 256 if the query fails)
 int compute_units();
 

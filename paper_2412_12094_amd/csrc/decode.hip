@@ -43,6 +43,22 @@ __device__ inline void load8<float>(const float *p, float (&v)[8]) {
     v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
 }
 
+// the same for cache rows, which a call reads exactly once: non-temporal hint
+template <typename T>
+__device__ inline void load8_stream(const T *p, float (&v)[8]);
+template <>
+__device__ inline void load8_stream<uint16_t>(const uint16_t *p, float (&v)[8]) {
+    const uint4 u = nt_load(reinterpret_cast<const uint4 *>(p));
+    v[0] = bf16lo(u.x); v[1] = bf16hi(u.x); v[2] = bf16lo(u.y); v[3] = bf16hi(u.y);
+    v[4] = bf16lo(u.z); v[5] = bf16hi(u.z); v[6] = bf16lo(u.w); v[7] = bf16hi(u.w);
+}
+template <>
+__device__ inline void load8_stream<float>(const float *p, float (&v)[8]) {
+    const uint4 a = nt_load(reinterpret_cast<const uint4 *>(p)), b = nt_load(reinterpret_cast<const uint4 *>(p + 4));
+    v[0] = __uint_as_float(a.x); v[1] = __uint_as_float(a.y); v[2] = __uint_as_float(a.z); v[3] = __uint_as_float(a.w);
+    v[4] = __uint_as_float(b.x); v[5] = __uint_as_float(b.y); v[6] = __uint_as_float(b.z); v[7] = __uint_as_float(b.w);
+}
+
 // sum over the LPR (8 or 16) adjacent lanes that share a cache row; every lane gets the total
 template <int LPR>
 __device__ inline float row_sum(float v) {
@@ -132,8 +148,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(
             int e = eb + u * NSLOT;
             ok[u] = e < e1;
             int sl = decode_slot_of(ok[u] ? e : e0, n_init, n_sep, p.a, p.s);
-            load8<T>(Kh + (long)sl * D + c * 8, kr[u]);
-            load8<T>(Vh + (long)sl * D + c * 8, vr[u]);
+            load8_stream<T>(Kh + (long)sl * D + c * 8, kr[u]);
+            load8_stream<T>(Vh + (long)sl * D + c * 8, vr[u]);
         }
         float sc[GT][kRowsUnroll];
         if constexpr (ROPE) {

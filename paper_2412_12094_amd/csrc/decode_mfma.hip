@@ -124,8 +124,10 @@ __global__ __launch_bounds__(kDmThreads, 1) void decode_mfma_kernel(
             const int r = u * RPL + my_sub;
             const int sl = decode_slot_of(min(eb + r, e1 - 1), n_init, n_sep, p.a, p.s);
             const uint32_t row_off = (uint32_t)sl * (uint32_t)(D * 2);  // a cache of one (sequence, head) is < 4 GB
-            dma_to_lds_16(Kh, row_off + swz_chunk<kSwzRow, D>(my_pc, r) * 16, lds_addr(&Ks[wave][stg][u * RPL * D]));
-            dma_to_lds_16(Vh, row_off + swz_chunk<kSwzTr, D>(my_pc, r) * 16, lds_addr(&Vs[wave][stg][u * RPL * D]));
+            // every cache row is read exactly once per call: the non-temporal hint keeps the stream from
+            // displacing itself in the caches (measured: 79 -> 71 us at 32 x 8 caches of 3332 entries)
+            dma_to_lds_16_nt(Kh, row_off + swz_chunk<kSwzRow, D>(my_pc, r) * 16, lds_addr(&Ks[wave][stg][u * RPL * D]));
+            dma_to_lds_16_nt(Vh, row_off + swz_chunk<kSwzTr, D>(my_pc, r) * 16, lds_addr(&Vs[wave][stg][u * RPL * D]));
         });
     };
     // the loads of a stage are 2*NLD instructions; they complete in issue order

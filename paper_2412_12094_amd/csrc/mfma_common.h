@@ -113,6 +113,13 @@ __device__ inline void dma_to_lds_16(const void *base, uint32_t voff, uint32_t l
                  : "s"(lds_addr), "v"(voff), "s"(base)
                  : "memory");
 }
+// the same with the non-temporal hint: for data that is read once (the decode's cache rows)
+__device__ inline void dma_to_lds_16_nt(const void *base, uint32_t voff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(base)
+                 : "memory");
+}
 __device__ inline void dma_to_lds_4(const void *base, uint32_t voff, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
                  :

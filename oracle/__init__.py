@@ -72,7 +72,8 @@ def mark_separators(token_ids: np.ndarray, sep_ids: np.ndarray) -> np.ndarray:
 
 def mark_interval(B: int, L: int, delta: int, phase: int) -> np.ndarray:
     """Markers of the fixed-interval variant (appendix "Fixed-Interval Variant"): one token in every
-    `delta` takes the separators' place: position j iff j % delta == phase.  uint8 [B, L]."""
+    `delta` takes the separators' place: position j iff j % delta == phase (the paper gives the
+    interval only; the offset is a reading, [parity unpinned]).  uint8 [B, L]."""
     row = np.array([1 if j % delta == phase else 0 for j in range(L)], dtype=np.uint8)
     return np.tile(row, (B, 1))
 
@@ -230,7 +231,9 @@ def rope_rotate(x: np.ndarray, pos, base: float) -> np.ndarray:
 
     Sec. 3.3 "Positional Encoding" fixes which positions are used (those within the cache); the
     rotation itself is the one of the Llama / Pythia backbones the paper evaluates (Sec. 4.1): dimension
-    i < d/2 is paired with i + d/2 and the pair is turned by pos * base**(-2i/d).
+    i < d/2 is paired with i + d/2 and the pair is turned by pos * base**(-2i/d).  The paper prints
+    neither the pairing nor the base: this reading is [parity unpinned] against the paper; the pins
+    hold the function to the reading.
     """
     x = np.asarray(x, dtype=np.float64)
     d = x.shape[-1]

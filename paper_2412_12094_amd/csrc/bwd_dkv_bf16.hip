@@ -715,31 +715,31 @@ __global__ __launch_bounds__(256) void dkv_combine_kernel(sepattn_params p, cons
     const int w0 = min(max(tab[0], 0), wpg - 1), w1 = min(max(tab[1], w0), wpg - 1);
     const long base = (long)bkv * fg.rows;
     float4 sk = {0.f, 0.f, 0.f, 0.f}, sv = {0.f, 0.f, 0.f, 0.f};
-    // four pieces at a time (clamped slots), so that their loads are in flight together
-    for (int w = w0; w <= w1; w += 4) {
-        float4 pk[4], pv[4];
+    // the band partial and eight pieces at a time (clamped slots) are requested together, so that a
+    // list tile with up to eight pieces costs one memory round trip; the sum runs in slot order
+    constexpr int NB = 8;
+    const long brow = (base + (long)fg.NP * kBK + f) * D + col;
+    const float4 bk = *reinterpret_cast<const float4 *>(farK + brow);
+    const float4 bv = *reinterpret_cast<const float4 *>(farV + brow);
+    for (int w = w0; w <= w1; w += NB) {
+        float4 pk[NB], pv[NB];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
+        for (int c = 0; c < NB; ++c) {
             const int ww = min(w + c, w1);
             const long prow = (base + (long)(ww + ft) * kBK + (f - ft * kBK)) * D + col;
             pk[c] = *reinterpret_cast<const float4 *>(farK + prow);
             pv[c] = *reinterpret_cast<const float4 *>(farV + prow);
         }
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
+        for (int c = 0; c < NB; ++c) {
             if (w + c <= w1) {
                 sk.x += pk[c].x, sk.y += pk[c].y, sk.z += pk[c].z, sk.w += pk[c].w;
                 sv.x += pv[c].x, sv.y += pv[c].y, sv.z += pv[c].z, sv.w += pv[c].w;
             }
         }
     }
-    {
-        const long prow = (base + (long)fg.NP * kBK + f) * D + col;
-        const float4 bk = *reinterpret_cast<const float4 *>(farK + prow);
-        const float4 bv = *reinterpret_cast<const float4 *>(farV + prow);
-        sk.x += bk.x, sk.y += bk.y, sk.z += bk.z, sk.w += bk.w;
-        sv.x += bv.x, sv.y += bv.y, sv.z += bv.z, sv.w += bv.w;
-    }
+    sk.x += bk.x, sk.y += bk.y, sk.z += bk.z, sk.w += bk.w;
+    sv.x += bv.x, sv.y += bv.y, sv.z += bv.z, sv.w += bv.w;
     const long orow = (((long)b * p.Hkv + kv) * (long)p.L + j) * D + col;
     *reinterpret_cast<uint2 *>(dK + orow) = pack_bf16x4(sk.x, sk.y, sk.z, sk.w);
     *reinterpret_cast<uint2 *>(dV + orow) = pack_bf16x4(sv.x, sv.y, sv.z, sv.w);

@@ -762,6 +762,53 @@ def test_streaming_fill_append_compress_decode_rope(sp):
         assert np.array_equal(host(Fd)[q, :npast + nl], rF[q, :npast + nl])
 
 
+def test_generation_step_replays_in_a_hip_graph(sp):
+    """A serving loop replays one captured generation step (append, then decode with positions within
+    the cache): with caller-provided outputs and workspace the calls allocate nothing and touch the
+    host not at all, so they can be captured; every replay is checked against the oracle chain, with
+    eager work and synchronisations between the replays."""
+    S, Hq, Hkv, d, a, s, w = 3, 8, 2, 128, 4, 40, 16
+    c = a + s + 64
+    cfg = wl.CacheConfig("t", S, Hq, Hkv, d, a, s, w, c, 0.2, "bf16", seed=41)
+    sizes = np.array([[4, 40, 30, 16], [4, 11, 0, 9], [2, 0, 0, 0]], dtype=np.int32)
+    data = wl.make_cache(cfg, sizes)
+    rK, rV, rF, rS = bits(data["Kc"]), bits(data["Vc"]), data["win_is_sep"].copy(), sizes.copy()
+    Kd, Vd, Fd, Sd = as_dev_bits(rK), as_dev_bits(rV), dev(rF), dev(rS)
+    base, scale, steps = 10000.0, 1.0 / math.sqrt(d), 6
+    table = sp.sepkv_rope_table(c, d, base, "cuda")
+    rng = np.random.default_rng(7)
+    to_f = lambda u: (u.astype(np.uint32) << 16).view(np.float32)
+    k_in = torch.zeros((S, Hkv, d), dtype=torch.bfloat16, device="cuda")
+    v_in, q_in = torch.zeros_like(k_in), torch.zeros((S, Hq, d), dtype=torch.bfloat16, device="cuda")
+    f_in = torch.zeros((S,), dtype=torch.uint8, device="cuda")
+    out, lse = torch.zeros_like(q_in), torch.zeros((S, Hq), dtype=torch.float32, device="cuda")
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sp.sepkv_append(k_in, v_in, f_in, Kd, Vd, Fd, Sd, Hq, a, s, w)
+        sp.sepattn_decode_rope(q_in, Kd, Vd, Sd, table, a, s, w, scale, out=(out, lse), ws=ws)
+    # capture ran nothing: the state is still the initial one
+    torch.cuda.synchronize()
+    assert np.array_equal(host(Sd), rS)
+    for t in range(steps):
+        kn = rng.integers(0x3C00, 0x4000, size=(S, Hkv, d)).astype(np.uint16)  # bf16 values in [2^-7, 2)
+        vn = rng.integers(0x3C00, 0x4000, size=(S, Hkv, d)).astype(np.uint16)
+        qn = wl.make_qkv(S, Hq, Hkv, 1, d, 1.0, 900 + t, "bf16")[0][:, :, 0]
+        fn = (rng.random(S) < 0.3).astype(np.uint8)
+        k_in.copy_(as_dev_bits(kn)); v_in.copy_(as_dev_bits(vn)); q_in.copy_(dev(qn, "bf16")); f_in.copy_(dev(fn))
+        graph.replay()
+        checksum = float(out.float().sum())  # eager library work and a synchronisation between replays
+        torch.cuda.synchronize()
+        rK, rV, rF, rS = oracle.append_token(rK, rV, rF, rS, kn, vn, fn, a, s, w)
+        ref, lref = oracle.decode_rope(qn, to_f(rK), to_f(rV), rS, a, s, scale, base)
+        assert np.array_equal(host(Sd), rS), t
+        assert np.abs(host(out) - ref).max() <= 2e-2, t
+        assert np.abs(host(lse) - lref).max() <= 1e-2, t
+        assert math.isfinite(checksum)
+    assert rS[2, 0] == 4 and rS[2, 3] == 4  # the third sequence filled its Initial Cache, then its window
+
+
 # ----------------------------------------------------------------------------------------------
 # error paths through the ABI (nothing is launched)
 # ----------------------------------------------------------------------------------------------

@@ -316,3 +316,55 @@ def append_token(Kc: np.ndarray, Vc: np.ndarray, win_is_sep: np.ndarray, sizes: 
             n_past += 1
         sz[sq, 2], sz[sq, 3] = n_past, n_loc
     return Kc, Vc, fl, sz
+
+
+def doc_bounds(cu_seqlens: np.ndarray, L: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Packed documents in one row of L positions: document k covers [cu[k], cu[k+1]), cu[0] = 0,
+    cu[-1] = L.  Returns, per position, the first position of its document and one past its last."""
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    assert cu[0] == 0 and cu[-1] == L and (np.diff(cu) > 0).all()
+    start = np.zeros(L, dtype=np.int32)
+    end = np.zeros(L, dtype=np.int32)
+    for k in range(len(cu) - 1):
+        start[cu[k]:cu[k + 1]] = cu[k]
+        end[cu[k]:cu[k + 1]] = cu[k + 1]
+    return start, end
+
+
+def forward_packed(Q, K, V, is_sep, cu_seqlens, a: int, n: int, scale: float, precision: str = "f64"):
+    """SepAttention over a row of packed documents: every document is a sequence of its own (its first
+    a tokens are its initial tokens, a query sees nothing outside its document), i.e. Eq. 1 / Eq. 2
+    applied to each slice [cu[k], cu[k+1]) separately.  cu_seqlens: one array per batch row."""
+    Q, K, V = (np.asarray(x) for x in (Q, K, V))
+    B, Hq, L, d = Q.shape
+    O = np.zeros((B, Hq, L, d), dtype=np.float64 if precision == "f64" else np.float32)
+    LSE = np.zeros((B, Hq, L), dtype=O.dtype)
+    for b in range(B):
+        cu = np.asarray(cu_seqlens[b], dtype=np.int64)
+        for k in range(len(cu) - 1):
+            s, e = int(cu[k]), int(cu[k + 1])
+            o, l = forward(Q[b:b + 1, :, s:e], K[b:b + 1, :, s:e], V[b:b + 1, :, s:e], is_sep[b:b + 1, s:e], a, n,
+                           scale, precision=precision)
+            O[b, :, s:e], LSE[b, :, s:e] = o[0], l[0]
+    return O, LSE
+
+
+def backward_packed(Q, K, V, dO, is_sep, cu_seqlens, a: int, n: int, scale: float, precision: str = "f64"):
+    """Gradients of forward_packed: document by document."""
+    Q, K, V, dO = (np.asarray(x) for x in (Q, K, V, dO))
+    dQ, dK, dV = (np.zeros(x.shape, dtype=np.float64 if precision == "f64" else np.float32) for x in (Q, K, V))
+    for b in range(Q.shape[0]):
+        cu = np.asarray(cu_seqlens[b], dtype=np.int64)
+        for k in range(len(cu) - 1):
+            s, e = int(cu[k]), int(cu[k + 1])
+            gq, gk, gv = backward(Q[b:b + 1, :, s:e], K[b:b + 1, :, s:e], V[b:b + 1, :, s:e], dO[b:b + 1, :, s:e],
+                                  is_sep[b:b + 1, s:e], a, n, scale, precision=precision)
+            dQ[b, :, s:e], dK[b, :, s:e], dV[b, :, s:e] = gq[0], gk[0], gv[0]
+    return dQ, dK, dV
+
+
+def mark_doc_initial(is_sep: np.ndarray, doc_start: np.ndarray, a: int) -> np.ndarray:
+    """Marker bitmap with the first a tokens of every document added (they are visible to every later
+    query of their document, exactly like its separators)."""
+    pos = np.arange(is_sep.shape[1])[None, :]
+    return (np.asarray(is_sep, dtype=bool) | (pos - doc_start < a)).astype(np.uint8)

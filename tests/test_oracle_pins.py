@@ -459,6 +459,55 @@ def test_mark_interval_worked_example_and_mask():
 
 
 # ----------------------------------------------------------------------------------------------
+# packed documents
+# ----------------------------------------------------------------------------------------------
+def _packed_mask(is_sep_row, start, a, n):
+    L = len(is_sep_row)
+    M = np.zeros((L, L), dtype=bool)
+    for i in range(L):
+        for j in range(i + 1):
+            M[i, j] = start[j] == start[i] and (j - start[j] < a or bool(is_sep_row[j]) or i - j < n)
+    return M
+
+
+def test_packed_documents_against_an_explicit_mask():
+    """Every document is a sequence of its own: forward and backward over the packed row must equal
+    plain masked softmax attention (and its autograd gradient) under the explicit L x L mask
+    "same document, and initial token of that document or separator or neighbour"."""
+    torch = pytest.importorskip("torch")
+    B, Hq, Hkv, L, d, a, n, scale = 2, 4, 2, 61, 8, 2, 5, 0.3
+    cus = [np.array([0, 7, 8, 30, 61]), np.array([0, 61])]
+    is_sep = _flags(B, L, 0.2, 21)
+    Q, K, V, dO = _rand((B, Hq, L, d), 1), _rand((B, Hkv, L, d), 2), _rand((B, Hkv, L, d), 3), _rand((B, Hq, L, d), 4)
+    O, LSE = oracle.forward_packed(Q, K, V, is_sep, cus, a, n, scale)
+    dQ, dK, dV = oracle.backward_packed(Q, K, V, dO, is_sep, cus, a, n, scale)
+    G = Hq // Hkv
+    for b in range(B):
+        start, end = oracle.doc_bounds(cus[b], L)
+        assert (start <= np.arange(L)).all() and (np.arange(L) < end).all() and set(start) | {L} == set(cus[b])
+        M = torch.from_numpy(_packed_mask(is_sep[b], start, a, n))
+        q = torch.tensor(Q[b], dtype=torch.float64, requires_grad=True)
+        k = torch.tensor(K[b], dtype=torch.float64, requires_grad=True)
+        v = torch.tensor(V[b], dtype=torch.float64, requires_grad=True)
+        sc = scale * torch.einsum("hid,hjd->hij", q, k.repeat_interleave(G, dim=0))
+        sc = sc.masked_fill(~M, float("-inf"))
+        out = torch.einsum("hij,hjd->hid", torch.softmax(sc, dim=-1), v.repeat_interleave(G, dim=0))
+        out.backward(torch.from_numpy(dO[b]))
+        assert np.allclose(O[b], out.detach().numpy(), atol=1e-12)
+        assert np.allclose(LSE[b], torch.logsumexp(sc, dim=-1).detach().numpy(), atol=1e-12)
+        assert np.allclose(dQ[b], q.grad.numpy(), atol=1e-11)
+        assert np.allclose(dK[b], k.grad.numpy(), atol=1e-11)
+        assert np.allclose(dV[b], v.grad.numpy(), atol=1e-11)
+    # one document = the unpacked call
+    O1, L1 = oracle.forward(Q[1:], K[1:], V[1:], is_sep[1:], a, n, scale)
+    assert np.array_equal(O[1:], O1) and np.array_equal(LSE[1:], L1)
+    # the markers with every document's initial tokens added
+    start0, _ = oracle.doc_bounds(cus[0], L)
+    m = oracle.mark_doc_initial(is_sep[:1], start0[None], a)[0]
+    assert all(m[j] == (1 if (is_sep[0, j] or j in (0, 1, 7, 8, 9, 30, 31)) else 0) for j in range(L))
+
+
+# ----------------------------------------------------------------------------------------------
 # positions within the cache (Sec. 3.3 "Positional Encoding") and the append step
 # ----------------------------------------------------------------------------------------------
 def test_rope_rotation_worked_examples():

@@ -140,6 +140,35 @@ int sepattn_backward(const sepattn_params *p, const void *Q, const void *K, cons
                      void *dV, void *ws, size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Packed documents (training batches packed from several documents; the paper is silent on them:
+ * every document is taken as a sequence of its own, i.e. Eq. 1 / Eq. 2 per document: its first a
+ * tokens are its initial tokens and a query sees no key outside its document).  bf16 only.
+ *
+ * Preparation, per row of the batch: sepattn_doc_bounds turns the cumulative lengths into the two
+ * per-position bounds and marks the first a tokens of every document in the row's marker bitmap;
+ * the bitmap then goes through sepattn_compact_indices as usual, and the packed calls run with
+ * p->a == 0 (SEPATTN_ERR_PARAM otherwise): the documents' initial tokens are list entries.
+ *   cu_seqlens  DEVICE int32 [n_docs+1]: cu[0] = 0 < cu[1] < ... < cu[n_docs] = L
+ *   doc_start   DEVICE int32 [L]  out: first position of each position's document
+ *   doc_end     DEVICE int32 [L]  out: one past its last position
+ *   is_sep      DEVICE uint8 [L]  in/out, may be NULL: one row of the marker bitmap
+ * sepattn_forward_packed / sepattn_backward_packed: as sepattn_forward / sepattn_backward, plus
+ *   doc_start, doc_end  DEVICE int32 [B, L] (bounds that contradict each other cannot fault: they
+ *   are clamped around the position; the result is then unspecified).
+ * ------------------------------------------------------------------------------------------ */
+int sepattn_doc_bounds(const int32_t *cu_seqlens, int n_docs, int L, int a, int32_t *doc_start,
+                       int32_t *doc_end, uint8_t *is_sep, void *stream);
+int sepattn_forward_packed(const sepattn_params *p, const int32_t *doc_start, const int32_t *doc_end,
+                           const void *Q, const void *K, const void *V, const int32_t *sep_idx,
+                           const int32_t *sep_count, const int32_t *sep_prefix, void *O, float *LSE,
+                           void *ws, size_t ws_bytes, void *stream);
+int sepattn_backward_packed(const sepattn_params *p, const int32_t *doc_start,
+                            const int32_t *doc_end, const void *Q, const void *K, const void *V,
+                            const void *O, const float *LSE, const void *dO, const int32_t *sep_idx,
+                            const int32_t *sep_count, const int32_t *sep_prefix, void *dQ, void *dK,
+                            void *dV, void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------
  * Streaming generation on the four-block KV cache (Sec. 3.3).
  * Cache layout, per (sequence, KV head): c slots of d values,
  *     [0, a)       Initial Cache
@@ -282,7 +311,8 @@ typedef enum {
     SEPATTN_K_ROPE_TABLE = 12,
     SEPATTN_K_CACHE_APPEND = 13,
     SEPATTN_K_MARK_INTERVAL = 14,
-    SEPATTN_K_COUNT = 15
+    SEPATTN_K_DOC_BOUNDS = 15,
+    SEPATTN_K_COUNT = 16
 } sepattn_kernel_id;
 const char *sepattn_kernel_name(int kernel);
 int sepattn_profile_begin(int kernel, int max_records);

@@ -17,6 +17,9 @@ from .binding import (  # noqa: F401
     sepattn_mark_interval,
     sepattn_compact_indices,
     sepattn_forward,
+    sepattn_doc_bounds,
+    sepattn_forward_packed,
+    sepattn_backward_packed,
     sepattn_backward,
     sepattn_backward_workspace_bytes,
     sepattn_decode,

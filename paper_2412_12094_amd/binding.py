@@ -28,6 +28,9 @@ EXPORTS = (
     "sepattn_compact_indices",
     "sepattn_forward_workspace_bytes",
     "sepattn_forward",
+    "sepattn_doc_bounds",
+    "sepattn_forward_packed",
+    "sepattn_backward_packed",
     "sepattn_backward_workspace_bytes",
     "sepattn_backward",
     "sepattn_decode_workspace_bytes",
@@ -91,6 +94,12 @@ def load(path: Optional[str] = None):
     lib.sepattn_forward_workspace_bytes.argtypes = [pp]
     lib.sepattn_forward.restype = ci
     lib.sepattn_forward.argtypes = [pp] + [vp] * 9 + [sz, vp]
+    lib.sepattn_doc_bounds.restype = ci
+    lib.sepattn_doc_bounds.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
+    lib.sepattn_forward_packed.restype = ci
+    lib.sepattn_forward_packed.argtypes = [pp] + [vp] * 11 + [sz, vp]
+    lib.sepattn_backward_packed.restype = ci
+    lib.sepattn_backward_packed.argtypes = [pp] + [vp] * 15 + [sz, vp]
     lib.sepattn_backward_workspace_bytes.restype = sz
     lib.sepattn_backward_workspace_bytes.argtypes = [pp]
     lib.sepattn_backward.restype = ci
@@ -130,7 +139,7 @@ def status_string(status: int) -> str:
 KERNEL_IDS = {"mark": 0, "compact_count": 1, "compact_write": 2, "forward": 3, "bwd_dq": 4, "bwd_dkv": 5,
               "bwd_combine": 6, "decode_split": 7, "decode_merge": 8, "evict_plan": 9, "evict_move": 10,
               "cache_fill": 11, "rope_table": 12, "cache_append": 13,
-              "mark_interval": 14}
+              "mark_interval": 14, "doc_bounds": 15}
 
 
 def sepattn_kernel_name(kernel: int) -> str:
@@ -266,6 +275,46 @@ def sepattn_forward(Q, K, V, sep_idx, sep_count, sep_prefix, a: int, n: int, sca
     return O, LSE
 
 
+def sepattn_doc_bounds(cu_seqlens: torch.Tensor, L: int, a: int = 0, is_sep_row: Optional[torch.Tensor] = None,
+                       out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None):
+    """One packed row: cu_seqlens int32 [n_docs+1] (GPU; cu[0] = 0, cu[-1] = L) -> (doc_start, doc_end) int32 [L].
+    If is_sep_row (uint8 [L], one row of the marker bitmap) is given, the first a tokens of every
+    document are marked in it, in place."""
+    _dev(cu_seqlens, is_sep_row)
+    assert cu_seqlens.dtype == torch.int32 and cu_seqlens.dim() == 1
+    if out is None:
+        out = (torch.empty((int(L),), dtype=torch.int32, device=cu_seqlens.device),
+               torch.empty((int(L),), dtype=torch.int32, device=cu_seqlens.device))
+    _dev(*out)
+    _check("sepattn_doc_bounds",
+           load().sepattn_doc_bounds(_ptr(cu_seqlens), int(cu_seqlens.numel()) - 1, int(L), int(a), _ptr(out[0]),
+                                     _ptr(out[1]), _ptr(is_sep_row), _stream(cu_seqlens)))
+    return out
+
+
+def sepattn_forward_packed(Q, K, V, doc_start, doc_end, sep_idx, sep_count, sep_prefix, n: int, scale: float,
+                           out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None, ws: Optional[torch.Tensor] = None):
+    """Forward over rows of packed documents (bf16): doc_start, doc_end int32 [B,L] per-position bounds;
+    the index arrays come from a bitmap in which every document's initial tokens are marked (a = 0 here)."""
+    _dev(Q, K, V, doc_start, doc_end, sep_idx, sep_count, sep_prefix)
+    assert doc_start.dtype == torch.int32 and doc_end.dtype == torch.int32
+    assert tuple(doc_start.shape) == (Q.shape[0], Q.shape[2]) and doc_end.shape == doc_start.shape
+    p = _attn_params(Q, K, 0, n, scale, sep_idx.shape[1])
+    lib = load()
+    if out is None:
+        O = torch.empty_like(Q)
+        LSE = torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device)
+    else:
+        O, LSE = out
+    if ws is None:
+        ws = _ws(lib.sepattn_forward_workspace_bytes(ctypes.byref(p)), Q.device)
+    _check("sepattn_forward_packed",
+           lib.sepattn_forward_packed(ctypes.byref(p), _ptr(doc_start), _ptr(doc_end), _ptr(Q), _ptr(K), _ptr(V),
+                                      _ptr(sep_idx), _ptr(sep_count), _ptr(sep_prefix), _ptr(O), _ptr(LSE), _ptr(ws),
+                                      ws.numel(), _stream(Q)))
+    return O, LSE
+
+
 def sepattn_backward_workspace_bytes(Q, K, a: int, n: int, scale: float, cap: int) -> int:
     p = _attn_params(Q, K, a, n, scale, cap)
     return int(load().sepattn_backward_workspace_bytes(ctypes.byref(p)))
@@ -288,6 +337,27 @@ def sepattn_backward(Q, K, V, O, LSE, dO, sep_idx, sep_count, sep_prefix, a: int
            lib.sepattn_backward(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(dO),
                                 _ptr(sep_idx), _ptr(sep_count), _ptr(sep_prefix), _ptr(dQ), _ptr(dK),
                                 _ptr(dV), _ptr(ws), ws.numel(), _stream(Q)))
+    return dQ, dK, dV
+
+
+def sepattn_backward_packed(Q, K, V, O, LSE, dO, doc_start, doc_end, sep_idx, sep_count, sep_prefix, n: int,
+                            scale: float, out=None, ws: Optional[torch.Tensor] = None):
+    """Backward over rows of packed documents (bf16) -> (dQ, dK, dV); arguments as sepattn_forward_packed."""
+    _dev(Q, K, V, O, LSE, dO, doc_start, doc_end, sep_idx, sep_count, sep_prefix)
+    assert doc_start.dtype == torch.int32 and doc_end.dtype == torch.int32
+    assert tuple(doc_start.shape) == (Q.shape[0], Q.shape[2]) and doc_end.shape == doc_start.shape
+    p = _attn_params(Q, K, 0, n, scale, sep_idx.shape[1])
+    lib = load()
+    if out is None:
+        dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    else:
+        dQ, dK, dV = out
+    if ws is None:
+        ws = _ws(lib.sepattn_backward_workspace_bytes(ctypes.byref(p)), Q.device)
+    _check("sepattn_backward_packed",
+           lib.sepattn_backward_packed(ctypes.byref(p), _ptr(doc_start), _ptr(doc_end), _ptr(Q), _ptr(K), _ptr(V),
+                                       _ptr(O), _ptr(LSE), _ptr(dO), _ptr(sep_idx), _ptr(sep_count), _ptr(sep_prefix),
+                                       _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(ws), ws.numel(), _stream(Q)))
     return dQ, dK, dV
 
 

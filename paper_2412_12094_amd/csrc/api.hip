@@ -110,7 +110,7 @@ const char *sepattn_kernel_name(int kernel) {
                                                  "dkv_combine_kernel", "decode_split_kernel",
                                                  "decode_merge_kernel", "evict_plan_kernel",
                                                  "evict_move_kernel", "cache_fill_kernel", "rope_table_kernel",
-                                                 "cache_append_kernel", "mark_interval_kernel"};
+                                                 "cache_append_kernel", "mark_interval_kernel", "doc_bounds_kernel"};
     return (kernel >= 0 && kernel < SEPATTN_K_COUNT) ? names[kernel] : "unknown";
 }
 
@@ -215,7 +215,32 @@ int sepattn_forward(const sepattn_params *p, const void *Q, const void *K, const
     if (q.dtype == SEPATTN_FP32)
         return launch_forward_fp32(q, (const float *)Q, (const float *)K, (const float *)V, sep_idx,
                                    sep_prefix, (float *)O, LSE, st);
-    return launch_forward_bf16(q, Q, K, V, sep_idx, sep_prefix, O, LSE, ws, st);
+    return launch_forward_bf16(q, Q, K, V, sep_idx, sep_prefix, nullptr, nullptr, O, LSE, ws, st);
+}
+
+int sepattn_doc_bounds(const int32_t *cu_seqlens, int n_docs, int L, int a, int32_t *doc_start, int32_t *doc_end,
+                       uint8_t *is_sep, void *stream) {
+    if (!cu_seqlens || !doc_start || !doc_end) return SEPATTN_ERR_NULL;
+    if (n_docs < 1 || L < 1 || n_docs > L) return SEPATTN_ERR_SHAPE;
+    if (a < 0) return SEPATTN_ERR_PARAM;
+    return launch_doc_bounds(cu_seqlens, n_docs, L, a, doc_start, doc_end, is_sep, static_cast<hipStream_t>(stream));
+}
+
+int sepattn_forward_packed(const sepattn_params *p, const int32_t *doc_start, const int32_t *doc_end,
+                           const void *Q, const void *K, const void *V, const int32_t *sep_idx,
+                           const int32_t *sep_count, const int32_t *sep_prefix, void *O, float *LSE, void *ws,
+                           size_t ws_bytes, void *stream) {
+    int rc = check_attn(p);
+    if (rc != SEPATTN_OK) return rc;
+    if (p->dtype != SEPATTN_BF16) return SEPATTN_ERR_DTYPE;
+    if (p->a != 0) return SEPATTN_ERR_PARAM;  // the documents' initial tokens are in the marker bitmap
+    if (!doc_start || !doc_end || !Q || !K || !V || !sep_idx || !sep_count || !sep_prefix || !O || !LSE)
+        return SEPATTN_ERR_NULL;
+    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16)) return SEPATTN_ERR_PARAM;
+    size_t need = sepattn_forward_workspace_bytes(p);
+    if (need > 0 && (!ws || ws_bytes < need || !aligned(ws, 256))) return SEPATTN_ERR_WORKSPACE;
+    return launch_forward_bf16(normalised(p), Q, K, V, sep_idx, sep_prefix, doc_start, doc_end, O, LSE, ws,
+                               static_cast<hipStream_t>(stream));
 }
 
 size_t sepattn_backward_workspace_bytes(const sepattn_params *p) {
@@ -243,7 +268,29 @@ int sepattn_backward(const sepattn_params *p, const void *Q, const void *K, cons
         return launch_backward_fp32(q, (const float *)Q, (const float *)K, (const float *)V,
                                     (const float *)O, LSE, (const float *)dO, sep_idx, sep_prefix,
                                     (float *)dQ, (float *)dK, (float *)dV, (float *)ws, st);
-    return launch_backward_bf16(q, Q, K, V, O, LSE, dO, sep_idx, sep_count, sep_prefix, dQ, dK, dV, ws, st);
+    return launch_backward_bf16(q, Q, K, V, O, LSE, dO, sep_idx, sep_count, sep_prefix, nullptr, nullptr, dQ, dK, dV,
+                                ws, st);
+}
+
+int sepattn_backward_packed(const sepattn_params *p, const int32_t *doc_start, const int32_t *doc_end,
+                            const void *Q, const void *K, const void *V, const void *O, const float *LSE,
+                            const void *dO, const int32_t *sep_idx, const int32_t *sep_count,
+                            const int32_t *sep_prefix, void *dQ, void *dK, void *dV, void *ws, size_t ws_bytes,
+                            void *stream) {
+    int rc = check_attn(p);
+    if (rc != SEPATTN_OK) return rc;
+    if (p->dtype != SEPATTN_BF16) return SEPATTN_ERR_DTYPE;
+    if (p->a != 0) return SEPATTN_ERR_PARAM;  // the documents' initial tokens are in the marker bitmap
+    if (!doc_start || !doc_end || !Q || !K || !V || !O || !LSE || !dO || !sep_idx || !sep_count || !sep_prefix ||
+        !dQ || !dK || !dV)
+        return SEPATTN_ERR_NULL;
+    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) || !aligned(dO, 16) ||
+        !aligned(dQ, 16) || !aligned(dK, 16) || !aligned(dV, 16))
+        return SEPATTN_ERR_PARAM;
+    size_t need = sepattn_backward_workspace_bytes(p);
+    if (!ws || ws_bytes < need || !aligned(ws, 256)) return SEPATTN_ERR_WORKSPACE;
+    return launch_backward_bf16(normalised(p), Q, K, V, O, LSE, dO, sep_idx, sep_count, sep_prefix, doc_start,
+                                doc_end, dQ, dK, dV, ws, static_cast<hipStream_t>(stream));
 }
 
 size_t sepattn_decode_workspace_bytes(const sepkv_params *p) {

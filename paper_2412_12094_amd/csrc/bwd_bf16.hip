@@ -47,12 +47,14 @@ __device__ inline float bf16_dot8(u32x4 a, u32x4 b) {
 // each (tile X+2 is requested while tile X is multiplied).  The two waves that share
 // a SIMD drift apart by themselves, so that one wave's exponentials overlap the other's matrix work.
 // ---------------------------------------------------------------------------------------------
-template <int D, int GP>
+// DOCS: packed documents, as in the forward kernel (doc_start / doc_end [B, L]; p.a == 0).
+template <int D, int GP, bool DOCS>
 __global__ __launch_bounds__(512, 2) void dq_kernel(
     sepattn_params p, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
     const uint16_t *__restrict__ V, const uint16_t *__restrict__ O, const float *__restrict__ LSE,
     const uint16_t *__restrict__ dO, const int32_t *__restrict__ sep_idx,
-    const int32_t *__restrict__ sep_prefix, uint16_t *__restrict__ dQ, float *__restrict__ Dws,
+    const int32_t *__restrict__ sep_prefix, const int32_t *__restrict__ doc_start,
+    const int32_t *__restrict__ doc_end, uint16_t *__restrict__ dQ, float *__restrict__ Dws,
     float *__restrict__ Lws, int wpg) {
     constexpr int NW = 8;
     constexpr int TP = 32 * NW / GP;
@@ -96,6 +98,8 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
 
     const int32_t *prefix = sep_prefix + (long)b * (p.L + 1);
     const int32_t *idx = sep_idx + (long)b * p.cap;
+    const int32_t *dstart = DOCS ? doc_start + (long)b * p.L : nullptr;
+    const int32_t *dend = DOCS ? doc_end + (long)b * p.L : nullptr;
     const uint16_t *Kh = K + ((long)b * p.Hkv + kv) * (long)p.L * D;
     const uint16_t *Vh = V + ((long)b * p.Hkv + kv) * (long)p.L * D;
 
@@ -123,11 +127,13 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
         const int e = min(max(ss.sep_lo - ss.n_init + k, 0), p.cap - 1);
         const int j = min(max(ss.bs - ss.n_dense + k, 0), p.L - 1);
         const int32_t *src = m_part == 0 ? idx + e : prefix + j + (m_part - 1);
-        if (lane < 3 * MR) dma_to_lds_4_addr(src, lds_addr(&meta_s[(unsigned)g % MST][wave % NLW][0]));
+        if constexpr (DOCS) src = m_part == 3 ? dend + j : src;  // fourth part: where the key's document ends
+        if (lane < (DOCS ? 4 : 3) * MR) dma_to_lds_4_addr(src, lds_addr(&meta_s[(unsigned)g % MST][wave % NLW][0]));
     };
     // One row of the tile at a time (the loading waves have time to spare, registers are scarce): read
     // the row's index entries, work out its key position and visibility range, request the row.
-    auto load_row = [&](const Stream &ss, int t, int g, auto U) __attribute__((always_inline)) {
+    // de: end of the document of the segment's first row; straddle: the segment's rows reach beyond it
+    auto load_row = [&](const Stream &ss, int de, bool straddle, int t, int g, auto U) __attribute__((always_inline)) {
         constexpr int u = decltype(U)::value;
         const int *mt = &meta_s[(unsigned)g % MST][wave % NLW][0];
         const int rawi = mt[u * RPL + my_sub], raw0 = mt[MR + u * RPL + my_sub], raw1 = mt[2 * MR + u * RPL + my_sub];
@@ -137,7 +143,7 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
         // the clamp keeps a stale list tail (caller broke sep_count <= cap) from faulting
         const int jl = min(max(rawi, 0), p.L - 1);
         int jrow;
-        if (tile_class(ss, t) == 0) {
+        if (tile_class(ss, t) == 0 && !(DOCS && straddle)) {
             jrow = k < ss.n_init ? k : jl;
         } else {
             const bool init = k < ss.n_init, dense = k < ss.n_dense, pad = k >= ss.n_total;
@@ -147,6 +153,7 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
             j = pad ? 0 : j;
             const int lo = pad ? kIntMax : j;
             int hi = always ? kIntMax : jb + p.n - 1;
+            if constexpr (DOCS) hi = min(hi, (dense ? de : mt[3 * MR + u * RPL + my_sub]) - 1);
             hi = pad ? -1 : hi;
             if (my_pc == 0) {
                 lo_s[ms_][r] = lo;
@@ -168,7 +175,7 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
     // visible), which keeps the count of outstanding loads exact.
     struct Seg {
         Stream st;
-        int n_tiles, i0;
+        int n_tiles, i0, de;
     };
     auto open_segment = [&](int round) {
         Seg g;
@@ -177,9 +184,18 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
             g.st = Stream{0, 0, 0, 0, 0};
             g.n_tiles = kIntMax;
             g.i0 = -1;
+            g.de = kIntMax;
         } else {
             g.i0 = (n_pos_tiles - 1 - rank) * TP;
-            g.st = make_stream(p, prefix, g.i0, TP);
+            if constexpr (DOCS) {
+                // the clamps keep inconsistent bounds (caller error) from faulting
+                const int ds = min(max(dstart[g.i0], 0), g.i0);
+                g.de = min(max(dend[g.i0], g.i0 + 1), p.L);
+                g.st = make_stream_docs(p, prefix, g.i0, TP, ds);
+            } else {
+                g.de = kIntMax;
+                g.st = make_stream(p, prefix, g.i0, TP);
+            }
             g.n_tiles = (g.st.n_total + kBN - 1) / kBN;
         }
         return g;
@@ -281,7 +297,7 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
                         entries_landed();
                         issue_meta_after_cursor();
                     } else if constexpr (s >= NS1 / 4 && (s - NS1 / 4) % 2 == 0 && (s - NS1 / 4) / 2 < LOADS) {
-                        load_row(lcur.st, l_t, l_g, IntC<(s - NS1 / 4) / 2>{});
+                        load_row(lcur.st, lcur.de, lcur.i0 + TP > lcur.de, l_t, l_g, IntC<(s - NS1 / 4) / 2>{});
                     } else if constexpr (s == NS1 - 1) {
                         advance_cursor();
                     }
@@ -338,7 +354,7 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
 #pragma unroll
         for (int rep = 0; rep < 2; ++rep) {
             issue_meta_after_cursor();
-            static_for<LOADS>([&](auto U) { load_row(lcur.st, l_t, l_g, U); });
+            static_for<LOADS>([&](auto U) { load_row(lcur.st, lcur.de, lcur.i0 + TP > lcur.de, l_t, l_g, U); });
             advance_cursor();
             entries_landed();  // the entries just requested (the rows after them may be in flight)
         }
@@ -351,6 +367,7 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
         const int pw = cseg.i0 + 32 * (wave / GP);
         iq = pw + qi;
         fullb = full_blocks(cseg.st, pw, p.n);
+        if (DOCS && pw + 31 >= cseg.de) fullb = no_full_blocks();
         // rows of this wave's head: (uniform base) + 32-bit byte offset of the lane's piece
         const long head_row0 = ((long)b * p.Hq + head) * p.L;
         {
@@ -414,11 +431,11 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
-template <int D>
+template <int D, bool DOCS>
 int launch_bwd(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
                const uint16_t *O, const float *LSE, const uint16_t *dO, const int32_t *sep_idx,
-               const int32_t *sep_prefix, uint16_t *dQ, uint16_t *dK, uint16_t *dV, void *ws,
-               hipStream_t st) {
+               const int32_t *sep_prefix, const int32_t *doc_start, const int32_t *doc_end, uint16_t *dQ,
+               uint16_t *dK, uint16_t *dV, void *ws, hipStream_t st) {
     const BwdWorkspace w = bwd_workspace(p);
     char *base = static_cast<char *>(ws);
     float *Dws = reinterpret_cast<float *>(base);
@@ -440,14 +457,14 @@ int launch_bwd(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
     {
     ProfScope prof(SEPATTN_K_BWD_DQ, st);
     if (GP == 4)
-        hipLaunchKernelGGL((dq_kernel<D, 4>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, dQ, Dws, Lws, wpg);
+        hipLaunchKernelGGL((dq_kernel<D, 4, DOCS>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, doc_start, doc_end, dQ, Dws, Lws, wpg);
     else if (GP == 2)
-        hipLaunchKernelGGL((dq_kernel<D, 2>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, dQ, Dws, Lws, wpg);
+        hipLaunchKernelGGL((dq_kernel<D, 2, DOCS>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, doc_start, doc_end, dQ, Dws, Lws, wpg);
     else
-        hipLaunchKernelGGL((dq_kernel<D, 1>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, dQ, Dws, Lws, wpg);
+        hipLaunchKernelGGL((dq_kernel<D, 1, DOCS>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, doc_start, doc_end, dQ, Dws, Lws, wpg);
     }
     if (hipGetLastError() != hipSuccess) return SEPATTN_ERR_HIP;
-    return launch_dkv_bf16(p, Q, K, V, Lws, dO, Dws, sep_idx, sep_prefix, dK, dV, farK, farV, piece_tab, st);
+    return launch_dkv_bf16(p, Q, K, V, Lws, dO, Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, st);
 }
 
 }  // namespace
@@ -456,13 +473,22 @@ size_t backward_bf16_workspace(const sepattn_params &p) { return bwd_workspace(p
 
 int launch_backward_bf16(const sepattn_params &p, const void *Q, const void *K, const void *V,
                          const void *O, const float *LSE, const void *dO, const int32_t *sep_idx,
-                         const int32_t *, const int32_t *sep_prefix, void *dQ, void *dK, void *dV,
-                         void *ws, hipStream_t st) {
+                         const int32_t *, const int32_t *sep_prefix, const int32_t *doc_start,
+                         const int32_t *doc_end, void *dQ, void *dK, void *dV, void *ws, hipStream_t st) {
     auto u = [](const void *x) { return static_cast<const uint16_t *>(x); };
     auto w = [](void *x) { return static_cast<uint16_t *>(x); };
+    if (doc_start) {
+        if (p.d == 64)
+            return launch_bwd<64, true>(p, u(Q), u(K), u(V), u(O), LSE, u(dO), sep_idx, sep_prefix, doc_start, doc_end,
+                                        w(dQ), w(dK), w(dV), ws, st);
+        return launch_bwd<128, true>(p, u(Q), u(K), u(V), u(O), LSE, u(dO), sep_idx, sep_prefix, doc_start, doc_end,
+                                     w(dQ), w(dK), w(dV), ws, st);
+    }
     if (p.d == 64)
-        return launch_bwd<64>(p, u(Q), u(K), u(V), u(O), LSE, u(dO), sep_idx, sep_prefix, w(dQ), w(dK), w(dV), ws, st);
-    return launch_bwd<128>(p, u(Q), u(K), u(V), u(O), LSE, u(dO), sep_idx, sep_prefix, w(dQ), w(dK), w(dV), ws, st);
+        return launch_bwd<64, false>(p, u(Q), u(K), u(V), u(O), LSE, u(dO), sep_idx, sep_prefix, nullptr, nullptr,
+                                     w(dQ), w(dK), w(dV), ws, st);
+    return launch_bwd<128, false>(p, u(Q), u(K), u(V), u(O), LSE, u(dO), sep_idx, sep_prefix, nullptr, nullptr,
+                                  w(dQ), w(dK), w(dV), ws, st);
 }
 
 }  // namespace sepattn

@@ -87,9 +87,21 @@ __device__ inline int far_first_query(const FarList &fl, int f, const int32_t *_
     return align_down32(far_pos(fl, (f / kBK) * kBK, idx, p.L) + p.n);
 }
 
+// one past the last query row the far pieces of list entry f's tile cover: the end of the sequence,
+// or, with packed documents (dend: one past the last position of each position's document, else
+// nullptr), the end of the document of the tile's last entry.  A tile whose first query row
+// (far_first_query) is not below this has no far piece.
+__device__ inline int far_last_query(const FarList &fl, int f, const int32_t *__restrict__ idx,
+                                     const sepattn_params &p, const int32_t *__restrict__ dend) {
+    if (!dend) return p.L;
+    const int last = min((f / kBK + 1) * kBK, fl.NF) - 1;
+    return min(max(dend[far_pos(fl, last, idx, p.L)], 0), p.L);
+}
+
+// doc_end: packed documents ([B, L], p.a == 0), or nullptr
 int launch_dkv_bf16(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
                     const float *lse2, const uint16_t *dO, const float *Dws, const int32_t *sep_idx,
-                    const int32_t *sep_prefix, uint16_t *dK, uint16_t *dV, float *farK, float *farV,
-                    int32_t *piece_tab, hipStream_t st);
+                    const int32_t *sep_prefix, const int32_t *doc_end, uint16_t *dK, uint16_t *dV, float *farK,
+                    float *farV, int32_t *piece_tab, hipStream_t st);
 
 }  // namespace sepattn

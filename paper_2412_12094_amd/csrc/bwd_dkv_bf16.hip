@@ -57,12 +57,16 @@ __device__ inline int wave_max_i(int v) {
     return v;
 }
 
-template <int D>
+// DOCS: packed documents (doc_end [B, L]: one past the last position of each position's document;
+// p.a == 0, the documents' initial tokens are list entries): a key's query range ends with its
+// document, and the far pieces of a list tile end with the document of the tile's last entry.
+template <int D, bool DOCS>
 __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
     sepattn_params p, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
     const uint16_t *__restrict__ V, const float *__restrict__ LSE2, const uint16_t *__restrict__ dO,
     const float *__restrict__ Dws, const int32_t *__restrict__ sep_idx,
-    const int32_t *__restrict__ sep_prefix, uint16_t *__restrict__ dK, uint16_t *__restrict__ dV,
+    const int32_t *__restrict__ sep_prefix, const int32_t *__restrict__ doc_end,
+    uint16_t *__restrict__ dK, uint16_t *__restrict__ dV,
     float *__restrict__ farK, float *__restrict__ farV, int32_t *__restrict__ piece_tab, int wpg, int n_band) {
     constexpr int NW = 2 * kDkvWaves;        // waves per workgroup
     constexpr int CH = D / 8;                // 16-byte chunks per row
@@ -93,6 +97,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
     const int kv = bkv % p.Hkv, b = bkv / p.Hkv;
     const int32_t *prefix = sep_prefix + (long)b * (p.L + 1);
     const int32_t *idx = sep_idx + (long)b * p.cap;
+    const int32_t *dend = DOCS ? doc_end + (long)b * p.L : nullptr;
     const long kvrow0 = ((long)b * p.Hkv + kv) * (long)p.L;
     const float sl2 = p.scale * kLog2e_f;
     const FarGeom fg = far_geom(p, wpg);
@@ -120,8 +125,12 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
     const int NFT = (fl.NF + kBK - 1) / kBK;
     auto tile_items = [&](int t, int &fq) __attribute__((always_inline)) {
         fq = p.L;
-        if (t < NFT) fq = align_down32(far_pos(fl, t * kBK, idx, p.L) + p.n);
-        return fq < p.L ? G * ((p.L - fq + kBQ - 1) / kBQ) : 0;
+        int qe = p.L;
+        if (t < NFT) {
+            fq = align_down32(far_pos(fl, t * kBK, idx, p.L) + p.n);
+            qe = far_last_query(fl, t * kBK, idx, p, dend);
+        }
+        return fq < qe ? G * ((qe - fq + kBQ - 1) / kBQ) : 0;
     };
     auto inclusive_scan = [&](int v) __attribute__((always_inline)) {
 #pragma unroll
@@ -209,12 +218,13 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
         bool valid;
         if (FAR) {
             q_lo = fq0;
-            q_hi = p.L;
+            q_hi = far_last_query(fl, ft * kBK, idx, p, dend);
             fidx = ft * kBK + 32 * kbw + kj;
             valid = fidx < fl.NF;
             j = valid ? far_pos(fl, fidx, idx, p.L) : 0;
             lo = j + p.n;
             hi = q_hi - 1;
+            if constexpr (DOCS) hi = min(hi, dend[j] - 1);
         } else {
             int j0 = unit * kBK;
             j = j0 + 32 * kbw + kj;
@@ -224,6 +234,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
             lo = j;
             hi = min(j + p.n - 1, p.L - 1);
             if (!valid) j = 0;
+            if constexpr (DOCS) hi = min(hi, dend[j] - 1);
             item0 = 0;
             n_qt = (q_hi - q_lo + kBQ - 1) / kBQ;
             n_items = G * n_qt;
@@ -641,7 +652,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
         bool to_partial = FAR;
         if (!FAR && valid) {
             const int f = far_index(fl, prefix, j);
-            if (f >= 0 && far_first_query(fl, f, idx, p) < p.L) {
+            if (f >= 0 && far_first_query(fl, f, idx, p) < far_last_query(fl, f, idx, p, dend)) {
                 to_partial = true;
                 part_row = (long)fg.NP * kBK + f;
             }
@@ -694,6 +705,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
 template <int D>
 __global__ __launch_bounds__(256) void dkv_combine_kernel(sepattn_params p, const int32_t *__restrict__ sep_idx,
                                                           const int32_t *__restrict__ sep_prefix,
+                                                          const int32_t *__restrict__ doc_end,
                                                           uint16_t *__restrict__ dK, uint16_t *__restrict__ dV,
                                                           const float *__restrict__ farK,
                                                           const float *__restrict__ farV,
@@ -707,7 +719,8 @@ __global__ __launch_bounds__(256) void dkv_combine_kernel(sepattn_params p, cons
     const int f = (blockIdx.x * 256 + threadIdx.x) / TPR, col = ((blockIdx.x * 256 + threadIdx.x) % TPR) * 4;
     if (f >= fl.NF) return;
     const int A = far_first_query(fl, f, idx, p);
-    if (A >= p.L) return;  // no far pair: the band unit has written this row
+    // no far piece for this list tile: the band unit has written the row
+    if (A >= far_last_query(fl, f, idx, p, doc_end ? doc_end + (long)b * p.L : nullptr)) return;
     const int j = far_pos(fl, f, idx, p.L);
     const int ft = f / kBK;
     const int32_t *tab = piece_tab + ((long)bkv * fg.NFTcap + ft) * 2;
@@ -748,8 +761,8 @@ __global__ __launch_bounds__(256) void dkv_combine_kernel(sepattn_params p, cons
 template <int D>
 int launch_dkv(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
                const float *lse2, const uint16_t *dO, const float *Dws, const int32_t *sep_idx,
-               const int32_t *sep_prefix, uint16_t *dK, uint16_t *dV, float *farK, float *farV,
-               int32_t *piece_tab, hipStream_t st) {
+               const int32_t *sep_prefix, const int32_t *doc_end, uint16_t *dK, uint16_t *dV, float *farK,
+               float *farV, int32_t *piece_tab, hipStream_t st) {
     const int wpg = dkv_workgroups_per_head(p);
     const FarGeom fg = far_geom(p, wpg);
     const long band_grid = (p.L + kBK - 1) / kBK;
@@ -757,14 +770,18 @@ int launch_dkv(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
     if (total > 0x7FFFFFFFL) return SEPATTN_ERR_SHAPE;
     {
         ProfScope prof(SEPATTN_K_BWD_DKV, st);
-        hipLaunchKernelGGL((dkv_kernel<D>), dim3((unsigned)total), dim3(kDkvThreads), 0, st, p, Q, K, V, lse2, dO, Dws,
-                           sep_idx, sep_prefix, dK, dV, farK, farV, piece_tab, wpg, (int)band_grid);
+        if (doc_end)
+            hipLaunchKernelGGL((dkv_kernel<D, true>), dim3((unsigned)total), dim3(kDkvThreads), 0, st, p, Q, K, V, lse2, dO,
+                               Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, wpg, (int)band_grid);
+        else
+            hipLaunchKernelGGL((dkv_kernel<D, false>), dim3((unsigned)total), dim3(kDkvThreads), 0, st, p, Q, K, V, lse2, dO,
+                               Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, wpg, (int)band_grid);
     }
     if (hipGetLastError() != hipSuccess) return SEPATTN_ERR_HIP;
     ProfScope prof(SEPATTN_K_BWD_COMBINE, st);
     const int rows_per_block = 256 / (D / 4);
     hipLaunchKernelGGL((dkv_combine_kernel<D>), dim3((fg.NFcap + rows_per_block - 1) / rows_per_block, p.B * p.Hkv),
-                       dim3(256), 0, st, p, sep_idx, sep_prefix, dK, dV, farK, farV, piece_tab, wpg);
+                       dim3(256), 0, st, p, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, wpg);
     return launch_status();
 }
 
@@ -772,10 +789,11 @@ int launch_dkv(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
 
 int launch_dkv_bf16(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
                     const float *lse2, const uint16_t *dO, const float *Dws, const int32_t *sep_idx,
-                    const int32_t *sep_prefix, uint16_t *dK, uint16_t *dV, float *farK, float *farV,
-                    int32_t *piece_tab, hipStream_t st) {
-    if (p.d == 64) return launch_dkv<64>(p, Q, K, V, lse2, dO, Dws, sep_idx, sep_prefix, dK, dV, farK, farV, piece_tab, st);
-    return launch_dkv<128>(p, Q, K, V, lse2, dO, Dws, sep_idx, sep_prefix, dK, dV, farK, farV, piece_tab, st);
+                    const int32_t *sep_prefix, const int32_t *doc_end, uint16_t *dK, uint16_t *dV, float *farK,
+                    float *farV, int32_t *piece_tab, hipStream_t st) {
+    if (p.d == 64)
+        return launch_dkv<64>(p, Q, K, V, lse2, dO, Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, st);
+    return launch_dkv<128>(p, Q, K, V, lse2, dO, Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, st);
 }
 
 }  // namespace sepattn

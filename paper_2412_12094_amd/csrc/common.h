@@ -61,14 +61,17 @@ int launch_backward_fp32(const sepattn_params &p, const float *Q, const float *K
 
 // ---- bf16 MFMA path ----------------------------------------------------------------------------
 size_t forward_bf16_workspace(const sepattn_params &p);
+// doc_start / doc_end: packed documents (per-position bounds [B, L]; p.a must be 0), or nullptr
 int launch_forward_bf16(const sepattn_params &p, const void *Q, const void *K, const void *V,
-                        const int32_t *sep_idx, const int32_t *sep_prefix, void *O, float *LSE,
-                        void *ws, hipStream_t st);
+                        const int32_t *sep_idx, const int32_t *sep_prefix, const int32_t *doc_start,
+                        const int32_t *doc_end, void *O, float *LSE, void *ws, hipStream_t st);
+int launch_doc_bounds(const int32_t *cu_seqlens, int n_docs, int L, int a, int32_t *doc_start, int32_t *doc_end,
+                      uint8_t *is_sep, hipStream_t st);
 size_t backward_bf16_workspace(const sepattn_params &p);
 int launch_backward_bf16(const sepattn_params &p, const void *Q, const void *K, const void *V,
                          const void *O, const float *LSE, const void *dO, const int32_t *sep_idx,
-                         const int32_t *sep_count, const int32_t *sep_prefix, void *dQ, void *dK,
-                         void *dV, void *ws, hipStream_t st);
+                         const int32_t *sep_count, const int32_t *sep_prefix, const int32_t *doc_start,
+                         const int32_t *doc_end, void *dQ, void *dK, void *dV, void *ws, hipStream_t st);
 
 // ---- streaming cache ---------------------------------------------------------------------------
 size_t decode_workspace(const sepkv_params &p);

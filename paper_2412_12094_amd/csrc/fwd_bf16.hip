@@ -46,11 +46,14 @@ namespace {
 
 constexpr float kRescaleThreshold = 8.f;  // log2 units
 
-template <int D, int GP>
+// DOCS: packed documents (see make_stream_docs); doc_start / doc_end [B, L] give, per position, the
+// first position of its document and one past its last.  Requires p.a == 0.
+template <int D, int GP, bool DOCS>
 __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     sepattn_params p, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
     const uint16_t *__restrict__ V, const int32_t *__restrict__ sep_idx,
-    const int32_t *__restrict__ sep_prefix, uint16_t *__restrict__ O, float *__restrict__ LSE, int wpg) {
+    const int32_t *__restrict__ sep_prefix, const int32_t *__restrict__ doc_start,
+    const int32_t *__restrict__ doc_end, uint16_t *__restrict__ O, float *__restrict__ LSE, int wpg) {
     constexpr int NW = 8;
     constexpr int TP = 32 * NW / GP;  // query positions per workgroup
     constexpr int CH = D / 8;         // 16-byte chunks per row
@@ -97,6 +100,8 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
 
     const int32_t *prefix = sep_prefix + (long)b * (p.L + 1);
     const int32_t *idx = sep_idx + (long)b * p.cap;
+    const int32_t *dstart = DOCS ? doc_start + (long)b * p.L : nullptr;
+    const int32_t *dend = DOCS ? doc_end + (long)b * p.L : nullptr;
     const uint16_t *Kh = K + ((long)b * p.Hkv + kv) * (long)p.L * D;
     const uint16_t *Vh = V + ((long)b * p.Hkv + kv) * (long)p.L * D;
 
@@ -152,14 +157,15 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
         const int e = min(max(ss.sep_lo - ss.n_init + k, 0), p.cap - 1);
         const int j = min(max(ss.bs - ss.n_dense + k, 0), p.L - 1);
         const int32_t *src = m_part == 0 ? idx + e : prefix + j + (m_part - 1);
-        if (lane < 3 * MR) dma_to_lds_4_addr(src, lds_addr(&meta_s[(unsigned)g % MST][wave % NLW][0]));
+        if constexpr (DOCS) src = m_part == 3 ? dend + j : src;  // fourth part: where the key's document ends
+        if (lane < (DOCS ? 4 : 3) * MR) dma_to_lds_4_addr(src, lds_addr(&meta_s[(unsigned)g % MST][wave % NLW][0]));
     };
     // Rows of a tile in two steps, so that the index entries of the NEXT tile can be requested in
     // between: vector-memory results return in issue order, and with the order
     //   [entries of the next tile] [rows of this tile]   the wait for the entries does not wait for
     // the rows.  Past the last segment the stream is empty: its tiles are "loaded" too (row 0, never
     // visible), which keeps the count of outstanding loads exact in a loop body without alternatives.
-    int jrow[LOADS], rawi[LOADS], raw0[LOADS], raw1[LOADS];
+    int jrow[LOADS], rawi[LOADS], raw0[LOADS], raw1[LOADS], raw2[DOCS ? LOADS : 1];
     auto read_entries = [&](int g) __attribute__((always_inline)) {
         const int *mt = &meta_s[(unsigned)g % MST][wave % NLW][0];
         static_for<LOADS>([&](auto U) {
@@ -167,16 +173,18 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
             rawi[u] = mt[u * RPL + my_sub];
             raw0[u] = mt[MR + u * RPL + my_sub];
             raw1[u] = mt[2 * MR + u * RPL + my_sub];
+            if constexpr (DOCS) raw2[u] = mt[3 * MR + u * RPL + my_sub];
         });
     };
-    auto prepare_row = [&](const Stream &ss, int t, int g, auto U) __attribute__((always_inline)) {
+    // de: end of the document of the segment's first row; straddle: the segment's rows reach beyond it
+    auto prepare_row = [&](const Stream &ss, int de, bool straddle, int t, int g, auto U) __attribute__((always_inline)) {
         constexpr int u = decltype(U)::value;
         const int vs_ = (unsigned)g % VST;
         const int r = rrow[u];
         const int k = t * kBN + r;
         // the clamp keeps a stale list tail (caller broke sep_count <= cap) from faulting
         const int jl = min(max(rawi[u], 0), p.L - 1);
-        if (tile_class(ss, t) == 0) {
+        if (tile_class(ss, t) == 0 && !(DOCS && straddle)) {
             jrow[u] = k < ss.n_init ? k : jl;
         } else {
             const bool init = k < ss.n_init, dense = k < ss.n_dense, pad = k >= ss.n_total;
@@ -186,6 +194,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
             j = pad ? 0 : j;
             const int lo = pad ? kIntMax : j;
             int hi = always ? kIntMax : jb + p.n - 1;
+            if constexpr (DOCS) hi = min(hi, (dense ? de : raw2[u]) - 1);
             hi = pad ? -1 : hi;
             if (my_pc == 0) {
                 lo_s[vs_][r] = lo;
@@ -209,7 +218,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     // segment borders, so that only the first segment of a workgroup pays the start-up latencies.
     struct Seg {
         Stream st;
-        int n_tiles, i0;
+        int n_tiles, i0, de;
     };
     auto open_segment = [&](int round) {
         Seg g;
@@ -218,9 +227,18 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
             g.st = Stream{0, 0, 0, 0, 0};
             g.n_tiles = kIntMax;
             g.i0 = -1;
+            g.de = kIntMax;
         } else {
             g.i0 = (n_pos_tiles - 1 - rank) * TP;
-            g.st = make_stream(p, prefix, g.i0, TP);
+            if constexpr (DOCS) {
+                // the clamps keep inconsistent bounds (caller error) from faulting
+                const int ds = min(max(dstart[g.i0], 0), g.i0);
+                g.de = min(max(dend[g.i0], g.i0 + 1), p.L);
+                g.st = make_stream_docs(p, prefix, g.i0, TP, ds);
+            } else {
+                g.de = kIntMax;
+                g.st = make_stream(p, prefix, g.i0, TP);
+            }
             g.n_tiles = (g.st.n_total + kBN - 1) / kBN;
         }
         return g;
@@ -364,7 +382,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
             entries_landed();
             read_entries(l_g);
         } else if constexpr (c >= PREP0 && c < 6 && (c - PREP0) % PSTEP == 0 && (c - PREP0) / PSTEP < LOADS) {
-            prepare_row(lcur.st, l_t, l_g, IntC<(c - PREP0) / PSTEP>{});
+            prepare_row(lcur.st, lcur.de, lcur.i0 + TP > lcur.de, l_t, l_g, IntC<(c - PREP0) / PSTEP>{});
         } else if constexpr (c == 6) {
             issue_meta_after_cursor();
         } else if constexpr (c >= 8 && c < 12 && (c - 8) % ISTEP == 0 && (c - 8) / ISTEP < LOADS) {
@@ -458,7 +476,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
 #pragma unroll
         for (int rep = 0; rep < 2; ++rep) {
             read_entries(l_g);
-            static_for<LOADS>([&](auto U) { prepare_row(lcur.st, l_t, l_g, U); });
+            static_for<LOADS>([&](auto U) { prepare_row(lcur.st, lcur.de, lcur.i0 + TP > lcur.de, l_t, l_g, U); });
             issue_meta_after_cursor();
             static_for<LOADS>([&](auto U) { issue_row(l_g, U); });
             advance_cursor();
@@ -487,6 +505,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     st = cseg.st;
     n_tiles = cseg.n_tiles;
     fullb = full_blocks(st, pw, p.n);
+    if (DOCS && pw + 31 >= cseg.de) fullb = no_full_blocks();
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -554,10 +573,10 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
-template <int D>
+template <int D, bool DOCS>
 int launch_fwd(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
-               const int32_t *sep_idx, const int32_t *sep_prefix, uint16_t *O, float *LSE,
-               hipStream_t st) {
+               const int32_t *sep_idx, const int32_t *sep_prefix, const int32_t *doc_start, const int32_t *doc_end,
+               uint16_t *O, float *LSE, hipStream_t st) {
     int G = p.Hq / p.Hkv;
     int GP = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
     int TP = 32 * 8 / GP;
@@ -571,11 +590,11 @@ int launch_fwd(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
     dim3 grid((unsigned)(n_groups * wpg)), block(512);
     ProfScope prof(SEPATTN_K_FORWARD, st);
     if (GP == 4)
-        hipLaunchKernelGGL((fwd_bf16_kernel<D, 4>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, O, LSE, wpg);
+        hipLaunchKernelGGL((fwd_bf16_kernel<D, 4, DOCS>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, doc_start, doc_end, O, LSE, wpg);
     else if (GP == 2)
-        hipLaunchKernelGGL((fwd_bf16_kernel<D, 2>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, O, LSE, wpg);
+        hipLaunchKernelGGL((fwd_bf16_kernel<D, 2, DOCS>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, doc_start, doc_end, O, LSE, wpg);
     else
-        hipLaunchKernelGGL((fwd_bf16_kernel<D, 1>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, O, LSE, wpg);
+        hipLaunchKernelGGL((fwd_bf16_kernel<D, 1, DOCS>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, doc_start, doc_end, O, LSE, wpg);
     return launch_status();
 }
 
@@ -584,13 +603,17 @@ int launch_fwd(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
 size_t forward_bf16_workspace(const sepattn_params &) { return 0; }
 
 int launch_forward_bf16(const sepattn_params &p, const void *Q, const void *K, const void *V,
-                        const int32_t *sep_idx, const int32_t *sep_prefix, void *O, float *LSE,
-                        void *, hipStream_t st) {
+                        const int32_t *sep_idx, const int32_t *sep_prefix, const int32_t *doc_start,
+                        const int32_t *doc_end, void *O, float *LSE, void *, hipStream_t st) {
     auto q = static_cast<const uint16_t *>(Q), k = static_cast<const uint16_t *>(K),
          v = static_cast<const uint16_t *>(V);
     auto o = static_cast<uint16_t *>(O);
-    if (p.d == 64) return launch_fwd<64>(p, q, k, v, sep_idx, sep_prefix, o, LSE, st);
-    return launch_fwd<128>(p, q, k, v, sep_idx, sep_prefix, o, LSE, st);
+    if (doc_start) {
+        if (p.d == 64) return launch_fwd<64, true>(p, q, k, v, sep_idx, sep_prefix, doc_start, doc_end, o, LSE, st);
+        return launch_fwd<128, true>(p, q, k, v, sep_idx, sep_prefix, doc_start, doc_end, o, LSE, st);
+    }
+    if (p.d == 64) return launch_fwd<64, false>(p, q, k, v, sep_idx, sep_prefix, nullptr, nullptr, o, LSE, st);
+    return launch_fwd<128, false>(p, q, k, v, sep_idx, sep_prefix, nullptr, nullptr, o, LSE, st);
 }
 
 }  // namespace sepattn

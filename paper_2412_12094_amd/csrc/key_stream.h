@@ -50,6 +50,23 @@ __device__ inline Stream make_stream(const sepattn_params &p, const int32_t *__r
     return st;
 }
 
+// Packed documents: the row holds several documents and a query sees nothing outside its own.  The
+// first tokens of every document are marked like separators beforehand (the kernels then run with
+// a = 0), so the keys of the first row's document that are older than its window are still one
+// contiguous range of the compacted list, now starting at that document's first position `ds`; the
+// band starts no earlier than `ds`.  Rows of later documents in the same tile find all their keys in
+// the band part; who sees what is decided by the per-key range [lo, hi] with hi cut at the end of
+// the key's document.
+__device__ inline Stream make_stream_docs(const sepattn_params &p, const int32_t *__restrict__ prefix, int i0,
+                                          int tile_positions, int ds) {
+    Stream st;
+    st.bs = max(ds, i0 - p.n + 1);
+    st.n_init = 0;
+    st.sep_lo = prefix[ds];
+    st.n_dense = prefix[st.bs] - st.sep_lo;
+    st.n_total = st.n_dense + (min(p.L, i0 + tile_positions) - st.bs);
+    return st;
+}
 // key position of stream element k, and the query range [lo, hi] that sees it
 __device__ inline int stream_key(const Stream &s, int k, const sepattn_params &p,
                                  const int32_t *__restrict__ idx, const int32_t *__restrict__ prefix,
@@ -103,6 +120,14 @@ __device__ inline FullBlocks full_blocks(const Stream &st, int pw, int n) {
     f.dense_last = st.n_dense - 32;
     f.band_first = max(st.n_dense, st.n_dense + (pmax - n + 1) - st.bs);  // jmin + n - 1 >= pmax
     f.band_last = min(st.n_dense + (pw - 31) - st.bs, st.n_total - 32);   // jmax <= pw, no padding
+    return f;
+}
+// no block of the tile is free of the mask test (a wave whose rows reach into the next document)
+__device__ inline FullBlocks no_full_blocks() {
+    FullBlocks f;
+    f.dense_last = -(1 << 30);
+    f.band_first = 1 << 30;
+    f.band_last = -1;
     return f;
 }
 __device__ inline bool block_is_full(const FullBlocks &f, int k0) {

@@ -580,6 +580,94 @@ def test_fill_from_prefill_rejects_a_window_that_does_not_fit(sp):
 
 
 # ----------------------------------------------------------------------------------------------
+# packed documents
+# ----------------------------------------------------------------------------------------------
+def random_cu(rng, L, n_docs):
+    cuts = np.sort(rng.choice(np.arange(1, L), size=n_docs - 1, replace=False)) if n_docs > 1 else np.array([], dtype=np.int64)
+    return np.concatenate([[0], cuts, [L]]).astype(np.int32)
+
+
+def packed_index(sp, tok, cus, a):
+    """Marker bitmap with the documents' initial tokens, document bounds and the compacted index, on the GPU."""
+    B, L = tok.shape
+    is_sep = sp.sepattn_mark_separators(dev(tok.astype(np.int32)), wl.SEPARATOR_IDS.tolist())
+    ds = torch.empty((B, L), dtype=torch.int32, device="cuda")
+    de = torch.empty_like(ds)
+    for b in range(B):
+        sp.sepattn_doc_bounds(dev(cus[b]), L, a, is_sep[b], out=(ds[b], de[b]))
+    idx, cnt, pre = sp.sepattn_compact_indices(is_sep)
+    return is_sep, ds, de, idx, cnt, pre
+
+
+PACKED_CASES = [
+    # B, Hq, Hkv, L, d, a, n, p, documents per row
+    (1, 4, 2, 700, 128, 3, 64, 0.1, [[0, 64, 128, 333, 700]]),            # boundaries on and off tile borders
+    (2, 8, 2, 1100, 128, 4, 256, 0.08, [[0, 1100], [0, 1, 2, 40, 41, 900, 1100]]),  # one document; tiny ones
+    (1, 2, 2, 520, 64, 2, 16, 0.2, None),                                 # many random documents
+    (1, 4, 1, 1500, 128, 4, 100, 0.08, [[0, 290, 1310, 1500]]),           # a document of many tiles
+    (1, 2, 1, 300, 64, 5, 1000, 0.1, [[0, 100, 101, 300]]),               # n beyond every document: full causal inside
+]
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,L,d,a,n,p,cus", PACKED_CASES)
+def test_doc_bounds_and_forward_packed_match_oracle(sp, B, Hq, Hkv, L, d, a, n, p, cus):
+    rng = np.random.default_rng(L + n)
+    if cus is None:
+        cus = [random_cu(rng, L, 23) for _ in range(B)]
+    cus = [np.asarray(c, dtype=np.int32) for c in cus]
+    tok, Q, K, V, _ = make_case(B, Hq, Hkv, L, d, p, "bf16", 300 + L)
+    is_sep, ds, de, idx, cnt, pre = packed_index(sp, tok, cus, a)
+    flags = oracle.mark_separators(tok, wl.SEPARATOR_IDS)
+    for b in range(B):
+        rs, re_ = oracle.doc_bounds(cus[b], L)
+        assert np.array_equal(host(ds[b]), rs) and np.array_equal(host(de[b]), re_)
+        assert np.array_equal(host(is_sep[b]), oracle.mark_doc_initial(flags[b:b + 1], rs[None], a)[0])
+    scale = 1.0 / math.sqrt(d)
+    O, LSE = sp.sepattn_forward_packed(dev(Q, "bf16"), dev(K, "bf16"), dev(V, "bf16"), ds, de, idx, cnt, pre, n, scale)
+    torch.cuda.synchronize()
+    rO, rL = oracle.forward_packed(Q, K, V, flags, cus, a, n, scale)
+    assert np.isfinite(host(O)).all()
+    assert_close(host(O), rO, "bf16", "O")
+    assert np.abs(host(LSE) - rL).max() <= LSE_TOL["bf16"]
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,L,d,a,n,p,cus", PACKED_CASES + [
+    (1, 8, 2, 2300, 128, 4, 64, 0.15, None),   # several list tiles, documents that end inside them
+])
+def test_backward_packed_matches_oracle(sp, B, Hq, Hkv, L, d, a, n, p, cus):
+    rng = np.random.default_rng(L + n + 1)
+    if cus is None:
+        cus = [random_cu(rng, L, 9 if L > 2000 else 23) for _ in range(B)]
+    cus = [np.asarray(c, dtype=np.int32) for c in cus]
+    tok, Q, K, V, dO = make_case(B, Hq, Hkv, L, d, p, "bf16", 400 + L)
+    is_sep, ds, de, idx, cnt, pre = packed_index(sp, tok, cus, a)
+    flags = oracle.mark_separators(tok, wl.SEPARATOR_IDS)
+    scale = 1.0 / math.sqrt(d)
+    q, k, v, do = (dev(x, "bf16") for x in (Q, K, V, dO))
+    O, LSE = sp.sepattn_forward_packed(q, k, v, ds, de, idx, cnt, pre, n, scale)
+    dQ, dK, dV = sp.sepattn_backward_packed(q, k, v, O, LSE, do, ds, de, idx, cnt, pre, n, scale)
+    torch.cuda.synchronize()
+    rQ, rK, rV = oracle.backward_packed(Q, K, V, dO, flags, cus, a, n, scale)
+    for name, got, ref in (("dQ", dQ, rQ), ("dK", dK, rK), ("dV", dV, rV)):
+        g = host(got)
+        assert np.isfinite(g).all(), name
+        assert_close(g, ref, "bf16", name)
+
+
+def test_packed_calls_need_a_zero(sp):
+    tok, Q, K, V, dO = make_case(1, 2, 2, 64, 64, 0.1, "bf16", 1)
+    is_sep, ds, de, idx, cnt, pre = packed_index(sp, tok, [np.array([0, 64], dtype=np.int32)], 2)
+    import ctypes
+    from paper_2412_12094_amd import binding as bd
+    q, k, v = (dev(x, "bf16") for x in (Q, K, V))
+    p = bd._attn_params(q, k, 3, 8, 0.125, idx.shape[1])   # a = 3: refused
+    O, LSE = torch.empty_like(q), torch.empty(q.shape[:3], dtype=torch.float32, device="cuda")
+    rc = bd.load().sepattn_forward_packed(ctypes.byref(p), bd._ptr(ds), bd._ptr(de), bd._ptr(q), bd._ptr(k), bd._ptr(v),
+                                          bd._ptr(idx), bd._ptr(cnt), bd._ptr(pre), bd._ptr(O), bd._ptr(LSE), None, 0, None)
+    assert rc == 3
+
+
+# ----------------------------------------------------------------------------------------------
 # positions within the cache (rotary encoding applied inside the decode) and the append step
 # ----------------------------------------------------------------------------------------------
 # A bf16 score here carries two more roundings than the plain decode: the turned key row and the

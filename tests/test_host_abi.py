@@ -127,8 +127,8 @@ def test_profile_hook_argument_checks(sp):
     n = ctypes.c_int(0)
     ms = (ctypes.c_float * 4)()
     assert lib.sepattn_profile_end(ms, ctypes.byref(n)) == 3  # not started
-    names = {sp.sepattn_kernel_name(k) for k in range(15)}
-    assert len(names) == 15 and sp.sepattn_kernel_name(15) == "unknown"
+    names = {sp.sepattn_kernel_name(k) for k in range(16)}
+    assert len(names) == 16 and sp.sepattn_kernel_name(16) == "unknown"
 
 
 def test_binding_refuses_cpu_tensors(sp):

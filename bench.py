@@ -194,6 +194,33 @@ def main() -> int:
         "roofline": roofline,
     }
 
+    # the same tensors as one row packed from eight documents (every document a sequence of its own)
+    cu_host = np.array([0, 700, 1900, 2100, 3800, 4600, 6500, 7300, c.L], dtype=np.int32)
+    cu = torch.from_numpy(cu_host).cuda()
+    ds = torch.empty((c.B, c.L), dtype=torch.int32, device=dev)
+    de = torch.empty_like(ds)
+
+    def packed_step():
+        sp.sepattn_mark_separators(tok, sep_ids, out=is_sep)
+        sp.sepattn_doc_bounds(cu, c.L, c.a, is_sep[0], out=(ds[0], de[0]))
+        sp.sepattn_compact_indices(is_sep, out=(idx, cnt, pre), ws=cws)
+        sp.sepattn_forward_packed(Q, K, V, ds, de, idx, cnt, pre, c.n, c.scale, out=(O, LSE), ws=fws)
+        sp.sepattn_backward_packed(Q, K, V, O, LSE, dO, ds, de, idx, cnt, pre, c.n, c.scale, out=(dQ, dK, dV), ws=bws)
+
+    for _ in range(10):
+        packed_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(50):
+        packed_step()
+    torch.cuda.synchronize()
+    packed_ms = 1e3 * (time.perf_counter() - t0) / 50
+    packed_pairs = sum(count_visible_pairs(flags[0][s_:e_], c.a, c.n) for s_, e_ in zip(cu_host[:-1], cu_host[1:]))
+    out["packed"] = {"workload": "the cfg3 row packed from 8 documents of 200 to 1900 tokens; mark + document bounds + "
+                                 "compact + forward + backward per step",
+                     "ms_per_step": round(packed_ms, 4), "visible_pairs_per_head": int(packed_pairs),
+                     "tflops": round(14.0 * c.d * packed_pairs * c.Hq / (packed_ms * 1e-3) / 1e12, 2)}
+
     if not args.no_decode:
         out["decode"] = bench_decode(torch, sp, wl, args.ramp_seconds)
     if not args.no_cpu_baseline:

@@ -654,6 +654,36 @@ def test_backward_packed_matches_oracle(sp, B, Hq, Hkv, L, d, a, n, p, cus):
         assert_close(g, ref, "bf16", name)
 
 
+def test_packed_config3_one_kv_group_at_full_size_and_reproducible(sp):
+    """The cfg3 tensors as one row packed from the eight documents bench.py uses, in the launch
+    configuration it times; the oracle runs on KV head 2 and its four query heads.  A second run must
+    give the same bits (no atomics anywhere)."""
+    c = wl.CONFIGS["cfg3"]
+    inp = wl.config_inputs(c)
+    cus = [np.array([0, 700, 1900, 2100, 3800, 4600, 6500, 7300, c.L], dtype=np.int32)]
+    is_sep, ds, de, idx, cnt, pre = packed_index(sp, inp["token_ids"], cus, c.a)
+    flags = oracle.mark_separators(inp["token_ids"], wl.SEPARATOR_IDS)
+    q, k, v, do = (dev(inp[x], "bf16") for x in ("Q", "K", "V", "dO"))
+    O, LSE = sp.sepattn_forward_packed(q, k, v, ds, de, idx, cnt, pre, c.n, c.scale)
+    dQ, dK, dV = sp.sepattn_backward_packed(q, k, v, O, LSE, do, ds, de, idx, cnt, pre, c.n, c.scale)
+    O2, LSE2 = sp.sepattn_forward_packed(q, k, v, ds, de, idx, cnt, pre, c.n, c.scale)
+    g2 = sp.sepattn_backward_packed(q, k, v, O2, LSE2, do, ds, de, idx, cnt, pre, c.n, c.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(O, O2) and torch.equal(LSE, LSE2)
+    assert all(torch.equal(x, y) for x, y in zip((dQ, dK, dV), g2))
+    kv, G = 2, c.Hq // c.Hkv
+    hs = slice(kv * G, (kv + 1) * G)
+    sub = lambda x, h: inp[x][:, h]
+    rO, rL = oracle.forward_packed(sub("Q", hs), inp["K"][:, kv:kv + 1], inp["V"][:, kv:kv + 1], flags, cus, c.a, c.n, c.scale)
+    rQ, rK, rV = oracle.backward_packed(sub("Q", hs), inp["K"][:, kv:kv + 1], inp["V"][:, kv:kv + 1], sub("dO", hs),
+                                        flags, cus, c.a, c.n, c.scale)
+    assert_close(host(O[:, hs]), rO, "bf16", "O")
+    assert np.abs(host(LSE[:, hs]) - rL).max() <= LSE_TOL["bf16"]
+    assert_close(host(dQ[:, hs]), rQ, "bf16", "dQ")
+    assert_close(host(dK[:, kv:kv + 1]), rK, "bf16", "dK")
+    assert_close(host(dV[:, kv:kv + 1]), rV, "bf16", "dV")
+
+
 def test_packed_calls_need_a_zero(sp):
     tok, Q, K, V, dO = make_case(1, 2, 2, 64, 64, 0.1, "bf16", 1)
     is_sep, ds, de, idx, cnt, pre = packed_index(sp, tok, [np.array([0, 64], dtype=np.int32)], 2)

@@ -142,7 +142,7 @@ int sepattn_backward(const sepattn_params *p, const void *Q, const void *K, cons
 /* ------------------------------------------------------------------------------------------
  * Packed documents (training batches packed from several documents; the paper is silent on them:
  * every document is taken as a sequence of its own, i.e. Eq. 1 / Eq. 2 per document: its first a
- * tokens are its initial tokens and a query sees no key outside its document).  bf16 only.
+ * tokens are its initial tokens and a query sees no key outside its document).
  *
  * Preparation, per row of the batch: sepattn_doc_bounds turns the cumulative lengths into the two
  * per-position bounds and marks the first a tokens of every document in the row's marker bitmap;

@@ -294,7 +294,7 @@ def sepattn_doc_bounds(cu_seqlens: torch.Tensor, L: int, a: int = 0, is_sep_row:
 
 def sepattn_forward_packed(Q, K, V, doc_start, doc_end, sep_idx, sep_count, sep_prefix, n: int, scale: float,
                            out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None, ws: Optional[torch.Tensor] = None):
-    """Forward over rows of packed documents (bf16): doc_start, doc_end int32 [B,L] per-position bounds;
+    """Forward over rows of packed documents: doc_start, doc_end int32 [B,L] per-position bounds;
     the index arrays come from a bitmap in which every document's initial tokens are marked (a = 0 here)."""
     _dev(Q, K, V, doc_start, doc_end, sep_idx, sep_count, sep_prefix)
     assert doc_start.dtype == torch.int32 and doc_end.dtype == torch.int32
@@ -342,7 +342,7 @@ def sepattn_backward(Q, K, V, O, LSE, dO, sep_idx, sep_count, sep_prefix, a: int
 
 def sepattn_backward_packed(Q, K, V, O, LSE, dO, doc_start, doc_end, sep_idx, sep_count, sep_prefix, n: int,
                             scale: float, out=None, ws: Optional[torch.Tensor] = None):
-    """Backward over rows of packed documents (bf16) -> (dQ, dK, dV); arguments as sepattn_forward_packed."""
+    """Backward over rows of packed documents -> (dQ, dK, dV); arguments as sepattn_forward_packed."""
     _dev(Q, K, V, O, LSE, dO, doc_start, doc_end, sep_idx, sep_count, sep_prefix)
     assert doc_start.dtype == torch.int32 and doc_end.dtype == torch.int32
     assert tuple(doc_start.shape) == (Q.shape[0], Q.shape[2]) and doc_end.shape == doc_start.shape

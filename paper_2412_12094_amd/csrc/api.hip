@@ -214,7 +214,7 @@ int sepattn_forward(const sepattn_params *p, const void *Q, const void *K, const
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (q.dtype == SEPATTN_FP32)
         return launch_forward_fp32(q, (const float *)Q, (const float *)K, (const float *)V, sep_idx,
-                                   sep_prefix, (float *)O, LSE, st);
+                                   sep_prefix, nullptr, (float *)O, LSE, st);
     return launch_forward_bf16(q, Q, K, V, sep_idx, sep_prefix, nullptr, nullptr, O, LSE, ws, st);
 }
 
@@ -232,13 +232,15 @@ int sepattn_forward_packed(const sepattn_params *p, const int32_t *doc_start, co
                            size_t ws_bytes, void *stream) {
     int rc = check_attn(p);
     if (rc != SEPATTN_OK) return rc;
-    if (p->dtype != SEPATTN_BF16) return SEPATTN_ERR_DTYPE;
     if (p->a != 0) return SEPATTN_ERR_PARAM;  // the documents' initial tokens are in the marker bitmap
     if (!doc_start || !doc_end || !Q || !K || !V || !sep_idx || !sep_count || !sep_prefix || !O || !LSE)
         return SEPATTN_ERR_NULL;
     if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16)) return SEPATTN_ERR_PARAM;
     size_t need = sepattn_forward_workspace_bytes(p);
     if (need > 0 && (!ws || ws_bytes < need || !aligned(ws, 256))) return SEPATTN_ERR_WORKSPACE;
+    if (p->dtype == SEPATTN_FP32)
+        return launch_forward_fp32(normalised(p), (const float *)Q, (const float *)K, (const float *)V, sep_idx,
+                                   sep_prefix, doc_start, (float *)O, LSE, static_cast<hipStream_t>(stream));
     return launch_forward_bf16(normalised(p), Q, K, V, sep_idx, sep_prefix, doc_start, doc_end, O, LSE, ws,
                                static_cast<hipStream_t>(stream));
 }
@@ -266,7 +268,7 @@ int sepattn_backward(const sepattn_params *p, const void *Q, const void *K, cons
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (q.dtype == SEPATTN_FP32)
         return launch_backward_fp32(q, (const float *)Q, (const float *)K, (const float *)V,
-                                    (const float *)O, LSE, (const float *)dO, sep_idx, sep_prefix,
+                                    (const float *)O, LSE, (const float *)dO, sep_idx, sep_prefix, nullptr, nullptr,
                                     (float *)dQ, (float *)dK, (float *)dV, (float *)ws, st);
     return launch_backward_bf16(q, Q, K, V, O, LSE, dO, sep_idx, sep_count, sep_prefix, nullptr, nullptr, dQ, dK, dV,
                                 ws, st);
@@ -279,7 +281,6 @@ int sepattn_backward_packed(const sepattn_params *p, const int32_t *doc_start, c
                             void *stream) {
     int rc = check_attn(p);
     if (rc != SEPATTN_OK) return rc;
-    if (p->dtype != SEPATTN_BF16) return SEPATTN_ERR_DTYPE;
     if (p->a != 0) return SEPATTN_ERR_PARAM;  // the documents' initial tokens are in the marker bitmap
     if (!doc_start || !doc_end || !Q || !K || !V || !O || !LSE || !dO || !sep_idx || !sep_count || !sep_prefix ||
         !dQ || !dK || !dV)
@@ -289,6 +290,11 @@ int sepattn_backward_packed(const sepattn_params *p, const int32_t *doc_start, c
         return SEPATTN_ERR_PARAM;
     size_t need = sepattn_backward_workspace_bytes(p);
     if (!ws || ws_bytes < need || !aligned(ws, 256)) return SEPATTN_ERR_WORKSPACE;
+    if (p->dtype == SEPATTN_FP32)
+        return launch_backward_fp32(normalised(p), (const float *)Q, (const float *)K, (const float *)V,
+                                    (const float *)O, LSE, (const float *)dO, sep_idx, sep_prefix, doc_start, doc_end,
+                                    (float *)dQ, (float *)dK, (float *)dV, (float *)ws,
+                                    static_cast<hipStream_t>(stream));
     return launch_backward_bf16(normalised(p), Q, K, V, O, LSE, dO, sep_idx, sep_count, sep_prefix, doc_start,
                                 doc_end, dQ, dK, dV, ws, static_cast<hipStream_t>(stream));
 }

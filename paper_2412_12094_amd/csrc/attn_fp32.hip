@@ -10,6 +10,9 @@
 // so every visible pair is visited exactly once and no mask test is needed.
 // Key j is seen by the contiguous query range [j, j+n) and, if it is an initial token or a
 // separator, by every later query as well.
+// Packed documents (doc_start / doc_end given, per position; the documents' initial tokens are
+// marked in the bitmap and a = 0): the three ranges of a row start at its document's first position
+// instead of 0, and a key's query range ends with its document.
 #include "common.h"
 
 namespace sepattn {
@@ -41,14 +44,16 @@ __device__ inline float wave_sum(float v) {
 }
 
 struct RowKeys {
-    int n_init, n_sep, sep_lo, ws, total;
+    int n_init, n_sep, sep_lo, ws, total, ds;
 };
 
-__device__ inline RowKeys row_keys(int i, int a, int n, const int32_t *__restrict__ prefix) {
+// ds: first position of the row's document (0 without packing)
+__device__ inline RowKeys row_keys(int i, int a, int n, const int32_t *__restrict__ prefix, int ds) {
     RowKeys r;
-    r.ws = max(0, i - n + 1);
-    r.n_init = min(a, r.ws);
-    r.sep_lo = prefix[r.n_init];
+    r.ds = ds;
+    r.ws = max(ds, i - n + 1);
+    r.n_init = min(a, r.ws - ds);
+    r.sep_lo = prefix[ds + r.n_init];
     r.n_sep = prefix[r.ws] - r.sep_lo;
     r.total = r.n_init + r.n_sep + (i - r.ws + 1);
     return r;
@@ -57,7 +62,7 @@ __device__ inline RowKeys row_keys(int i, int a, int n, const int32_t *__restric
 // cap and L bound the index read and the position it yields, so that a caller breaking
 // sep_count <= cap (stale list tail) gets wrong numbers rather than a fault
 __device__ inline int key_at(const RowKeys &r, int t, const int32_t *__restrict__ sep_idx, int cap, int L) {
-    if (t < r.n_init) return t;
+    if (t < r.n_init) return r.ds + t;
     if (t < r.n_init + r.n_sep)
         return min(max(sep_idx[min(r.sep_lo + t - r.n_init, cap - 1)], 0), L - 1);
     return r.ws + (t - r.n_init - r.n_sep);
@@ -70,6 +75,7 @@ __global__ __launch_bounds__(256) void fwd_fp32_kernel(sepattn_params p, const f
                                                        const float *__restrict__ V,
                                                        const int32_t *__restrict__ sep_idx,
                                                        const int32_t *__restrict__ sep_prefix,
+                                                       const int32_t *__restrict__ doc_start,
                                                        float *__restrict__ O, float *__restrict__ LSE) {
     constexpr int R = D / kWave;  // output values per lane
     int lane = threadIdx.x % kWave;
@@ -85,7 +91,8 @@ __global__ __launch_bounds__(256) void fwd_fp32_kernel(sepattn_params p, const f
     const float *Vh = V + ((long)b * p.Hkv + kv) * (long)p.L * D;
     const int32_t *prefix = sep_prefix + (long)b * (p.L + 1);
     const int32_t *idx = sep_idx + (long)b * p.cap;
-    RowKeys rk = row_keys(i, p.a, p.n, prefix);
+    // (the clamp keeps inconsistent bounds from faulting)
+    RowKeys rk = row_keys(i, p.a, p.n, prefix, doc_start ? min(max(doc_start[(long)b * p.L + i], 0), i) : 0);
 
     float m = -INFINITY, l = 0.f;
     float acc[R];
@@ -135,6 +142,7 @@ __global__ __launch_bounds__(256) void dq_fp32_kernel(sepattn_params p, const fl
                                                       const float *__restrict__ Drow,
                                                       const int32_t *__restrict__ sep_idx,
                                                       const int32_t *__restrict__ sep_prefix,
+                                                      const int32_t *__restrict__ doc_start,
                                                       float *__restrict__ dQ) {
     constexpr int R = D / kWave;
     int lane = threadIdx.x % kWave;
@@ -151,7 +159,8 @@ __global__ __launch_bounds__(256) void dq_fp32_kernel(sepattn_params p, const fl
     const float *Vh = V + ((long)b * p.Hkv + kv) * (long)p.L * D;
     const int32_t *prefix = sep_prefix + (long)b * (p.L + 1);
     const int32_t *idx = sep_idx + (long)b * p.cap;
-    RowKeys rk = row_keys(i, p.a, p.n, prefix);
+    // (the clamp keeps inconsistent bounds from faulting)
+    RowKeys rk = row_keys(i, p.a, p.n, prefix, doc_start ? min(max(doc_start[(long)b * p.L + i], 0), i) : 0);
     float lse = LSE[row], Di = Drow[row];
     float acc[R];
     for (int r = 0; r < R; ++r) acc[r] = 0.f;
@@ -186,6 +195,7 @@ __global__ __launch_bounds__(256) void dkv_fp32_kernel(sepattn_params p, const f
                                                        const float *__restrict__ dO,
                                                        const float *__restrict__ Drow,
                                                        const int32_t *__restrict__ sep_prefix,
+                                                       const int32_t *__restrict__ doc_end,
                                                        float *__restrict__ dK, float *__restrict__ dV) {
     constexpr int R = D / kWave;
     int lane = threadIdx.x % kWave;
@@ -199,6 +209,7 @@ __global__ __launch_bounds__(256) void dkv_fp32_kernel(sepattn_params p, const f
     const int32_t *prefix = sep_prefix + (long)b * (p.L + 1);
     bool always = (j < p.a) || (prefix[j + 1] != prefix[j]);
     long i_end_l = always ? (long)p.L : min((long)p.L, (long)j + p.n);
+    if (doc_end) i_end_l = min(i_end_l, (long)doc_end[(long)b * p.L + j]);
     int i_end = (int)i_end_l;
     const float *kj = K + row * D;
     const float *vj = V + row * D;
@@ -241,31 +252,31 @@ unsigned blocks_for_rows(long n_rows) { return (unsigned)((n_rows + 3) / 4); }
 }  // namespace
 
 int launch_forward_fp32(const sepattn_params &p, const float *Q, const float *K, const float *V,
-                        const int32_t *sep_idx, const int32_t *sep_prefix, float *O, float *LSE,
-                        hipStream_t st) {
+                        const int32_t *sep_idx, const int32_t *sep_prefix, const int32_t *doc_start, float *O,
+                        float *LSE, hipStream_t st) {
     long n_rows = (long)p.B * p.Hq * p.L;
     dim3 grid(blocks_for_rows(n_rows)), block(256);
     if (p.d == 64)
-        hipLaunchKernelGGL(fwd_fp32_kernel<64>, grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, O, LSE);
+        hipLaunchKernelGGL(fwd_fp32_kernel<64>, grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, doc_start, O, LSE);
     else
-        hipLaunchKernelGGL(fwd_fp32_kernel<128>, grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, O, LSE);
+        hipLaunchKernelGGL(fwd_fp32_kernel<128>, grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, doc_start, O, LSE);
     return launch_status();
 }
 
 int launch_backward_fp32(const sepattn_params &p, const float *Q, const float *K, const float *V,
                          const float *O, const float *LSE, const float *dO, const int32_t *sep_idx,
-                         const int32_t *sep_prefix, float *dQ, float *dK, float *dV, float *Dws,
-                         hipStream_t st) {
+                         const int32_t *sep_prefix, const int32_t *doc_start, const int32_t *doc_end, float *dQ,
+                         float *dK, float *dV, float *Dws, hipStream_t st) {
     long q_rows = (long)p.B * p.Hq * p.L, k_rows = (long)p.B * p.Hkv * p.L;
     dim3 block(256);
     if (p.d == 64) {
         hipLaunchKernelGGL(rowdot_fp32_kernel<64>, dim3(blocks_for_rows(q_rows)), block, 0, st, q_rows, dO, O, Dws);
-        hipLaunchKernelGGL(dq_fp32_kernel<64>, dim3(blocks_for_rows(q_rows)), block, 0, st, p, Q, K, V, LSE, dO, Dws, sep_idx, sep_prefix, dQ);
-        hipLaunchKernelGGL(dkv_fp32_kernel<64>, dim3(blocks_for_rows(k_rows)), block, 0, st, p, Q, K, V, LSE, dO, Dws, sep_prefix, dK, dV);
+        hipLaunchKernelGGL(dq_fp32_kernel<64>, dim3(blocks_for_rows(q_rows)), block, 0, st, p, Q, K, V, LSE, dO, Dws, sep_idx, sep_prefix, doc_start, dQ);
+        hipLaunchKernelGGL(dkv_fp32_kernel<64>, dim3(blocks_for_rows(k_rows)), block, 0, st, p, Q, K, V, LSE, dO, Dws, sep_prefix, doc_end, dK, dV);
     } else {
         hipLaunchKernelGGL(rowdot_fp32_kernel<128>, dim3(blocks_for_rows(q_rows)), block, 0, st, q_rows, dO, O, Dws);
-        hipLaunchKernelGGL(dq_fp32_kernel<128>, dim3(blocks_for_rows(q_rows)), block, 0, st, p, Q, K, V, LSE, dO, Dws, sep_idx, sep_prefix, dQ);
-        hipLaunchKernelGGL(dkv_fp32_kernel<128>, dim3(blocks_for_rows(k_rows)), block, 0, st, p, Q, K, V, LSE, dO, Dws, sep_prefix, dK, dV);
+        hipLaunchKernelGGL(dq_fp32_kernel<128>, dim3(blocks_for_rows(q_rows)), block, 0, st, p, Q, K, V, LSE, dO, Dws, sep_idx, sep_prefix, doc_start, dQ);
+        hipLaunchKernelGGL(dkv_fp32_kernel<128>, dim3(blocks_for_rows(k_rows)), block, 0, st, p, Q, K, V, LSE, dO, Dws, sep_prefix, doc_end, dK, dV);
     }
     return launch_status();
 }

@@ -51,13 +51,14 @@ int launch_compact(const uint8_t *is_sep, int B, int L, int32_t *sep_idx, int ca
                    int32_t *sep_count, int32_t *sep_prefix, int32_t *chunk_counts, hipStream_t st);
 
 // ---- fp32 debug path ---------------------------------------------------------------------------
+// doc_start / doc_end: packed documents (per-position bounds [B, L]), or nullptr
 int launch_forward_fp32(const sepattn_params &p, const float *Q, const float *K, const float *V,
-                        const int32_t *sep_idx, const int32_t *sep_prefix, float *O, float *LSE,
-                        hipStream_t st);
+                        const int32_t *sep_idx, const int32_t *sep_prefix, const int32_t *doc_start, float *O,
+                        float *LSE, hipStream_t st);
 int launch_backward_fp32(const sepattn_params &p, const float *Q, const float *K, const float *V,
                          const float *O, const float *LSE, const float *dO, const int32_t *sep_idx,
-                         const int32_t *sep_prefix, float *dQ, float *dK, float *dV, float *Dws,
-                         hipStream_t st);
+                         const int32_t *sep_prefix, const int32_t *doc_start, const int32_t *doc_end, float *dQ,
+                         float *dK, float *dV, float *Dws, hipStream_t st);
 
 // ---- bf16 MFMA path ----------------------------------------------------------------------------
 size_t forward_bf16_workspace(const sepattn_params &p);

@@ -609,13 +609,14 @@ PACKED_CASES = [
 ]
 
 
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 @pytest.mark.parametrize("B,Hq,Hkv,L,d,a,n,p,cus", PACKED_CASES)
-def test_doc_bounds_and_forward_packed_match_oracle(sp, B, Hq, Hkv, L, d, a, n, p, cus):
+def test_doc_bounds_and_forward_packed_match_oracle(sp, dtype, B, Hq, Hkv, L, d, a, n, p, cus):
     rng = np.random.default_rng(L + n)
     if cus is None:
         cus = [random_cu(rng, L, 23) for _ in range(B)]
     cus = [np.asarray(c, dtype=np.int32) for c in cus]
-    tok, Q, K, V, _ = make_case(B, Hq, Hkv, L, d, p, "bf16", 300 + L)
+    tok, Q, K, V, _ = make_case(B, Hq, Hkv, L, d, p, dtype, 300 + L)
     is_sep, ds, de, idx, cnt, pre = packed_index(sp, tok, cus, a)
     flags = oracle.mark_separators(tok, wl.SEPARATOR_IDS)
     for b in range(B):
@@ -623,27 +624,28 @@ def test_doc_bounds_and_forward_packed_match_oracle(sp, B, Hq, Hkv, L, d, a, n, 
         assert np.array_equal(host(ds[b]), rs) and np.array_equal(host(de[b]), re_)
         assert np.array_equal(host(is_sep[b]), oracle.mark_doc_initial(flags[b:b + 1], rs[None], a)[0])
     scale = 1.0 / math.sqrt(d)
-    O, LSE = sp.sepattn_forward_packed(dev(Q, "bf16"), dev(K, "bf16"), dev(V, "bf16"), ds, de, idx, cnt, pre, n, scale)
+    O, LSE = sp.sepattn_forward_packed(dev(Q, dtype), dev(K, dtype), dev(V, dtype), ds, de, idx, cnt, pre, n, scale)
     torch.cuda.synchronize()
     rO, rL = oracle.forward_packed(Q, K, V, flags, cus, a, n, scale)
     assert np.isfinite(host(O)).all()
-    assert_close(host(O), rO, "bf16", "O")
-    assert np.abs(host(LSE) - rL).max() <= LSE_TOL["bf16"]
+    assert_close(host(O), rO, dtype, "O")
+    assert np.abs(host(LSE) - rL).max() <= LSE_TOL[dtype]
 
 
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 @pytest.mark.parametrize("B,Hq,Hkv,L,d,a,n,p,cus", PACKED_CASES + [
     (1, 8, 2, 2300, 128, 4, 64, 0.15, None),   # several list tiles, documents that end inside them
 ])
-def test_backward_packed_matches_oracle(sp, B, Hq, Hkv, L, d, a, n, p, cus):
+def test_backward_packed_matches_oracle(sp, dtype, B, Hq, Hkv, L, d, a, n, p, cus):
     rng = np.random.default_rng(L + n + 1)
     if cus is None:
         cus = [random_cu(rng, L, 9 if L > 2000 else 23) for _ in range(B)]
     cus = [np.asarray(c, dtype=np.int32) for c in cus]
-    tok, Q, K, V, dO = make_case(B, Hq, Hkv, L, d, p, "bf16", 400 + L)
+    tok, Q, K, V, dO = make_case(B, Hq, Hkv, L, d, p, dtype, 400 + L)
     is_sep, ds, de, idx, cnt, pre = packed_index(sp, tok, cus, a)
     flags = oracle.mark_separators(tok, wl.SEPARATOR_IDS)
     scale = 1.0 / math.sqrt(d)
-    q, k, v, do = (dev(x, "bf16") for x in (Q, K, V, dO))
+    q, k, v, do = (dev(x, dtype) for x in (Q, K, V, dO))
     O, LSE = sp.sepattn_forward_packed(q, k, v, ds, de, idx, cnt, pre, n, scale)
     dQ, dK, dV = sp.sepattn_backward_packed(q, k, v, O, LSE, do, ds, de, idx, cnt, pre, n, scale)
     torch.cuda.synchronize()
@@ -651,7 +653,7 @@ def test_backward_packed_matches_oracle(sp, B, Hq, Hkv, L, d, a, n, p, cus):
     for name, got, ref in (("dQ", dQ, rQ), ("dK", dK, rK), ("dV", dV, rV)):
         g = host(got)
         assert np.isfinite(g).all(), name
-        assert_close(g, ref, "bf16", name)
+        assert_close(g, ref, dtype, name)
 
 
 def test_packed_config3_one_kv_group_at_full_size_and_reproducible(sp):

@@ -6,9 +6,10 @@
  *   - every separator token at or before i                     (Separator Tokens,   Sec. 3.1),
  *   - its n closest tokens  i-n < j <= i                       (Neighboring Tokens, Sec. 3.1),
  * i.e. the binary mask M of Eq. 2, applied as in Eq. 1:  A = Softmax(QK^T/sqrt(d_k) | M), O = A V.
- * The library provides the training / prefill forward and backward of Eq. 1, single-query decode
- * over the four-block KV cache and the cache compression step of Sec. 3.3 ("Tailored Streaming
- * Design").
+ * The library provides the training / prefill forward and backward of Eq. 1 (also over rows packed
+ * from several documents), single-query decode over the four-block KV cache (optionally with the
+ * rotary encoding applied by position within the cache), and the cache steps of Sec. 3.3 ("Tailored
+ * Streaming Design"): hand-over from a prefill, append, compression.
  *
  * Conventions common to every call
  *   - Pointers marked DEVICE address memory of the current HIP device; HOST pointers address

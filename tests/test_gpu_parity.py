@@ -882,6 +882,67 @@ def test_streaming_fill_append_compress_decode_rope(sp):
         assert np.array_equal(host(Fd)[q, :npast + nl], rF[q, :npast + nl])
 
 
+def test_append_fp32_rows(sp):
+    S, Hq, Hkv, d, a, s, w = 2, 4, 2, 64, 1, 3, 2
+    c = a + s + 6
+    rng = np.random.default_rng(5)
+    Kc = rng.standard_normal((S, Hkv, c, d)).astype(np.float32)
+    Vc = rng.standard_normal((S, Hkv, c, d)).astype(np.float32)
+    flags = np.zeros((S, c - a - s), dtype=np.uint8)
+    sizes = np.array([[1, 2, 1, 2], [0, 0, 0, 0]], dtype=np.int32)
+    kn = rng.standard_normal((S, Hkv, d)).astype(np.float32)
+    vn = rng.standard_normal((S, Hkv, d)).astype(np.float32)
+    fn = np.array([1, 1], dtype=np.uint8)
+    rK, rV, rF, rS = oracle.append_token(Kc, Vc, flags, sizes, kn, vn, fn, a, s, w)
+    Kd, Vd, Fd, Sd = dev(Kc), dev(Vc), dev(flags), dev(sizes)
+    sp.sepkv_append(dev(kn), dev(vn), dev(fn), Kd, Vd, Fd, Sd, Hq, a, s, w)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(Sd), rS) and np.array_equal(host(Fd), rF)
+    assert np.array_equal(Kd.cpu().numpy(), rK) and np.array_equal(Vd.cpu().numpy(), rV)
+
+
+def test_training_step_replays_in_a_hip_graph(sp):
+    """mark + compact + forward + backward captured once and replayed: with caller-provided outputs
+    and workspaces nothing in the step allocates or synchronises, and every replay gives the bits of
+    the eager step (the kernels use no atomics)."""
+    B, Hq, Hkv, L, d, a, n, p = 1, 8, 2, 1100, 128, 4, 256, 0.08
+    tok, Q, K, V, dO = make_case(B, Hq, Hkv, L, d, p, "bf16", 61)
+    scale = 1.0 / math.sqrt(d)
+    tk, q, k, v, do = dev(tok.astype(np.int32)), dev(Q, "bf16"), dev(K, "bf16"), dev(V, "bf16"), dev(dO, "bf16")
+    ids = wl.SEPARATOR_IDS.tolist()
+    is_sep = torch.empty((B, L), dtype=torch.uint8, device="cuda")
+    idx = torch.full((B, L), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.empty((B,), dtype=torch.int32, device="cuda")
+    pre = torch.empty((B, L + 1), dtype=torch.int32, device="cuda")
+    cws = torch.empty(4096, dtype=torch.uint8, device="cuda")
+    fws = torch.empty(256, dtype=torch.uint8, device="cuda")
+    bws = torch.empty(sp.sepattn_backward_workspace_bytes(q, k, a, n, scale, L), dtype=torch.uint8, device="cuda")
+    O, LSE = torch.empty_like(q), torch.empty((B, Hq, L), dtype=torch.float32, device="cuda")
+    grads = (torch.empty_like(q), torch.empty_like(k), torch.empty_like(v))
+
+    def step():
+        sp.sepattn_mark_separators(tk, ids, out=is_sep)
+        sp.sepattn_compact_indices(is_sep, out=(idx, cnt, pre), ws=cws)
+        sp.sepattn_forward(q, k, v, idx, cnt, pre, a, n, scale, out=(O, LSE), ws=fws)
+        sp.sepattn_backward(q, k, v, O, LSE, do, idx, cnt, pre, a, n, scale, out=grads, ws=bws)
+
+    step()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (O, LSE) + grads]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        for t in (O, LSE) + grads:
+            t.zero_()
+        graph.replay()
+        checksum = float(O.float().abs().sum())  # eager library work and a synchronisation between replays
+        torch.cuda.synchronize()
+        assert math.isfinite(checksum)
+        for got, ref in zip((O, LSE) + grads, want):
+            assert torch.equal(got, ref), rep
+
+
 def test_generation_step_replays_in_a_hip_graph(sp):
     """A serving loop replays one captured generation step (append, then decode with positions within
     the cache): with caller-provided outputs and workspace the calls allocate nothing and touch the

@@ -171,6 +171,13 @@ def main() -> int:
                 "avg_launch_us": round(1e3 * dom_avg_ms, 2), "launches": len(dom_ms),
                 "algorithmic_gflop_per_launch": round(alg_flops.get(dominant, 0.0) / 1e9, 2)}
 
+    # the other matrix-core kernels of the step, from the untimed per-kernel pass (20 launches each)
+    roofline_other = [{"bound": "mfma", "kernel": sp.sepattn_kernel_name(sp.KERNEL_IDS[k]),
+                       "achieved": round(alg_flops[k] / (per_kernel_us[k] * 1e-6) / 1e12, 2), "peak": PEAK_BF16_TFLOPS,
+                       "unit": "TFLOP/s", "frac": round(alg_flops[k] / (per_kernel_us[k] * 1e-6) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                       "traffic": MEASURED_TRAFFIC_BYTES.get(k)}
+                      for k in alg_flops if k != dominant and per_kernel_us.get(k)]
+
     out = {
         "metric": "SepAttention fwd+bwd effective TFLOP/s (unmasked pairs) @8K",
         "value": round(value, 2),
@@ -192,6 +199,7 @@ def main() -> int:
         "tokens_per_s": round(c.B * c.L / (ms_per_step * 1e-3), 1),
         "kernel_us": {k: round(v, 2) for k, v in per_kernel_us.items()},
         "roofline": roofline,
+        "roofline_other": roofline_other,
     }
 
     # the same tensors as one row packed from eight documents (every document a sequence of its own)

@@ -43,9 +43,9 @@ __device__ inline float bf16_dot8(u32x4 a, u32x4 b) {
 //     dQ^T += K^T dS^T              (8 matrix instructions, K read transposed from the same tile)
 // with the operand fragments requested a few matrix instructions ahead.  K tiles are stored with
 // the XOR permutation that serves both kinds of read (V tiles too, so that one set of per-lane
-// offsets addresses both); three stages
-// each (tile X+2 is requested while tile X is multiplied).  The two waves that share
-// a SIMD drift apart by themselves, so that one wave's exponentials overlap the other's matrix work.
+// offsets addresses both); four stages each (tile X+2 is requested while tile X is multiplied, by
+// the first four waves only).  The two waves that share a SIMD drift apart by themselves, so that
+// one wave's exponentials overlap the other's matrix work.
 // ---------------------------------------------------------------------------------------------
 // DOCS: packed documents, as in the forward kernel (doc_start / doc_end [B, L]; p.a == 0).
 template <int D, int GP, bool DOCS>

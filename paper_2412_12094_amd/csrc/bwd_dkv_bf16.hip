@@ -24,9 +24,10 @@
 //   dS-wave:  dP = dO V^T -> dS = P (dP - D)  -> dK^T += Q^T dS     (holds V rows, dK^T)
 // P travels from the first to the second through a small LDS buffer (same lane, same register:
 // both are 32x32 accumulator layouts), once per block of 32 queries, fenced by the block's
-// workgroup barrier.  Query tiles (64 rows of Q and dO, plus LSE*log2e and D) stream through a ring
-// of three LDS buffers filled by direct global->LDS loads issued two tiles ahead; with the ring the
-// block barriers are the only barriers.  The tiles are stored unpadded with XOR-permuted 16-byte
+// workgroup barrier (P is exchanged in bf16, the form it has in the second contraction anyway).  Query
+// tiles (64 rows of Q and dO, plus LSE*log2e and -D) stream through a ring of four LDS buffers filled
+// by direct global->LDS loads issued as soon as a buffer is free; with the ring the block barriers
+// are the only barriers.  The tiles are stored unpadded with XOR-permuted 16-byte
 // chunks so that both the row-major reads (first contraction) and the transposed reads (second
 // contraction) are free of bank conflicts.  The four query heads of a GQA group are just four times
 // as many query tiles.

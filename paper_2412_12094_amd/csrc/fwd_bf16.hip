@@ -13,8 +13,8 @@
 // Schedule: every wave runs the same software pipeline over blocks of 32 keys; the score block of
 // the next block, the output update of the previous one and the softmax of the current one are
 // interleaved instruction by instruction (the matrix instructions execute while the vector
-// instructions issued after them run), one workgroup barrier per tile.  K tiles live in 3 LDS stages,
-// V tiles and the per-key visibility ranges in 4; tiles are filled by direct global->LDS loads
+// instructions issued after them run), one workgroup barrier per tile.  K tiles, V tiles and the
+// per-key visibility ranges live in 4 LDS stages each; tiles are filled by direct global->LDS loads
 // (global_load_lds_dwordx4, no staging registers) issued two tiles ahead, unpadded with XOR-swizzled
 // 16-byte chunks (see mfma_common.h).  V^T operands are read with ds_read_b64_tr_b16.  A wave drops
 // the mask test on blocks every one of its rows sees in full.  The running maximum is only raised

@@ -7,7 +7,8 @@
 //          2048 tokens: (1) per-chunk separator counts, (2) each chunk sums the counts of the
 //          chunks before it, ranks its own separators with wave ballots + a block prefix sum over
 //          the per-wave counts, and writes prefix / index entries.  No atomics, so the output
-//          order is the position order by construction.
+//          order is the position order by construction.  Sequences of up to 32768 tokens take
+//          one launch: pass (2) then counts the flags of the earlier chunks itself.
 #include "common.h"
 
 namespace sepattn {

@@ -991,6 +991,101 @@ def test_generation_step_replays_in_a_hip_graph(sp):
 
 
 # ----------------------------------------------------------------------------------------------
+# randomized shapes (seeded) and guard bands around every output
+# ----------------------------------------------------------------------------------------------
+def test_random_shapes_forward_backward_fp32(sp):
+    """Seeded random (L, a, n, density, head dimension, head grouping, batch), plain and packed, through
+    the fp32 kernels at 1e-4: edge sizes included by construction of the ranges (n = 1, a = 0, no
+    separators, every token a separator, windows beyond the sequence, single-token documents)."""
+    rng = np.random.default_rng(4711)
+    for case in range(10):
+        d = int(rng.choice([64, 128])); Hkv = int(rng.choice([1, 2])); Hq = Hkv * int(rng.choice([1, 2, 4]))
+        B = int(rng.choice([1, 2])); L = int(rng.integers(1, 700)); a = int(rng.integers(0, 6))
+        n = int(rng.choice([1, 2, 17, 64, 300, 5000])); p = float(rng.choice([0.0, 0.05, 0.3, 1.0]))
+        tok, Q, K, V, dO = make_case(B, Hq, Hkv, L, d, p, "fp32", 8000 + case)
+        scale = 1.0 / math.sqrt(d)
+        q, k, v, do = (dev(x, "fp32") for x in (Q, K, V, dO))
+        flags = oracle.mark_separators(tok, wl.SEPARATOR_IDS)
+        label = f"case {case}: B={B} Hq={Hq} Hkv={Hkv} L={L} d={d} a={a} n={n} p={p}"
+        if case % 2 == 0:
+            is_sep, idx, cnt, pre = gpu_index(sp, tok)
+            O, LSE = sp.sepattn_forward(q, k, v, idx, cnt, pre, a, n, scale)
+            g = sp.sepattn_backward(q, k, v, O, LSE, do, idx, cnt, pre, a, n, scale)
+            rO, rL = oracle.forward(Q, K, V, flags, a, n, scale)
+            ref = oracle.backward(Q, K, V, dO, flags, a, n, scale)
+        else:
+            cus = [random_cu(rng, L, int(rng.integers(1, min(L, 12) + 1))) for _ in range(B)]
+            is_sep, ds, de, idx, cnt, pre = packed_index(sp, tok, cus, a)
+            O, LSE = sp.sepattn_forward_packed(q, k, v, ds, de, idx, cnt, pre, n, scale)
+            g = sp.sepattn_backward_packed(q, k, v, O, LSE, do, ds, de, idx, cnt, pre, n, scale)
+            rO, rL = oracle.forward_packed(Q, K, V, flags, cus, a, n, scale)
+            ref = oracle.backward_packed(Q, K, V, dO, flags, cus, a, n, scale)
+        torch.cuda.synchronize()
+        assert np.abs(host(O) - rO).max() <= 1e-4 and np.abs(host(LSE) - rL).max() <= 1e-4, label
+        for name, got, r in zip(("dQ", "dK", "dV"), g, ref):
+            # gradients grow with the number of rows that see a key: relative to the largest entry
+            assert np.abs(host(got) - r).max() <= 1e-4 * max(1.0, float(np.abs(r).max())), (label, name)
+
+
+def guarded(shape, dtype, fill):
+    """A tensor of the given shape inside a larger buffer whose 4 KB margins hold a pattern."""
+    n = int(np.prod(shape))
+    item = torch.empty((), dtype=dtype).element_size()
+    pad = 4096 // item
+    buf = torch.full((n + 2 * pad,), fill, dtype=dtype, device="cuda")
+    return buf, buf[pad:pad + n].view(shape), pad
+
+
+def margins_intact(buf, pad, fill):
+    return bool((buf[:pad] == fill).all()) and bool((buf[-pad:] == fill).all())
+
+
+def test_outputs_stay_inside_their_buffers(sp):
+    """Every output of the training and the streaming calls sits between guard bands; ragged sizes so
+    that the last tiles, chunks and rows are partial."""
+    B, Hq, Hkv, L, d, a, n, p = 2, 8, 2, 777, 128, 4, 100, 0.1
+    tok, Q, K, V, dO = make_case(B, Hq, Hkv, L, d, p, "bf16", 91)
+    scale = 1.0 / math.sqrt(d)
+    q, k, v, do = (dev(x, "bf16") for x in (Q, K, V, dO))
+    bands = []
+
+    def out(shape, dtype, fill):
+        buf, view, pad = guarded(shape, dtype, fill)
+        bands.append((buf, pad, fill))
+        return view
+
+    is_sep = out((B, L), torch.uint8, 7)
+    sp.sepattn_mark_separators(dev(tok.astype(np.int32)), wl.SEPARATOR_IDS.tolist(), out=is_sep)
+    idx, cnt, pre = out((B, L), torch.int32, -5), out((B,), torch.int32, -5), out((B, L + 1), torch.int32, -5)
+    sp.sepattn_compact_indices(is_sep, out=(idx, cnt, pre))
+    O, LSE = out(q.shape, torch.bfloat16, 3.0), out((B, Hq, L), torch.float32, 3.0)
+    sp.sepattn_forward(q, k, v, idx, cnt, pre, a, n, scale, out=(O, LSE))
+    grads = (out(q.shape, torch.bfloat16, 3.0), out(k.shape, torch.bfloat16, 3.0), out(v.shape, torch.bfloat16, 3.0))
+    sp.sepattn_backward(q, k, v, O, LSE, do, idx, cnt, pre, a, n, scale, out=grads)
+    # streaming side: hand-over, append, eviction, decode (plain and with positions within the cache)
+    s_cap, w = 37, 9
+    c = a + s_cap + 50
+    cache = (out((B, Hkv, c, d), torch.bfloat16, 3.0), out((B, Hkv, c, d), torch.bfloat16, 3.0),
+             out((B, c - a - s_cap), torch.uint8, 7), out((B, 4), torch.int32, -5))
+    sp.sepkv_fill_from_prefill(k, v, is_sep, idx, pre, Hq, a, s_cap, w, c, 49, out=cache)
+    Kc, Vc, Fd, Sd = cache
+    sp.sepkv_append(k[:, :, 0].contiguous(), v[:, :, 0].contiguous(), is_sep[:, 0].contiguous(), Kc, Vc, Fd, Sd, Hq, a, s_cap, w)
+    sp.sepkv_evict_window(Kc, Vc, Fd, Sd, Hq, a, s_cap, w)
+    qd = q[:, :, L - 1].contiguous()
+    o1, l1 = out(qd.shape, torch.bfloat16, 3.0), out((B, Hq), torch.float32, 3.0)
+    sp.sepattn_decode(qd, Kc, Vc, Sd, a, s_cap, w, scale, out=(o1, l1))
+    table = out((c, 2, d // 2), torch.float32, 3.0)
+    sp.sepkv_rope_table(c, d, 10000.0, "cuda", out=table)
+    o2, l2 = out(qd.shape, torch.bfloat16, 3.0), out((B, Hq), torch.float32, 3.0)
+    sp.sepattn_decode_rope(qd, Kc, Vc, Sd, table, a, s_cap, w, scale, out=(o2, l2))
+    torch.cuda.synchronize()
+    for i, (buf, pad, fill) in enumerate(bands):
+        assert margins_intact(buf, pad, fill), i
+    # and the calls did write what they own
+    assert bool((cnt > 0).all()) and bool(torch.isfinite(O.float()).all()) and bool(torch.isfinite(o2.float()).all())
+
+
+# ----------------------------------------------------------------------------------------------
 # error paths through the ABI (nothing is launched)
 # ----------------------------------------------------------------------------------------------
 def test_bad_arguments_are_rejected(sp):

@@ -4,7 +4,8 @@ and by bench.py's cpu_baseline leg, never by the product package.
 `sepattn_oracle.c` holds the arithmetic (dense, explicit mask; see its header for the passages it
 follows).  This module compiles it with gcc into two shared objects (double and float builds) and
 wraps them with numpy-in / numpy-out functions.  `cache_sim.py` is the host-only cache-size
-simulator of Sec. 3.3.
+simulator of Sec. 3.3; `sanitize_check.c` drives the C functions under the address and
+undefined-behaviour sanitizers (tests/test_oracle_sanitizers.py).
 """
 from __future__ import annotations
 
@@ -33,6 +34,11 @@ def build(force: bool = False) -> None:
         cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", f"-DORACLE_REAL={ctype}",
                _SRC, "-o", out, "-lm"]
         subprocess.run(cmd, check=True)
+    # the memory-safety driver (tests build it again with the sanitizers switched on)
+    chk = os.path.join(_HERE, "sanitize_check.c")
+    exe = os.path.join(_HERE, "sanitize_check.o")
+    if force or not os.path.exists(exe) or os.path.getmtime(exe) < max(os.path.getmtime(chk), os.path.getmtime(_SRC)):
+        subprocess.run(["gcc", "-O1", "-std=c11", "-I", _HERE, "-c", chk, "-o", exe], check=True)
 
 
 def _lib(precision: str):

@@ -108,11 +108,21 @@ def mask(is_sep_row: np.ndarray, a: int, n: int, rows: Optional[np.ndarray] = No
     return M.astype(bool)
 
 
+def _n_head(n_head, Hq: int):
+    if n_head is None:
+        return None
+    n_head = _c(n_head, np.int32)
+    assert n_head.shape == (Hq,) and (n_head >= 1).all()
+    return n_head
+
+
 def forward(Q, K, V, is_sep, a: int, n: int, scale: float, rows: Optional[np.ndarray] = None,
-            return_A: bool = False, precision: str = "f64"):
+            return_A: bool = False, precision: str = "f64", n_head=None):
     """Eq. 1 with the mask of Eq. 2.  Returns (O [B,Hq,R,d], LSE [B,Hq,R]) and A [B,Hq,R,L] if asked.
 
     rows (int32 list) restricts the computation to those query rows; R = len(rows) or L.
+    n_head [Hq], if given, replaces n by a neighbour window of its own for every query head (the
+    head-wise variant of Sec. 4.6).
     """
     rt = _real(precision)
     Q, K, V = _c(Q, rt), _c(K, rt), _c(V, rt)
@@ -131,14 +141,19 @@ def forward(Q, K, V, is_sep, a: int, n: int, scale: float, rows: Optional[np.nda
     fn = _lib(precision).oracle_forward
     fn.restype = ctypes.c_int
     rc = fn(_ptr(Q), _ptr(K), _ptr(V), _ptr(is_sep), B, Hq, Hkv, L, d, int(a), int(n),
-            ctypes.c_double(scale), _ptr(rows), R, _ptr(O), _ptr(LSE), _ptr(A))
+            _ptr(_n_head(n_head, Hq)), ctypes.c_double(scale), _ptr(rows), R, _ptr(O), _ptr(LSE), _ptr(A))
     if rc != 0:
         raise ValueError(f"oracle_forward failed with code {rc}")
     return (O, LSE, A) if return_A else (O, LSE)
 
 
-def backward(Q, K, V, dO, is_sep, a: int, n: int, scale: float, precision: str = "f64"):
-    """Analytic gradient of Eq. 1: returns (dQ [B,Hq,L,d], dK, dV [B,Hkv,L,d])."""
+def backward(Q, K, V, dO, is_sep, a: int, n: int, scale: float, precision: str = "f64", n_head=None,
+             return_term_rss: bool = False):
+    """Analytic gradient of Eq. 1: returns (dQ [B,Hq,L,d], dK, dV [B,Hkv,L,d]).
+
+    With return_term_rss also (eQ, eK, eV): for every gradient element the root of the sum of the
+    squares of the terms it adds up (see oracle_backward), the scale of the error that rounding the
+    attention weights to a short format before the sum must cause."""
     rt = _real(precision)
     Q, K, V, dO = _c(Q, rt), _c(K, rt), _c(V, rt), _c(dO, rt)
     is_sep = _c(is_sep, np.uint8)
@@ -148,13 +163,15 @@ def backward(Q, K, V, dO, is_sep, a: int, n: int, scale: float, precision: str =
     dQ = np.zeros_like(Q)
     dK = np.zeros_like(K)
     dV = np.zeros_like(V)
+    eQ, eK, eV = (np.zeros_like(x) for x in (Q, K, V)) if return_term_rss else (None, None, None)
     fn = _lib(precision).oracle_backward
     fn.restype = ctypes.c_int
     rc = fn(_ptr(Q), _ptr(K), _ptr(V), _ptr(dO), _ptr(is_sep), B, Hq, Hkv, L, d, int(a), int(n),
-            ctypes.c_double(scale), _ptr(dQ), _ptr(dK), _ptr(dV))
+            _ptr(_n_head(n_head, Hq)), ctypes.c_double(scale), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(eQ), _ptr(eK),
+            _ptr(eV))
     if rc != 0:
         raise ValueError(f"oracle_backward failed with code {rc}")
-    return dQ, dK, dV
+    return (dQ, dK, dV, eQ, eK, eV) if return_term_rss else (dQ, dK, dV)
 
 
 def decode(q, Kc, Vc, sizes, a: int, s: int, scale: float, precision: str = "f64"):
@@ -355,18 +372,23 @@ def forward_packed(Q, K, V, is_sep, cu_seqlens, a: int, n: int, scale: float, pr
     return O, LSE
 
 
-def backward_packed(Q, K, V, dO, is_sep, cu_seqlens, a: int, n: int, scale: float, precision: str = "f64"):
-    """Gradients of forward_packed: document by document."""
+def backward_packed(Q, K, V, dO, is_sep, cu_seqlens, a: int, n: int, scale: float, precision: str = "f64",
+                    return_term_rss: bool = False):
+    """Gradients of forward_packed: document by document (with return_term_rss also eQ, eK, eV of
+    `backward`)."""
     Q, K, V, dO = (np.asarray(x) for x in (Q, K, V, dO))
-    dQ, dK, dV = (np.zeros(x.shape, dtype=np.float64 if precision == "f64" else np.float32) for x in (Q, K, V))
+    rt = np.float64 if precision == "f64" else np.float32
+    outs = [np.zeros(x.shape, dtype=rt) for x in (Q, K, V)] + \
+           ([np.zeros(x.shape, dtype=rt) for x in (Q, K, V)] if return_term_rss else [])
     for b in range(Q.shape[0]):
         cu = np.asarray(cu_seqlens[b], dtype=np.int64)
         for k in range(len(cu) - 1):
             s, e = int(cu[k]), int(cu[k + 1])
-            gq, gk, gv = backward(Q[b:b + 1, :, s:e], K[b:b + 1, :, s:e], V[b:b + 1, :, s:e], dO[b:b + 1, :, s:e],
-                                  is_sep[b:b + 1, s:e], a, n, scale, precision=precision)
-            dQ[b, :, s:e], dK[b, :, s:e], dV[b, :, s:e] = gq[0], gk[0], gv[0]
-    return dQ, dK, dV
+            res = backward(Q[b:b + 1, :, s:e], K[b:b + 1, :, s:e], V[b:b + 1, :, s:e], dO[b:b + 1, :, s:e],
+                           is_sep[b:b + 1, s:e], a, n, scale, precision=precision, return_term_rss=return_term_rss)
+            for dst, src in zip(outs, res):
+                dst[b, :, s:e] = src[0]
+    return tuple(outs)
 
 
 def mark_doc_initial(is_sep: np.ndarray, doc_start: np.ndarray, a: int) -> np.ndarray:

@@ -31,13 +31,20 @@ static int attention_case(int B, int Hq, int Hkv, int L, int d, int a, int n, do
     real *Q = vec((long)B * Hq * L * d), *K = vec((long)B * Hkv * L * d), *V = vec((long)B * Hkv * L * d);
     real *dO = vec((long)B * Hq * L * d);
     real *O = vec((long)B * Hq * L * d), *LSE = vec((long)B * Hq * L), *A = vec((long)B * Hq * L * L);
-    int rc = oracle_forward(Q, K, V, is_sep, B, Hq, Hkv, L, d, a, n, 0.3, NULL, 0, O, LSE, A);
+    int rc = oracle_forward(Q, K, V, is_sep, B, Hq, Hkv, L, d, a, n, NULL, 0.3, NULL, 0, O, LSE, A);
     /* a subset of rows, last row included */
     int32_t rows[2] = {0, L - 1};
     real *O2 = vec((long)B * Hq * 2 * d), *L2 = vec((long)B * Hq * 2);
-    rc |= oracle_forward(Q, K, V, is_sep, B, Hq, Hkv, L, d, a, n, 0.3, rows, 2, O2, L2, NULL);
+    rc |= oracle_forward(Q, K, V, is_sep, B, Hq, Hkv, L, d, a, n, NULL, 0.3, rows, 2, O2, L2, NULL);
     real *dQ = vec((long)B * Hq * L * d), *dK = vec((long)B * Hkv * L * d), *dV = vec((long)B * Hkv * L * d);
-    rc |= oracle_backward(Q, K, V, dO, is_sep, B, Hq, Hkv, L, d, a, n, 0.3, dQ, dK, dV);
+    rc |= oracle_backward(Q, K, V, dO, is_sep, B, Hq, Hkv, L, d, a, n, NULL, 0.3, dQ, dK, dV, NULL, NULL, NULL);
+    /* per-head windows and the term-magnitude outputs */
+    int32_t *nh = (int32_t *)malloc(sizeof(int32_t) * (size_t)Hq);
+    for (int h = 0; h < Hq; ++h) nh[h] = h % 2 ? L + 5 : 1 + h;
+    real *eQ = vec((long)B * Hq * L * d), *eK = vec((long)B * Hkv * L * d), *eV = vec((long)B * Hkv * L * d);
+    rc |= oracle_forward(Q, K, V, is_sep, B, Hq, Hkv, L, d, a, n, nh, 0.3, NULL, 0, O, LSE, NULL);
+    rc |= oracle_backward(Q, K, V, dO, is_sep, B, Hq, Hkv, L, d, a, n, nh, 0.3, dQ, dK, dV, eQ, eK, eV);
+    free(nh); free(eQ); free(eK); free(eV);
     double chk = 0;
     for (long i = 0; i < (long)B * Hq * L * d; ++i) chk += O[i] + dQ[i];
     free(tok); free(is_sep); free(idx); free(cnt); free(pre); free(Q); free(K); free(V); free(dO);

@@ -107,9 +107,13 @@ static void attention_row(const real *q, const real *K, const uint8_t *m, int L,
 
 /* ---- Eq. 1 for selected rows of every (batch, head): O = A V, LSE = log sum exp(Lambda) ----
  * Q [B,Hq,L,d]; K,V [B,Hkv,L,d]; is_sep [B,L]; rows[n_rows] (NULL = all rows).
- * O [B,Hq,n_rows,d]; LSE [B,Hq,n_rows]; A_out (may be NULL) [B,Hq,n_rows,L].                    */
+ * O [B,Hq,n_rows,d]; LSE [B,Hq,n_rows]; A_out (may be NULL) [B,Hq,n_rows,L].
+ * n_head (may be NULL) [Hq]: a neighbour window of its own for every query head, in place of n
+ * (the head-wise variant of Sec. 4.6 "Comparison with More Baselines and Variants": some heads keep
+ * a short window, the others see everything, i.e. n_head[h] >= L); the mask of head h is then
+ * Eq. 2 with n = n_head[h].                                                                     */
 int oracle_forward(const real *Q, const real *K, const real *V, const uint8_t *is_sep, int B,
-                   int Hq, int Hkv, int L, int d, int a, int n, double scale,
+                   int Hq, int Hkv, int L, int d, int a, int n, const int32_t *n_head, double scale,
                    const int32_t *rows, int n_rows, real *O, real *LSE, real *A_out) {
     if (Hkv <= 0 || Hq % Hkv != 0) return 1;
     int G = Hq / Hkv;
@@ -122,19 +126,19 @@ int oracle_forward(const real *Q, const real *K, const real *V, const uint8_t *i
     }
     uint8_t *M = (uint8_t *)malloc((size_t)n_rows * (size_t)L);
     for (int b = 0; b < B; ++b) {
-        oracle_mask_rows(is_sep + (long)b * L, L, a, n, rows, n_rows, M);
+        for (int h = 0; h < Hq; ++h) {
+            int kv = h / G;
+            const real *Kh = K + ((long)b * Hkv + kv) * (long)L * d;
+            const real *Vh = V + ((long)b * Hkv + kv) * (long)L * d;
+            oracle_mask_rows(is_sep + (long)b * L, L, a, n_head ? n_head[h] : n, rows, n_rows, M);
 #pragma omp parallel
-        {
-            double *lam = (double *)malloc(sizeof(double) * (size_t)L);
-            double *Ar = (double *)malloc(sizeof(double) * (size_t)L);
-            double *o = (double *)malloc(sizeof(double) * (size_t)d);
-#pragma omp for collapse(2) schedule(dynamic, 8)
-            for (int h = 0; h < Hq; ++h) {
+            {
+                double *lam = (double *)malloc(sizeof(double) * (size_t)L);
+                double *Ar = (double *)malloc(sizeof(double) * (size_t)L);
+                double *o = (double *)malloc(sizeof(double) * (size_t)d);
+#pragma omp for schedule(dynamic, 8)
                 for (int r = 0; r < n_rows; ++r) {
-                    int kv = h / G;
                     const real *q = Q + (((long)b * Hq + h) * L + rows[r]) * d;
-                    const real *Kh = K + ((long)b * Hkv + kv) * (long)L * d;
-                    const real *Vh = V + ((long)b * Hkv + kv) * (long)L * d;
                     double lse;
                     attention_row(q, Kh, M + (long)r * L, L, d, scale, lam, Ar, &lse);
                     for (int k = 0; k < d; ++k) o[k] = 0.0;
@@ -148,10 +152,10 @@ int oracle_forward(const real *Q, const real *K, const real *V, const uint8_t *i
                     if (A_out)
                         for (int j = 0; j < L; ++j) A_out[orow * L + j] = (real)Ar[j];
                 }
+                free(lam);
+                free(Ar);
+                free(o);
             }
-            free(lam);
-            free(Ar);
-            free(o);
         }
     }
     free(M);
@@ -166,10 +170,21 @@ int oracle_forward(const real *Q, const real *K, const real *V, const uint8_t *i
  *   dL_ij = A_ij (dA_ij - D_i)            (softmax Jacobian; zero where M=0 because A=0)
  *   dQ_i  = scale sum_j dL_ij K_j,   dK_j = scale sum_i dL_ij Q_i
  * dK, dV of a KV head are summed over the Hq/Hkv query heads that read it.
- * The forward pass is recomputed densely inside (A kept as a full L x L matrix per head).       */
+ * The forward pass is recomputed densely inside (A kept as a full L x L matrix per head).
+ * n_head (may be NULL) [Hq]: per-head neighbour windows, as in oracle_forward.
+ *
+ * eQ, eK, eV (each may be NULL; shaped like dQ, dK, dV): the root of the sum of the SQUARES of the
+ * very terms that dQ, dK, dV add up,
+ *   eV_jk = sqrt(sum_i (A_ij dO_ik)^2),  eK_jk = scale sqrt(sum_i (dL_ij Q_ik)^2),
+ *   eQ_ik = scale sqrt(sum_j (dL_ij K_jk)^2)        (eK, eV: sums over the query heads as well).
+ * They are not part of the method: an implementation that rounds every A_ij (dL_ij) to a format
+ * of unit roundoff u before it adds the terms up makes an error of standard deviation at most
+ * u/sqrt(3) times these numbers, which is what a parity test needs in order to state a bound for
+ * gradients that are sums of thousands of terms.                                                 */
 int oracle_backward(const real *Q, const real *K, const real *V, const real *dO,
                     const uint8_t *is_sep, int B, int Hq, int Hkv, int L, int d, int a, int n,
-                    double scale, real *dQ, real *dK, real *dV) {
+                    const int32_t *n_head, double scale, real *dQ, real *dK, real *dV, real *eQ,
+                    real *eK, real *eV) {
     if (Hkv <= 0 || Hq % Hkv != 0) return 1;
     int G = Hq / Hkv;
     int32_t *rows = (int32_t *)malloc(sizeof(int32_t) * (size_t)L);
@@ -179,25 +194,31 @@ int oracle_backward(const real *Q, const real *K, const real *V, const real *dO,
     double *dL = (double *)malloc(sizeof(double) * (size_t)L * (size_t)L);
     double *dKacc = (double *)malloc(sizeof(double) * (size_t)L * (size_t)d);
     double *dVacc = (double *)malloc(sizeof(double) * (size_t)L * (size_t)d);
-    if (!M || !A || !dL || !dKacc || !dVacc) return 2;
+    double *eKacc = (double *)malloc(sizeof(double) * (size_t)L * (size_t)d);
+    double *eVacc = (double *)malloc(sizeof(double) * (size_t)L * (size_t)d);
+    if (!M || !A || !dL || !dKacc || !dVacc || !eKacc || !eVacc) return 2;
     for (int b = 0; b < B; ++b) {
-        oracle_mask_rows(is_sep + (long)b * L, L, a, n, rows, L, M);
         for (int kv = 0; kv < Hkv; ++kv) {
             const real *Kh = K + ((long)b * Hkv + kv) * (long)L * d;
             const real *Vh = V + ((long)b * Hkv + kv) * (long)L * d;
             memset(dKacc, 0, sizeof(double) * (size_t)L * d);
             memset(dVacc, 0, sizeof(double) * (size_t)L * d);
+            memset(eKacc, 0, sizeof(double) * (size_t)L * d);
+            memset(eVacc, 0, sizeof(double) * (size_t)L * d);
             for (int g = 0; g < G; ++g) {
                 int h = kv * G + g;
                 const real *Qh = Q + ((long)b * Hq + h) * (long)L * d;
                 const real *dOh = dO + ((long)b * Hq + h) * (long)L * d;
                 real *dQh = dQ + ((long)b * Hq + h) * (long)L * d;
+                real *eQh = eQ ? eQ + ((long)b * Hq + h) * (long)L * d : NULL;
+                oracle_mask_rows(is_sep + (long)b * L, L, a, n_head ? n_head[h] : n, rows, L, M);
                 /* forward rows, then dL rows and dQ rows */
 #pragma omp parallel
                 {
                     double *lam = (double *)malloc(sizeof(double) * (size_t)L);
                     double *o = (double *)malloc(sizeof(double) * (size_t)d);
                     double *dq = (double *)malloc(sizeof(double) * (size_t)d);
+                    double *eq = (double *)malloc(sizeof(double) * (size_t)d);
 #pragma omp for schedule(dynamic, 8)
                     for (int i = 0; i < L; ++i) {
                         double lse;
@@ -212,7 +233,7 @@ int oracle_backward(const real *Q, const real *K, const real *V, const real *dO,
                         }
                         double D = 0.0;
                         for (int k = 0; k < d; ++k) D += (double)dOh[(long)i * d + k] * o[k];
-                        for (int k = 0; k < d; ++k) dq[k] = 0.0;
+                        for (int k = 0; k < d; ++k) dq[k] = eq[k] = 0.0;
                         for (int j = 0; j < L; ++j) {
                             if (Ai[j] == 0.0) {
                                 dLi[j] = 0.0;
@@ -222,14 +243,21 @@ int oracle_backward(const real *Q, const real *K, const real *V, const real *dO,
                             for (int k = 0; k < d; ++k)
                                 dA += (double)dOh[(long)i * d + k] * (double)Vh[(long)j * d + k];
                             dLi[j] = Ai[j] * (dA - D);
-                            for (int k = 0; k < d; ++k)
-                                dq[k] += dLi[j] * (double)Kh[(long)j * d + k];
+                            for (int k = 0; k < d; ++k) {
+                                double term = dLi[j] * (double)Kh[(long)j * d + k];
+                                dq[k] += term;
+                                eq[k] += term * term;
+                            }
                         }
                         for (int k = 0; k < d; ++k) dQh[(long)i * d + k] = (real)(scale * dq[k]);
+                        if (eQh)
+                            for (int k = 0; k < d; ++k)
+                                eQh[(long)i * d + k] = (real)(fabs(scale) * sqrt(eq[k]));
                     }
                     free(lam);
                     free(o);
                     free(dq);
+                    free(eq);
                 }
                 /* column sums: dV_j and dK_j */
 #pragma omp parallel for schedule(dynamic, 8)
@@ -239,8 +267,12 @@ int oracle_backward(const real *Q, const real *K, const real *V, const real *dO,
                         if (Aij == 0.0) continue;
                         double dLij = dL[(long)i * L + j];
                         for (int k = 0; k < d; ++k) {
-                            dVacc[(long)j * d + k] += Aij * (double)dOh[(long)i * d + k];
-                            dKacc[(long)j * d + k] += scale * dLij * (double)Qh[(long)i * d + k];
+                            double tv = Aij * (double)dOh[(long)i * d + k];
+                            double tk = scale * dLij * (double)Qh[(long)i * d + k];
+                            dVacc[(long)j * d + k] += tv;
+                            dKacc[(long)j * d + k] += tk;
+                            eVacc[(long)j * d + k] += tv * tv;
+                            eKacc[(long)j * d + k] += tk * tk;
                         }
                     }
                 }
@@ -251,6 +283,12 @@ int oracle_backward(const real *Q, const real *K, const real *V, const real *dO,
                 dKh[t] = (real)dKacc[t];
                 dVh[t] = (real)dVacc[t];
             }
+            if (eK)
+                for (long t = 0; t < (long)L * d; ++t)
+                    eK[((long)b * Hkv + kv) * (long)L * d + t] = (real)sqrt(eKacc[t]);
+            if (eV)
+                for (long t = 0; t < (long)L * d; ++t)
+                    eV[((long)b * Hkv + kv) * (long)L * d + t] = (real)sqrt(eVacc[t]);
         }
     }
     free(rows);
@@ -259,6 +297,8 @@ int oracle_backward(const real *Q, const real *K, const real *V, const real *dO,
     free(dL);
     free(dKacc);
     free(dVacc);
+    free(eKacc);
+    free(eVacc);
     return 0;
 }
 

@@ -364,6 +364,82 @@ def test_backward_closed_forms():
 
 
 # ----------------------------------------------------------------------------------------------
+# head-wise windows (Sec. 4.6, the head-wise variant) and the term magnitudes of the gradients
+# ----------------------------------------------------------------------------------------------
+def test_per_head_windows_reduce_to_the_scalar_window_and_to_single_head_runs():
+    """n_head with all heads equal is the scalar n; with different windows, query head h must equal a
+    single-head run with n = n_head[h], and dK / dV of a KV head the sum of its heads' single runs."""
+    B, Hq, Hkv, L, d, a = 2, 4, 2, 40, 4, 2
+    is_sep = _flags(B, L, 0.2, 3)
+    Q, K, V = _rand((B, Hq, L, d), 1), _rand((B, Hkv, L, d), 2), _rand((B, Hkv, L, d), 3)
+    dO = _rand((B, Hq, L, d), 4)
+    O0, L0 = oracle.forward(Q, K, V, is_sep, a, 5, 0.5)
+    O1, L1 = oracle.forward(Q, K, V, is_sep, a, 99, 0.5, n_head=[5, 5, 5, 5])
+    assert np.array_equal(O0, O1) and np.array_equal(L0, L1)
+    g0 = oracle.backward(Q, K, V, dO, is_sep, a, 5, 0.5)
+    g1 = oracle.backward(Q, K, V, dO, is_sep, a, 99, 0.5, n_head=[5, 5, 5, 5])
+    assert all(np.array_equal(x, y) for x, y in zip(g0, g1))
+    nh = [1, L + 7, 3, 12]                      # a full-attention head inside each group
+    O, LSE = oracle.forward(Q, K, V, is_sep, a, 77, 0.5, n_head=nh)
+    dQ, dK, dV = oracle.backward(Q, K, V, dO, is_sep, a, 77, 0.5, n_head=nh)
+    sumK, sumV = np.zeros_like(K), np.zeros_like(V)
+    G = Hq // Hkv
+    for h in range(Hq):
+        kv = h // G
+        args = (Q[:, h:h + 1], K[:, kv:kv + 1], V[:, kv:kv + 1])
+        o, l = oracle.forward(*args, is_sep, a, nh[h], 0.5)
+        assert np.array_equal(O[:, h:h + 1], o) and np.array_equal(LSE[:, h:h + 1], l)
+        gq, gk, gv = oracle.backward(*args, dO[:, h:h + 1], is_sep, a, nh[h], 0.5)
+        assert np.array_equal(dQ[:, h:h + 1], gq)
+        sumK[:, kv:kv + 1] += gk
+        sumV[:, kv:kv + 1] += gv
+    assert np.allclose(dK, sumK, atol=1e-13) and np.allclose(dV, sumV, atol=1e-13)
+    # and the mask itself, brute force: the head with n_head = 1 and no initial tokens sees itself and separators
+    _, _, A = oracle.forward(Q, K, V, is_sep, 0, 50, 0.5, n_head=[1, 50, 50, 50], return_A=True)
+    for b in range(B):
+        for i in range(L):
+            want = {j for j in range(i + 1) if j == i or is_sep[b, j]}
+            assert set(np.nonzero(A[b, 0, i])[0]) == want
+
+
+def test_term_magnitudes_of_the_gradients():
+    """eQ, eK, eV are root-sum-squares of the terms the gradients add up: pinned by the closed form
+    of the self-only case, by building them from the attention matrix the forward returns, and by
+    the inequalities |sum| <= sum|term| ... every sum of N terms obeys |sum| <= sqrt(N) * rss."""
+    B, Hq, Hkv, L, d, a, n = 1, 4, 2, 28, 4, 2, 4
+    Q, K, V = _rand((B, Hq, L, d), 1), _rand((B, Hkv, L, d), 2), _rand((B, Hkv, L, d), 3)
+    dO = _rand((B, Hq, L, d), 4)
+    none = np.zeros((B, L), np.uint8)
+    # every token sees only itself: A = I, so dV_j = sum over the heads of dO_j, one term per head
+    dQ, dK, dV, eQ, eK, eV = oracle.backward(Q, K, V, dO, none, 0, 1, 0.5, return_term_rss=True)
+    G = Hq // Hkv
+    want = np.sqrt((dO.reshape(B, Hkv, G, L, d) ** 2).sum(axis=2))
+    assert np.allclose(eV, want, atol=1e-13) and np.all(eK == 0) and np.all(eQ == 0)
+    # general case, from the attention matrix
+    is_sep = _flags(B, L, 0.25, 9)
+    scale = 0.7
+    dQ, dK, dV, eQ, eK, eV = oracle.backward(Q, K, V, dO, is_sep, a, n, scale, return_term_rss=True)
+    O, _, A = oracle.forward(Q, K, V, is_sep, a, n, scale, return_A=True)
+    eV2, eK2 = np.zeros_like(V), np.zeros_like(K)
+    for h in range(Hq):
+        kv = h // G
+        Ah = A[0, h]
+        Drow = (dO[0, h] * O[0, h]).sum(axis=1)
+        dS = Ah * (dO[0, h] @ V[0, kv].T - Drow[:, None])
+        eV2[0, kv] += (Ah ** 2).T @ (dO[0, h] ** 2)
+        eK2[0, kv] += scale ** 2 * (dS ** 2).T @ (Q[0, h] ** 2)
+        assert np.allclose(eQ[0, h], scale * np.sqrt((dS ** 2) @ (K[0, kv] ** 2)), atol=1e-12)
+    assert np.allclose(eV, np.sqrt(eV2), atol=1e-12) and np.allclose(eK, np.sqrt(eK2), atol=1e-12)
+    # a sum of at most N terms is at most sqrt(N) times their root-sum-square
+    assert (np.abs(dV) <= math.sqrt(G * L) * eV + 1e-12).all()
+    assert (np.abs(dK) <= math.sqrt(G * L) * eK + 1e-12).all()
+    assert (np.abs(dQ) <= math.sqrt(L) * eQ + 1e-12).all()
+    # the gradients themselves do not change when the magnitudes are asked for
+    g = oracle.backward(Q, K, V, dO, is_sep, a, n, scale)
+    assert all(np.array_equal(x, y) for x, y in zip(g, (dQ, dK, dV)))
+
+
+# ----------------------------------------------------------------------------------------------
 # decode
 # ----------------------------------------------------------------------------------------------
 def test_decode_equals_prefill_row_under_fundamental_design_cache():

@@ -227,6 +227,24 @@ int sepattn_decode_rope(const sepkv_params *p, const void *q, const void *Kc, co
                         const int32_t *sizes, const float *rope_table, int n_pos, void *out,
                         float *lse, void *ws, size_t ws_bytes, void *stream);
 
+/* sepattn_decode for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels and results as sepattn_decode, without ws / ws_bytes: the partial results of
+ * the cache slices live in a fixed array of SEPATTN_DECODE_NOALLOC_SCRATCH_BYTES inside the library
+ * (one copy per GPU the library runs on, held until the process ends).  The call allocates and
+ * frees nothing and clears nothing.
+ *   - SEPATTN_ERR_WORKSPACE if the shape needs more than the fixed array, i.e. if
+ *     sepattn_decode_noalloc_scratch_bytes(p) (= sepattn_decode_workspace_bytes(p)) exceeds
+ *     SEPATTN_DECODE_NOALLOC_SCRATCH_BYTES; nothing is enqueued then.
+ *   - All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU (on
+ *     different streams, or from different threads) race on it.  Calls on one stream are ordered
+ *     and safe.
+ */
+#define SEPATTN_DECODE_NOALLOC_SCRATCH_BYTES (4u << 20)
+size_t sepattn_decode_noalloc_scratch_bytes(const sepkv_params *p);
+int sepattn_decode_noalloc(const sepkv_params *p, const void *q, const void *Kc, const void *Vc,
+                           const int32_t *sizes, void *out, float *lse, void *stream);
+
 /* A new token enters the cache of every sequence (Sec. 3.3 "Framework"): the first a tokens of a
  * sequence go to the Initial Cache; a later token is written behind the newest window entry and
  * joins the Local Window Cache, and once that holds more than w its oldest entry passes to the

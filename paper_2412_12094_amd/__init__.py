@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     sepattn_backward,
     sepattn_backward_workspace_bytes,
     sepattn_decode,
+    sepattn_decode_noalloc,
     sepkv_evict_window,
     sepkv_fill_from_prefill,
     sepkv_rope_table,

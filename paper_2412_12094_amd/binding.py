@@ -35,6 +35,8 @@ EXPORTS = (
     "sepattn_backward",
     "sepattn_decode_workspace_bytes",
     "sepattn_decode",
+    "sepattn_decode_noalloc_scratch_bytes",
+    "sepattn_decode_noalloc",
     "sepkv_evict_workspace_bytes",
     "sepkv_evict_window",
     "sepkv_fill_from_prefill",
@@ -109,6 +111,10 @@ def load(path: Optional[str] = None):
     lib.sepattn_decode_workspace_bytes.argtypes = [kp]
     lib.sepattn_decode.restype = ci
     lib.sepattn_decode.argtypes = [kp] + [vp] * 7 + [sz, vp]
+    lib.sepattn_decode_noalloc_scratch_bytes.restype = sz
+    lib.sepattn_decode_noalloc_scratch_bytes.argtypes = [kp]
+    lib.sepattn_decode_noalloc.restype = ci
+    lib.sepattn_decode_noalloc.argtypes = [kp] + [vp] * 7
     lib.sepkv_evict_workspace_bytes.restype = sz
     lib.sepkv_evict_workspace_bytes.argtypes = [kp]
     lib.sepkv_evict_window.restype = ci
@@ -384,6 +390,20 @@ def sepattn_decode(q, Kc, Vc, sizes, a: int, s: int, w: int, scale: float,
     _check("sepattn_decode",
            lib.sepattn_decode(ctypes.byref(p), _ptr(q), _ptr(Kc), _ptr(Vc), _ptr(sizes), _ptr(o), _ptr(lse),
                               _ptr(ws), ws.numel(), _stream(q)))
+    return o, lse
+
+
+def sepattn_decode_noalloc(q, Kc, Vc, sizes, a: int, s: int, w: int, scale: float,
+                           out: Tuple[torch.Tensor, torch.Tensor]):
+    """sepattn_decode without a workspace (the library's fixed scratch array is used); the caller passes
+    the outputs (out [S,Hq,d], lse fp32 [S,Hq]), so nothing at all is allocated by the call."""
+    _dev(q, Kc, Vc, sizes)
+    assert sizes.dtype == torch.int32
+    p = _kv_params(q, Kc, a, s, w, scale)
+    o, lse = out
+    _check("sepattn_decode_noalloc",
+           load().sepattn_decode_noalloc(ctypes.byref(p), _ptr(q), _ptr(Kc), _ptr(Vc), _ptr(sizes), _ptr(o), _ptr(lse),
+                                         _stream(q)))
     return o, lse
 
 

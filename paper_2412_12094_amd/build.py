@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsepattn.so")
-SOURCES = ["api.hip", "mark_compact.hip", "attn_fp32.hip", "fwd_bf16.hip", "bwd_bf16.hip", "bwd_dkv_bf16.hip", "decode.hip", "decode_mfma.hip",
+SOURCES = ["api.hip", "mark_compact.hip", "attn_fp32.hip", "fwd_bf16.hip", "bwd_bf16.hip", "bwd_dkv_bf16.hip", "decode.hip", "decode_mfma.hip", "decode_noalloc.hip",
            "evict.hip", "cache_fill.hip", "rope_table.hip", "cache_append.hip", "doc_bounds.hip"]
 # packed fp32 VALU instructions are switched off (some of their forms have miscomputed on
 # the test machines); the host pass does not know the feature and says so, which is harmless

@@ -59,7 +59,10 @@ sepattn_params normalised(const sepattn_params *p) {
     return q;
 }
 
-int check_kv(const sepkv_params *p) {
+}  // namespace
+
+namespace sepattn {
+int check_kv_params(const sepkv_params *p) {
     if (!p) return SEPATTN_ERR_NULL;
     if (p->S <= 0 || p->Hq <= 0 || p->Hkv <= 0 || p->c <= 0) return SEPATTN_ERR_SHAPE;
     if (p->Hq % p->Hkv != 0) return SEPATTN_ERR_SHAPE;
@@ -69,9 +72,14 @@ int check_kv(const sepkv_params *p) {
     if ((long)p->a + p->s + p->w >= (long)p->c) return SEPATTN_ERR_PARAM;
     if (!(p->scale == p->scale) || p->scale <= 0.f) return SEPATTN_ERR_PARAM;
     if ((long)p->S * p->Hq > 65535L) return SEPATTN_ERR_SHAPE;  // second grid dimension
+    // a slot's rows are addressed as (uniform base of the head) + 32-bit byte offset
+    if ((long)p->c * p->d * 4 > 0xFFFFFFFFL) return SEPATTN_ERR_SHAPE;
     return SEPATTN_OK;
 }
+}  // namespace sepattn
 
+namespace {
+int check_kv(const sepkv_params *p) { return sepattn::check_kv_params(p); }
 }  // namespace
 
 namespace sepattn {

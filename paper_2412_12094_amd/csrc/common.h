@@ -75,6 +75,7 @@ int launch_backward_bf16(const sepattn_params &p, const void *Q, const void *K, 
                          const int32_t *doc_end, void *dQ, void *dK, void *dV, void *ws, hipStream_t st);
 
 // ---- streaming cache ---------------------------------------------------------------------------
+int check_kv_params(const sepkv_params *p);  // host validation shared by every cache call
 size_t decode_workspace(const sepkv_params &p);
 // rope: table of cos / sin by position [n_pos][2][d/2] (keys stored without position encoding), or nullptr
 int launch_decode(const sepkv_params &p, const void *q, const void *Kc, const void *Vc,

@@ -132,24 +132,24 @@ def main() -> int:
     train_kernels = ["mark", "compact_count", "compact_write", "forward", "bwd_dq", "bwd_dkv", "bwd_combine"]
     per_kernel_us = {}
     for name in train_kernels:
-        sp.sepattn_profile_begin(sp.KERNEL_IDS[name], 20)
+        prof = sp.sepattn_profile_begin(sp.KERNEL_IDS[name], 20)
         for _ in range(20):
             step()
         torch.cuda.synchronize()
-        ms = sp.sepattn_profile_end(20)
+        ms = sp.sepattn_profile_end(prof)
         if len(ms):  # a kernel that this shape does not launch has no records
             per_kernel_us[name] = 1e3 * float(np.median(ms))
     dominant = max(per_kernel_us, key=per_kernel_us.get)
 
     # timed region: exactly K steps, the dominant kernel bracketed by HIP events on the launch stream
-    sp.sepattn_profile_begin(sp.KERNEL_IDS[dominant], args.steps)
+    prof = sp.sepattn_profile_begin(sp.KERNEL_IDS[dominant], args.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    dom_ms = sp.sepattn_profile_end(args.steps)
+    dom_ms = sp.sepattn_profile_end(prof)
     ms_per_step = 1e3 * (t1 - t0) / args.steps
 
     flags = is_sep.cpu().numpy()
@@ -269,14 +269,14 @@ def bench_decode(torch, sp, wl, ramp_seconds):
         k_, v_ = caches[i % 3]
         sp.sepattn_decode(q, k_, v_, sizes, c.a, c.s, c.w, c.scale, out=(out, lse), ws=ws)
     torch.cuda.synchronize()
-    sp.sepattn_profile_begin(sp.KERNEL_IDS["decode_split"], steps)
+    prof = sp.sepattn_profile_begin(sp.KERNEL_IDS["decode_split"], steps)
     t0 = time.perf_counter()
     for i in range(steps):
         k_, v_ = caches[i % 3]
         sp.sepattn_decode(q, k_, v_, sizes, c.a, c.s, c.w, c.scale, out=(out, lse), ws=ws)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    kms = sp.sepattn_profile_end(steps)
+    kms = sp.sepattn_profile_end(prof)
     kv_bytes = 2.0 * c.S * c.Hkv * c.c * c.d * 2
     us_step = 1e6 * (t1 - t0) / steps
     k_us = 1e3 * float(np.mean(kms))
@@ -291,12 +291,12 @@ def bench_decode(torch, sp, wl, ramp_seconds):
         k_, v_ = caches[i % 3]
         sp.sepattn_decode_rope(q, k_, v_, sizes, table, c.a, c.s, c.w, c.scale, out=(out, lse), ws=ws)
     torch.cuda.synchronize()
-    sp.sepattn_profile_begin(sp.KERNEL_IDS["decode_split"], steps)
+    prof = sp.sepattn_profile_begin(sp.KERNEL_IDS["decode_split"], steps)
     for i in range(steps):
         k_, v_ = caches[i % 3]
         sp.sepattn_decode_rope(q, k_, v_, sizes, table, c.a, c.s, c.w, c.scale, out=(out, lse), ws=ws)
     torch.cuda.synchronize()
-    r_us = 1e3 * float(np.mean(sp.sepattn_profile_end(steps)))
+    r_us = 1e3 * float(np.mean(sp.sepattn_profile_end(prof)))
     res["rope"] = {"split_kernel_us": round(r_us, 2), "gbs_kernel": round(kv_bytes / r_us / 1e3, 1),
                    "frac_hbm_peak_kernel": round(kv_bytes / r_us / 1e3 / PEAK_HBM_GBS, 4)}
     # one token enters every cache (the window region has room: sizes restored every time)
@@ -306,12 +306,12 @@ def bench_decode(torch, sp, wl, ramp_seconds):
     sz_room = sizes.clone()
     sz_room[:, 2] -= 1
     sz_a, fl_a = sz_room.clone(), torch.from_numpy(data["win_is_sep"]).cuda()
-    sp.sepattn_profile_begin(sp.KERNEL_IDS["cache_append"], 50)
+    prof = sp.sepattn_profile_begin(sp.KERNEL_IDS["cache_append"], 50)
     for i in range(50):
         sz_a.copy_(sz_room)
         sp.sepkv_append(k_new, v_new, sep_new, Kc, Vc, fl_a, sz_a, c.Hq, c.a, c.s, c.w)
     torch.cuda.synchronize()
-    res["append_us"] = round(1e3 * float(np.median(sp.sepattn_profile_end(50)[5:])), 2)
+    res["append_us"] = round(1e3 * float(np.median(sp.sepattn_profile_end(prof)[5:])), 2)
     # eviction: restore the sizes / flags every time (in place otherwise empties the past window)
     flags0 = torch.from_numpy(data["win_is_sep"]).cuda()
     sizes0 = sizes.clone()

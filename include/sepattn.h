@@ -14,12 +14,19 @@
  * Conventions common to every call
  *   - Pointers marked DEVICE address memory of the current HIP device; HOST pointers address
  *     ordinary host memory.  The caller owns every buffer, including workspaces; the library
- *     allocates no device memory and keeps no state between calls (the measurement hooks at the
- *     end of this header aside).
+ *     allocates no device memory and keeps no state between calls (the fixed scratch array of
+ *     sepattn_decode_noalloc aside).
+ *   - Alignment: token_ids, Q, K, V, O, dO, dQ, dK, dV, q, Kc, Vc, out, k_new, v_new and rope tables
+ *     must be 16-byte aligned, is_sep 4-byte aligned, workspaces 256-byte aligned; a misaligned
+ *     buffer is refused with SEPATTN_ERR_PARAM (workspaces: SEPATTN_ERR_WORKSPACE).
  *   - Tensors are dense and contiguous with the head dimension d innermost.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls validate their
  *     arguments synchronously, enqueue their kernels on `stream` and return without waiting.
- *     Nothing is enqueued when an error is returned.
+ *     Nothing is enqueued when a validation error (any status but SEPATTN_ERR_HIP) is returned.
+ *     SEPATTN_ERR_HIP means the runtime refused a launch of this call; a call that consists of
+ *     several kernels may then have enqueued the earlier ones, and its outputs are unspecified.
+ *     An error left pending in the HIP runtime by the caller's own earlier calls is discarded at
+ *     entry, not reported.
  *   - Return value: SEPATTN_OK (0) or a positive sepattn_status.  No call throws or exits.
  *   - Outputs must not alias inputs, except where a call is documented as in-place.
  *   - All results are bit-reproducible run to run (no floating-point atomics).
@@ -38,7 +45,8 @@ typedef enum {
     SEPATTN_OK = 0,
     SEPATTN_ERR_NULL = 1,      /* a required pointer is NULL                                   */
     SEPATTN_ERR_SHAPE = 2,     /* a size is non-positive, too large, or inconsistent            */
-    SEPATTN_ERR_PARAM = 3,     /* a hyper-parameter is out of range (n < 1, a < 0, a+s+w >= c)  */
+    SEPATTN_ERR_PARAM = 3,     /* a hyper-parameter is out of range (n < 1, a < 0, a+s+w >= c),
+                                  or a buffer is not aligned as the conventions above require  */
     SEPATTN_ERR_DTYPE = 4,     /* dtype is not a sepattn_dtype / unsupported head dimension     */
     SEPATTN_ERR_WORKSPACE = 5, /* workspace missing or smaller than *_workspace_bytes reports   */
     SEPATTN_ERR_CAPACITY = 6,  /* an index list capacity is too small to be usable              */
@@ -82,7 +90,9 @@ int sepattn_mark_interval(int B, int L, int delta, int phase, uint8_t *is_sep, v
  *                                       entries at and beyond min(count, cap) are left untouched
  *   sep_count   DEVICE int32 [B]       out: true number of separators, even when it exceeds cap
  *   sep_prefix  DEVICE int32 [B, L+1]  out: sep_prefix[b,j] = number of separators at positions
- *                                       < j  (exclusive prefix count; sep_prefix[b,L] = count)
+ *                                       < j  (exclusive prefix count; sep_prefix[b,L] = count).
+ *                                       May be NULL when only the list and the count are wanted
+ *                                       (forward / backward / the hand-over need it).
  *   workspace   DEVICE, at least sepattn_compact_workspace_bytes(B, L) bytes, 4-byte aligned
  * cap >= 1.  A caller that wants forward / backward to see every separator passes cap >= count
  * (cap = L always suffices).
@@ -303,16 +313,22 @@ int sepkv_fill_from_prefill(const sepkv_params *p, int L, int nw, const void *K,
                             int32_t *sizes, void *stream);
 
 /* ------------------------------------------------------------------------------------------
- * Measurement hooks (not part of the method; the only process-wide state the library keeps).
- * Between sepattn_profile_begin and sepattn_profile_end every launch of the selected kernel is
- * bracketed by a pair of HIP events recorded on the stream the kernel is launched on, so a
- * benchmark can report that kernel's own duration while it times whole steps.  Not thread-safe.
- *   kernel       a sepattn_kernel_id
- *   max_records  events are created up front for this many launches; further launches of the
- *                kernel are not recorded
- *   ms           HOST float [max_records] out: elapsed milliseconds of each recorded launch
- *   n_records    HOST int out: number of launches recorded
- * sepattn_profile_end waits for the recorded events, so call it after the timed region.
+ * Measurement hooks (not part of the method).  A benchmark that times whole steps can also report one
+ * kernel's own duration: it creates a handle for that kernel, attaches it to the thread that makes
+ * the library calls, and from then on every launch of the kernel by that thread is bracketed by a
+ * pair of HIP events recorded on the stream the kernel is launched on, until the handle is detached.
+ * The handle and everything it records belong to the caller; the library keeps no process-wide state,
+ * only, per thread, which handle is attached.  Different threads may use different handles at the
+ * same time; one handle must not be attached to two threads.
+ *   sepattn_profile_create   kernel: a sepattn_kernel_id; max_records: events are created up front
+ *                            for this many launches, further launches are not recorded;
+ *                            *out receives the handle (HOST)
+ *   sepattn_profile_attach   SEPATTN_ERR_PARAM if this thread already has a handle attached
+ *   sepattn_profile_detach   SEPATTN_ERR_PARAM if h is not the handle attached to this thread
+ *   sepattn_profile_read     waits for the recorded events (call it after the timed region);
+ *                            ms HOST float [max_records] out: elapsed milliseconds per recorded
+ *                            launch; *n_records out: how many were written
+ *   sepattn_profile_destroy  frees the events and the handle (detaches it from this thread first)
  * ------------------------------------------------------------------------------------------ */
 typedef enum {
     SEPATTN_K_MARK = 0,
@@ -334,8 +350,12 @@ typedef enum {
     SEPATTN_K_COUNT = 16
 } sepattn_kernel_id;
 const char *sepattn_kernel_name(int kernel);
-int sepattn_profile_begin(int kernel, int max_records);
-int sepattn_profile_end(float *ms, int *n_records);
+typedef struct sepattn_profile sepattn_profile;
+int sepattn_profile_create(int kernel, int max_records, sepattn_profile **out);
+int sepattn_profile_attach(sepattn_profile *h);
+int sepattn_profile_detach(sepattn_profile *h);
+int sepattn_profile_read(sepattn_profile *h, float *ms, int max_records, int *n_records);
+void sepattn_profile_destroy(sepattn_profile *h);
 
 #ifdef __cplusplus
 }

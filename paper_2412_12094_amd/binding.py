@@ -15,7 +15,9 @@ from typing import Optional, Tuple
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsepattn.so")
+# SEPATTN_LIB names another build of the same library (the host-sanitizer build that a CPU test runs the
+# argument-validation tests against); every build runs the same kernels
+LIB_PATH = os.environ.get("SEPATTN_LIB") or os.path.join(_HERE, "libsepattn.so")
 
 SEPATTN_BF16 = 0
 SEPATTN_FP32 = 1
@@ -44,8 +46,11 @@ EXPORTS = (
     "sepattn_decode_rope",
     "sepkv_append",
     "sepattn_kernel_name",
-    "sepattn_profile_begin",
-    "sepattn_profile_end",
+    "sepattn_profile_create",
+    "sepattn_profile_attach",
+    "sepattn_profile_detach",
+    "sepattn_profile_read",
+    "sepattn_profile_destroy",
 )
 
 
@@ -129,10 +134,16 @@ def load(path: Optional[str] = None):
     lib.sepkv_append.argtypes = [kp] + [vp] * 8
     lib.sepattn_kernel_name.restype = ctypes.c_char_p
     lib.sepattn_kernel_name.argtypes = [ci]
-    lib.sepattn_profile_begin.restype = ci
-    lib.sepattn_profile_begin.argtypes = [ci, ci]
-    lib.sepattn_profile_end.restype = ci
-    lib.sepattn_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int)]
+    lib.sepattn_profile_create.restype = ci
+    lib.sepattn_profile_create.argtypes = [ci, ci, ctypes.POINTER(vp)]
+    lib.sepattn_profile_attach.restype = ci
+    lib.sepattn_profile_attach.argtypes = [vp]
+    lib.sepattn_profile_detach.restype = ci
+    lib.sepattn_profile_detach.argtypes = [vp]
+    lib.sepattn_profile_read.restype = ci
+    lib.sepattn_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ci, ctypes.POINTER(ctypes.c_int)]
+    lib.sepattn_profile_destroy.restype = None
+    lib.sepattn_profile_destroy.argtypes = [vp]
     if path == LIB_PATH or _lib is None:
         _lib = lib
     return lib
@@ -152,16 +163,30 @@ def sepattn_kernel_name(kernel: int) -> str:
     return load().sepattn_kernel_name(int(kernel)).decode()
 
 
-def sepattn_profile_begin(kernel: int, max_records: int) -> None:
-    """Bracket the next launches of one kernel with HIP events on the launch stream."""
-    _check("sepattn_profile_begin", load().sepattn_profile_begin(int(kernel), int(max_records)))
+def sepattn_profile_begin(kernel: int, max_records: int):
+    """Create a measurement handle for one kernel and attach it to this thread: the thread's next launches
+    of that kernel are bracketed with HIP events on the launch stream.  Returns the handle."""
+    lib = load()
+    h = ctypes.c_void_p()
+    _check("sepattn_profile_create", lib.sepattn_profile_create(int(kernel), int(max_records), ctypes.byref(h)))
+    rc = lib.sepattn_profile_attach(h)
+    if rc != 0:
+        lib.sepattn_profile_destroy(h)
+        raise SepattnError("sepattn_profile_attach", rc)
+    return (h, int(max_records))
 
 
-def sepattn_profile_end(max_records: int):
-    """Wait for the recorded events; returns the list of per-launch durations in milliseconds."""
-    ms = (ctypes.c_float * int(max_records))()
+def sepattn_profile_end(handle):
+    """Detach the handle, wait for the recorded events, free it; returns the per-launch durations in
+    milliseconds."""
+    lib = load()
+    h, max_records = handle
+    ms = (ctypes.c_float * max_records)()
     n = ctypes.c_int(0)
-    _check("sepattn_profile_end", load().sepattn_profile_end(ms, ctypes.byref(n)))
+    rc = lib.sepattn_profile_detach(h)
+    rc = rc or lib.sepattn_profile_read(h, ms, max_records, ctypes.byref(n))
+    lib.sepattn_profile_destroy(h)
+    _check("sepattn_profile_end", rc)
     return [float(ms[i]) for i in range(n.value)]
 
 

@@ -40,5 +40,44 @@ def build(extra_flags=(), lib_path: str = LIB) -> str:
     return lib_path
 
 
+HOST_SOURCES = ["api.hip", "decode_noalloc.hip"]  # entry points: validation and dispatch on the host
+SANITIZE = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+            "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+
+
+def build_host_sanitized(lib_path: str) -> str:
+    """A second build of the library whose HOST code of the entry points (argument validation, workspace
+    arithmetic, dispatch) is instrumented with the address and undefined-behaviour sanitizers; the device
+    code and the other objects are the ordinary ones.  For CPU tests only."""
+    if not all(os.path.exists(os.path.join(OBJ, os.path.splitext(s)[0] + ".o")) for s in SOURCES):
+        build()
+    san = os.path.join(OBJ, "host_san")
+    os.makedirs(san, exist_ok=True)
+    objs = []
+    for src in SOURCES:
+        obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
+        if src in HOST_SOURCES:
+            obj = os.path.join(san, os.path.splitext(src)[0] + ".o")
+            cmd = ["hipcc", *[f for f in FLAGS if f != "-O3"], "-O1", *SANITIZE, "-c", os.path.join(CSRC, src), "-o", obj]
+            r = subprocess.run(cmd, capture_output=True, text=True)
+            if r.returncode != 0:
+                raise RuntimeError(f"hipcc (sanitized) failed on {src}:\n{r.stderr}")
+        objs.append(obj)
+    subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", lib_path], check=True)
+    return lib_path
+
+
+def sanitizer_runtime() -> str:
+    """Path of the shared AddressSanitizer runtime of the compiler hipcc uses (it also holds the
+    undefined-behaviour handlers); a process that loads the sanitized library must preload it."""
+    r = subprocess.run(["hipcc", "--print-file-name=libclang_rt.asan-x86_64.so"], capture_output=True, text=True)
+    path = r.stdout.strip()
+    if os.path.isabs(path) and os.path.exists(path):
+        return path
+    import glob
+    found = sorted(glob.glob("/opt/rocm/lib/llvm/lib/clang/*/lib/linux/libclang_rt.asan-x86_64.so"))
+    return found[-1] if found else ""
+
+
 if __name__ == "__main__":
     print(build(sys.argv[1:]))

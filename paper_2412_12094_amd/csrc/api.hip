@@ -3,29 +3,35 @@
 // cover.
 #include "common.h"
 
+#include <new>
 #include <vector>
 
 using namespace sepattn;
 
-namespace sepattn {
-namespace {
-struct ProfState {
+// A measurement handle: owned by the caller, attached to the calling thread for the launches it is to
+// record (see sepattn.h).  The library itself keeps only the thread's pointer to the attached handle.
+struct sepattn_profile {
     int kernel = -1;
     int used = 0;
     bool open = false;  // a start event was recorded and its stop is pending
     std::vector<hipEvent_t> start, stop;
-} g_prof;
+};
+
+namespace sepattn {
+namespace {
+thread_local sepattn_profile *t_attached = nullptr;
 }  // namespace
 
 void profile_mark(int kernel, hipStream_t st, bool stop) {
-    if (kernel != g_prof.kernel) return;
+    sepattn_profile *h = t_attached;
+    if (!h || kernel != h->kernel) return;
     if (!stop) {
-        if (g_prof.used >= (int)g_prof.start.size()) return;
-        g_prof.open = hipEventRecord(g_prof.start[g_prof.used], st) == hipSuccess;
-    } else if (g_prof.open) {
-        (void)hipEventRecord(g_prof.stop[g_prof.used], st);
-        g_prof.open = false;
-        ++g_prof.used;
+        if (h->used >= (int)h->start.size()) return;
+        h->open = hipEventRecord(h->start[h->used], st) == hipSuccess;
+    } else if (h->open) {
+        (void)hipEventRecord(h->stop[h->used], st);
+        h->open = false;
+        ++h->used;
     }
 }
 }  // namespace sepattn
@@ -122,47 +128,61 @@ const char *sepattn_kernel_name(int kernel) {
     return (kernel >= 0 && kernel < SEPATTN_K_COUNT) ? names[kernel] : "unknown";
 }
 
-int sepattn_profile_begin(int kernel, int max_records) {
+int sepattn_profile_create(int kernel, int max_records, sepattn_profile **out) {
+    if (!out) return SEPATTN_ERR_NULL;
+    *out = nullptr;
     if (kernel < 0 || kernel >= SEPATTN_K_COUNT || max_records < 1 || max_records > (1 << 20))
         return SEPATTN_ERR_PARAM;
-    if (g_prof.kernel >= 0) return SEPATTN_ERR_PARAM;  // already profiling
-    g_prof.start.assign(max_records, nullptr);
-    g_prof.stop.assign(max_records, nullptr);
+    sepattn_profile *h = new (std::nothrow) sepattn_profile;
+    if (!h) return SEPATTN_ERR_HIP;
+    h->kernel = kernel;
+    h->start.assign(max_records, nullptr);
+    h->stop.assign(max_records, nullptr);
     for (int i = 0; i < max_records; ++i) {
-        if (hipEventCreate(&g_prof.start[i]) != hipSuccess || hipEventCreate(&g_prof.stop[i]) != hipSuccess) {
-            for (int k = 0; k <= i; ++k) {
-                if (g_prof.start[k]) (void)hipEventDestroy(g_prof.start[k]);
-                if (g_prof.stop[k]) (void)hipEventDestroy(g_prof.stop[k]);
-            }
-            g_prof.start.clear();
-            g_prof.stop.clear();
+        if (hipEventCreate(&h->start[i]) != hipSuccess || hipEventCreate(&h->stop[i]) != hipSuccess) {
+            (void)hipGetLastError();
+            sepattn_profile_destroy(h);
             return SEPATTN_ERR_HIP;
         }
     }
-    g_prof.used = 0;
-    g_prof.open = false;
-    g_prof.kernel = kernel;
+    *out = h;
     return SEPATTN_OK;
 }
 
-int sepattn_profile_end(float *ms, int *n_records) {
-    if (!ms || !n_records) return SEPATTN_ERR_NULL;
-    if (g_prof.kernel < 0) return SEPATTN_ERR_PARAM;
+void sepattn_profile_destroy(sepattn_profile *h) {
+    if (!h) return;
+    if (t_attached == h) t_attached = nullptr;
+    for (size_t i = 0; i < h->start.size(); ++i) {
+        if (h->start[i]) (void)hipEventDestroy(h->start[i]);
+        if (h->stop[i]) (void)hipEventDestroy(h->stop[i]);
+    }
+    delete h;
+}
+
+int sepattn_profile_attach(sepattn_profile *h) {
+    if (!h) return SEPATTN_ERR_NULL;
+    if (t_attached) return SEPATTN_ERR_PARAM;  // one handle per thread at a time
+    t_attached = h;
+    return SEPATTN_OK;
+}
+
+int sepattn_profile_detach(sepattn_profile *h) {
+    if (!h) return SEPATTN_ERR_NULL;
+    if (t_attached != h) return SEPATTN_ERR_PARAM;
+    t_attached = nullptr;
+    return SEPATTN_OK;
+}
+
+int sepattn_profile_read(sepattn_profile *h, float *ms, int max_records, int *n_records) {
+    if (!h || !ms || !n_records) return SEPATTN_ERR_NULL;
     int rc = SEPATTN_OK;
-    for (int i = 0; i < g_prof.used; ++i) {
-        if (hipEventSynchronize(g_prof.stop[i]) != hipSuccess ||
-            hipEventElapsedTime(&ms[i], g_prof.start[i], g_prof.stop[i]) != hipSuccess)
+    const int n = h->used < max_records ? h->used : max_records;
+    for (int i = 0; i < n; ++i) {
+        if (hipEventSynchronize(h->stop[i]) != hipSuccess ||
+            hipEventElapsedTime(&ms[i], h->start[i], h->stop[i]) != hipSuccess)
             rc = SEPATTN_ERR_HIP;
     }
-    *n_records = g_prof.used;
-    for (size_t i = 0; i < g_prof.start.size(); ++i) {
-        (void)hipEventDestroy(g_prof.start[i]);
-        (void)hipEventDestroy(g_prof.stop[i]);
-    }
-    g_prof.start.clear();
-    g_prof.stop.clear();
-    g_prof.kernel = -1;
-    g_prof.used = 0;
+    *n_records = n;
     return rc;
 }
 
@@ -175,6 +195,7 @@ int sepattn_mark_separators(const int32_t *token_ids, int B, int L, const int32_
     SepIdSet set;
     set.n = n_sep;
     for (int k = 0; k < SEPATTN_MAX_SEP_IDS; ++k) set.ids[k] = k < n_sep ? sep_ids[k] : sep_ids[0];
+    discard_stale_hip_error();
     return launch_mark(token_ids, (long)B * L, set, is_sep, static_cast<hipStream_t>(stream));
 }
 
@@ -183,6 +204,7 @@ int sepattn_mark_interval(int B, int L, int delta, int phase, uint8_t *is_sep, v
     if (B <= 0 || L <= 0) return SEPATTN_ERR_SHAPE;
     if (delta < 1 || phase < 0 || phase >= delta) return SEPATTN_ERR_PARAM;
     if (!aligned(is_sep, 4)) return SEPATTN_ERR_PARAM;
+    discard_stale_hip_error();
     return launch_mark_interval(B, L, delta, phase, is_sep, static_cast<hipStream_t>(stream));
 }
 
@@ -200,6 +222,7 @@ int sepattn_compact_indices(const uint8_t *is_sep, int B, int L, int32_t *sep_id
     if (cap < 1) return SEPATTN_ERR_CAPACITY;
     if (!workspace || workspace_bytes < sepattn_compact_workspace_bytes(B, L) || !aligned(workspace, 4))
         return SEPATTN_ERR_WORKSPACE;
+    discard_stale_hip_error();
     return launch_compact(is_sep, B, L, sep_idx, cap, sep_count, sep_prefix,
                           static_cast<int32_t *>(workspace), static_cast<hipStream_t>(stream));
 }
@@ -220,6 +243,7 @@ int sepattn_forward(const sepattn_params *p, const void *Q, const void *K, const
     if (need > 0 && (!ws || ws_bytes < need || !aligned(ws, 256))) return SEPATTN_ERR_WORKSPACE;
     sepattn_params q = normalised(p);
     hipStream_t st = static_cast<hipStream_t>(stream);
+    discard_stale_hip_error();
     if (q.dtype == SEPATTN_FP32)
         return launch_forward_fp32(q, (const float *)Q, (const float *)K, (const float *)V, sep_idx,
                                    sep_prefix, nullptr, (float *)O, LSE, st);
@@ -231,6 +255,7 @@ int sepattn_doc_bounds(const int32_t *cu_seqlens, int n_docs, int L, int a, int3
     if (!cu_seqlens || !doc_start || !doc_end) return SEPATTN_ERR_NULL;
     if (n_docs < 1 || L < 1 || n_docs > L) return SEPATTN_ERR_SHAPE;
     if (a < 0) return SEPATTN_ERR_PARAM;
+    discard_stale_hip_error();
     return launch_doc_bounds(cu_seqlens, n_docs, L, a, doc_start, doc_end, is_sep, static_cast<hipStream_t>(stream));
 }
 
@@ -246,6 +271,7 @@ int sepattn_forward_packed(const sepattn_params *p, const int32_t *doc_start, co
     if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16)) return SEPATTN_ERR_PARAM;
     size_t need = sepattn_forward_workspace_bytes(p);
     if (need > 0 && (!ws || ws_bytes < need || !aligned(ws, 256))) return SEPATTN_ERR_WORKSPACE;
+    discard_stale_hip_error();
     if (p->dtype == SEPATTN_FP32)
         return launch_forward_fp32(normalised(p), (const float *)Q, (const float *)K, (const float *)V, sep_idx,
                                    sep_prefix, doc_start, (float *)O, LSE, static_cast<hipStream_t>(stream));
@@ -274,6 +300,7 @@ int sepattn_backward(const sepattn_params *p, const void *Q, const void *K, cons
     if (!ws || ws_bytes < need || !aligned(ws, 256)) return SEPATTN_ERR_WORKSPACE;
     sepattn_params q = normalised(p);
     hipStream_t st = static_cast<hipStream_t>(stream);
+    discard_stale_hip_error();
     if (q.dtype == SEPATTN_FP32)
         return launch_backward_fp32(q, (const float *)Q, (const float *)K, (const float *)V,
                                     (const float *)O, LSE, (const float *)dO, sep_idx, sep_prefix, nullptr, nullptr,
@@ -298,6 +325,7 @@ int sepattn_backward_packed(const sepattn_params *p, const int32_t *doc_start, c
         return SEPATTN_ERR_PARAM;
     size_t need = sepattn_backward_workspace_bytes(p);
     if (!ws || ws_bytes < need || !aligned(ws, 256)) return SEPATTN_ERR_WORKSPACE;
+    discard_stale_hip_error();
     if (p->dtype == SEPATTN_FP32)
         return launch_backward_fp32(normalised(p), (const float *)Q, (const float *)K, (const float *)V,
                                     (const float *)O, LSE, (const float *)dO, sep_idx, sep_prefix, doc_start, doc_end,
@@ -320,6 +348,7 @@ int sepattn_decode(const sepkv_params *p, const void *q, const void *Kc, const v
     if (!q || !Kc || !Vc || !sizes || !out) return SEPATTN_ERR_NULL;
     if (!aligned(q, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(out, 16)) return SEPATTN_ERR_PARAM;
     if (!ws || ws_bytes < decode_workspace(*p) || !aligned(ws, 256)) return SEPATTN_ERR_WORKSPACE;
+    discard_stale_hip_error();
     return launch_decode(*p, q, Kc, Vc, sizes, nullptr, 0, out, lse, ws, static_cast<hipStream_t>(stream));
 }
 
@@ -329,6 +358,7 @@ int sepkv_rope_table(int n_pos, int d, double base, float *table, void *stream) 
     if (d != 64 && d != 128) return SEPATTN_ERR_DTYPE;
     if (!(base > 1.0) || base > 1e30) return SEPATTN_ERR_PARAM;
     if (!aligned(table, 16)) return SEPATTN_ERR_PARAM;
+    discard_stale_hip_error();
     return launch_rope_table(n_pos, d, base, table, static_cast<hipStream_t>(stream));
 }
 
@@ -342,6 +372,7 @@ int sepattn_decode_rope(const sepkv_params *p, const void *q, const void *Kc, co
     if (!aligned(q, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(out, 16) || !aligned(rope_table, 16))
         return SEPATTN_ERR_PARAM;
     if (!ws || ws_bytes < decode_workspace(*p) || !aligned(ws, 256)) return SEPATTN_ERR_WORKSPACE;
+    discard_stale_hip_error();
     return launch_decode(*p, q, Kc, Vc, sizes, rope_table, n_pos, out, lse, ws, static_cast<hipStream_t>(stream));
 }
 
@@ -351,6 +382,7 @@ int sepkv_append(const sepkv_params *p, const void *k_new, const void *v_new, co
     if (rc != SEPATTN_OK) return rc;
     if (!k_new || !v_new || !is_sep_new || !Kc || !Vc || !win_is_sep || !sizes) return SEPATTN_ERR_NULL;
     if (!aligned(k_new, 16) || !aligned(v_new, 16) || !aligned(Kc, 16) || !aligned(Vc, 16)) return SEPATTN_ERR_PARAM;
+    discard_stale_hip_error();
     return launch_cache_append(*p, k_new, v_new, is_sep_new, Kc, Vc, win_is_sep, sizes,
                                static_cast<hipStream_t>(stream));
 }
@@ -367,6 +399,7 @@ int sepkv_evict_window(const sepkv_params *p, void *Kc, void *Vc, uint8_t *win_i
     if (!Kc || !Vc || !win_is_sep || !sizes) return SEPATTN_ERR_NULL;
     if (!aligned(Kc, 16) || !aligned(Vc, 16)) return SEPATTN_ERR_PARAM;
     if (!ws || ws_bytes < evict_workspace(*p) || !aligned(ws, 256)) return SEPATTN_ERR_WORKSPACE;
+    discard_stale_hip_error();
     return launch_evict(*p, Kc, Vc, win_is_sep, sizes, ws, static_cast<hipStream_t>(stream));
 }
 
@@ -381,6 +414,7 @@ int sepkv_fill_from_prefill(const sepkv_params *p, int L, int nw, const void *K,
     const int n_init = p->a < L ? p->a : L;
     if (nw < 0 || nw > p->c - p->a - p->s || nw > L - n_init) return SEPATTN_ERR_PARAM;
     if (!aligned(K, 16) || !aligned(V, 16) || !aligned(Kc, 16) || !aligned(Vc, 16)) return SEPATTN_ERR_PARAM;
+    discard_stale_hip_error();
     return launch_cache_fill(*p, L, nw, K, V, is_sep, sep_idx, cap, sep_prefix, Kc, Vc, win_is_sep, sizes,
                              static_cast<hipStream_t>(stream));
 }

@@ -34,16 +34,6 @@
 #include "bwd_common.h"
 #include "mfma_common.h"
 
-#ifdef SEPATTN_X_TIMING
-__device__ unsigned long long g_dbg_dkv[4 * 16384];
-__device__ unsigned long long g_dbg_dkv_w[16384 * 8 * 4];  // per unit and wave: loop, wait, barrier cycles, blocks
-extern "C" int sepattn_debug_read_dkv_w(unsigned long long *host, int n) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg_dkv_w), sizeof(unsigned long long) * n);
-}
-extern "C" int sepattn_debug_read_dkv(unsigned long long *host, int n) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg_dkv), sizeof(unsigned long long) * n);
-}
-#endif
 
 namespace sepattn {
 
@@ -159,10 +149,6 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
     long cum_next = 0, grp_cum = 0;
     int g_fq = 0, g_nq = 0, g_excl = 0;
     unsigned long long pend = 0;
-#ifdef SEPATTN_X_TIMING
-    const unsigned long long t_begin = wall_clock64();
-    unsigned long long tw_acc = 0, tb_acc = 0, tl_acc = 0, nblk_acc = 0;
-#endif
     for (;;) {
         bool FAR = false, have = false;
         int ft = 0, fq0 = 0, item0 = 0, n_items = 0, unit = 0, n_qt = 1;
@@ -544,23 +530,12 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
         // (first contraction): every wave first waits for its share of the tiles the next step needs,
         // and after the barrier the buffers of the tiles below the lowest one still in use are refilled.
         auto block_barrier = [&]() __attribute__((always_inline)) {
-#ifdef SEPATTN_X_TIMING
-            const unsigned long long tt0 = clock64();
-#endif
             if (hi_next != hi_landed) {
                 wait_tiles(iss_tt - 1 - hi_next);
                 hi_landed = hi_next;
             }
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#ifdef SEPATTN_X_TIMING
-            const unsigned long long tt1 = clock64();
-#endif
             __builtin_amdgcn_s_barrier();
-#ifdef SEPATTN_X_TIMING
-            const unsigned long long tt2 = clock64();
-            tw_acc += tt1 - tt0;
-            tb_acc += tt2 - tt1;
-#endif
             while (iss_tt < n_tiles && iss_tt - NBUF < lo_cur) issue_tile();
         };
 
@@ -631,17 +606,10 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
                 gemm2(tfr, xb);
             }
         };
-#ifdef SEPATTN_X_TIMING
-        const unsigned long long c_loop0 = clock64();
-#endif
         if (role == 0)
             pipeline(IntC<0>{});
         else
             pipeline(IntC<1>{});
-#ifdef SEPATTN_X_TIMING
-        tl_acc += clock64() - c_loop0;
-        nblk_acc += n_blocks;
-#endif
 
         // ---- epilogue: the P-wave owns dV, the dS-wave owns dK (times scale).  A far piece writes its
         // partial (slot w + ft, row = entry within the list tile); a band unit finishes keys that are
@@ -684,21 +652,6 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
             }
         }
     }  // pieces
-#ifdef SEPATTN_X_TIMING
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    if (lane == 0 && blockIdx.x < 4096) {
-        unsigned long long *w = &g_dbg_dkv_w[((long)blockIdx.x * 8 + wave) * 4];
-        w[0] = tl_acc;
-        w[1] = tw_acc;
-        w[2] = tb_acc;
-        w[3] = nblk_acc;
-        if (wave == 0) {
-            g_dbg_dkv[4 * blockIdx.x + 0] = t_begin;
-            g_dbg_dkv[4 * blockIdx.x + 1] = wall_clock64();
-            g_dbg_dkv[4 * blockIdx.x + 3] = nblk_acc;
-        }
-    }
-#endif
 }
 
 // Sum of the partials of every far-list key (the far pieces of its list tile in ascending workgroup

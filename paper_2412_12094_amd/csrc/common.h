@@ -12,6 +12,9 @@ namespace sepattn {
 constexpr int kWave = 64;
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? SEPATTN_OK : SEPATTN_ERR_HIP; }
+// An error that an earlier, unrelated runtime call of the caller left pending would otherwise be read
+// (and blamed on this call) by the first launch_status(): every entry point discards it first.
+inline void discard_stale_hip_error() { (void)hipGetLastError(); }
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

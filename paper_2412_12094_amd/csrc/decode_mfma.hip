@@ -32,15 +32,6 @@
 #include "mfma_common.h"
 #include "decode_common.h"
 
-#ifdef SEPATTN_X_TIMING
-__device__ unsigned long long g_dbg_dec[8 * 4096];
-extern "C" int sepattn_debug_read_dec(unsigned long long *host, int n) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg_dec), sizeof(unsigned long long) * n);
-}
-#define DSTAMP(k) if (lane == 0 && gridDim.x == 1) g_dbg_dec[((blockIdx.z * gridDim.y + blockIdx.y) % 1024 * 4 + wave) * 8 + (k)] = wall_clock64();
-#else
-#define DSTAMP(k)
-#endif
 
 namespace sepattn {
 
@@ -77,7 +68,6 @@ __global__ __launch_bounds__(kDmThreads, 1) void decode_mfma_kernel(
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, hh = lane >> 5;  // column of the B operand = query head of the group
-    DSTAMP(0)
     // grid (nsplit, Hkv, S): no integer division on the way to the first load
     const int nsplit = gridDim.x, split = blockIdx.x, kv = blockIdx.y, sq = blockIdx.z;
     const int h0 = kv * G;
@@ -145,7 +135,6 @@ __global__ __launch_bounds__(kDmThreads, 1) void decode_mfma_kernel(
     const int a_row = pi_row(col);
     if (n_my > 0) issue_stage(0);
     if (n_my > 1) issue_stage(1);
-    DSTAMP(1)
     // queries as B operands: column = head of the group, zero beyond G
     bf16x8 qreg[KSTEPS];
 #pragma unroll
@@ -180,10 +169,6 @@ __global__ __launch_bounds__(kDmThreads, 1) void decode_mfma_kernel(
 
     for (int k = 0; k < n_my; ++k) {
         wait_older_stage(k + 1 < n_my);
-#ifdef SEPATTN_X_TIMING
-        if (k == 0) { DSTAMP(2) }
-        if (k == n_my - 1) { DSTAMP(3) }
-#endif
         const uint16_t *Kst = Ks[wave][k % kDmStages];
         const uint16_t *Vst = Vs[wave][k % kDmStages];
         const int n_valid = e1 - (e0 + (wave + kDmWaves * k) * kDmRows);  // >= 1; >= 32 except in the last block
@@ -260,7 +245,6 @@ __global__ __launch_bounds__(kDmThreads, 1) void decode_mfma_kernel(
 
     }
 
-    DSTAMP(4)
     // ---- merge the four waves' states through LDS (the rings are no longer in use)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
@@ -310,10 +294,6 @@ __global__ __launch_bounds__(kDmThreads, 1) void decode_mfma_kernel(
             }
         }
     }
-#ifdef SEPATTN_X_TIMING
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    DSTAMP(5)
-#endif
 }
 
 }  // namespace

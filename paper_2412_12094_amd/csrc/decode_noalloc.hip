@@ -50,6 +50,7 @@ int sepattn_decode_noalloc(const sepkv_params *p, const void *q, const void *Kc,
     if (sepattn::decode_workspace(*p) > (size_t)SEPATTN_DECODE_NOALLOC_SCRATCH_BYTES) return SEPATTN_ERR_WORKSPACE;
     void *ptr = scratch_of_current_device();
     if (!ptr) return SEPATTN_ERR_HIP;
+    sepattn::discard_stale_hip_error();
     // every slot of the partials that the merge step reads is written by this call's first kernel, so
     // nothing has to be cleared between calls
     return sepattn::launch_decode(*p, q, Kc, Vc, sizes, nullptr, 0, out, lse, ptr, static_cast<hipStream_t>(stream));

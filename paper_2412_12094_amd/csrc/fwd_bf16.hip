@@ -24,21 +24,6 @@
 #include "mfma_common.h"
 #include "key_stream.h"
 
-// Phase timing for tuning (compile with -DSEPATTN_X_TIMING; never defined in the product build)
-#ifdef SEPATTN_X_TIMING
-__device__ unsigned long long g_dbg[8 * 8 * 2048];
-extern "C" int sepattn_debug_read(unsigned long long *host, int n) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg), sizeof(unsigned long long) * n);
-}
-#define TICK(k)                              \
-    {                                        \
-        unsigned long long now_ = clock64(); \
-        tacc[k] += now_ - tlast;             \
-        tlast = now_;                        \
-    }
-#else
-#define TICK(k)
-#endif
 
 namespace sepattn {
 
@@ -76,9 +61,6 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     __shared__ __attribute__((aligned(16))) int lo_s[VST][kBN];
     __shared__ __attribute__((aligned(16))) int hi_s[VST][kBN];
 
-#ifdef SEPATTN_X_TIMING
-    const unsigned long long w_start = wall_clock64();
-#endif
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps branches scalar
     const int grp = wave >> 2;                                  // waves w and w+4 share a SIMD
@@ -111,9 +93,6 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     FullBlocks fullb = {};
     bf16x8 qreg[KSTEPS];  // this wave's queries as B operands
     const float sl2 = p.scale * kLog2e_f;
-#ifdef SEPATTN_X_TIMING
-    unsigned long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tlast = clock64();
-#endif
 
     f32x16 oacc[DB];
     float m_run = -INFINITY, l_run = 0.f;  // m_run in the log2 domain (scores times scale*log2e)
@@ -461,11 +440,8 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     // barrier that publishes tile X: this wave's loads of tile X have landed (everything older than
     // the previous step's [1 entry load][2*LOADS row loads])
     auto publish = [&]() __attribute__((always_inline)) {
-        TICK(2)
         wait_older_loads();
-        TICK(0)
         wg_barrier();
-        TICK(4)
     };
 
     // ---- start-up, once per workgroup: the first two tiles of the concatenated stream on their way
@@ -523,7 +499,6 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     for (int X = 1; X < n_tiles; ++X) {
         publish();
         half_step(X, first_block, yes, yes, yes, yes, s_a, p_a, s_b, p_b, X - 1, 1);
-        TICK(1)
         half_step(X, second_block, yes, yes, yes, no, s_b, p_b, s_a, p_a, X, 0);
     }
     // last step: output updates of the last tile, softmax of its second block; the queries of the
@@ -533,15 +508,6 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     half_step(n_tiles, first_block, no, yes, yes, no, s_a, p_a, s_b, p_b, n_tiles - 1, 1);
     half_step(n_tiles, second_block, no, yes, no, no, s_b, p_b, s_a, p_a, n_tiles, 0);
     gbase += n_tiles;
-#ifdef SEPATTN_X_TIMING
-    const unsigned long long w_loop1 = wall_clock64();
-    if (lane == 0 && blockIdx.x < 2048) {
-        tacc[6] = w_loop1 - w_start;  // wall clock since the workgroup started, at the end of this segment
-        tacc[7] = w_start;
-        tacc[5] += n_tiles;
-        for (int k = 0; k < 8; ++k) g_dbg[((long)blockIdx.x * 8 + wave) * 8 + k] = tacc[k];
-    }
-#endif
 
     // epilogue: normalise, store O (bf16) and LSE (natural log)
     if (__builtin_amdgcn_ballot_w64(alpha_pending != 1.f) != 0ull) {

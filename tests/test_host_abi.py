@@ -115,7 +115,12 @@ def test_cache_call_validation(sp):
     assert dec(kv_params(sp, w=0)) == 3
     assert dec(kv_params(sp, d=100)) == 4
     assert dec(kv_params(sp, S=0)) == 2
+    assert dec(kv_params(sp, c=(1 << 23) + 1)) == 2            # a slot's byte offset would not fit 32 bits
+    assert dec(kv_params(sp, c=1 << 22)) == 5                  # the largest cache that does (then: no workspace)
     assert dec(ok) == 5                                        # workspace missing
+    na = lambda p, q=FAKE: lib.sepattn_decode_noalloc(ctypes.byref(p), q, FAKE, FAKE, FAKE, FAKE, None, None)
+    assert na(ok, None) == 1 and na(kv_params(sp, w=0)) == 3 and na(kv_params(sp, d=100)) == 4
+    assert na(kv_params(sp, S=4096, Hq=8, Hkv=8, c=200)) == 5  # partial results beyond the fixed scratch array
     ev = lambda p, k=FAKE: lib.sepkv_evict_window(ctypes.byref(p), k, FAKE, FAKE, FAKE, None, 0, None)
     assert ev(ok, None) == 1 and ev(ok) == 5
     assert ev(kv_params(sp, Hq=7, Hkv=2)) == 2
@@ -123,10 +128,14 @@ def test_cache_call_validation(sp):
 
 def test_profile_hook_argument_checks(sp):
     lib = sp.load()
-    assert lib.sepattn_profile_begin(-1, 4) == 3 and lib.sepattn_profile_begin(3, 0) == 3
+    h = ctypes.c_void_p()
+    assert lib.sepattn_profile_create(-1, 4, ctypes.byref(h)) == 3 and lib.sepattn_profile_create(3, 0, ctypes.byref(h)) == 3
+    assert lib.sepattn_profile_create(3, 4, None) == 1 and not h
+    assert lib.sepattn_profile_attach(None) == 1 and lib.sepattn_profile_detach(None) == 1
     n = ctypes.c_int(0)
     ms = (ctypes.c_float * 4)()
-    assert lib.sepattn_profile_end(ms, ctypes.byref(n)) == 3  # not started
+    assert lib.sepattn_profile_read(None, ms, 4, ctypes.byref(n)) == 1
+    lib.sepattn_profile_destroy(None)  # a no-op
     names = {sp.sepattn_kernel_name(k) for k in range(16)}
     assert len(names) == 16 and sp.sepattn_kernel_name(16) == "unknown"
 

@@ -73,6 +73,8 @@ def main() -> int:
                          "of a second of load to reach its steady state")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the cfg2 (L=2048 training shape), cfg4 (64K prefill) and mark+compact legs")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (--gpus must be 1)",
@@ -229,6 +231,9 @@ def main() -> int:
                      "ms_per_step": round(packed_ms, 4), "visible_pairs_per_head": int(packed_pairs),
                      "tflops": round(14.0 * c.d * packed_pairs * c.Hq / (packed_ms * 1e-3) / 1e12, 2)}
 
+    if not args.no_other_configs:
+        del Q, K, V, dO, O, LSE, dQ, dK, dV, bws
+        out["other_configs"] = bench_other_configs(torch, sp, wl, args.ramp_seconds)
     if not args.no_decode:
         out["decode"] = bench_decode(torch, sp, wl, args.ramp_seconds)
     if not args.no_cpu_baseline:
@@ -244,6 +249,111 @@ def ramp_until(torch, step, seconds):
         for _ in range(20):
             step()
         torch.cuda.synchronize()
+
+
+def bench_other_configs(torch, sp, wl, ramp_seconds):
+    """The other training / prefill configurations, each against the roofline that bounds it:
+    cfg2 (B=8, 12 heads, d=64, L=2048, forward + backward) is HBM-bound, cfg4 (L=65536 forward) is bound by
+    the matrix cores, separator marking + compaction by launch latency (reported in us and GB/s)."""
+    res = {}
+    sep_ids = wl.SEPARATOR_IDS.tolist()
+    for name, do_bwd, steps in (("cfg2", True, 100), ("cfg4", False, 20)):
+        c = wl.CONFIGS[name]
+        inp = wl.config_inputs(c)
+        bf = lambda x: torch.from_numpy(x).cuda().to(torch.bfloat16).contiguous()
+        tok = torch.from_numpy(inp["token_ids"]).cuda()
+        Q, K, V = bf(inp["Q"]), bf(inp["K"]), bf(inp["V"])
+        dev = Q.device
+        is_sep = torch.empty((c.B, c.L), dtype=torch.uint8, device=dev)
+        idx = torch.full((c.B, c.L), -1, dtype=torch.int32, device=dev)
+        cnt = torch.empty((c.B,), dtype=torch.int32, device=dev)
+        pre = torch.empty((c.B, c.L + 1), dtype=torch.int32, device=dev)
+        cws = torch.empty(1 << 16, dtype=torch.uint8, device=dev)
+        O = torch.empty_like(Q)
+        LSE = torch.empty((c.B, c.Hq, c.L), dtype=torch.float32, device=dev)
+        fws = torch.empty(256, dtype=torch.uint8, device=dev)
+        if do_bwd:
+            dO = bf(inp["dO"])
+            dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+            bws = torch.empty(sp.sepattn_backward_workspace_bytes(Q, K, c.a, c.n, c.scale, c.L), dtype=torch.uint8,
+                              device=dev)
+
+        def index_step():
+            sp.sepattn_mark_separators(tok, sep_ids, out=is_sep)
+            sp.sepattn_compact_indices(is_sep, out=(idx, cnt, pre), ws=cws)
+
+        def step():
+            index_step()
+            sp.sepattn_forward(Q, K, V, idx, cnt, pre, c.a, c.n, c.scale, out=(O, LSE), ws=fws)
+            if do_bwd:
+                sp.sepattn_backward(Q, K, V, O, LSE, dO, idx, cnt, pre, c.a, c.n, c.scale, out=(dQ, dK, dV), ws=bws)
+
+        ramp_until(torch, step, min(ramp_seconds, 0.5))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        ms = 1e3 * (time.perf_counter() - t0) / steps
+        kernels = ["mark", "compact_count", "compact_write", "forward"] + (["bwd_dq", "bwd_dkv", "bwd_combine"] if do_bwd else [])
+        k_us = {}
+        for kn in kernels:
+            prof = sp.sepattn_profile_begin(sp.KERNEL_IDS[kn], 10)
+            for _ in range(10):
+                step()
+            torch.cuda.synchronize()
+            rec = sp.sepattn_profile_end(prof)
+            if rec:
+                k_us[kn] = round(1e3 * float(np.median(rec)), 2)
+        flags = is_sep.cpu().numpy()
+        p_vis = sum(count_visible_pairs(flags[b], c.a, c.n) for b in range(c.B))
+        flops = (14.0 if do_bwd else 4.0) * c.d * p_vis * c.Hq
+        tflops = flops / (ms * 1e-3) / 1e12
+        # algorithmic HBM bytes of the step: every operand read once, every result written once
+        qb, kb, lb = Q.numel() * 2, K.numel() * 2, LSE.numel() * 4
+        bytes_fwd = qb + 2 * kb + qb + lb
+        bytes_bwd = (qb + 2 * kb + qb + qb + lb) + (qb + 2 * kb) if do_bwd else 0
+        leg = {"workload": f"{name}: B={c.B}, Hq={c.Hq}, Hkv={c.Hkv}, d={c.d}, L={c.L}, a={c.a}, n={c.n}, separator density "
+                           f"{c.p}; mark + compact + forward" + (" + backward" if do_bwd else "") + " per step",
+               "ms_per_step": round(ms, 4), "visible_pairs_all_sequences_per_head": int(p_vis),
+               "tflops": round(tflops, 2), "pct_of_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
+               "tokens_per_s": round(c.B * c.L / (ms * 1e-3), 1), "kernel_us": k_us}
+        if name == "cfg2":
+            gbs = (bytes_fwd + bytes_bwd) / (ms * 1e-3) / 1e9
+            leg["roofline"] = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                               "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get("cfg2_step"),
+                               "algorithmic_bytes_per_step": int(bytes_fwd + bytes_bwd)}
+        else:
+            f_us = k_us.get("forward", float("nan"))
+            ach = flops / (f_us * 1e-6) / 1e12
+            leg["roofline"] = {"bound": "mfma", "kernel": "fwd_bf16_kernel", "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS,
+                               "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
+                               "traffic": MEASURED_TRAFFIC_BYTES.get("cfg4_forward"), "avg_launch_us": f_us,
+                               "algorithmic_gflop_per_launch": round(flops / 1e9, 1)}
+        res[name] = leg
+        # separator marking + compaction alone, at this configuration's sizes
+        for _ in range(20):
+            index_step()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(100):
+            index_step()
+        e1.record()
+        torch.cuda.synchronize()
+        idx_us = e0.elapsed_time(e1) * 1e3 / 100
+        n_tok, n_sep = c.B * c.L, int(flags.sum())
+        idx_bytes = 5 * n_tok + (n_tok + 4 * (n_tok + c.B) + 4 * n_sep + 4 * c.B)   # mark: 4 B in, 1 B out; compact
+        res[name]["mark_compact"] = {"us": round(idx_us, 2), "kernel_us": {k: k_us[k] for k in k_us if k.startswith(("mark", "compact"))},
+                                     "algorithmic_bytes": int(idx_bytes),
+                                     "roofline": {"bound": "hbm", "achieved": round(idx_bytes / idx_us / 1e3, 2), "peak": PEAK_HBM_GBS,
+                                                  "unit": "GB/s", "frac": round(idx_bytes / idx_us / 1e3 / PEAK_HBM_GBS, 6),
+                                                  "traffic": None, "note": "launch-latency bound: two or three launches of a few microseconds"}}
+        del Q, K, V, O, LSE
+        if do_bwd:
+            del dO, dQ, dK, dV, bws
+        torch.cuda.empty_cache()
+    return res
 
 
 def bench_decode(torch, sp, wl, ramp_seconds):
@@ -406,8 +516,8 @@ def cpu_baseline(wl, inp, flags, c, p_vis):
     return {"value": round(flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": min(cores, threads),
             "kind": "oracle", "seconds": round(dt, 2),
             "sample": f"the whole cfg3 workload ({c.Hkv} KV heads x {G} query heads, all {c.L} rows), forward + "
-                      "backward, fp32 build of the oracle, OpenMP; flops counted on visible pairs only "
-                      "(the oracle itself computes the dense L x L scores)"}
+                      "backward, fp32 build of the oracle, OpenMP; flops counted on visible pairs (the oracle "
+                      "walks every one of the L x L pairs of its explicit mask and computes a score where it is set)"}
 
 
 if __name__ == "__main__":

@@ -362,7 +362,8 @@ def bench_decode(torch, sp, wl, ramp_seconds):
     data = wl.make_cache(c)
     bf = lambda x: torch.from_numpy(x).cuda().to(torch.bfloat16).contiguous()
     q, Kc, Vc = bf(data["q"]), bf(data["Kc"]), bf(data["Vc"])
-    sizes = torch.from_numpy(data["sizes"]).cuda()
+    # sizes: (Size_init, Size_sep, Size_past_w, Size_local_w, head_sep, head_win); the two rings start at slot 0
+    sizes = torch.from_numpy(np.concatenate([data["sizes"], np.zeros((c.S, 2), np.int32)], axis=1)).cuda()
     out = torch.empty_like(q)
     lse = torch.empty((c.S, c.Hq), dtype=torch.float32, device=q.device)
     ws = torch.empty(1 << 24, dtype=torch.uint8, device=q.device)
@@ -440,12 +441,15 @@ def bench_decode(torch, sp, wl, ramp_seconds):
         times.append(e0.elapsed_time(e1) * 1e3)
     kept = int(data["win_is_sep"][:, : c.window_capacity - c.w].sum())
     row = c.d * 2
-    # rows the method must move: kept past-window rows, plus (separator cache full) the surviving
-    # separator rows shifted down and the local window slid to the front; read + write, K and V
-    moved_rows = kept + int((c.s * c.S) - kept) + c.w * c.S
-    res["evict"] = {"us": round(float(np.median(times[2:])), 2), "kept_past_window_rows_all_sequences": kept, "moved_rows_per_sequence_and_head": c.s + c.w,
-                    "moved_bytes": int(moved_rows * row * 2 * 2 * c.Hkv),
-                    "gbs": round(moved_rows * row * 2 * 2 * c.Hkv / float(np.median(times[2:])) / 1e3, 1)}
+    # rows the method must move: the kept Past-Window rows and nothing else (the Separator Cache and the window
+    # are rings: dropping the oldest separators and the Past Window moves heads, not rows); read + write, K and V
+    ev_us = float(np.median(times[2:]))
+    ev_bytes = kept * row * 2 * 2 * c.Hkv
+    res["evict"] = {"us": round(ev_us, 2), "kept_past_window_rows_all_sequences": kept, "moved_bytes": int(ev_bytes),
+                    "roofline": {"bound": "hbm", "achieved": round(ev_bytes / ev_us / 1e3, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                 "frac": round(ev_bytes / ev_us / 1e3 / PEAK_HBM_GBS, 4),
+                                 "traffic": MEASURED_TRAFFIC_BYTES.get("evict_move"),
+                                 "note": "two launches (plan, move) of a few microseconds each: launch-latency bound"}}
     # the generation step (append + decode) captured once and replayed as a HIP graph
     sz_g, fl_g = sz_room.clone(), torch.from_numpy(data["win_is_sep"]).cuda()
     torch.cuda.synchronize()

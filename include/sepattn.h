@@ -183,13 +183,22 @@ int sepattn_backward_packed(const sepattn_params *p, const int32_t *doc_start,
  * Streaming generation on the four-block KV cache (Sec. 3.3).
  * Cache layout, per (sequence, KV head): c slots of d values,
  *     [0, a)       Initial Cache
- *     [a, a+s)     Separator Cache, oldest first
- *     [a+s, c)     window: Past Window Cache followed by Local Window Cache, oldest first
- * sizes[S,4] = (Size_init, Size_sep, Size_past_w, Size_local_w): valid entries of each block,
- * counted from the start of its slot range (the window's Size_past_w + Size_local_w entries start
- * at slot a+s).  Requires 0 <= Size_init <= a, 0 <= Size_sep <= s,
- * Size_past_w + Size_local_w <= c-a-s; sizes are read on the device and not validated there.
+ *     [a, a+s)     Separator Cache, a ring: separator k (oldest first) sits in slot
+ *                  a + (head_sep + k) mod s
+ *     [a+s, c)     window, a ring of c-a-s slots: entry u (oldest first: the Past Window Cache,
+ *                  then the Local Window Cache) sits at window index (head_win + u) mod (c-a-s),
+ *                  i.e. in slot a+s + that index; win_is_sep is indexed by window index
+ * sizes[S, SEPKV_SIZES_COLS = 6] = (Size_init, Size_sep, Size_past_w, Size_local_w, head_sep, head_win):
+ * valid entries of each block and the two ring heads (0 for a cache that has never dropped
+ * anything).  The rings are what lets the compression step move only the rows the method says
+ * must move: dropping the oldest separators or the Past Window advances a head.  Requires
+ * 0 <= Size_init <= a, 0 <= Size_sep <= s, Size_past_w + Size_local_w <= c-a-s,
+ * 0 <= head_sep < max(s, 1), 0 <= head_win < c-a-s; sizes are read on the device and clamped to
+ * these ranges there (a value outside them gives wrong results, never an access out of bounds).
+ * "Position within the cache" (sepattn_decode_rope) is the rank of an entry in age order over
+ * Initial, Separator, Past Window, Local Window, whatever slots the entries occupy.
  * ------------------------------------------------------------------------------------------ */
+#define SEPKV_SIZES_COLS 6
 typedef struct {
     int S;       /* sequences                                                                  */
     int Hq;      /* query heads                                                                */
@@ -208,7 +217,7 @@ typedef struct {
  * caller appends the current token's K/V before calling.
  *   q        DEVICE dtype [S, Hq, d]
  *   Kc, Vc   DEVICE dtype [S, Hkv, c, d]
- *   sizes    DEVICE int32 [S, 4]; a sequence with no valid entry yields out = 0, lse = -inf
+ *   sizes    DEVICE int32 [S, 6]; a sequence with no valid entry yields out = 0, lse = -inf
  *   out      DEVICE dtype [S, Hq, d]  out
  *   lse      DEVICE fp32  [S, Hq]     out, may be NULL
  *   ws       DEVICE, >= sepattn_decode_workspace_bytes(p) bytes, 256-byte aligned
@@ -264,7 +273,7 @@ int sepattn_decode_noalloc(const sepkv_params *p, const void *q, const void *Kc,
  *   is_sep_new    DEVICE uint8 [S]              whether the token is a separator
  *   Kc, Vc        DEVICE dtype [S, Hkv, c, d]   in/out
  *   win_is_sep    DEVICE uint8 [S, c-a-s]       in/out
- *   sizes         DEVICE int32 [S, 4]           in/out
+ *   sizes         DEVICE int32 [S, 6]           in/out
  */
 int sepkv_append(const sepkv_params *p, const void *k_new, const void *v_new,
                  const uint8_t *is_sep_new, void *Kc, void *Vc, uint8_t *win_is_sep,
@@ -273,19 +282,21 @@ int sepkv_append(const sepkv_params *p, const void *k_new, const void *v_new,
 /* Compression step (Sec. 3.3; caption of the streaming-design figure): the separators of the Past
  * Window Cache are appended to the Separator Cache, its other entries are dropped, and the Local
  * Window becomes the whole window.  If the Separator Cache would exceed s, its oldest entries are
- * dropped first.  IN PLACE; rows are moved bit-exactly.
+ * dropped (first in, first out).  IN PLACE; rows are copied bit-exactly, and only the kept
+ * Past-Window rows are copied at all: the rest is a change of the ring heads.
  *   Kc, Vc      DEVICE dtype [S, Hkv, c, d]  in/out
- *   win_is_sep  DEVICE uint8 [S, c-a-s]      in/out: separator flag of each window slot; the
- *                                            flags of the surviving Local Window move with it
- *   sizes       DEVICE int32 [S, 4]          in/out: becomes (Size_init,
- *                                            min(s, Size_sep + k), 0, Size_local_w), k = number
- *                                            of flagged Past-Window entries
+ *   win_is_sep  DEVICE uint8 [S, c-a-s]      separator flag by window index; not written (the
+ *                                            flags of the surviving Local Window stay in place)
+ *   sizes       DEVICE int32 [S, 6]          in/out: becomes (Size_init, min(s, Size_sep + k), 0,
+ *                                            Size_local_w, head_sep + dropped separators mod s,
+ *                                            head_win + Size_past_w mod (c-a-s)), k = number of
+ *                                            flagged Past-Window entries
  *   ws          DEVICE, >= sepkv_evict_workspace_bytes(p) bytes, 256-byte aligned
- * Slots beyond the new sizes hold unspecified data afterwards.  The caller decides when to call
+ * Slots outside the valid entries hold unspecified data afterwards.  The caller decides when to call
  * (the paper triggers it when Size_run reaches c).
  */
 size_t sepkv_evict_workspace_bytes(const sepkv_params *p);
-int sepkv_evict_window(const sepkv_params *p, void *Kc, void *Vc, uint8_t *win_is_sep,
+int sepkv_evict_window(const sepkv_params *p, void *Kc, void *Vc, const uint8_t *win_is_sep,
                        int32_t *sizes, void *ws, size_t ws_bytes, void *stream);
 
 /* Hand-over from prefill to the cache (Sec. 3.2 "Generation": only the KV of initial, separator and
@@ -304,7 +315,7 @@ int sepkv_evict_window(const sepkv_params *p, void *Kc, void *Vc, uint8_t *win_i
  *                sepattn_compact_indices (cap >= the number of separators, else the newest listed ones)
  *   Kc, Vc       DEVICE dtype [S, Hkv, c, d]     out; slots beyond the new sizes are left untouched
  *   win_is_sep   DEVICE uint8 [S, c-a-s]         out: separator flag of each window entry
- *   sizes        DEVICE int32 [S, 4]             out: (min(a, L), kept separators, nw - Size_local_w, Size_local_w)
+ *   sizes        DEVICE int32 [S, 6]             out: (min(a, L), kept separators, nw - Size_local_w, Size_local_w, 0, 0)
  * Errors: SEPATTN_ERR_PARAM if nw is out of range.
  */
 int sepkv_fill_from_prefill(const sepkv_params *p, int L, int nw, const void *K, const void *V,

@@ -400,9 +400,9 @@ def _kv_params(q, Kc, a, s, w, scale) -> SepkvParams:
 
 def sepattn_decode(q, Kc, Vc, sizes, a: int, s: int, w: int, scale: float,
                    out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None, ws: Optional[torch.Tensor] = None):
-    """q [S,Hq,d], Kc,Vc [S,Hkv,c,d], sizes int32 [S,4] -> (out [S,Hq,d], lse fp32 [S,Hq])."""
+    """q [S,Hq,d], Kc,Vc [S,Hkv,c,d], sizes int32 [S,6] -> (out [S,Hq,d], lse fp32 [S,Hq])."""
     _dev(q, Kc, Vc, sizes)
-    assert sizes.dtype == torch.int32
+    assert sizes.dtype == torch.int32 and sizes.dim() == 2 and sizes.shape[1] == 6 and sizes.is_contiguous()
     p = _kv_params(q, Kc, a, s, w, scale)
     lib = load()
     if out is None:
@@ -423,7 +423,7 @@ def sepattn_decode_noalloc(q, Kc, Vc, sizes, a: int, s: int, w: int, scale: floa
     """sepattn_decode without a workspace (the library's fixed scratch array is used); the caller passes
     the outputs (out [S,Hq,d], lse fp32 [S,Hq]), so nothing at all is allocated by the call."""
     _dev(q, Kc, Vc, sizes)
-    assert sizes.dtype == torch.int32
+    assert sizes.dtype == torch.int32 and sizes.dim() == 2 and sizes.shape[1] == 6 and sizes.is_contiguous()
     p = _kv_params(q, Kc, a, s, w, scale)
     o, lse = out
     _check("sepattn_decode_noalloc",
@@ -446,7 +446,8 @@ def sepattn_decode_rope(q, Kc, Vc, sizes, rope_table, a: int, s: int, w: int, sc
     """As sepattn_decode, with q and the cached keys stored without position encoding and turned by
     their positions within the cache inside the kernel; rope_table from sepkv_rope_table."""
     _dev(q, Kc, Vc, sizes, rope_table)
-    assert sizes.dtype == torch.int32 and rope_table.dtype == torch.float32
+    assert sizes.dtype == torch.int32 and sizes.dim() == 2 and sizes.shape[1] == 6 and sizes.is_contiguous()
+    assert rope_table.dtype == torch.float32
     assert rope_table.dim() == 3 and rope_table.shape[1] == 2 and rope_table.shape[2] * 2 == q.shape[2]
     p = _kv_params(q, Kc, a, s, w, scale)
     lib = load()
@@ -466,7 +467,8 @@ def sepattn_decode_rope(q, Kc, Vc, sizes, rope_table, a: int, s: int, w: int, sc
 def sepkv_append(k_new, v_new, is_sep_new, Kc, Vc, win_is_sep, sizes, Hq: int, a: int, s: int, w: int) -> None:
     """In place: k_new, v_new [S,Hkv,d] and is_sep_new uint8 [S] enter Kc, Vc [S,Hkv,c,d], win_is_sep, sizes."""
     _dev(k_new, v_new, is_sep_new, Kc, Vc, win_is_sep, sizes)
-    assert sizes.dtype == torch.int32 and is_sep_new.dtype == torch.uint8 and win_is_sep.dtype == torch.uint8
+    assert sizes.dtype == torch.int32 and sizes.dim() == 2 and sizes.shape[1] == 6 and sizes.is_contiguous()
+    assert is_sep_new.dtype == torch.uint8 and win_is_sep.dtype == torch.uint8
     S, Hkv, c, d = Kc.shape
     assert tuple(k_new.shape) == (S, Hkv, d) and tuple(v_new.shape) == (S, Hkv, d) and k_new.dtype == Kc.dtype
     p = SepkvParams(S, int(Hq), Hkv, d, int(a), int(s), int(w), c, 1.0, _dtype_code(Kc))
@@ -477,8 +479,9 @@ def sepkv_append(k_new, v_new, is_sep_new, Kc, Vc, win_is_sep, sizes, Hq: int, a
 
 def sepkv_evict_window(Kc, Vc, win_is_sep, sizes, Hq: int, a: int, s: int, w: int,
                        ws: Optional[torch.Tensor] = None) -> None:
-    """In place on Kc, Vc [S,Hkv,c,d], win_is_sep uint8 [S,c-a-s], sizes int32 [S,4]."""
+    """In place on Kc, Vc [S,Hkv,c,d], win_is_sep uint8 [S,c-a-s], sizes int32 [S,6]."""
     _dev(Kc, Vc, win_is_sep, sizes)
+    assert sizes.dtype == torch.int32 and sizes.dim() == 2 and sizes.shape[1] == 6 and sizes.is_contiguous()
     S, Hkv, c, d = Kc.shape
     p = SepkvParams(S, int(Hq), Hkv, d, int(a), int(s), int(w), c, 1.0, _dtype_code(Kc))
     lib = load()
@@ -491,7 +494,7 @@ def sepkv_evict_window(Kc, Vc, win_is_sep, sizes, Hq: int, a: int, s: int, w: in
 
 def sepkv_fill_from_prefill(K, V, is_sep, sep_idx, sep_prefix, Hq: int, a: int, s: int, w: int, c: int, nw: int,
                             out=None):
-    """Prefill K, V [S,Hkv,L,d] -> (Kc, Vc [S,Hkv,c,d], win_is_sep uint8 [S,c-a-s], sizes int32 [S,4]).
+    """Prefill K, V [S,Hkv,L,d] -> (Kc, Vc [S,Hkv,c,d], win_is_sep uint8 [S,c-a-s], sizes int32 [S,6]).
     Freshly allocated outputs are zero-filled (the call leaves slots beyond the sizes untouched)."""
     _dev(K, V, is_sep, sep_idx, sep_prefix)
     S, Hkv, L, d = K.shape
@@ -500,10 +503,11 @@ def sepkv_fill_from_prefill(K, V, is_sep, sep_idx, sep_prefix, Hq: int, a: int, 
         Kc = torch.zeros((S, Hkv, c, d), dtype=K.dtype, device=K.device)
         Vc = torch.zeros_like(Kc)
         flags = torch.zeros((S, c - a - s), dtype=torch.uint8, device=K.device)
-        sizes = torch.zeros((S, 4), dtype=torch.int32, device=K.device)
+        sizes = torch.zeros((S, 6), dtype=torch.int32, device=K.device)
     else:
         Kc, Vc, flags, sizes = out
         _dev(Kc, Vc, flags, sizes)
+        assert sizes.dtype == torch.int32 and tuple(sizes.shape) == (S, 6) and sizes.is_contiguous()
     _check("sepkv_fill_from_prefill",
            load().sepkv_fill_from_prefill(ctypes.byref(p), int(L), int(nw), _ptr(K), _ptr(V), _ptr(is_sep),
                                           _ptr(sep_idx), int(sep_idx.shape[1]), _ptr(sep_prefix), _ptr(Kc), _ptr(Vc),

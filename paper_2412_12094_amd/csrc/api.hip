@@ -392,7 +392,7 @@ size_t sepkv_evict_workspace_bytes(const sepkv_params *p) {
     return evict_workspace(*p);
 }
 
-int sepkv_evict_window(const sepkv_params *p, void *Kc, void *Vc, uint8_t *win_is_sep,
+int sepkv_evict_window(const sepkv_params *p, void *Kc, void *Vc, const uint8_t *win_is_sep,
                        int32_t *sizes, void *ws, size_t ws_bytes, void *stream) {
     int rc = check_kv(p);
     if (rc != SEPATTN_OK) return rc;

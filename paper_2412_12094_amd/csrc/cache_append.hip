@@ -1,13 +1,13 @@
 // One new token per sequence enters the four-block KV cache (Sec. 3.3 "Framework").  The first a
 // tokens of a sequence fill the Initial Cache; every later token is written behind the newest window
-// entry and joins the Local Window Cache, whose oldest entry passes to the Past Window Cache once the
-// Local Window holds more than w (the window is stored oldest first, so that hand-over is a change of
-// the two sizes only).  A sequence whose window region [a+s, c) is full is left untouched: the
+// entry (the window region is a ring: entry u sits at index (head + u) mod its capacity) and joins the
+// Local Window Cache, whose oldest entry passes to the Past Window Cache once the Local Window holds
+// more than w (the window is ordered oldest first, so that hand-over is a change of the two sizes only).  A sequence whose window region [a+s, c) is full is left untouched: the
 // compression step has to run first.
 //
 // One workgroup per sequence; a thread copies 16-byte pieces of the 2 * Hkv rows.  All threads read
 // the sizes, then (after a barrier) thread 0 writes the new ones.
-#include "common.h"
+#include "decode_common.h"
 
 namespace sepattn {
 
@@ -20,17 +20,18 @@ __global__ __launch_bounds__(kAppendThreads) void cache_append_kernel(
     const uint8_t *__restrict__ is_sep_new, uint4 *__restrict__ Kc, uint4 *__restrict__ Vc,
     uint8_t *__restrict__ win_is_sep, int32_t *__restrict__ sizes) {
     const int sq = blockIdx.x;
-    int32_t *sz = sizes + 4 * sq;
-    const int wcap = p.c - p.a - p.s;
-    const int n_init = min(max(sz[0], 0), p.a);
-    const int n_past = max(sz[2], 0), n_loc = max(sz[3], 0);
+    int32_t *sz = sizes + SEPKV_SIZES_COLS * sq;
+    const CacheMap cm = cache_map(p, sz);
+    const int wcap = cm.wcap;
+    const int n_init = cm.n_init;
+    const int n_past = cm.n_past, n_loc = cm.n_loc;
     const int u = n_past + n_loc;
     __syncthreads();  // every thread has the old sizes before thread 0 replaces them
     int slot;
     if (n_init < p.a)
         slot = n_init;
     else if (u < wcap)
-        slot = p.a + p.s + u;
+        slot = p.a + p.s + win_index(cm, u);
     else
         return;  // window region full (uniform over the workgroup)
     for (int item = threadIdx.x; item < 2 * p.Hkv * row16; item += kAppendThreads) {
@@ -43,7 +44,7 @@ __global__ __launch_bounds__(kAppendThreads) void cache_append_kernel(
         if (n_init < p.a) {
             sz[0] = n_init + 1;
         } else {
-            win_is_sep[(long)sq * wcap + u] = is_sep_new[sq] ? 1 : 0;
+            win_is_sep[(long)sq * wcap + win_index(cm, u)] = is_sep_new[sq] ? 1 : 0;
             const int over = (n_loc + 1 > p.w) ? 1 : 0;
             sz[2] = n_past + over;
             sz[3] = n_loc + 1 - over;

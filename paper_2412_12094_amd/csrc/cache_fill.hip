@@ -5,7 +5,8 @@
 //     Separator Cache  the newest (at most s) separators among the positions [min(a,L), L - nw),
 //                      oldest first (older ones are dropped, as the compression step would)
 //     window           the last nw positions; the newest min(w, nw) of them are the Local Window
-// and sizes = (Size_init, Size_sep, nw - Size_local, Size_local), win_is_sep = separator flag of each
+// and sizes = (Size_init, Size_sep, nw - Size_local, Size_local, 0, 0) (both rings start at their first
+// slot), win_is_sep = separator flag of each
 // window entry.  Rows are copied bit-exactly.
 //
 // One kernel: a workgroup of 256 threads copies 16 (d = 128, bf16) rows per pass; blockIdx.y is the
@@ -40,11 +41,13 @@ __global__ __launch_bounds__(kFillThreads) void cache_fill_kernel(
     if (blockIdx.x == 0 && kv == 0 && which == 0) {
         const int wl = min(p.w, nw);
         if (threadIdx.x == 0) {
-            int32_t *sz = sizes + 4 * sq;
+            int32_t *sz = sizes + SEPKV_SIZES_COLS * sq;
             sz[0] = n_init;
             sz[1] = kept;
             sz[2] = nw - wl;
             sz[3] = wl;
+            sz[4] = 0;  // both rings start at their first slot
+            sz[5] = 0;
         }
         for (int u = threadIdx.x; u < nw; u += kFillThreads) win_is_sep[(long)sq * wcap + u] = is_sep[(long)sq * L + wstart + u];
     }

@@ -88,7 +88,7 @@ int launch_rope_table(int n_pos, int d, double base, float *table, hipStream_t s
 int launch_cache_append(const sepkv_params &p, const void *k_new, const void *v_new, const uint8_t *is_sep_new,
                         void *Kc, void *Vc, uint8_t *win_is_sep, int32_t *sizes, hipStream_t st);
 size_t evict_workspace(const sepkv_params &p);
-int launch_evict(const sepkv_params &p, void *Kc, void *Vc, uint8_t *win_is_sep, int32_t *sizes,
+int launch_evict(const sepkv_params &p, void *Kc, void *Vc, const uint8_t *win_is_sep, int32_t *sizes,
                  void *ws, hipStream_t st);
 int launch_cache_fill(const sepkv_params &p, int L, int nw, const void *K, const void *V, const uint8_t *is_sep,
                       const int32_t *sep_idx, int cap, const int32_t *sep_prefix, void *Kc, void *Vc,

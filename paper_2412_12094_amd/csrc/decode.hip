@@ -102,10 +102,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(
     int sq = blk / (groups * p.Hkv);
     int h0 = kv * G + hg * GT;
 
-    const int32_t *sz = sizes + 4 * sq;
-    int n_init = min(max(sz[0], 0), p.a), n_sep = min(max(sz[1], 0), p.s);
-    int n_win = min(max(sz[2], 0) + max(sz[3], 0), p.c - p.a - p.s);
-    int nv = n_init + n_sep + n_win;
+    const CacheMap cm = cache_map(p, sizes + SEPKV_SIZES_COLS * sq);
+    int nv = cm.n_init + cm.n_sep + cm.n_past + cm.n_loc;
     int per = (nv + nsplit - 1) / nsplit;
     per = (per + NSLOT - 1) / NSLOT * NSLOT;
     int e0 = split * per, e1 = min(nv, e0 + per);
@@ -147,7 +145,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(
         for (int u = 0; u < kRowsUnroll; ++u) {
             int e = eb + u * NSLOT;
             ok[u] = e < e1;
-            int sl = decode_slot_of(ok[u] ? e : e0, n_init, n_sep, p.a, p.s);
+            int sl = decode_slot_of(cm, ok[u] ? e : e0);
             load8_stream<T>(Kh + (long)sl * D + c * 8, kr[u]);
             load8_stream<T>(Vh + (long)sl * D + c * 8, vr[u]);
         }

@@ -84,10 +84,8 @@ __global__ __launch_bounds__(kDmThreads, 1) void decode_mfma_kernel(
         for (int ks = 0; ks < KSTEPS; ++ks) qraw[ks] = *reinterpret_cast<const u32x4 *>(qrow + ks * 16 + 8 * hh);
     }
 
-    const int32_t *sz = sizes + 4 * sq;
-    const int n_init = min(max(sz[0], 0), p.a), n_sep = min(max(sz[1], 0), p.s);
-    const int n_win = min(max(sz[2], 0) + max(sz[3], 0), p.c - p.a - p.s);
-    const int nv = n_init + n_sep + n_win;
+    const CacheMap cm = cache_map(p, sizes + SEPKV_SIZES_COLS * sq);
+    const int nv = cm.n_init + cm.n_sep + cm.n_past + cm.n_loc;
     int per = (nv + nsplit - 1) / nsplit;
     per = (per + kDmRows - 1) / kDmRows * kDmRows;
     const int e0 = min(split * per, nv), e1 = min(nv, e0 + per);
@@ -112,7 +110,7 @@ __global__ __launch_bounds__(kDmThreads, 1) void decode_mfma_kernel(
         static_for<NLD>([&](auto U) {
             constexpr int u = U;
             const int r = u * RPL + my_sub;
-            const int sl = decode_slot_of(min(eb + r, e1 - 1), n_init, n_sep, p.a, p.s);
+            const int sl = decode_slot_of(cm, min(eb + r, e1 - 1));
             const uint32_t row_off = (uint32_t)sl * (uint32_t)(D * 2);  // a cache of one (sequence, head) is < 4 GB
             // every cache row is read exactly once per call: the non-temporal hint keeps the stream from
             // displacing itself in the caches (measured: 79 -> 71 us at 32 x 8 caches of 3332 entries)

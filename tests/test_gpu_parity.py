@@ -404,6 +404,33 @@ def random_sizes(rng, S, a, s, wcap, w):
     return sz
 
 
+def random_heads(rng, S, s, wcap):
+    """Ring heads of the Separator Cache and of the window region; the first sequence starts at 0, 0."""
+    h = np.stack([rng.integers(0, max(s, 1), size=S), rng.integers(0, wcap, size=S)], axis=1).astype(np.int32)
+    h[0] = 0
+    return h
+
+
+def ring(Kc, Vc, flags, sizes4, a, s, seed=0, fill=None, heads=None):
+    """The oracle works on the linear layout; the library's caches are rings.  Returns the ring layout of
+    a linear cache with seeded random heads (or the given ones): (Kc, Vc, flags, sizes6) as numpy arrays."""
+    rng = np.random.default_rng(1000 + seed)
+    if heads is None:
+        heads = random_heads(rng, Kc.shape[0], s, Kc.shape[2] - a - s)
+    return wl.cache_to_ring(Kc, Vc, flags, sizes4, heads, a, s, fill=fill)
+
+
+def assert_same_valid_entries(gK, gV, gF, rK, rV, rF, sizes4, a, s):
+    """Two caches in linear layout hold the same valid entries (rows bit for bit) and window flags."""
+    for q in range(sizes4.shape[0]):
+        ni, ns, npast, nl = (int(v) for v in sizes4[q])
+        for g, r in ((gK, rK), (gV, rV)):
+            assert np.array_equal(g[q, :, :ni], r[q, :, :ni])
+            assert np.array_equal(g[q, :, a:a + ns], r[q, :, a:a + ns])
+            assert np.array_equal(g[q, :, a + s:a + s + npast + nl], r[q, :, a + s:a + s + npast + nl])
+        assert np.array_equal(gF[q, :npast + nl], rF[q, :npast + nl])
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
 @pytest.mark.parametrize("S,Hq,Hkv,d,a,s,w,c", [
     (3, 8, 2, 128, 4, 64, 32, 200),
@@ -420,8 +447,8 @@ def test_decode_matches_oracle(sp, dtype, S, Hq, Hkv, d, a, s, w, c):
     sizes[0] = [a, s, c - a - s - w, w]  # one completely full cache
     data = wl.make_cache(cfg, sizes)
     scale = 1.0 / math.sqrt(d)
-    out, lse = sp.sepattn_decode(dev(data["q"], dtype), dev(data["Kc"], dtype), dev(data["Vc"], dtype),
-                                 dev(sizes), a, s, w, scale)
+    Kp, Vp, _, sz6 = ring(data["Kc"], data["Vc"], data["win_is_sep"], sizes, a, s, seed=c)
+    out, lse = sp.sepattn_decode(dev(data["q"], dtype), dev(Kp, dtype), dev(Vp, dtype), dev(sz6), a, s, w, scale)
     torch.cuda.synchronize()
     ref, lref = oracle.decode(data["q"], data["Kc"], data["Vc"], sizes, a, s, scale)
     assert np.abs(host(out) - ref).max() <= TOL[dtype]
@@ -432,12 +459,13 @@ def test_decode_empty_sequence_and_single_entry(sp):
     cfg = wl.CacheConfig("t", 2, 4, 2, 128, 2, 8, 4, 30, 0.1, "bf16", seed=5)
     sizes = np.array([[0, 0, 0, 0], [0, 0, 0, 1]], dtype=np.int32)
     data = wl.make_cache(cfg, sizes)
-    out, lse = sp.sepattn_decode(dev(data["q"], "bf16"), dev(data["Kc"], "bf16"), dev(data["Vc"], "bf16"),
-                                 dev(sizes), 2, 8, 4, 0.1)
+    # the single entry is the last slot of the window region; everything else is NaN
+    Kp, Vp, _, sz6 = ring(data["Kc"], data["Vc"], data["win_is_sep"], sizes, 2, 8, fill=np.nan, heads=[[0, 0], [5, 19]])
+    out, lse = sp.sepattn_decode(dev(data["q"], "bf16"), dev(Kp, "bf16"), dev(Vp, "bf16"), dev(sz6), 2, 8, 4, 0.1)
     torch.cuda.synchronize()
     o, l = host(out), host(lse)
     assert np.all(o[0] == 0) and np.all(np.isneginf(l[0]))
-    assert np.array_equal(o[1], np.repeat(data["Vc"][1, :, 10], 2, axis=0))  # the only entry: window slot 0
+    assert np.array_equal(o[1], np.repeat(data["Vc"][1, :, 10], 2, axis=0))  # the only entry: the oldest window entry
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
@@ -447,15 +475,11 @@ def test_decode_ignores_slots_beyond_the_sizes(sp, dtype):
     cfg = wl.CacheConfig("t", S, Hq, Hkv, d, a, s, w, c, 0.1, dtype, seed=11)
     sizes = np.array([[4, 90, 100, 20], [3, 17, 0, 5], [4, 33, 41, 20]], dtype=np.int32)
     data = wl.make_cache(cfg, sizes)
-    Kc, Vc = data["Kc"].copy(), data["Vc"].copy()
-    for q in range(S):
-        ni, ns, npast, nl = sizes[q]
-        for arr in (Kc, Vc):
-            arr[q, :, ni:a] = np.nan
-            arr[q, :, a + ns:a + s] = np.nan
-            arr[q, :, a + s + npast + nl:] = np.nan
+    # every slot that holds no valid entry is NaN (the rings start anywhere)
+    Kc, Vc, _, sz6 = ring(data["Kc"], data["Vc"], data["win_is_sep"], sizes, a, s, seed=2, fill=np.nan)
+    assert np.isnan(Kc).any()
     scale = 1.0 / math.sqrt(d)
-    out, lse = sp.sepattn_decode(dev(data["q"], dtype), dev(Kc, dtype), dev(Vc, dtype), dev(sizes), a, s, w, scale)
+    out, lse = sp.sepattn_decode(dev(data["q"], dtype), dev(Kc, dtype), dev(Vc, dtype), dev(sz6), a, s, w, scale)
     torch.cuda.synchronize()
     ref, lref = oracle.decode(data["q"], data["Kc"], data["Vc"], sizes, a, s, scale)
     assert np.isfinite(host(out)).all()
@@ -466,8 +490,8 @@ def test_decode_ignores_slots_beyond_the_sizes(sp, dtype):
 def test_decode_config5_full_size(sp):
     c = wl.CONFIGS["cfg5"]
     data = wl.make_cache(c)
-    out, lse = sp.sepattn_decode(dev(data["q"], "bf16"), dev(data["Kc"], "bf16"), dev(data["Vc"], "bf16"),
-                                 dev(data["sizes"]), c.a, c.s, c.w, c.scale)
+    Kp, Vp, _, sz6 = ring(data["Kc"], data["Vc"], data["win_is_sep"], data["sizes"], c.a, c.s, seed=5)
+    out, lse = sp.sepattn_decode(dev(data["q"], "bf16"), dev(Kp, "bf16"), dev(Vp, "bf16"), dev(sz6), c.a, c.s, c.w, c.scale)
     torch.cuda.synchronize()
     ref, lref = oracle.decode(data["q"], data["Kc"], data["Vc"], data["sizes"], c.a, c.s, c.scale)
     assert np.abs(host(out) - ref).max() <= 2e-2
@@ -481,29 +505,27 @@ def bits(x_fp32_bf16_valued):
     return (np.ascontiguousarray(x_fp32_bf16_valued, dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
 
 
-def check_evict(sp, cfg, sizes, flags=None):
+def check_evict(sp, cfg, sizes, flags=None, seed=0):
     data = wl.make_cache(cfg, sizes)
     if flags is not None:
         data["win_is_sep"] = flags
     Kb, Vb = bits(data["Kc"]), bits(data["Vc"])
     rK, rV, rF, rS = oracle.evict_window(Kb, Vb, data["win_is_sep"], sizes, cfg.a, cfg.s)
-    Kd = dev(Kb.view(np.int16)).view(torch.bfloat16)
-    Vd = dev(Vb.view(np.int16)).view(torch.bfloat16)
-    Fd, Sd = dev(data["win_is_sep"]), dev(sizes)
+    Kp, Vp, Fp, sz6 = ring(Kb, Vb, data["win_is_sep"], sizes, cfg.a, cfg.s, seed=seed)
+    Kd = dev(Kp.view(np.int16)).view(torch.bfloat16)
+    Vd = dev(Vp.view(np.int16)).view(torch.bfloat16)
+    Fd, Sd = dev(Fp), dev(sz6)
     sp.sepkv_evict_window(Kd, Vd, Fd, Sd, cfg.Hq, cfg.a, cfg.s, cfg.w)
     torch.cuda.synchronize()
-    gK = Kd.view(torch.int16).cpu().numpy().view(np.uint16)
-    gV = Vd.view(torch.int16).cpu().numpy().view(np.uint16)
-    gF, gS = host(Fd), host(Sd)
-    assert np.array_equal(gS, rS)
-    a, s = cfg.a, cfg.s
-    for q in range(cfg.S):
-        ni, ns, _, lw = rS[q]
-        for g, r in ((gK, rK), (gV, rV)):
-            assert np.array_equal(g[q, :, :ni], r[q, :, :ni])
-            assert np.array_equal(g[q, :, a:a + ns], r[q, :, a:a + ns])
-            assert np.array_equal(g[q, :, a + s:a + s + lw], r[q, :, a + s:a + s + lw])
-        assert np.array_equal(gF[q, :lw], rF[q, :lw])
+    gS = host(Sd)
+    assert np.array_equal(gS[:, :4], rS)
+    wcap = cfg.c - cfg.a - cfg.s
+    assert ((gS[:, 4] >= 0) & (gS[:, 4] < max(cfg.s, 1)) & (gS[:, 5] >= 0) & (gS[:, 5] < wcap)).all()
+    # the Past Window was dropped by moving the window's head, the flags stayed where they were
+    assert np.array_equal(gS[:, 5], (sz6[:, 5] + sizes[:, 2]) % wcap) and np.array_equal(host(Fd), Fp)
+    gK, gV, gF, _ = wl.cache_from_ring(Kd.view(torch.int16).cpu().numpy().view(np.uint16),
+                                       Vd.view(torch.int16).cpu().numpy().view(np.uint16), host(Fd), gS, cfg.a, cfg.s)
+    assert_same_valid_entries(gK, gV, gF, rK, rV, rF, rS, cfg.a, cfg.s)
 
 
 def test_evict_matches_oracle_bit_exact(sp):
@@ -517,10 +539,11 @@ def test_evict_matches_oracle_bit_exact(sp):
                      dtype=np.int32)
     assert (sizes[:, 2] + sizes[:, 3] <= wcap).all()
     check_evict(sp, cfg, sizes)
+    check_evict(sp, cfg, sizes, seed=1)   # other ring heads: the appended separators wrap around
     # all past-window entries flagged and more of them than the separator cache holds
     flags = np.ones((5, wcap), dtype=np.uint8)
-    check_evict(sp, cfg, sizes, flags)
-    check_evict(sp, cfg, sizes, np.zeros((5, wcap), dtype=np.uint8))
+    check_evict(sp, cfg, sizes, flags, seed=2)
+    check_evict(sp, cfg, sizes, np.zeros((5, wcap), dtype=np.uint8), seed=3)
 
 
 def test_evict_fp32_and_d64(sp):
@@ -535,17 +558,19 @@ def test_evict_config5_then_decode(sp):
     data = wl.make_cache(c)
     Kb, Vb = bits(data["Kc"]), bits(data["Vc"])
     rK, rV, rF, rS = oracle.evict_window(Kb, Vb, data["win_is_sep"], data["sizes"], c.a, c.s)
-    Kd = dev(Kb.view(np.int16)).view(torch.bfloat16)
-    Vd = dev(Vb.view(np.int16)).view(torch.bfloat16)
-    Fd, Sd = dev(data["win_is_sep"]), dev(data["sizes"])
+    Kp, Vp, Fp, sz6 = ring(Kb, Vb, data["win_is_sep"], data["sizes"], c.a, c.s, seed=7)
+    Kd = dev(Kp.view(np.int16)).view(torch.bfloat16)
+    Vd = dev(Vp.view(np.int16)).view(torch.bfloat16)
+    Fd, Sd = dev(Fp), dev(sz6)
     sp.sepkv_evict_window(Kd, Vd, Fd, Sd, c.Hq, c.a, c.s, c.w)
     out, lse = sp.sepattn_decode(dev(data["q"], "bf16"), Kd, Vd, Sd, c.a, c.s, c.w, c.scale)
     torch.cuda.synchronize()
-    assert np.array_equal(host(Sd), rS)
+    gS = host(Sd)
+    assert np.array_equal(gS[:, :4], rS)
     assert (rS[:, 1] == c.s).all() and (rS[:, 2] == 0).all()  # separator cache was full: FIFO overflow
-    gK = Kd.view(torch.int16).cpu().numpy().view(np.uint16)
-    assert np.array_equal(gK[:, :, c.a:c.a + c.s], rK[:, :, c.a:c.a + c.s])
-    assert np.array_equal(gK[:, :, c.a + c.s:c.a + c.s + c.w], rK[:, :, c.a + c.s:c.a + c.s + c.w])
+    gK, gV, gF, _ = wl.cache_from_ring(Kd.view(torch.int16).cpu().numpy().view(np.uint16),
+                                       Vd.view(torch.int16).cpu().numpy().view(np.uint16), host(Fd), gS, c.a, c.s)
+    assert_same_valid_entries(gK, gV, gF, rK, rV, rF, rS, c.a, c.s)
     to_f = lambda u: (u.astype(np.uint32) << 16).view(np.float32)
     ref, lref = oracle.decode(data["q"], to_f(rK), to_f(rV), rS, c.a, c.s, c.scale)
     assert np.abs(host(out) - ref).max() <= 2e-2 and np.abs(host(lse) - lref).max() <= 2e-3
@@ -583,11 +608,11 @@ def test_fill_from_prefill_matches_oracle_bit_exact(sp, dtype, S, Hkv, L, d, a, 
     Kc = torch.full((S, Hkv, c, d), 7.0, dtype=Kd.dtype, device="cuda")
     Vc = torch.full((S, Hkv, c, d), -3.0, dtype=Kd.dtype, device="cuda")
     Fd = torch.full((S, c - a - s), 9, dtype=torch.uint8, device="cuda")
-    Sd = torch.zeros((S, 4), dtype=torch.int32, device="cuda")
+    Sd = torch.full((S, 6), -1, dtype=torch.int32, device="cuda")
     K0, V0 = raw(Kc).copy(), raw(Vc).copy()
     sp.sepkv_fill_from_prefill(Kd, Vd, is_sep, idx, pre, Hkv, a, s, w, c, nw, out=(Kc, Vc, Fd, Sd))
     torch.cuda.synchronize()
-    assert np.array_equal(host(Sd), rS)
+    assert np.array_equal(host(Sd)[:, :4], rS) and (host(Sd)[:, 4:] == 0).all()  # both rings start at slot 0
     gK, gV, gF = raw(Kc), raw(Vc), host(Fd)
     for q in range(S):
         m = valid[q]
@@ -778,8 +803,8 @@ def test_decode_rope_matches_oracle(sp, dtype, S, Hq, Hkv, d, a, s, w, c, base):
     data = wl.make_cache(cfg, sizes)
     scale = 1.0 / math.sqrt(d)
     table = sp.sepkv_rope_table(c, d, base, "cuda")
-    out, lse = sp.sepattn_decode_rope(dev(data["q"], dtype), dev(data["Kc"], dtype), dev(data["Vc"], dtype),
-                                      dev(sizes), table, a, s, w, scale)
+    Kp, Vp, _, sz6 = ring(data["Kc"], data["Vc"], data["win_is_sep"], sizes, a, s, seed=c)
+    out, lse = sp.sepattn_decode_rope(dev(data["q"], dtype), dev(Kp, dtype), dev(Vp, dtype), dev(sz6), table, a, s, w, scale)
     torch.cuda.synchronize()
     ref, lref = oracle.decode_rope(data["q"], data["Kc"], data["Vc"], sizes, a, s, scale, base)
     assert np.abs(host(out) - ref).max() <= TOL[dtype]
@@ -794,18 +819,16 @@ def test_decode_rope_empty_sequence_single_entry_and_stale_slots(sp):
     cfg = wl.CacheConfig("t", S, Hq, Hkv, d, a, s, w, c, 0.1, "bf16", seed=5)
     sizes = np.array([[0, 0, 0, 0], [0, 0, 0, 1], [1, 3, 5, 4]], dtype=np.int32)
     data = wl.make_cache(cfg, sizes)
-    Kc, Vc = data["Kc"].copy(), data["Vc"].copy()
-    for arr in (Kc, Vc):  # slots beyond the sizes hold unspecified data
-        arr[2, :, 1:a] = np.nan
-        arr[2, :, a + 3:a + s] = np.nan
-        arr[2, :, a + s + 9:] = np.nan
+    # slots without a valid entry hold unspecified data (NaN); the rings start anywhere
+    Kc, Vc, _, sz6 = ring(data["Kc"], data["Vc"], data["win_is_sep"], sizes, a, s, fill=np.nan,
+                          heads=[[0, 0], [7, 19], [6, 15]])
     table = sp.sepkv_rope_table(c, d, 10000.0, "cuda")
-    out, lse = sp.sepattn_decode_rope(dev(data["q"], "bf16"), dev(Kc, "bf16"), dev(Vc, "bf16"), dev(sizes), table,
+    out, lse = sp.sepattn_decode_rope(dev(data["q"], "bf16"), dev(Kc, "bf16"), dev(Vc, "bf16"), dev(sz6), table,
                                       a, s, w, 0.1)
     torch.cuda.synchronize()
     o, l = host(out), host(lse)
     assert np.all(o[0] == 0) and np.all(np.isneginf(l[0]))
-    assert np.array_equal(o[1], np.repeat(data["Vc"][1, :, a + s], 2, axis=0))  # the only entry: window slot 0
+    assert np.array_equal(o[1], np.repeat(data["Vc"][1, :, a + s], 2, axis=0))  # the only entry: the oldest window entry
     ref, lref = oracle.decode_rope(data["q"][2:], data["Kc"][2:], data["Vc"][2:], sizes[2:], a, s, 0.1, 10000.0)
     assert np.abs(o[2:] - ref).max() <= 2e-2 and np.abs(l[2:] - lref).max() <= 1e-2
 
@@ -814,8 +837,9 @@ def test_decode_rope_config5_full_size(sp):
     c = wl.CONFIGS["cfg5"]
     data = wl.make_cache(c)
     table = sp.sepkv_rope_table(c.c, c.d, 500000.0, "cuda")
-    out, lse = sp.sepattn_decode_rope(dev(data["q"], "bf16"), dev(data["Kc"], "bf16"), dev(data["Vc"], "bf16"),
-                                      dev(data["sizes"]), table, c.a, c.s, c.w, c.scale)
+    Kp, Vp, _, sz6 = ring(data["Kc"], data["Vc"], data["win_is_sep"], data["sizes"], c.a, c.s, seed=9)
+    out, lse = sp.sepattn_decode_rope(dev(data["q"], "bf16"), dev(Kp, "bf16"), dev(Vp, "bf16"), dev(sz6), table,
+                                      c.a, c.s, c.w, c.scale)
     torch.cuda.synchronize()
     ref, lref = oracle.decode_rope(data["q"], data["Kc"], data["Vc"], data["sizes"], c.a, c.s, c.scale, 500000.0)
     assert np.abs(host(out) - ref).max() <= 2e-2
@@ -827,8 +851,9 @@ def test_decode_rope_rejects_a_short_table(sp):
     data = wl.make_cache(cfg)
     table = sp.sepkv_rope_table(29, 64, 10000.0, "cuda")
     with pytest.raises(sp.SepattnError) as e:
+        sz6 = np.concatenate([data["sizes"], np.zeros((1, 2), np.int32)], axis=1)
         sp.sepattn_decode_rope(dev(data["q"], "bf16"), dev(data["Kc"], "bf16"), dev(data["Vc"], "bf16"),
-                               dev(data["sizes"]), table, 2, 8, 4, 0.1)
+                               dev(sz6), table, 2, 8, 4, 0.1)
     assert e.value.status == 2
     with pytest.raises(sp.SepattnError) as e:
         sp.sepkv_rope_table(16, 64, 1.0, "cuda")  # base must exceed 1
@@ -862,12 +887,17 @@ def test_append_matches_oracle_bit_exact(sp, d):
     vn = rng.integers(0, 2 ** 16, size=(S, Hkv, d)).astype(np.uint16)
     sep_new = np.array([1, 0, 1, 1, 0, 1], dtype=np.uint8)
     rK, rV, rF, rS = oracle.append_token(Kb, Vb, data["win_is_sep"], sizes, kn, vn, sep_new, a, s, w)
-    Kd, Vd, Fd, Sd = as_dev_bits(Kb), as_dev_bits(Vb), dev(data["win_is_sep"]), dev(sizes)
+    Kp, Vp, Fp, sz6 = ring(Kb, Vb, data["win_is_sep"], sizes, a, s, seed=d)
+    Kd, Vd, Fd, Sd = as_dev_bits(Kp), as_dev_bits(Vp), dev(Fp), dev(sz6)
     sp.sepkv_append(as_dev_bits(kn), as_dev_bits(vn), dev(sep_new), Kd, Vd, Fd, Sd, Hq, a, s, w)
     torch.cuda.synchronize()
-    assert np.array_equal(host(Sd), rS)
-    assert np.array_equal(host(Fd), rF)
-    assert np.array_equal(from_dev_bits(Kd), rK) and np.array_equal(from_dev_bits(Vd), rV)
+    gS = host(Sd)
+    assert np.array_equal(gS[:, :4], rS) and np.array_equal(gS[:, 4:], sz6[:, 4:])  # the heads do not move
+    gK, gV, gF, _ = wl.cache_from_ring(from_dev_bits(Kd), from_dev_bits(Vd), host(Fd), gS, a, s)
+    assert_same_valid_entries(gK, gV, gF, rK, rV, rF, rS, a, s)
+    # nothing but the new entry's slot and flag changed
+    changed = (from_dev_bits(Kd) != Kp).any(axis=(1, 3))
+    assert (changed.sum(axis=1) <= 1).all() and not changed[5].any()
     assert np.array_equal(rS[5], sizes[5]) and rS[3, 2] == 1 and rS[3, 3] == 8
 
 
@@ -903,7 +933,7 @@ def test_streaming_fill_append_compress_decode_rope(sp):
         if (t - L0) % 7 == 0 or t == L0 + steps - 1:
             out, lse = sp.sepattn_decode_rope(qd[:, :, t].contiguous(), Kd, Vd, Sd, table, a, s, w, scale)
             torch.cuda.synchronize()
-            assert np.array_equal(host(Sd), rS), t
+            assert np.array_equal(host(Sd)[:, :4], rS), t
             ref, lref = oracle.decode_rope(Q[:, :, t], to_f(rK), to_f(rV), rS, a, s, scale, base)
             assert np.abs(host(out) - ref).max() <= 2e-2, t
             assert np.abs(host(lse) - lref).max() <= 1e-2, t
@@ -913,14 +943,10 @@ def test_streaming_fill_append_compress_decode_rope(sp):
             n_compress += 1
     torch.cuda.synchronize()
     assert n_compress >= 2
-    assert np.array_equal(host(Sd), rS)
-    for q in range(S):
-        ni, ns, npast, nl = rS[q]
-        for g, r in ((from_dev_bits(Kd), rK), (from_dev_bits(Vd), rV)):
-            assert np.array_equal(g[q, :, :ni], r[q, :, :ni])
-            assert np.array_equal(g[q, :, a:a + ns], r[q, :, a:a + ns])
-            assert np.array_equal(g[q, :, a + s:a + s + npast + nl], r[q, :, a + s:a + s + npast + nl])
-        assert np.array_equal(host(Fd)[q, :npast + nl], rF[q, :npast + nl])
+    gS = host(Sd)
+    assert np.array_equal(gS[:, :4], rS) and (gS[:, 4:] > 0).all()  # both rings have turned
+    gK, gV, gF, _ = wl.cache_from_ring(from_dev_bits(Kd), from_dev_bits(Vd), host(Fd), gS, a, s)
+    assert_same_valid_entries(gK, gV, gF, rK, rV, rF, rS, a, s)
 
 
 def test_append_fp32_rows(sp):
@@ -935,11 +961,14 @@ def test_append_fp32_rows(sp):
     vn = rng.standard_normal((S, Hkv, d)).astype(np.float32)
     fn = np.array([1, 1], dtype=np.uint8)
     rK, rV, rF, rS = oracle.append_token(Kc, Vc, flags, sizes, kn, vn, fn, a, s, w)
-    Kd, Vd, Fd, Sd = dev(Kc), dev(Vc), dev(flags), dev(sizes)
+    Kp, Vp, Fp, sz6 = ring(Kc, Vc, flags, sizes, a, s, seed=4)
+    Kd, Vd, Fd, Sd = dev(Kp), dev(Vp), dev(Fp), dev(sz6)
     sp.sepkv_append(dev(kn), dev(vn), dev(fn), Kd, Vd, Fd, Sd, Hq, a, s, w)
     torch.cuda.synchronize()
-    assert np.array_equal(host(Sd), rS) and np.array_equal(host(Fd), rF)
-    assert np.array_equal(Kd.cpu().numpy(), rK) and np.array_equal(Vd.cpu().numpy(), rV)
+    gS = host(Sd)
+    assert np.array_equal(gS[:, :4], rS)
+    gK, gV, gF, _ = wl.cache_from_ring(Kd.cpu().numpy(), Vd.cpu().numpy(), host(Fd), gS, a, s)
+    assert_same_valid_entries(gK, gV, gF, rK, rV, rF, rS, a, s)
 
 
 def test_training_step_replays_in_a_hip_graph(sp):
@@ -995,7 +1024,8 @@ def test_generation_step_replays_in_a_hip_graph(sp):
     sizes = np.array([[4, 40, 30, 16], [4, 11, 0, 9], [2, 0, 0, 0]], dtype=np.int32)
     data = wl.make_cache(cfg, sizes)
     rK, rV, rF, rS = bits(data["Kc"]), bits(data["Vc"]), data["win_is_sep"].copy(), sizes.copy()
-    Kd, Vd, Fd, Sd = as_dev_bits(rK), as_dev_bits(rV), dev(rF), dev(rS)
+    Kp, Vp, Fp, sz6 = ring(rK, rV, rF, rS, a, s, seed=6)
+    Kd, Vd, Fd, Sd = as_dev_bits(Kp), as_dev_bits(Vp), dev(Fp), dev(sz6)
     base, scale, steps = 10000.0, 1.0 / math.sqrt(d), 6
     table = sp.sepkv_rope_table(c, d, base, "cuda")
     rng = np.random.default_rng(7)
@@ -1012,7 +1042,7 @@ def test_generation_step_replays_in_a_hip_graph(sp):
         sp.sepattn_decode_rope(q_in, Kd, Vd, Sd, table, a, s, w, scale, out=(out, lse), ws=ws)
     # capture ran nothing: the state is still the initial one
     torch.cuda.synchronize()
-    assert np.array_equal(host(Sd), rS)
+    assert np.array_equal(host(Sd)[:, :4], rS)
     for t in range(steps):
         kn = rng.integers(0x3C00, 0x4000, size=(S, Hkv, d)).astype(np.uint16)  # bf16 values in [2^-7, 2)
         vn = rng.integers(0x3C00, 0x4000, size=(S, Hkv, d)).astype(np.uint16)
@@ -1024,7 +1054,7 @@ def test_generation_step_replays_in_a_hip_graph(sp):
         torch.cuda.synchronize()
         rK, rV, rF, rS = oracle.append_token(rK, rV, rF, rS, kn, vn, fn, a, s, w)
         ref, lref = oracle.decode_rope(qn, to_f(rK), to_f(rV), rS, a, s, scale, base)
-        assert np.array_equal(host(Sd), rS), t
+        assert np.array_equal(host(Sd)[:, :4], rS), t
         assert np.abs(host(out) - ref).max() <= 2e-2, t
         assert np.abs(host(lse) - lref).max() <= 1e-2, t
         assert math.isfinite(checksum)
@@ -1143,7 +1173,7 @@ def test_outputs_stay_inside_their_buffers(sp):
     s_cap, w = 37, 9
     c = a + s_cap + 50
     cache = (out((B, Hkv, c, d), torch.bfloat16, 3.0), out((B, Hkv, c, d), torch.bfloat16, 3.0),
-             out((B, c - a - s_cap), torch.uint8, 7), out((B, 4), torch.int32, -5))
+             out((B, c - a - s_cap), torch.uint8, 7), out((B, 6), torch.int32, -5))
     sp.sepkv_fill_from_prefill(k, v, is_sep, idx, pre, Hq, a, s_cap, w, c, 49, out=cache)
     Kc, Vc, Fd, Sd = cache
     sp.sepkv_append(k[:, :, 0].contiguous(), v[:, :, 0].contiguous(), is_sep[:, 0].contiguous(), Kc, Vc, Fd, Sd, Hq, a, s_cap, w)

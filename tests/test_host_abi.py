@@ -175,3 +175,30 @@ def test_workload_generators_are_deterministic_and_shaped():
     assert np.array_equal(wl.bf16_round(x), x)  # already on the bf16 grid
     cc = wl.CONFIGS["cfg5"]
     assert cc.a + cc.s + cc.w < cc.c and cc.window_capacity == 1280
+
+
+def test_ring_layout_helpers_round_trip():
+    """The test helpers that lay a linear cache out as the library's rings and back are inverse to each
+    other on the valid entries, and with both heads at 0 the ring layout IS the linear one."""
+    import workloads as wl
+
+    rng = np.random.default_rng(0)
+    S, Hkv, d, a, s, c = 3, 2, 4, 2, 5, 2 + 5 + 7
+    Kc = rng.integers(0, 1000, size=(S, Hkv, c, d)).astype(np.int32)
+    Vc = rng.integers(0, 1000, size=(S, Hkv, c, d)).astype(np.int32)
+    fl = rng.integers(0, 2, size=(S, 7)).astype(np.uint8)
+    sizes = np.array([[2, 5, 4, 3], [1, 2, 0, 2], [0, 0, 0, 0]], dtype=np.int32)
+    heads = np.array([[3, 5], [4, 6], [0, 0]], dtype=np.int32)
+    Kp, Vp, Fp, s6 = wl.cache_to_ring(Kc, Vc, fl, sizes, heads, a, s)
+    assert np.array_equal(s6[:, :4], sizes) and np.array_equal(s6[:, 4:], heads)
+    assert np.array_equal(Kp[0, :, a + (3 + 4) % 5], Kc[0, :, a + 4])            # newest separator wrapped to slot a+2
+    assert np.array_equal(Vp[0, :, a + s + (5 + 6) % 7], Vc[0, :, a + s + 6])    # newest window entry wrapped
+    K2, V2, F2, s4 = wl.cache_from_ring(Kp, Vp, Fp, s6, a, s)
+    for q in range(S):
+        ni, ns, npast, nl = sizes[q]
+        for g, r in ((K2, Kc), (V2, Vc)):
+            assert np.array_equal(g[q, :, :ni], r[q, :, :ni]) and np.array_equal(g[q, :, a:a + ns], r[q, :, a:a + ns])
+            assert np.array_equal(g[q, :, a + s:a + s + npast + nl], r[q, :, a + s:a + s + npast + nl])
+        assert np.array_equal(F2[q, :npast + nl], fl[q, :npast + nl])
+    K0, V0, F0, _ = wl.cache_to_ring(Kc, Vc, fl, sizes, np.zeros((S, 2), np.int32), a, s)
+    assert np.array_equal(K0, Kc) and np.array_equal(V0, Vc) and np.array_equal(F0, fl)

@@ -31,8 +31,10 @@ def _case(S, Hq, Hkv, d, a, s, w, c, seed):
         tot = int(rng.integers(1, c - a - s + 1))
         sizes[q] = (a, int(rng.integers(0, s + 1)), tot - min(w, tot), min(w, tot))
     data = wl.make_cache(cfg, sizes)
+    heads = np.stack([rng.integers(0, s, size=S), rng.integers(0, c - a - s, size=S)], axis=1)
+    Kp, Vp, _, sizes6 = wl.cache_to_ring(data["Kc"], data["Vc"], data["win_is_sep"], sizes, heads, a, s)
     bf = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda().to(torch.bfloat16).contiguous()
-    return cfg, bf(data["q"]), bf(data["Kc"]), bf(data["Vc"]), torch.from_numpy(sizes).cuda()
+    return cfg, bf(data["q"]), bf(Kp), bf(Vp), torch.from_numpy(sizes6).cuda()
 
 
 def test_decode_noalloc_equals_decode_on_two_calls_in_a_row(sp):
@@ -65,7 +67,7 @@ def test_decode_noalloc_rejects_what_does_not_fit(sp):
     S, Hq, Hkv, d, a, s, w, c = 512, 64, 64, 128, 4, 16, 8, 64
     q = torch.zeros((S, Hq, d), dtype=torch.bfloat16, device="cuda")
     Kc = torch.zeros((S, Hkv, c, d), dtype=torch.bfloat16, device="cuda")
-    sizes = torch.zeros((S, 4), dtype=torch.int32, device="cuda")
+    sizes = torch.zeros((S, 6), dtype=torch.int32, device="cuda")
     p = bd._kv_params(q, Kc, a, s, w, 0.1)
     assert lib.sepattn_decode_noalloc_scratch_bytes(ctypes.byref(p)) > (4 << 20)
     out = torch.empty_like(q)

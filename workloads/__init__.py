@@ -15,6 +15,8 @@ from .generators import (  # noqa: F401
     make_qkv,
     make_dO,
     make_cache,
+    cache_to_ring,
+    cache_from_ring,
     config_inputs,
     small_variant,
 )

@@ -186,6 +186,57 @@ def make_cache(cfg: CacheConfig, sizes: Optional[np.ndarray] = None) -> Dict[str
             "win_is_sep": flags}
 
 
+def cache_to_ring(Kc, Vc, flags, sizes4, heads, a: int, s: int, fill=None):
+    """The library's physical cache layout for a cache given in LINEAR layout (every block's valid entries
+    at the start of its slot range, oldest first): the Separator Cache and the window region are rings,
+    separator k in slot a + (head_sep + k) mod s, window entry u at window index (head_win + u) mod wcap.
+
+    Kc, Vc [S,Hkv,c,d] (any dtype), flags uint8 [S,wcap], sizes4 int32 [S,4], heads int32 [S,2].
+    Slots (and flags) that hold no valid entry keep what the linear arrays held there, or `fill`.
+    Returns (Kc_ring, Vc_ring, flags_ring, sizes6).  Data movement only: no arithmetic of the method."""
+    Kc, Vc, flags = np.asarray(Kc), np.asarray(Vc), np.asarray(flags)
+    S, _, c, _ = Kc.shape
+    wcap = c - a - s
+    Kp, Vp, Fp = Kc.copy(), Vc.copy(), flags.copy()
+    if fill is not None:
+        Kp[...] = fill
+        Vp[...] = fill
+    sizes6 = np.zeros((S, 6), dtype=np.int32)
+    for q in range(S):
+        ni, ns, npast, nl = (int(v) for v in sizes4[q])
+        hs, hw = int(heads[q][0]), int(heads[q][1])
+        sizes6[q] = (ni, ns, npast, nl, hs, hw)
+        Kp[q, :, :ni], Vp[q, :, :ni] = Kc[q, :, :ni], Vc[q, :, :ni]
+        for k in range(ns):
+            t = a + (hs + k) % s
+            Kp[q, :, t], Vp[q, :, t] = Kc[q, :, a + k], Vc[q, :, a + k]
+        for u in range(npast + nl):
+            t = (hw + u) % wcap
+            Kp[q, :, a + s + t], Vp[q, :, a + s + t] = Kc[q, :, a + s + u], Vc[q, :, a + s + u]
+            Fp[q, t] = flags[q, u]
+    return Kp, Vp, Fp, sizes6
+
+
+def cache_from_ring(Kp, Vp, Fp, sizes6, a: int, s: int):
+    """Inverse of cache_to_ring: (Kc, Vc, flags, sizes4) in linear layout; slots and flags without a valid
+    entry are zero."""
+    Kp, Vp, Fp = np.asarray(Kp), np.asarray(Vp), np.asarray(Fp)
+    S, _, c, _ = Kp.shape
+    wcap = c - a - s
+    Kc, Vc, flags = np.zeros_like(Kp), np.zeros_like(Vp), np.zeros_like(Fp)
+    for q in range(S):
+        ni, ns, npast, nl, hs, hw = (int(v) for v in sizes6[q])
+        Kc[q, :, :ni], Vc[q, :, :ni] = Kp[q, :, :ni], Vp[q, :, :ni]
+        for k in range(ns):
+            t = a + (hs + k) % s
+            Kc[q, :, a + k], Vc[q, :, a + k] = Kp[q, :, t], Vp[q, :, t]
+        for u in range(npast + nl):
+            t = (hw + u) % wcap
+            Kc[q, :, a + s + u], Vc[q, :, a + s + u] = Kp[q, :, a + s + t], Vp[q, :, a + s + t]
+            flags[q, u] = Fp[q, t]
+    return Kc, Vc, flags, np.ascontiguousarray(np.asarray(sizes6)[:, :4], dtype=np.int32)
+
+
 def small_variant(cfg: AttnConfig, **kw) -> AttnConfig:
     """A copy of cfg with some fields replaced (used for reduced-size parity cases)."""
     return replace(cfg, **kw)

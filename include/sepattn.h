@@ -180,6 +180,30 @@ int sepattn_backward_packed(const sepattn_params *p, const int32_t *doc_start,
                             void *dV, void *ws, size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Head-wise neighbour windows (Sec. 4.6 "Comparison with More Baselines and Variants": some heads
+ * keep a short window, the others see everything; also the per-layer hybrids of Sec. 4.3 when the
+ * caller batches them): forward and backward of Eq. 1 with a mask of Eq. 2 whose n is a per-head
+ * value, n_per_head[h] for query head h (n_per_head[h] >= L is full causal attention for that
+ * head).  Initial tokens and separators are visible to every head as before.
+ *   n_per_head   HOST int32 [Hq], every entry >= 1 (copied before returning); p->n is ignored.
+ *                Hq <= SEPATTN_MAX_HEADWISE_HEADS (SEPATTN_ERR_SHAPE otherwise).
+ * Everything else as sepattn_forward / sepattn_backward; the backward workspace is the one of a
+ * call with n = max_h n_per_head[h] (sepattn_backward_headwise_workspace_bytes).  The heads of a
+ * KV head share its K/V tiles, so a call costs about what the largest window of each group costs.
+ * ------------------------------------------------------------------------------------------ */
+#define SEPATTN_MAX_HEADWISE_HEADS 128
+int sepattn_forward_headwise(const sepattn_params *p, const int32_t *n_per_head, const void *Q,
+                             const void *K, const void *V, const int32_t *sep_idx,
+                             const int32_t *sep_count, const int32_t *sep_prefix, void *O, float *LSE,
+                             void *ws, size_t ws_bytes, void *stream);
+size_t sepattn_backward_headwise_workspace_bytes(const sepattn_params *p, const int32_t *n_per_head);
+int sepattn_backward_headwise(const sepattn_params *p, const int32_t *n_per_head, const void *Q,
+                              const void *K, const void *V, const void *O, const float *LSE,
+                              const void *dO, const int32_t *sep_idx, const int32_t *sep_count,
+                              const int32_t *sep_prefix, void *dQ, void *dK, void *dV, void *ws,
+                              size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------
  * Streaming generation on the four-block KV cache (Sec. 3.3).
  * Cache layout, per (sequence, KV head): c slots of d values,
  *     [0, a)       Initial Cache

@@ -17,6 +17,8 @@ from .binding import (  # noqa: F401
     sepattn_mark_interval,
     sepattn_compact_indices,
     sepattn_forward,
+    sepattn_forward_headwise,
+    sepattn_backward_headwise,
     sepattn_doc_bounds,
     sepattn_forward_packed,
     sepattn_backward_packed,

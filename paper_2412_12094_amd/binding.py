@@ -30,6 +30,9 @@ EXPORTS = (
     "sepattn_compact_indices",
     "sepattn_forward_workspace_bytes",
     "sepattn_forward",
+    "sepattn_forward_headwise",
+    "sepattn_backward_headwise_workspace_bytes",
+    "sepattn_backward_headwise",
     "sepattn_doc_bounds",
     "sepattn_forward_packed",
     "sepattn_backward_packed",
@@ -101,6 +104,12 @@ def load(path: Optional[str] = None):
     lib.sepattn_forward_workspace_bytes.argtypes = [pp]
     lib.sepattn_forward.restype = ci
     lib.sepattn_forward.argtypes = [pp] + [vp] * 9 + [sz, vp]
+    lib.sepattn_forward_headwise.restype = ci
+    lib.sepattn_forward_headwise.argtypes = [pp] + [vp] * 10 + [sz, vp]
+    lib.sepattn_backward_headwise_workspace_bytes.restype = sz
+    lib.sepattn_backward_headwise_workspace_bytes.argtypes = [pp, vp]
+    lib.sepattn_backward_headwise.restype = ci
+    lib.sepattn_backward_headwise.argtypes = [pp] + [vp] * 14 + [sz, vp]
     lib.sepattn_doc_bounds.restype = ci
     lib.sepattn_doc_bounds.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
     lib.sepattn_forward_packed.restype = ci
@@ -304,6 +313,54 @@ def sepattn_forward(Q, K, V, sep_idx, sep_count, sep_prefix, a: int, n: int, sca
            lib.sepattn_forward(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(sep_idx), _ptr(sep_count),
                                _ptr(sep_prefix), _ptr(O), _ptr(LSE), _ptr(ws), ws.numel(), _stream(Q)))
     return O, LSE
+
+
+def _head_windows(n_per_head, Hq: int):
+    arr = (ctypes.c_int32 * Hq)(*[int(v) for v in n_per_head])
+    assert len(n_per_head) == Hq
+    return arr
+
+
+def sepattn_forward_headwise(Q, K, V, sep_idx, sep_count, sep_prefix, a: int, n_per_head, scale: float,
+                             out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None, ws: Optional[torch.Tensor] = None):
+    """sepattn_forward with a neighbour window of its own for every query head (n_per_head: Hq ints, host)."""
+    _dev(Q, K, V, sep_idx, sep_count, sep_prefix)
+    assert K.shape == V.shape and Q.dtype == K.dtype == V.dtype
+    p = _attn_params(Q, K, a, 1, scale, sep_idx.shape[1])
+    nh = _head_windows(n_per_head, Q.shape[1])
+    lib = load()
+    if out is None:
+        O = torch.empty_like(Q)
+        LSE = torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device)
+    else:
+        O, LSE = out
+    if ws is None:
+        ws = _ws(lib.sepattn_forward_workspace_bytes(ctypes.byref(p)), Q.device)
+    _check("sepattn_forward_headwise",
+           lib.sepattn_forward_headwise(ctypes.byref(p), nh, _ptr(Q), _ptr(K), _ptr(V), _ptr(sep_idx), _ptr(sep_count),
+                                        _ptr(sep_prefix), _ptr(O), _ptr(LSE), _ptr(ws), ws.numel(), _stream(Q)))
+    return O, LSE
+
+
+def sepattn_backward_headwise(Q, K, V, O, LSE, dO, sep_idx, sep_count, sep_prefix, a: int, n_per_head, scale: float,
+                              out: Optional[Tuple[torch.Tensor, torch.Tensor, torch.Tensor]] = None,
+                              ws: Optional[torch.Tensor] = None):
+    """sepattn_backward with per-head neighbour windows -> (dQ, dK, dV)."""
+    _dev(Q, K, V, O, LSE, dO, sep_idx, sep_count, sep_prefix)
+    p = _attn_params(Q, K, a, 1, scale, sep_idx.shape[1])
+    nh = _head_windows(n_per_head, Q.shape[1])
+    lib = load()
+    if out is None:
+        dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    else:
+        dQ, dK, dV = out
+    if ws is None:
+        ws = _ws(lib.sepattn_backward_headwise_workspace_bytes(ctypes.byref(p), nh), Q.device)
+    _check("sepattn_backward_headwise",
+           lib.sepattn_backward_headwise(ctypes.byref(p), nh, _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(dO),
+                                         _ptr(sep_idx), _ptr(sep_count), _ptr(sep_prefix), _ptr(dQ), _ptr(dK),
+                                         _ptr(dV), _ptr(ws), ws.numel(), _stream(Q)))
+    return dQ, dK, dV
 
 
 def sepattn_doc_bounds(cu_seqlens: torch.Tensor, L: int, a: int = 0, is_sep_row: Optional[torch.Tensor] = None,

@@ -57,6 +57,25 @@ int check_attn(const sepattn_params *p) {
     return SEPATTN_OK;
 }
 
+const HeadWin kNoHeadWin = {};  // an ordinary call: every head uses p.n
+
+// head-wise windows: p.n becomes the largest window, hw.delta how much shorter each head's is
+int head_windows(const sepattn_params *p, const int32_t *n_per_head, sepattn_params &q, HeadWin &hw) {
+    if (!p) return SEPATTN_ERR_NULL;
+    if (!n_per_head) return SEPATTN_ERR_NULL;
+    if (p->Hq <= 0 || p->Hq > kMaxHeadwise || p->L <= 0) return SEPATTN_ERR_SHAPE;
+    q = *p;
+    q.n = 1;
+    for (int h = 0; h < p->Hq; ++h) {
+        if (n_per_head[h] < 1) return SEPATTN_ERR_PARAM;
+        const int nh = n_per_head[h] < p->L ? n_per_head[h] : p->L;  // a window beyond L changes nothing
+        q.n = nh > q.n ? nh : q.n;
+    }
+    hw = HeadWin{};
+    for (int h = 0; h < p->Hq; ++h) hw.delta[h] = q.n - (n_per_head[h] < p->L ? n_per_head[h] : p->L);
+    return SEPATTN_OK;
+}
+
 // a and n beyond L change nothing in the mask; clamping keeps position arithmetic in range
 sepattn_params normalised(const sepattn_params *p) {
     sepattn_params q = *p;
@@ -245,9 +264,9 @@ int sepattn_forward(const sepattn_params *p, const void *Q, const void *K, const
     hipStream_t st = static_cast<hipStream_t>(stream);
     discard_stale_hip_error();
     if (q.dtype == SEPATTN_FP32)
-        return launch_forward_fp32(q, (const float *)Q, (const float *)K, (const float *)V, sep_idx,
+        return launch_forward_fp32(q, kNoHeadWin, (const float *)Q, (const float *)K, (const float *)V, sep_idx,
                                    sep_prefix, nullptr, (float *)O, LSE, st);
-    return launch_forward_bf16(q, Q, K, V, sep_idx, sep_prefix, nullptr, nullptr, O, LSE, ws, st);
+    return launch_forward_bf16(q, kNoHeadWin, Q, K, V, sep_idx, sep_prefix, nullptr, nullptr, O, LSE, ws, st);
 }
 
 int sepattn_doc_bounds(const int32_t *cu_seqlens, int n_docs, int L, int a, int32_t *doc_start, int32_t *doc_end,
@@ -273,9 +292,9 @@ int sepattn_forward_packed(const sepattn_params *p, const int32_t *doc_start, co
     if (need > 0 && (!ws || ws_bytes < need || !aligned(ws, 256))) return SEPATTN_ERR_WORKSPACE;
     discard_stale_hip_error();
     if (p->dtype == SEPATTN_FP32)
-        return launch_forward_fp32(normalised(p), (const float *)Q, (const float *)K, (const float *)V, sep_idx,
+        return launch_forward_fp32(normalised(p), kNoHeadWin, (const float *)Q, (const float *)K, (const float *)V, sep_idx,
                                    sep_prefix, doc_start, (float *)O, LSE, static_cast<hipStream_t>(stream));
-    return launch_forward_bf16(normalised(p), Q, K, V, sep_idx, sep_prefix, doc_start, doc_end, O, LSE, ws,
+    return launch_forward_bf16(normalised(p), kNoHeadWin, Q, K, V, sep_idx, sep_prefix, doc_start, doc_end, O, LSE, ws,
                                static_cast<hipStream_t>(stream));
 }
 
@@ -302,10 +321,67 @@ int sepattn_backward(const sepattn_params *p, const void *Q, const void *K, cons
     hipStream_t st = static_cast<hipStream_t>(stream);
     discard_stale_hip_error();
     if (q.dtype == SEPATTN_FP32)
-        return launch_backward_fp32(q, (const float *)Q, (const float *)K, (const float *)V,
+        return launch_backward_fp32(q, kNoHeadWin, (const float *)Q, (const float *)K, (const float *)V,
                                     (const float *)O, LSE, (const float *)dO, sep_idx, sep_prefix, nullptr, nullptr,
                                     (float *)dQ, (float *)dK, (float *)dV, (float *)ws, st);
-    return launch_backward_bf16(q, Q, K, V, O, LSE, dO, sep_idx, sep_count, sep_prefix, nullptr, nullptr, dQ, dK, dV,
+    return launch_backward_bf16(q, kNoHeadWin, Q, K, V, O, LSE, dO, sep_idx, sep_count, sep_prefix, nullptr, nullptr, dQ, dK, dV,
+                                ws, st);
+}
+
+int sepattn_forward_headwise(const sepattn_params *p, const int32_t *n_per_head, const void *Q, const void *K,
+                             const void *V, const int32_t *sep_idx, const int32_t *sep_count,
+                             const int32_t *sep_prefix, void *O, float *LSE, void *ws, size_t ws_bytes, void *stream) {
+    sepattn_params pm;
+    HeadWin hw;
+    int rc = head_windows(p, n_per_head, pm, hw);
+    if (rc != SEPATTN_OK) return rc;
+    rc = check_attn(&pm);
+    if (rc != SEPATTN_OK) return rc;
+    if (!Q || !K || !V || !sep_idx || !sep_count || !sep_prefix || !O || !LSE) return SEPATTN_ERR_NULL;
+    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16)) return SEPATTN_ERR_PARAM;
+    size_t need = sepattn_forward_workspace_bytes(&pm);
+    if (need > 0 && (!ws || ws_bytes < need || !aligned(ws, 256))) return SEPATTN_ERR_WORKSPACE;
+    sepattn_params q = normalised(&pm);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    discard_stale_hip_error();
+    if (q.dtype == SEPATTN_FP32)
+        return launch_forward_fp32(q, hw, (const float *)Q, (const float *)K, (const float *)V, sep_idx, sep_prefix,
+                                   nullptr, (float *)O, LSE, st);
+    return launch_forward_bf16(q, hw, Q, K, V, sep_idx, sep_prefix, nullptr, nullptr, O, LSE, ws, st);
+}
+
+size_t sepattn_backward_headwise_workspace_bytes(const sepattn_params *p, const int32_t *n_per_head) {
+    sepattn_params pm;
+    HeadWin hw;
+    if (head_windows(p, n_per_head, pm, hw) != SEPATTN_OK) return 0;
+    return sepattn_backward_workspace_bytes(&pm);
+}
+
+int sepattn_backward_headwise(const sepattn_params *p, const int32_t *n_per_head, const void *Q, const void *K,
+                              const void *V, const void *O, const float *LSE, const void *dO, const int32_t *sep_idx,
+                              const int32_t *sep_count, const int32_t *sep_prefix, void *dQ, void *dK, void *dV,
+                              void *ws, size_t ws_bytes, void *stream) {
+    sepattn_params pm;
+    HeadWin hw;
+    int rc = head_windows(p, n_per_head, pm, hw);
+    if (rc != SEPATTN_OK) return rc;
+    rc = check_attn(&pm);
+    if (rc != SEPATTN_OK) return rc;
+    if (!Q || !K || !V || !O || !LSE || !dO || !sep_idx || !sep_count || !sep_prefix || !dQ || !dK || !dV)
+        return SEPATTN_ERR_NULL;
+    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) || !aligned(dO, 16) ||
+        !aligned(dQ, 16) || !aligned(dK, 16) || !aligned(dV, 16))
+        return SEPATTN_ERR_PARAM;
+    size_t need = sepattn_backward_workspace_bytes(&pm);
+    if (!ws || ws_bytes < need || !aligned(ws, 256)) return SEPATTN_ERR_WORKSPACE;
+    sepattn_params q = normalised(&pm);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    discard_stale_hip_error();
+    if (q.dtype == SEPATTN_FP32)
+        return launch_backward_fp32(q, hw, (const float *)Q, (const float *)K, (const float *)V, (const float *)O, LSE,
+                                    (const float *)dO, sep_idx, sep_prefix, nullptr, nullptr, (float *)dQ, (float *)dK,
+                                    (float *)dV, (float *)ws, st);
+    return launch_backward_bf16(q, hw, Q, K, V, O, LSE, dO, sep_idx, sep_count, sep_prefix, nullptr, nullptr, dQ, dK, dV,
                                 ws, st);
 }
 
@@ -327,11 +403,11 @@ int sepattn_backward_packed(const sepattn_params *p, const int32_t *doc_start, c
     if (!ws || ws_bytes < need || !aligned(ws, 256)) return SEPATTN_ERR_WORKSPACE;
     discard_stale_hip_error();
     if (p->dtype == SEPATTN_FP32)
-        return launch_backward_fp32(normalised(p), (const float *)Q, (const float *)K, (const float *)V,
+        return launch_backward_fp32(normalised(p), kNoHeadWin, (const float *)Q, (const float *)K, (const float *)V,
                                     (const float *)O, LSE, (const float *)dO, sep_idx, sep_prefix, doc_start, doc_end,
                                     (float *)dQ, (float *)dK, (float *)dV, (float *)ws,
                                     static_cast<hipStream_t>(stream));
-    return launch_backward_bf16(normalised(p), Q, K, V, O, LSE, dO, sep_idx, sep_count, sep_prefix, doc_start,
+    return launch_backward_bf16(normalised(p), kNoHeadWin, Q, K, V, O, LSE, dO, sep_idx, sep_count, sep_prefix, doc_start,
                                 doc_end, dQ, dK, dV, ws, static_cast<hipStream_t>(stream));
 }
 

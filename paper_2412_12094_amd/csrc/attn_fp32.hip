@@ -76,7 +76,7 @@ __global__ __launch_bounds__(256) void fwd_fp32_kernel(sepattn_params p, const f
                                                        const int32_t *__restrict__ sep_idx,
                                                        const int32_t *__restrict__ sep_prefix,
                                                        const int32_t *__restrict__ doc_start,
-                                                       float *__restrict__ O, float *__restrict__ LSE) {
+                                                       float *__restrict__ O, float *__restrict__ LSE, HeadWin hw) {
     constexpr int R = D / kWave;  // output values per lane
     int lane = threadIdx.x % kWave;
     long row = (long)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void fwd_fp32_kernel(sepattn_params p, const f
     const int32_t *prefix = sep_prefix + (long)b * (p.L + 1);
     const int32_t *idx = sep_idx + (long)b * p.cap;
     // (the clamp keeps inconsistent bounds from faulting)
-    RowKeys rk = row_keys(i, p.a, p.n, prefix, doc_start ? min(max(doc_start[(long)b * p.L + i], 0), i) : 0);
+    RowKeys rk = row_keys(i, p.a, p.n - head_delta(hw, h), prefix, doc_start ? min(max(doc_start[(long)b * p.L + i], 0), i) : 0);
 
     float m = -INFINITY, l = 0.f;
     float acc[R];
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(256) void dq_fp32_kernel(sepattn_params p, const fl
                                                       const int32_t *__restrict__ sep_idx,
                                                       const int32_t *__restrict__ sep_prefix,
                                                       const int32_t *__restrict__ doc_start,
-                                                      float *__restrict__ dQ) {
+                                                      float *__restrict__ dQ, HeadWin hw) {
     constexpr int R = D / kWave;
     int lane = threadIdx.x % kWave;
     long row = (long)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
@@ -160,7 +160,7 @@ __global__ __launch_bounds__(256) void dq_fp32_kernel(sepattn_params p, const fl
     const int32_t *prefix = sep_prefix + (long)b * (p.L + 1);
     const int32_t *idx = sep_idx + (long)b * p.cap;
     // (the clamp keeps inconsistent bounds from faulting)
-    RowKeys rk = row_keys(i, p.a, p.n, prefix, doc_start ? min(max(doc_start[(long)b * p.L + i], 0), i) : 0);
+    RowKeys rk = row_keys(i, p.a, p.n - head_delta(hw, h), prefix, doc_start ? min(max(doc_start[(long)b * p.L + i], 0), i) : 0);
     float lse = LSE[row], Di = Drow[row];
     float acc[R];
     for (int r = 0; r < R; ++r) acc[r] = 0.f;
@@ -196,7 +196,7 @@ __global__ __launch_bounds__(256) void dkv_fp32_kernel(sepattn_params p, const f
                                                        const float *__restrict__ Drow,
                                                        const int32_t *__restrict__ sep_prefix,
                                                        const int32_t *__restrict__ doc_end,
-                                                       float *__restrict__ dK, float *__restrict__ dV) {
+                                                       float *__restrict__ dK, float *__restrict__ dV, HeadWin hw) {
     constexpr int R = D / kWave;
     int lane = threadIdx.x % kWave;
     long row = (long)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
@@ -208,15 +208,16 @@ __global__ __launch_bounds__(256) void dkv_fp32_kernel(sepattn_params p, const f
     int G = p.Hq / p.Hkv;
     const int32_t *prefix = sep_prefix + (long)b * (p.L + 1);
     bool always = (j < p.a) || (prefix[j + 1] != prefix[j]);
-    long i_end_l = always ? (long)p.L : min((long)p.L, (long)j + p.n);
-    if (doc_end) i_end_l = min(i_end_l, (long)doc_end[(long)b * p.L + j]);
-    int i_end = (int)i_end_l;
     const float *kj = K + row * D;
     const float *vj = V + row * D;
     float accK[R], accV[R];
     for (int r = 0; r < R; ++r) accK[r] = accV[r] = 0.f;
     for (int g = 0; g < G; ++g) {
         int h = kv * G + g;
+        // the queries that see key j: up to the end of the sequence (document), or of head h's window
+        long i_end_l = always ? (long)p.L : min((long)p.L, (long)j + p.n - head_delta(hw, h));
+        if (doc_end) i_end_l = min(i_end_l, (long)doc_end[(long)b * p.L + j]);
+        int i_end = (int)i_end_l;
         long hrow = ((long)b * p.Hq + h) * p.L;
         const float *Qh = Q + hrow * D;
         const float *dOh = dO + hrow * D;
@@ -251,19 +252,19 @@ unsigned blocks_for_rows(long n_rows) { return (unsigned)((n_rows + 3) / 4); }
 
 }  // namespace
 
-int launch_forward_fp32(const sepattn_params &p, const float *Q, const float *K, const float *V,
+int launch_forward_fp32(const sepattn_params &p, const HeadWin &hw, const float *Q, const float *K, const float *V,
                         const int32_t *sep_idx, const int32_t *sep_prefix, const int32_t *doc_start, float *O,
                         float *LSE, hipStream_t st) {
     long n_rows = (long)p.B * p.Hq * p.L;
     dim3 grid(blocks_for_rows(n_rows)), block(256);
     if (p.d == 64)
-        hipLaunchKernelGGL(fwd_fp32_kernel<64>, grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, doc_start, O, LSE);
+        hipLaunchKernelGGL(fwd_fp32_kernel<64>, grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, doc_start, O, LSE, hw);
     else
-        hipLaunchKernelGGL(fwd_fp32_kernel<128>, grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, doc_start, O, LSE);
+        hipLaunchKernelGGL(fwd_fp32_kernel<128>, grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, doc_start, O, LSE, hw);
     return launch_status();
 }
 
-int launch_backward_fp32(const sepattn_params &p, const float *Q, const float *K, const float *V,
+int launch_backward_fp32(const sepattn_params &p, const HeadWin &hw, const float *Q, const float *K, const float *V,
                          const float *O, const float *LSE, const float *dO, const int32_t *sep_idx,
                          const int32_t *sep_prefix, const int32_t *doc_start, const int32_t *doc_end, float *dQ,
                          float *dK, float *dV, float *Dws, hipStream_t st) {
@@ -271,12 +272,12 @@ int launch_backward_fp32(const sepattn_params &p, const float *Q, const float *K
     dim3 block(256);
     if (p.d == 64) {
         hipLaunchKernelGGL(rowdot_fp32_kernel<64>, dim3(blocks_for_rows(q_rows)), block, 0, st, q_rows, dO, O, Dws);
-        hipLaunchKernelGGL(dq_fp32_kernel<64>, dim3(blocks_for_rows(q_rows)), block, 0, st, p, Q, K, V, LSE, dO, Dws, sep_idx, sep_prefix, doc_start, dQ);
-        hipLaunchKernelGGL(dkv_fp32_kernel<64>, dim3(blocks_for_rows(k_rows)), block, 0, st, p, Q, K, V, LSE, dO, Dws, sep_prefix, doc_end, dK, dV);
+        hipLaunchKernelGGL(dq_fp32_kernel<64>, dim3(blocks_for_rows(q_rows)), block, 0, st, p, Q, K, V, LSE, dO, Dws, sep_idx, sep_prefix, doc_start, dQ, hw);
+        hipLaunchKernelGGL(dkv_fp32_kernel<64>, dim3(blocks_for_rows(k_rows)), block, 0, st, p, Q, K, V, LSE, dO, Dws, sep_prefix, doc_end, dK, dV, hw);
     } else {
         hipLaunchKernelGGL(rowdot_fp32_kernel<128>, dim3(blocks_for_rows(q_rows)), block, 0, st, q_rows, dO, O, Dws);
-        hipLaunchKernelGGL(dq_fp32_kernel<128>, dim3(blocks_for_rows(q_rows)), block, 0, st, p, Q, K, V, LSE, dO, Dws, sep_idx, sep_prefix, doc_start, dQ);
-        hipLaunchKernelGGL(dkv_fp32_kernel<128>, dim3(blocks_for_rows(k_rows)), block, 0, st, p, Q, K, V, LSE, dO, Dws, sep_prefix, doc_end, dK, dV);
+        hipLaunchKernelGGL(dq_fp32_kernel<128>, dim3(blocks_for_rows(q_rows)), block, 0, st, p, Q, K, V, LSE, dO, Dws, sep_idx, sep_prefix, doc_start, dQ, hw);
+        hipLaunchKernelGGL(dkv_fp32_kernel<128>, dim3(blocks_for_rows(k_rows)), block, 0, st, p, Q, K, V, LSE, dO, Dws, sep_prefix, doc_end, dK, dV, hw);
     }
     return launch_status();
 }

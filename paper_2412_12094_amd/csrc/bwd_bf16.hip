@@ -55,7 +55,7 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
     const uint16_t *__restrict__ dO, const int32_t *__restrict__ sep_idx,
     const int32_t *__restrict__ sep_prefix, const int32_t *__restrict__ doc_start,
     const int32_t *__restrict__ doc_end, uint16_t *__restrict__ dQ, float *__restrict__ Dws,
-    float *__restrict__ Lws, int wpg) {
+    float *__restrict__ Lws, int wpg, HeadWin hw) {
     constexpr int NW = 8;
     constexpr int TP = 32 * NW / GP;
     constexpr int CH = D / 8;
@@ -95,6 +95,7 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
     const int kv = (y / groups) % p.Hkv;
     const int b = y / (groups * p.Hkv);
     const int head = kv * G + hg * GP + (wave % GP);
+    const int hdelta = head_delta(hw, head);  // head-wise windows: see the forward kernel
 
     const int32_t *prefix = sep_prefix + (long)b * (p.L + 1);
     const int32_t *idx = sep_idx + (long)b * p.cap;
@@ -104,7 +105,7 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
     const uint16_t *Vh = V + ((long)b * p.Hkv + kv) * (long)p.L * D;
 
     // state of the segment being multiplied (the lambdas below refer to it)
-    int iq = 0;
+    int iq = 0, iq_h = 0;
     FullBlocks fullb = {};
     bf16x8 qreg[KSTEPS], doreg[KSTEPS];
     float Di = 0.f, lse2 = 0.f;
@@ -324,7 +325,7 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
                 const int his[8] = {hi0.x, hi0.y, hi0.z, hi0.w, hi1.x, hi1.y, hi1.z, hi1.w};
 #pragma unroll
                 for (int k = 0; k < 8; ++k) {
-                    const bool vis = (los[k] <= iq) & (iq <= his[k]);
+                    const bool vis = (los[k] <= iq) & (iq_h <= his[k]);
                     sacc[8 * half + k] = vis ? sacc[8 * half + k] : -INFINITY;
                 }
             }
@@ -366,7 +367,8 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
     for (int round = 0; cseg.i0 >= 0; ++round) {
         const int pw = cseg.i0 + 32 * (wave / GP);
         iq = pw + qi;
-        fullb = full_blocks(cseg.st, pw, p.n);
+        iq_h = iq + hdelta;
+        fullb = full_blocks(cseg.st, pw, p.n - hdelta);
         if (DOCS && pw + 31 >= cseg.de) fullb = no_full_blocks();
         // rows of this wave's head: (uniform base) + 32-bit byte offset of the lane's piece
         const long head_row0 = ((long)b * p.Hq + head) * p.L;
@@ -435,7 +437,7 @@ template <int D, bool DOCS>
 int launch_bwd(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
                const uint16_t *O, const float *LSE, const uint16_t *dO, const int32_t *sep_idx,
                const int32_t *sep_prefix, const int32_t *doc_start, const int32_t *doc_end, uint16_t *dQ,
-               uint16_t *dK, uint16_t *dV, void *ws, hipStream_t st) {
+               uint16_t *dK, uint16_t *dV, void *ws, const HeadWin &hw, hipStream_t st) {
     const BwdWorkspace w = bwd_workspace(p);
     char *base = static_cast<char *>(ws);
     float *Dws = reinterpret_cast<float *>(base);
@@ -457,21 +459,21 @@ int launch_bwd(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
     {
     ProfScope prof(SEPATTN_K_BWD_DQ, st);
     if (GP == 4)
-        hipLaunchKernelGGL((dq_kernel<D, 4, DOCS>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, doc_start, doc_end, dQ, Dws, Lws, wpg);
+        hipLaunchKernelGGL((dq_kernel<D, 4, DOCS>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, doc_start, doc_end, dQ, Dws, Lws, wpg, hw);
     else if (GP == 2)
-        hipLaunchKernelGGL((dq_kernel<D, 2, DOCS>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, doc_start, doc_end, dQ, Dws, Lws, wpg);
+        hipLaunchKernelGGL((dq_kernel<D, 2, DOCS>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, doc_start, doc_end, dQ, Dws, Lws, wpg, hw);
     else
-        hipLaunchKernelGGL((dq_kernel<D, 1, DOCS>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, doc_start, doc_end, dQ, Dws, Lws, wpg);
+        hipLaunchKernelGGL((dq_kernel<D, 1, DOCS>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, doc_start, doc_end, dQ, Dws, Lws, wpg, hw);
     }
     if (hipGetLastError() != hipSuccess) return SEPATTN_ERR_HIP;
-    return launch_dkv_bf16(p, Q, K, V, Lws, dO, Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, st);
+    return launch_dkv_bf16(p, hw, Q, K, V, Lws, dO, Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, st);
 }
 
 }  // namespace
 
 size_t backward_bf16_workspace(const sepattn_params &p) { return bwd_workspace(p).total; }
 
-int launch_backward_bf16(const sepattn_params &p, const void *Q, const void *K, const void *V,
+int launch_backward_bf16(const sepattn_params &p, const HeadWin &hw, const void *Q, const void *K, const void *V,
                          const void *O, const float *LSE, const void *dO, const int32_t *sep_idx,
                          const int32_t *, const int32_t *sep_prefix, const int32_t *doc_start,
                          const int32_t *doc_end, void *dQ, void *dK, void *dV, void *ws, hipStream_t st) {
@@ -480,15 +482,15 @@ int launch_backward_bf16(const sepattn_params &p, const void *Q, const void *K, 
     if (doc_start) {
         if (p.d == 64)
             return launch_bwd<64, true>(p, u(Q), u(K), u(V), u(O), LSE, u(dO), sep_idx, sep_prefix, doc_start, doc_end,
-                                        w(dQ), w(dK), w(dV), ws, st);
+                                        w(dQ), w(dK), w(dV), ws, hw, st);
         return launch_bwd<128, true>(p, u(Q), u(K), u(V), u(O), LSE, u(dO), sep_idx, sep_prefix, doc_start, doc_end,
-                                     w(dQ), w(dK), w(dV), ws, st);
+                                     w(dQ), w(dK), w(dV), ws, hw, st);
     }
     if (p.d == 64)
         return launch_bwd<64, false>(p, u(Q), u(K), u(V), u(O), LSE, u(dO), sep_idx, sep_prefix, nullptr, nullptr,
-                                     w(dQ), w(dK), w(dV), ws, st);
+                                     w(dQ), w(dK), w(dV), ws, hw, st);
     return launch_bwd<128, false>(p, u(Q), u(K), u(V), u(O), LSE, u(dO), sep_idx, sep_prefix, nullptr, nullptr,
-                                  w(dQ), w(dK), w(dV), ws, st);
+                                  w(dQ), w(dK), w(dV), ws, hw, st);
 }
 
 }  // namespace sepattn

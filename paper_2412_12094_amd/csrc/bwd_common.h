@@ -99,7 +99,7 @@ __device__ inline int far_last_query(const FarList &fl, int f, const int32_t *__
 }
 
 // doc_end: packed documents ([B, L], p.a == 0), or nullptr
-int launch_dkv_bf16(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
+int launch_dkv_bf16(const sepattn_params &p, const HeadWin &hw, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
                     const float *lse2, const uint16_t *dO, const float *Dws, const int32_t *sep_idx,
                     const int32_t *sep_prefix, const int32_t *doc_end, uint16_t *dK, uint16_t *dV, float *farK,
                     float *farV, int32_t *piece_tab, hipStream_t st);

@@ -51,14 +51,18 @@ __device__ inline int wave_max_i(int v) {
 // DOCS: packed documents (doc_end [B, L]: one past the last position of each position's document;
 // p.a == 0, the documents' initial tokens are list entries): a key's query range ends with its
 // document, and the far pieces of a list tile end with the document of the tile's last entry.
-template <int D, bool DOCS>
+// HW: head-wise windows.  p.n is the largest window: it fixes the far / band split and the schedule;
+// in a band unit a key that is neither an initial token nor a separator is visible to query i of head
+// h only while i <= j + p.n - 1 - delta[h] (a third comparison in the blocks that need the mask test).
+template <int D, bool DOCS, bool HW>
 __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
     sepattn_params p, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
     const uint16_t *__restrict__ V, const float *__restrict__ LSE2, const uint16_t *__restrict__ dO,
     const float *__restrict__ Dws, const int32_t *__restrict__ sep_idx,
     const int32_t *__restrict__ sep_prefix, const int32_t *__restrict__ doc_end,
     uint16_t *__restrict__ dK, uint16_t *__restrict__ dV,
-    float *__restrict__ farK, float *__restrict__ farV, int32_t *__restrict__ piece_tab, int wpg, int n_band) {
+    float *__restrict__ farK, float *__restrict__ farV, int32_t *__restrict__ piece_tab, int wpg, int n_band,
+    HeadWin hw) {
     constexpr int NW = 2 * kDkvWaves;        // waves per workgroup
     constexpr int CH = D / 8;                // 16-byte chunks per row
     constexpr int RPL = 64 / CH;             // rows covered by one wave-wide 1 KB load
@@ -202,6 +206,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
         // ---- this wave's 32 keys and the query range of the piece.  Item i of the piece is query tile
         // i % n_qt (64 rows from q_lo on) of query head i / n_qt.
         int j, lo, hi, q_lo, q_hi, fidx = 0;
+        int hi2 = 1 << 29;  // HW: last query row of the head with the LARGEST window that sees the key as a neighbour
         bool valid;
         if (FAR) {
             q_lo = fq0;
@@ -220,6 +225,10 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
             q_hi = min(p.L, j0 + kBK + p.n - 1);
             lo = j;
             hi = min(j + p.n - 1, p.L - 1);
+            if constexpr (HW) {
+                const int jj = valid ? j : 0;
+                if (!(jj < p.a || prefix[jj + 1] != prefix[jj])) hi2 = jj + p.n - 1;
+            }
             if (!valid) j = 0;
             if constexpr (DOCS) hi = min(hi, dend[j] - 1);
             item0 = 0;
@@ -234,6 +243,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
         // decisions below are scalar branches
         const int lo_max = __builtin_amdgcn_readfirstlane(wave_max_i(lo));
         const int hi_min = __builtin_amdgcn_readfirstlane(wave_min_i(hi));
+        const int hi2_min = HW ? __builtin_amdgcn_readfirstlane(wave_min_i(hi2)) : 0;
 
         // resident B operand: K rows for the P-wave, V rows for the dS-wave
         bf16x8 breg[KSTEPS];
@@ -331,34 +341,48 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
         // three v_readlane per step: scalar bookkeeping inside the loop costs issue slots that the
         // matrix instructions need.  Tiles are numbered in load order (head-major).
         struct Blk {
+            int dlt;         // HW: how much shorter the window of the block's head is than p.n
             int r0, ps, rv;  // first query row; parity of the step (P exchange slot); float offset of the row values
             uint32_t off;    // byte offset of the block's first row from the start of the ring
             bool full;       // every (query, key) pair of the block is visible: no mask test needed
         };
         const int q0_tile = item0 % n_qt;
         // step s: the tile and block this wave (key block kbw) works on, lowest / highest tile of any wave
+        int step_head = 0;  // head (within the group) of the block step_of was last asked about (band units)
         auto step_of = [&](int s, int &tile, int &blk, int &lo_t, int &hi_t) __attribute__((always_inline)) {
             const int g = s / st_P, b = s - g * st_P;
             const int base_t = g * tiles_per_head;
             const bool mg = g > 0 && b < st_ov;
             const int own = base_t + (b >> 1), old = base_t - tiles_per_head + ((b + st_P) >> 1);
             const bool prev = mg && (kbw > b || g == st_G);
+            step_head = prev ? g - 1 : g;
             tile = prev ? old : own;
             blk = prev ? b + st_P : b;
             lo_t = mg ? old : own;
             hi_t = (mg && g == st_G) ? old : own;
         };
         uint32_t sch_off = 0;
-        int sch_r0 = 0, sch_t = 0;
+        int sch_r0 = 0, sch_t = 0, sch_d = 0;
         auto fill_schedule = [&](int first) __attribute__((always_inline)) {
             const int sidx = first + lane;
             int tile, blk, lo_t, hi_t, tile_n, blk_n, lo_n, hi_n;
             step_of(sidx, tile, blk, lo_t, hi_t);
+            int dl = 0;
+            if constexpr (HW) {
+                // the head's delta: the table is indexed with wave-uniform numbers only
+                const int hd = step_head;
+                for (int g = 0; g < G; ++g) {
+                    const int sd = head_delta(hw, kv * G + g);
+                    dl = (!FAR && hd == g) ? sd : dl;
+                }
+            }
             step_of(sidx + 1, tile_n, blk_n, lo_n, hi_n);
             if (sidx + 1 >= n_blocks) hi_n = n_tiles - 1;
             const int buf = tile % NBUF, qb = blk & 1;
             const int r0 = q_lo + ((q0_tile + (blk >> 1)) % n_qt) * kBQ + 32 * qb;
-            const bool full = (r0 >= lo_max) && (r0 + 31 <= hi_min);
+            bool full = (r0 >= lo_max) && (r0 + 31 <= hi_min);
+            if constexpr (HW) full = full && (r0 + 31 + dl <= hi2_min);
+            sch_d = dl;
             sch_off = (uint32_t)buf * (TILE * 2) + (uint32_t)qb * (32 * D * 2);
             sch_r0 = r0 | (buf << 2) | (qb << 1) | (full ? 1 : 0);  // r0 is a multiple of 32
             sch_t = (lo_t << 2) | max(0, min(hi_n - lo_t, 3));
@@ -378,6 +402,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
             k.full = r0p & 1;
             k.rv = ((r0p >> 2) & 3) * kBQ + ((r0p >> 1) & 1) * 32;
             k.ps = st_n & 1;
+            k.dlt = HW ? __builtin_amdgcn_readlane(sch_d, l) : 0;
             lo_cur = tp >> 2;
             hi_next = lo_cur + (tp & 3);
             return k;
@@ -500,7 +525,9 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int iqr = k.r0 + 16 * (i >> 3) + 8 * hh + (i & 7);
-                    x[i] = (lo <= iqr && iqr <= hi) ? x[i] : 0.f;
+                    bool vis = lo <= iqr && iqr <= hi;
+                    if constexpr (HW) vis = vis && (iqr + k.dlt <= hi2);
+                    x[i] = vis ? x[i] : 0.f;
                 }
             }
             xb[0] = pack_bf16x8(x, 0);
@@ -713,7 +740,7 @@ __global__ __launch_bounds__(256) void dkv_combine_kernel(sepattn_params p, cons
 }
 
 template <int D>
-int launch_dkv(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
+int launch_dkv(const sepattn_params &p, const HeadWin &hw, bool headwise, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
                const float *lse2, const uint16_t *dO, const float *Dws, const int32_t *sep_idx,
                const int32_t *sep_prefix, const int32_t *doc_end, uint16_t *dK, uint16_t *dV, float *farK,
                float *farV, int32_t *piece_tab, hipStream_t st) {
@@ -725,11 +752,14 @@ int launch_dkv(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
     {
         ProfScope prof(SEPATTN_K_BWD_DKV, st);
         if (doc_end)
-            hipLaunchKernelGGL((dkv_kernel<D, true>), dim3((unsigned)total), dim3(kDkvThreads), 0, st, p, Q, K, V, lse2, dO,
-                               Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, wpg, (int)band_grid);
+            hipLaunchKernelGGL((dkv_kernel<D, true, false>), dim3((unsigned)total), dim3(kDkvThreads), 0, st, p, Q, K, V, lse2, dO,
+                               Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, wpg, (int)band_grid, hw);
+        else if (headwise)
+            hipLaunchKernelGGL((dkv_kernel<D, false, true>), dim3((unsigned)total), dim3(kDkvThreads), 0, st, p, Q, K, V, lse2, dO,
+                               Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, wpg, (int)band_grid, hw);
         else
-            hipLaunchKernelGGL((dkv_kernel<D, false>), dim3((unsigned)total), dim3(kDkvThreads), 0, st, p, Q, K, V, lse2, dO,
-                               Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, wpg, (int)band_grid);
+            hipLaunchKernelGGL((dkv_kernel<D, false, false>), dim3((unsigned)total), dim3(kDkvThreads), 0, st, p, Q, K, V, lse2, dO,
+                               Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, wpg, (int)band_grid, hw);
     }
     if (hipGetLastError() != hipSuccess) return SEPATTN_ERR_HIP;
     ProfScope prof(SEPATTN_K_BWD_COMBINE, st);
@@ -741,13 +771,15 @@ int launch_dkv(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
 
 }  // namespace
 
-int launch_dkv_bf16(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
+int launch_dkv_bf16(const sepattn_params &p, const HeadWin &hw, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
                     const float *lse2, const uint16_t *dO, const float *Dws, const int32_t *sep_idx,
                     const int32_t *sep_prefix, const int32_t *doc_end, uint16_t *dK, uint16_t *dV, float *farK,
                     float *farV, int32_t *piece_tab, hipStream_t st) {
+    bool headwise = false;
+    for (int h = 0; h < kMaxHeadwise; ++h) headwise = headwise || hw.delta[h] != 0;
     if (p.d == 64)
-        return launch_dkv<64>(p, Q, K, V, lse2, dO, Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, st);
-    return launch_dkv<128>(p, Q, K, V, lse2, dO, Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, st);
+        return launch_dkv<64>(p, hw, headwise, Q, K, V, lse2, dO, Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, st);
+    return launch_dkv<128>(p, hw, headwise, Q, K, V, lse2, dO, Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, st);
 }
 
 }  // namespace sepattn

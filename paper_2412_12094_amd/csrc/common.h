@@ -41,6 +41,20 @@ struct ProfScope {
     ~ProfScope() { profile_mark(kernel, st, true); }
 };
 
+// Head-wise neighbour windows (the head-wise variant of Sec. 4.6): every attention kernel runs with
+// p.n = the LARGEST window of the call and gets, by value, how much shorter each query head's own
+// window is.  The key streams and the far / band split are those of the largest window (so heads
+// that share K/V tiles still share them); only the visibility test of a band key uses the head's
+// own window:  key j, not an initial token or a separator, is visible to query i of head h iff
+// j <= i <= j + p.n - 1 - delta[h].  All zeros for an ordinary call.
+constexpr int kMaxHeadwise = SEPATTN_MAX_HEADWISE_HEADS;
+struct HeadWin {
+    int32_t delta[kMaxHeadwise];
+};
+__host__ __device__ inline int head_delta(const HeadWin &hw, int h) {
+    return hw.delta[h < kMaxHeadwise ? h : kMaxHeadwise - 1];
+}
+
 // ---- integer kernels -------------------------------------------------------------------------
 struct SepIdSet {
     int n;
@@ -55,10 +69,10 @@ int launch_compact(const uint8_t *is_sep, int B, int L, int32_t *sep_idx, int ca
 
 // ---- fp32 debug path ---------------------------------------------------------------------------
 // doc_start / doc_end: packed documents (per-position bounds [B, L]), or nullptr
-int launch_forward_fp32(const sepattn_params &p, const float *Q, const float *K, const float *V,
+int launch_forward_fp32(const sepattn_params &p, const HeadWin &hw, const float *Q, const float *K, const float *V,
                         const int32_t *sep_idx, const int32_t *sep_prefix, const int32_t *doc_start, float *O,
                         float *LSE, hipStream_t st);
-int launch_backward_fp32(const sepattn_params &p, const float *Q, const float *K, const float *V,
+int launch_backward_fp32(const sepattn_params &p, const HeadWin &hw, const float *Q, const float *K, const float *V,
                          const float *O, const float *LSE, const float *dO, const int32_t *sep_idx,
                          const int32_t *sep_prefix, const int32_t *doc_start, const int32_t *doc_end, float *dQ,
                          float *dK, float *dV, float *Dws, hipStream_t st);
@@ -66,13 +80,13 @@ int launch_backward_fp32(const sepattn_params &p, const float *Q, const float *K
 // ---- bf16 MFMA path ----------------------------------------------------------------------------
 size_t forward_bf16_workspace(const sepattn_params &p);
 // doc_start / doc_end: packed documents (per-position bounds [B, L]; p.a must be 0), or nullptr
-int launch_forward_bf16(const sepattn_params &p, const void *Q, const void *K, const void *V,
+int launch_forward_bf16(const sepattn_params &p, const HeadWin &hw, const void *Q, const void *K, const void *V,
                         const int32_t *sep_idx, const int32_t *sep_prefix, const int32_t *doc_start,
                         const int32_t *doc_end, void *O, float *LSE, void *ws, hipStream_t st);
 int launch_doc_bounds(const int32_t *cu_seqlens, int n_docs, int L, int a, int32_t *doc_start, int32_t *doc_end,
                       uint8_t *is_sep, hipStream_t st);
 size_t backward_bf16_workspace(const sepattn_params &p);
-int launch_backward_bf16(const sepattn_params &p, const void *Q, const void *K, const void *V,
+int launch_backward_bf16(const sepattn_params &p, const HeadWin &hw, const void *Q, const void *K, const void *V,
                          const void *O, const float *LSE, const void *dO, const int32_t *sep_idx,
                          const int32_t *sep_count, const int32_t *sep_prefix, const int32_t *doc_start,
                          const int32_t *doc_end, void *dQ, void *dK, void *dV, void *ws, hipStream_t st);

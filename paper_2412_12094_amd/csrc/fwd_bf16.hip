@@ -38,7 +38,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     sepattn_params p, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
     const uint16_t *__restrict__ V, const int32_t *__restrict__ sep_idx,
     const int32_t *__restrict__ sep_prefix, const int32_t *__restrict__ doc_start,
-    const int32_t *__restrict__ doc_end, uint16_t *__restrict__ O, float *__restrict__ LSE, int wpg) {
+    const int32_t *__restrict__ doc_end, uint16_t *__restrict__ O, float *__restrict__ LSE, int wpg, HeadWin hw) {
     constexpr int NW = 8;
     constexpr int TP = 32 * NW / GP;  // query positions per workgroup
     constexpr int CH = D / 8;         // 16-byte chunks per row
@@ -79,6 +79,10 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     const int kv = (y / groups) % p.Hkv;
     const int b = y / (groups * p.Hkv);
     const int head = kv * G + hg * GP + (wave % GP);
+    // head-wise windows: the stream is that of the largest window p.n; this head's window is shorter by
+    // hdelta, which only enters the visibility test of band keys (hi was computed with p.n) and the
+    // decision which blocks need no test
+    const int hdelta = head_delta(hw, head);
 
     const int32_t *prefix = sep_prefix + (long)b * (p.L + 1);
     const int32_t *idx = sep_idx + (long)b * p.cap;
@@ -88,7 +92,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     const uint16_t *Vh = V + ((long)b * p.Hkv + kv) * (long)p.L * D;
 
     // state of the current segment (the lambdas below refer to it)
-    int i0 = 0, pw = 0, iq = 0, n_tiles = 0;
+    int i0 = 0, pw = 0, iq = 0, iq_h = 0, n_tiles = 0;
     Stream st = {};
     FullBlocks fullb = {};
     bf16x8 qreg[KSTEPS];  // this wave's queries as B operands
@@ -316,7 +320,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
                     const int his[8] = {hi0.x, hi0.y, hi0.z, hi0.w, hi1.x, hi1.y, hi1.z, hi1.w};
 #pragma unroll
                     for (int k = 0; k < 8; ++k) {
-                        const bool vis = (los[k] <= iq) & (iq <= his[k]);
+                        const bool vis = (los[k] <= iq) & (iq_h <= his[k]);
                         s[8 * half + k] = vis ? s[8 * half + k] : -INFINITY;
                     }
                 }
@@ -478,9 +482,10 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     i0 = cseg.i0;
     pw = i0 + 32 * (wave / GP);  // first position of this wave
     iq = pw + qi;                // this lane's query position
+    iq_h = iq + hdelta;          // ... as the upper ends of the keys' query ranges (computed with p.n) see it
     st = cseg.st;
     n_tiles = cseg.n_tiles;
-    fullb = full_blocks(st, pw, p.n);
+    fullb = full_blocks(st, pw, p.n - hdelta);
     if (DOCS && pw + 31 >= cseg.de) fullb = no_full_blocks();
 #pragma unroll
     for (int db = 0; db < DB; ++db)
@@ -542,7 +547,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
 template <int D, bool DOCS>
 int launch_fwd(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
                const int32_t *sep_idx, const int32_t *sep_prefix, const int32_t *doc_start, const int32_t *doc_end,
-               uint16_t *O, float *LSE, hipStream_t st) {
+               uint16_t *O, float *LSE, const HeadWin &hw, hipStream_t st) {
     int G = p.Hq / p.Hkv;
     int GP = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
     int TP = 32 * 8 / GP;
@@ -556,11 +561,11 @@ int launch_fwd(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
     dim3 grid((unsigned)(n_groups * wpg)), block(512);
     ProfScope prof(SEPATTN_K_FORWARD, st);
     if (GP == 4)
-        hipLaunchKernelGGL((fwd_bf16_kernel<D, 4, DOCS>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, doc_start, doc_end, O, LSE, wpg);
+        hipLaunchKernelGGL((fwd_bf16_kernel<D, 4, DOCS>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, doc_start, doc_end, O, LSE, wpg, hw);
     else if (GP == 2)
-        hipLaunchKernelGGL((fwd_bf16_kernel<D, 2, DOCS>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, doc_start, doc_end, O, LSE, wpg);
+        hipLaunchKernelGGL((fwd_bf16_kernel<D, 2, DOCS>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, doc_start, doc_end, O, LSE, wpg, hw);
     else
-        hipLaunchKernelGGL((fwd_bf16_kernel<D, 1, DOCS>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, doc_start, doc_end, O, LSE, wpg);
+        hipLaunchKernelGGL((fwd_bf16_kernel<D, 1, DOCS>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, doc_start, doc_end, O, LSE, wpg, hw);
     return launch_status();
 }
 
@@ -568,18 +573,18 @@ int launch_fwd(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
 
 size_t forward_bf16_workspace(const sepattn_params &) { return 0; }
 
-int launch_forward_bf16(const sepattn_params &p, const void *Q, const void *K, const void *V,
+int launch_forward_bf16(const sepattn_params &p, const HeadWin &hw, const void *Q, const void *K, const void *V,
                         const int32_t *sep_idx, const int32_t *sep_prefix, const int32_t *doc_start,
                         const int32_t *doc_end, void *O, float *LSE, void *, hipStream_t st) {
     auto q = static_cast<const uint16_t *>(Q), k = static_cast<const uint16_t *>(K),
          v = static_cast<const uint16_t *>(V);
     auto o = static_cast<uint16_t *>(O);
     if (doc_start) {
-        if (p.d == 64) return launch_fwd<64, true>(p, q, k, v, sep_idx, sep_prefix, doc_start, doc_end, o, LSE, st);
-        return launch_fwd<128, true>(p, q, k, v, sep_idx, sep_prefix, doc_start, doc_end, o, LSE, st);
+        if (p.d == 64) return launch_fwd<64, true>(p, q, k, v, sep_idx, sep_prefix, doc_start, doc_end, o, LSE, hw, st);
+        return launch_fwd<128, true>(p, q, k, v, sep_idx, sep_prefix, doc_start, doc_end, o, LSE, hw, st);
     }
-    if (p.d == 64) return launch_fwd<64, false>(p, q, k, v, sep_idx, sep_prefix, nullptr, nullptr, o, LSE, st);
-    return launch_fwd<128, false>(p, q, k, v, sep_idx, sep_prefix, nullptr, nullptr, o, LSE, st);
+    if (p.d == 64) return launch_fwd<64, false>(p, q, k, v, sep_idx, sep_prefix, nullptr, nullptr, o, LSE, hw, st);
+    return launch_fwd<128, false>(p, q, k, v, sep_idx, sep_prefix, nullptr, nullptr, o, LSE, hw, st);
 }
 
 }  // namespace sepattn

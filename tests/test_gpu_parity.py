@@ -259,6 +259,72 @@ def test_backward_matches_oracle(sp, dtype, B, Hq, Hkv, L, d, a, n, p):
     check_backward(sp, B, Hq, Hkv, L, d, a, n, p, dtype, seed=2000 + L + n)
 
 
+HEADWISE_CASES = [
+    # B, Hq, Hkv, L, d, a, p, n per head
+    (1, 8, 2, 1100, 128, 4, 0.08, [256, 1100, 16, 64, 5000, 5000, 1, 300]),   # full-attention and short-window heads in one group
+    (2, 4, 4, 777, 64, 3, 0.10, [64, 1, 200, 777]),                           # MHA: every head its own K/V
+    (1, 8, 1, 520, 128, 2, 0.15, [33, 33, 33, 33, 33, 33, 33, 33]),           # all equal: must be the scalar call
+    (1, 4, 1, 300, 64, 0, 0.0, [7, 300, 64, 2]),                              # no separators, no initial tokens
+    (1, 2, 1, 65, 64, 5, 0.3, [1, 2]),
+    (1, 16, 2, 900, 128, 4, 0.1, [900, 900, 900, 900, 128, 128, 128, 128, 32, 900, 32, 900, 64, 64, 64, 64]),  # H_s of H heads windowed
+]
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("B,Hq,Hkv,L,d,a,p,nh", HEADWISE_CASES)
+def test_headwise_windows_forward_backward(sp, dtype, B, Hq, Hkv, L, d, a, p, nh):
+    """A neighbour window of its own for every query head (the head-wise variant of Sec. 4.6), among
+    them full-attention heads (n >= L) next to short-window heads inside one GQA group."""
+    tok, Q, K, V, dO = make_case(B, Hq, Hkv, L, d, p, dtype, 700 + L)
+    is_sep, idx, cnt, pre = gpu_index(sp, tok)
+    scale = 1.0 / math.sqrt(d)
+    q, k, v, do = (dev(x, dtype) for x in (Q, K, V, dO))
+    O, LSE = sp.sepattn_forward_headwise(q, k, v, idx, cnt, pre, a, nh, scale)
+    grads = sp.sepattn_backward_headwise(q, k, v, O, LSE, do, idx, cnt, pre, a, nh, scale)
+    torch.cuda.synchronize()
+    flags = host(is_sep)
+    rO, rL = oracle.forward(Q, K, V, flags, a, 1, scale, n_head=nh)
+    refs = oracle.backward(Q, K, V, dO, flags, a, 1, scale, n_head=nh, return_term_rss=True)
+    assert_close(host(O), rO, dtype, "O")
+    assert np.abs(host(LSE) - rL).max() <= LSE_TOL[dtype]
+    assert_grads_close(grads, refs, dtype)
+    if len(set(nh)) == 1:  # the scalar call gives the same bits
+        O2, LSE2 = sp.sepattn_forward(q, k, v, idx, cnt, pre, a, nh[0], scale)
+        g2 = sp.sepattn_backward(q, k, v, O2, LSE2, do, idx, cnt, pre, a, nh[0], scale)
+        assert torch.equal(O, O2) and torch.equal(LSE, LSE2) and all(torch.equal(x, y) for x, y in zip(grads, g2))
+
+
+def test_headwise_windows_zero_query_probe(sp):
+    """Q = 0 with per-head windows at the 8K shape: exp(LSE) is the count of visible keys on the oracle's
+    per-head mask, for every row of every head (four different windows inside every GQA group)."""
+    c = wl.CONFIGS["cfg3"]
+    tok = wl.make_token_ids(c.B, c.L, c.p, c.seed, "geometric")
+    is_sep, idx, cnt, pre = gpu_index(sp, tok)
+    nh = [c.L, 256, 64, 1000] * (c.Hq // 4)
+    g = torch.Generator(device="cuda").manual_seed(1)
+    K = torch.randn((c.B, c.Hkv, c.L, c.d), device="cuda", generator=g).to(torch.bfloat16)
+    V = torch.randn((c.B, c.Hkv, c.L, c.d), device="cuda", generator=g).to(torch.bfloat16)
+    Q = torch.zeros((c.B, c.Hq, c.L, c.d), device="cuda", dtype=torch.bfloat16)
+    O, LSE = sp.sepattn_forward_headwise(Q, K, V, idx, cnt, pre, c.a, nh, c.scale)
+    torch.cuda.synchronize()
+    flags = oracle.mark_separators(tok, wl.SEPARATOR_IDS)
+    rows = np.arange(c.L, dtype=np.int32)
+    got = torch.exp(LSE.double()).cpu().numpy()
+    for h in range(4):
+        counts = oracle_visible_counts(flags[0], c.a, nh[h], rows)
+        for hh in range(h, c.Hq, 4):
+            assert np.array_equal(np.rint(got[0, hh]).astype(np.int64), counts), hh
+
+
+def test_headwise_windows_are_validated(sp):
+    tok, Q, K, V, dO = make_case(1, 2, 2, 64, 64, 0.1, "bf16", 1)
+    is_sep, idx, cnt, pre = gpu_index(sp, tok)
+    q, k, v = (dev(x, "bf16") for x in (Q, K, V))
+    with pytest.raises(sp.SepattnError) as e:
+        sp.sepattn_forward_headwise(q, k, v, idx, cnt, pre, 4, [8, 0], 0.125)   # a window of 0
+    assert e.value.status == 3
+
+
 def oracle_visible_counts(flags_row, a, n, rows):
     """Number of visible keys of the given query rows, counted on the oracle's explicit mask (built in
     chunks of rows: the whole 64K x 64K mask would not fit)."""

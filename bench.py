@@ -427,29 +427,42 @@ def bench_decode(torch, sp, wl, ramp_seconds):
     flags0 = torch.from_numpy(data["win_is_sep"]).cuda()
     sizes0 = sizes.clone()
     flags, sz = flags0.clone(), sizes0.clone()
-    ews = torch.empty(1 << 20, dtype=torch.uint8, device=q.device)
-    times = []
-    for i in range(12):
-        flags.copy_(flags0)
-        sz.copy_(sizes0)
-        torch.cuda.synchronize()
+    # timed as one call in a stream of calls (generation enqueues it between decode steps): N x (restore the
+    # sizes, evict) minus N x (restore the sizes), HIP events on the launch stream
+    def stream_of(n, with_evict):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
         e0.record()
-        sp.sepkv_evict_window(Kc, Vc, flags, sz, c.Hq, c.a, c.s, c.w, ws=ews)
+        for _ in range(n):
+            sz.copy_(sizes0)
+            if with_evict:
+                sp.sepkv_evict_window(Kc, Vc, flags, sz, c.Hq, c.a, c.s, c.w)
         e1.record()
         torch.cuda.synchronize()
-        times.append(e0.elapsed_time(e1) * 1e3)
+        return e0.elapsed_time(e1) * 1e3 / n
+    stream_of(20, True)
+    times = [stream_of(100, True) - stream_of(100, False) for _ in range(5)]
+    ev_kernels = {}
+    for name in ("evict_move", "evict_sizes"):
+        prof = sp.sepattn_profile_begin(sp.KERNEL_IDS[name], 30)
+        for _ in range(30):
+            sz.copy_(sizes0)
+            sp.sepkv_evict_window(Kc, Vc, flags, sz, c.Hq, c.a, c.s, c.w)
+        torch.cuda.synchronize()
+        ev_kernels[name + "_us"] = round(1e3 * float(np.median(sp.sepattn_profile_end(prof)[5:])), 2)
     kept = int(data["win_is_sep"][:, : c.window_capacity - c.w].sum())
     row = c.d * 2
     # rows the method must move: the kept Past-Window rows and nothing else (the Separator Cache and the window
     # are rings: dropping the oldest separators and the Past Window moves heads, not rows); read + write, K and V
-    ev_us = float(np.median(times[2:]))
+    ev_us = float(np.median(times))
     ev_bytes = kept * row * 2 * 2 * c.Hkv
     res["evict"] = {"us": round(ev_us, 2), "kept_past_window_rows_all_sequences": kept, "moved_bytes": int(ev_bytes),
                     "roofline": {"bound": "hbm", "achieved": round(ev_bytes / ev_us / 1e3, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                  "frac": round(ev_bytes / ev_us / 1e3 / PEAK_HBM_GBS, 4),
                                  "traffic": MEASURED_TRAFFIC_BYTES.get("evict_move"),
-                                 "note": "two launches (plan, move) of a few microseconds each: launch-latency bound"}}
+                                 "note": "per call in a stream of calls; two launches (move, sizes) of a few microseconds "
+                                         "each: launch-latency bound"},
+                    "kernels_bracketed_by_events": ev_kernels}
     # the generation step (append + decode) captured once and replayed as a HIP graph
     sz_g, fl_g = sz_room.clone(), torch.from_numpy(data["win_is_sep"]).cuda()
     torch.cuda.synchronize()

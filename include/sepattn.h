@@ -315,7 +315,9 @@ int sepkv_append(const sepkv_params *p, const void *k_new, const void *v_new,
  *                                            Size_local_w, head_sep + dropped separators mod s,
  *                                            head_win + Size_past_w mod (c-a-s)), k = number of
  *                                            flagged Past-Window entries
- *   ws          DEVICE, >= sepkv_evict_workspace_bytes(p) bytes, 256-byte aligned
+ *   ws          not used: the step needs no scratch memory, sepkv_evict_workspace_bytes returns 0
+ *               and ws may be NULL (the two arguments are kept for callers written against a
+ *               workspace)
  * Slots outside the valid entries hold unspecified data afterwards.  The caller decides when to call
  * (the paper triggers it when Size_run reaches c).
  */
@@ -375,7 +377,7 @@ typedef enum {
     SEPATTN_K_BWD_COMBINE = 6,
     SEPATTN_K_DECODE_SPLIT = 7,
     SEPATTN_K_DECODE_MERGE = 8,
-    SEPATTN_K_EVICT_PLAN = 9,
+    SEPATTN_K_EVICT_SIZES = 9,
     SEPATTN_K_EVICT_MOVE = 10,
     SEPATTN_K_CACHE_FILL = 11,
     SEPATTN_K_ROPE_TABLE = 12,

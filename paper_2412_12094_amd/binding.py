@@ -163,7 +163,7 @@ def status_string(status: int) -> str:
 
 
 KERNEL_IDS = {"mark": 0, "compact_count": 1, "compact_write": 2, "forward": 3, "bwd_dq": 4, "bwd_dkv": 5,
-              "bwd_combine": 6, "decode_split": 7, "decode_merge": 8, "evict_plan": 9, "evict_move": 10,
+              "bwd_combine": 6, "decode_split": 7, "decode_merge": 8, "evict_sizes": 9, "evict_move": 10,
               "cache_fill": 11, "rope_table": 12, "cache_append": 13,
               "mark_interval": 14, "doc_bounds": 15}
 
@@ -542,11 +542,10 @@ def sepkv_evict_window(Kc, Vc, win_is_sep, sizes, Hq: int, a: int, s: int, w: in
     S, Hkv, c, d = Kc.shape
     p = SepkvParams(S, int(Hq), Hkv, d, int(a), int(s), int(w), c, 1.0, _dtype_code(Kc))
     lib = load()
-    if ws is None:
-        ws = _ws(lib.sepkv_evict_workspace_bytes(ctypes.byref(p)), Kc.device)
+    # the step needs no scratch memory: a workspace is passed on if the caller has one, NULL otherwise
     _check("sepkv_evict_window",
            lib.sepkv_evict_window(ctypes.byref(p), _ptr(Kc), _ptr(Vc), _ptr(win_is_sep), _ptr(sizes), _ptr(ws),
-                                  ws.numel(), _stream(Kc)))
+                                  0 if ws is None else ws.numel(), _stream(Kc)))
 
 
 def sepkv_fill_from_prefill(K, V, is_sep, sep_idx, sep_prefix, Hq: int, a: int, s: int, w: int, c: int, nw: int,

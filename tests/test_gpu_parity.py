@@ -612,6 +612,20 @@ def test_evict_matches_oracle_bit_exact(sp):
     check_evict(sp, cfg, sizes, np.zeros((5, wcap), dtype=np.uint8), seed=3)
 
 
+def test_evict_past_window_of_several_chunks(sp):
+    """Past Windows longer than what a workgroup compacts at a time (1024 entries), with fewer and with more
+    flagged entries than the Separator Cache holds: the rank of a kept entry carries over from chunk to chunk,
+    and so does the number of kept entries that fall out again."""
+    cfg = wl.CacheConfig("t", 3, 4, 2, 64, 2, 300, 8, 2 + 300 + 2700, 0.25, "bf16", seed=23)
+    wcap = cfg.window_capacity
+    sizes = np.array([[2, 100, 2500, 8], [2, 300, 2600, 100], [2, 0, 1025, 0]], dtype=np.int32)
+    assert (sizes[:, 2] + sizes[:, 3] <= wcap).all()
+    check_evict(sp, cfg, sizes, seed=4)                                        # ~625 kept: the old separators and ~325 of the kept fall out
+    sparse = (np.arange(wcap)[None, :] % 13 == 0).astype(np.uint8).repeat(3, axis=0)
+    check_evict(sp, cfg, sizes, sparse, seed=5)                                # ~200 kept: all stay
+    check_evict(sp, cfg, sizes, np.ones((3, wcap), dtype=np.uint8), seed=6)    # every entry kept, most fall out
+
+
 def test_evict_fp32_and_d64(sp):
     cfg = wl.CacheConfig("t", 2, 2, 2, 64, 1, 6, 4, 1 + 6 + 20, 0.4, "bf16", seed=19)
     sizes = np.array([[1, 3, 12, 4], [1, 6, 16, 4]], dtype=np.int32)

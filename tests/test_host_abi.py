@@ -108,7 +108,7 @@ def test_cache_call_validation(sp):
     lib = sp.load()
     ok = kv_params(sp)
     assert lib.sepattn_decode_workspace_bytes(ctypes.byref(ok)) >= 2 * 8 * 130 * 4
-    assert lib.sepkv_evict_workspace_bytes(ctypes.byref(ok)) >= 2 * (200 - 68) * 4
+    assert lib.sepkv_evict_workspace_bytes(ctypes.byref(ok)) == 0   # the compression step needs no scratch memory
     dec = lambda p, q=FAKE: lib.sepattn_decode(ctypes.byref(p), q, FAKE, FAKE, FAKE, FAKE, None, None, 0, None)
     assert dec(ok, None) == 1
     assert dec(kv_params(sp, a=100, s=80, w=32, c=200)) == 3   # a + s + w >= c
@@ -122,7 +122,7 @@ def test_cache_call_validation(sp):
     assert na(ok, None) == 1 and na(kv_params(sp, w=0)) == 3 and na(kv_params(sp, d=100)) == 4
     assert na(kv_params(sp, S=4096, Hq=8, Hkv=8, c=200)) == 5  # partial results beyond the fixed scratch array
     ev = lambda p, k=FAKE: lib.sepkv_evict_window(ctypes.byref(p), k, FAKE, FAKE, FAKE, None, 0, None)
-    assert ev(ok, None) == 1 and ev(ok) == 5
+    assert ev(ok, None) == 1 and ev(ok, ctypes.c_void_p(0x1004)) == 3   # NULL; misaligned cache
     assert ev(kv_params(sp, Hq=7, Hkv=2)) == 2
 
 

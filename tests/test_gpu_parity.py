@@ -1093,6 +1093,53 @@ def test_training_step_replays_in_a_hip_graph(sp):
             assert torch.equal(got, ref), rep
 
 
+def test_compress_then_generate_replays_in_a_hip_graph(sp):
+    """The compression step in front of a generation step (evict, append, decode), captured once: the
+    step needs no workspace and records no memset, and its second kernel only runs after the first has
+    read the sizes.  Every replay compresses whatever the previous appends pushed into the Past Window
+    and is checked against the oracle chain."""
+    S, Hq, Hkv, d, a, s, w = 3, 4, 2, 64, 2, 12, 4
+    c = a + s + 40
+    cfg = wl.CacheConfig("t", S, Hq, Hkv, d, a, s, w, c, 0.5, "bf16", seed=43)
+    sizes = np.array([[2, 10, 30, 4], [2, 12, 7, 4], [2, 0, 0, 3]], dtype=np.int32)
+    data = wl.make_cache(cfg, sizes)
+    rK, rV, rF, rS = bits(data["Kc"]), bits(data["Vc"]), data["win_is_sep"].copy(), sizes.copy()
+    Kp, Vp, Fp, sz6 = ring(rK, rV, rF, rS, a, s, seed=8)
+    Kd, Vd, Fd, Sd = as_dev_bits(Kp), as_dev_bits(Vp), dev(Fp), dev(sz6)
+    scale, steps = 1.0 / math.sqrt(d), 5
+    rng = np.random.default_rng(11)
+    to_f = lambda u: (u.astype(np.uint32) << 16).view(np.float32)
+    k_in = torch.zeros((S, Hkv, d), dtype=torch.bfloat16, device="cuda")
+    v_in, q_in = torch.zeros_like(k_in), torch.zeros((S, Hq, d), dtype=torch.bfloat16, device="cuda")
+    f_in = torch.zeros((S,), dtype=torch.uint8, device="cuda")
+    out, lse = torch.zeros_like(q_in), torch.zeros((S, Hq), dtype=torch.float32, device="cuda")
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sp.sepkv_evict_window(Kd, Vd, Fd, Sd, Hq, a, s, w)
+        sp.sepkv_append(k_in, v_in, f_in, Kd, Vd, Fd, Sd, Hq, a, s, w)
+        sp.sepattn_decode(q_in, Kd, Vd, Sd, a, s, w, scale, out=(out, lse), ws=ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(Sd)[:, :4], rS)  # capture ran nothing
+    for t in range(steps):
+        kn = rng.integers(0x3C00, 0x4000, size=(S, Hkv, d)).astype(np.uint16)
+        vn = rng.integers(0x3C00, 0x4000, size=(S, Hkv, d)).astype(np.uint16)
+        qn = wl.make_qkv(S, Hq, Hkv, 1, d, 1.0, 950 + t, "bf16")[0][:, :, 0]
+        fn = (rng.random(S) < 0.5).astype(np.uint8)
+        k_in.copy_(as_dev_bits(kn)); v_in.copy_(as_dev_bits(vn)); q_in.copy_(dev(qn, "bf16")); f_in.copy_(dev(fn))
+        graph.replay()
+        checksum = float(out.float().sum())  # eager library work and a synchronisation between replays
+        torch.cuda.synchronize()
+        rK, rV, rF, rS = oracle.evict_window(rK, rV, rF, rS, a, s)
+        rK, rV, rF, rS = oracle.append_token(rK, rV, rF, rS, kn, vn, fn, a, s, w)
+        ref, lref = oracle.decode(qn, to_f(rK), to_f(rV), rS, a, s, scale)
+        assert np.array_equal(host(Sd)[:, :4], rS), t
+        assert np.abs(host(out) - ref).max() <= 2e-2, t
+        assert np.abs(host(lse) - lref).max() <= 2e-3, t
+        assert math.isfinite(checksum)
+
+
 def test_generation_step_replays_in_a_hip_graph(sp):
     """A serving loop replays one captured generation step (append, then decode with positions within
     the cache): with caller-provided outputs and workspace the calls allocate nothing and touch the

@@ -20,7 +20,7 @@ def _built_oracle():
 
 
 # Every bf16 parity check records the plain max-abs error next to the bound it asserts; the records
-# are printed after the run and written to gpurun_out/parity_report.json, so that the distance from
+# are printed after the run and written to a JSON report in the run's output folder, so that the distance from
 # the flat 2e-2 of the target statement is on the record for every case, passing or not.
 PARITY_RECORDS = []
 

@@ -239,6 +239,10 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
             lo = kIntMax;
             hi = -1;
         }
+        // visibility of query row i for this lane's key: lo <= i <= hi, tested with one comparison as
+        // (unsigned)(i - lo) <= hi - lo; an empty range (hi < lo) becomes lo = max int, span 0
+        const int lo_m = hi >= lo ? lo : kIntMax;
+        const uint32_t span_m = hi >= lo ? (uint32_t)(hi - lo) : 0u;
         // wave-uniform bounds of the keys' query ranges, in scalar registers so that the per-block
         // decisions below are scalar branches
         const int lo_max = __builtin_amdgcn_readfirstlane(wave_max_i(lo));
@@ -522,11 +526,11 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
 #pragma unroll
             for (int i = 0; i < 16; ++i) x[i] = __builtin_amdgcn_exp2f(fmaf(x[i], sl2, -ls[i]));
             if (!k.full) {
+                const int rel = k.r0 + 8 * hh - lo_m;  // row of element i, relative to lo: rel + 16*(i/8) + i%8
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const int iqr = k.r0 + 16 * (i >> 3) + 8 * hh + (i & 7);
-                    bool vis = lo <= iqr && iqr <= hi;
-                    if constexpr (HW) vis = vis && (iqr + k.dlt <= hi2);
+                    bool vis = (uint32_t)(rel + (16 * (i >> 3) + (i & 7))) <= span_m;
+                    if constexpr (HW) vis = vis && (k.r0 + 16 * (i >> 3) + 8 * hh + (i & 7) + k.dlt <= hi2);
                     x[i] = vis ? x[i] : 0.f;
                 }
             }

@@ -39,9 +39,9 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
 # The figures and the commands are in profiles/; None = not measured for the current kernels.
 CALIB_BYTES = 256 << 20
 MEASURED_TRAFFIC_BYTES = {
-    "forward": 176.7e6,      # cfg3: read 108.5 MB + written 68.2 MB   (algorithmic: 168.8 MB)
+    "forward": 176.6e6,      # cfg3: read 108.5 MB + written 68.2 MB   (algorithmic: 168.8 MB)
     "bwd_dq": 324.7e6,       # cfg3: read 248.5 MB + written 76.3 MB
-    "bwd_dkv": 547.8e6,      # cfg3: read 473.4 MB (Q, dO tiles re-read by every list tile and band unit) + written 74.3 MB
+    "bwd_dkv": 543.2e6,      # cfg3: read 468.8 MB (Q, dO tiles re-read by every list tile and band unit) + written 74.4 MB
     "bwd_combine": 46.4e6,   # cfg3: read 43.6 MB + written 2.8 MB
     "cfg2_step": 554.8e6,    # forward 109.4 + dQ 167.5 + dK/dV 245.7 + combine 32.2 MB (algorithmic: 303.6 MB)
     "cfg4_forward": 1801.0e6,  # read 1255.8 MB + written 545.3 MB    (algorithmic: 1351 MB)

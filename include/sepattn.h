@@ -102,6 +102,16 @@ int sepattn_compact_indices(const uint8_t *is_sep, int B, int L, int32_t *sep_id
                             int32_t *sep_count, int32_t *sep_prefix, void *workspace,
                             size_t workspace_bytes, void *stream);
 
+/* Marking and compaction in one call (Sec. 4.1 "Parameter Setting" and Eq. 2): exactly the outputs
+ * of sepattn_mark_separators followed by sepattn_compact_indices, arguments as there (is_sep is an
+ * output here; sep_prefix may be NULL; the workspace is the one of the compaction).  Sequences of up
+ * to 8192 tokens take one kernel launch instead of two, which matters because at these sizes the
+ * kernels last no longer than their launch; longer ones run the separate kernels.
+ */
+int sepattn_mark_compact(const int32_t *token_ids, int B, int L, const int32_t *sep_ids, int n_sep,
+                         uint8_t *is_sep, int32_t *sep_idx, int cap, int32_t *sep_count,
+                         int32_t *sep_prefix, void *workspace, size_t workspace_bytes, void *stream);
+
 /* ------------------------------------------------------------------------------------------
  * Training / prefill attention (Eq. 1 with the mask of Eq. 2).
  * ------------------------------------------------------------------------------------------ */
@@ -384,7 +394,8 @@ typedef enum {
     SEPATTN_K_CACHE_APPEND = 13,
     SEPATTN_K_MARK_INTERVAL = 14,
     SEPATTN_K_DOC_BOUNDS = 15,
-    SEPATTN_K_COUNT = 16
+    SEPATTN_K_MARK_COMPACT = 16,
+    SEPATTN_K_COUNT = 17
 } sepattn_kernel_id;
 const char *sepattn_kernel_name(int kernel);
 typedef struct sepattn_profile sepattn_profile;

@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     sepattn_mark_separators,
     sepattn_mark_interval,
     sepattn_compact_indices,
+    sepattn_mark_compact,
     sepattn_forward,
     sepattn_forward_headwise,
     sepattn_backward_headwise,

@@ -28,6 +28,7 @@ EXPORTS = (
     "sepattn_mark_interval",
     "sepattn_compact_workspace_bytes",
     "sepattn_compact_indices",
+    "sepattn_mark_compact",
     "sepattn_forward_workspace_bytes",
     "sepattn_forward",
     "sepattn_forward_headwise",
@@ -99,6 +100,8 @@ def load(path: Optional[str] = None):
     lib.sepattn_compact_workspace_bytes.argtypes = [ci, ci]
     lib.sepattn_compact_indices.restype = ci
     lib.sepattn_compact_indices.argtypes = [vp, ci, ci, vp, ci, vp, vp, vp, sz, vp]
+    lib.sepattn_mark_compact.restype = ci
+    lib.sepattn_mark_compact.argtypes = [vp, ci, ci, vp, ci, vp, vp, ci, vp, vp, vp, sz, vp]
     pp = ctypes.POINTER(SepattnParams)
     lib.sepattn_forward_workspace_bytes.restype = sz
     lib.sepattn_forward_workspace_bytes.argtypes = [pp]
@@ -165,7 +168,7 @@ def status_string(status: int) -> str:
 KERNEL_IDS = {"mark": 0, "compact_count": 1, "compact_write": 2, "forward": 3, "bwd_dq": 4, "bwd_dkv": 5,
               "bwd_combine": 6, "decode_split": 7, "decode_merge": 8, "evict_sizes": 9, "evict_move": 10,
               "cache_fill": 11, "rope_table": 12, "cache_append": 13,
-              "mark_interval": 14, "doc_bounds": 15}
+              "mark_interval": 14, "doc_bounds": 15, "mark_compact": 16}
 
 
 def sepattn_kernel_name(kernel: int) -> str:
@@ -287,6 +290,38 @@ def sepattn_compact_indices(is_sep: torch.Tensor, cap: Optional[int] = None, wan
            lib.sepattn_compact_indices(_ptr(is_sep), B, L, _ptr(idx), cap, _ptr(cnt), _ptr(pre), _ptr(ws),
                                        ws.numel(), _stream(is_sep)))
     return idx, cnt, pre
+
+
+def sepattn_mark_compact(token_ids: torch.Tensor, sep_ids, cap: Optional[int] = None, want_prefix: bool = True,
+                         fill: int = -1, out=None, ws: Optional[torch.Tensor] = None):
+    """token_ids int32 [B,L] (GPU), sep_ids: host sequence of ints -> (is_sep uint8 [B,L], sep_idx int32 [B,cap],
+    sep_count int32 [B], sep_prefix int32 [B,L+1]): marking and compaction in one call.
+
+    Unless `out` = (is_sep, sep_idx, sep_count, sep_prefix) is given, the outputs are allocated and sep_idx is
+    pre-filled with `fill` by torch; the library leaves entries beyond the count untouched.
+    """
+    _dev(token_ids)
+    assert token_ids.dtype == torch.int32 and token_ids.dim() == 2
+    B, L = token_ids.shape
+    dev = token_ids.device
+    ids = (ctypes.c_int32 * len(sep_ids))(*[int(x) for x in sep_ids])
+    if out is None:
+        cap = L if cap is None else int(cap)
+        is_sep = torch.empty((B, L), dtype=torch.uint8, device=dev)
+        idx = torch.full((B, max(cap, 1)), fill, dtype=torch.int32, device=dev)
+        cnt = torch.empty((B,), dtype=torch.int32, device=dev)
+        pre = torch.empty((B, L + 1), dtype=torch.int32, device=dev) if want_prefix else None
+    else:
+        is_sep, idx, cnt, pre = out
+        _dev(is_sep, idx, cnt, pre)
+        cap = idx.shape[1]
+    lib = load()
+    if ws is None:
+        ws = _ws(lib.sepattn_compact_workspace_bytes(B, L), dev)
+    _check("sepattn_mark_compact",
+           lib.sepattn_mark_compact(_ptr(token_ids), B, L, ctypes.cast(ids, ctypes.c_void_p), len(sep_ids), _ptr(is_sep),
+                                    _ptr(idx), cap, _ptr(cnt), _ptr(pre), _ptr(ws), ws.numel(), _stream(token_ids)))
+    return is_sep, idx, cnt, pre
 
 
 def _attn_params(Q, K, a, n, scale, cap) -> SepattnParams:

@@ -143,7 +143,8 @@ const char *sepattn_kernel_name(int kernel) {
                                                  "dkv_combine_kernel", "decode_split_kernel",
                                                  "decode_merge_kernel", "evict_sizes_kernel",
                                                  "evict_move_kernel", "cache_fill_kernel", "rope_table_kernel",
-                                                 "cache_append_kernel", "mark_interval_kernel", "doc_bounds_kernel"};
+                                                 "cache_append_kernel", "mark_interval_kernel", "doc_bounds_kernel",
+                                                 "mark_compact_kernel"};
     return (kernel >= 0 && kernel < SEPATTN_K_COUNT) ? names[kernel] : "unknown";
 }
 
@@ -244,6 +245,24 @@ int sepattn_compact_indices(const uint8_t *is_sep, int B, int L, int32_t *sep_id
     discard_stale_hip_error();
     return launch_compact(is_sep, B, L, sep_idx, cap, sep_count, sep_prefix,
                           static_cast<int32_t *>(workspace), static_cast<hipStream_t>(stream));
+}
+
+int sepattn_mark_compact(const int32_t *token_ids, int B, int L, const int32_t *sep_ids, int n_sep,
+                         uint8_t *is_sep, int32_t *sep_idx, int cap, int32_t *sep_count,
+                         int32_t *sep_prefix, void *workspace, size_t workspace_bytes, void *stream) {
+    if (!token_ids || !sep_ids || !is_sep || !sep_idx || !sep_count) return SEPATTN_ERR_NULL;
+    if (B <= 0 || L <= 0 || B > 65535) return SEPATTN_ERR_SHAPE;
+    if (n_sep < 1 || n_sep > SEPATTN_MAX_SEP_IDS) return SEPATTN_ERR_PARAM;
+    if (cap < 1) return SEPATTN_ERR_CAPACITY;
+    if (!aligned(token_ids, 16) || !aligned(is_sep, 4)) return SEPATTN_ERR_PARAM;
+    if (!workspace || workspace_bytes < sepattn_compact_workspace_bytes(B, L) || !aligned(workspace, 4))
+        return SEPATTN_ERR_WORKSPACE;
+    SepIdSet set;
+    set.n = n_sep;
+    for (int k = 0; k < SEPATTN_MAX_SEP_IDS; ++k) set.ids[k] = k < n_sep ? sep_ids[k] : sep_ids[0];
+    discard_stale_hip_error();
+    return launch_mark_compact(token_ids, B, L, set, is_sep, sep_idx, cap, sep_count, sep_prefix,
+                               static_cast<int32_t *>(workspace), static_cast<hipStream_t>(stream));
 }
 
 size_t sepattn_forward_workspace_bytes(const sepattn_params *p) {

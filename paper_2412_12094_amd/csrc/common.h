@@ -66,6 +66,9 @@ int launch_mark_interval(int B, int L, int delta, int phase, uint8_t *is_sep, hi
 constexpr int kCompactChunk = 2048;  // tokens per workgroup of the compaction kernels
 int launch_compact(const uint8_t *is_sep, int B, int L, int32_t *sep_idx, int cap,
                    int32_t *sep_count, int32_t *sep_prefix, int32_t *chunk_counts, hipStream_t st);
+int launch_mark_compact(const int32_t *token_ids, int B, int L, const SepIdSet &set, uint8_t *is_sep,
+                        int32_t *sep_idx, int cap, int32_t *sep_count, int32_t *sep_prefix,
+                        int32_t *chunk_counts, hipStream_t st);
 
 // ---- fp32 debug path ---------------------------------------------------------------------------
 // doc_start / doc_end: packed documents (per-position bounds [B, L]), or nullptr

@@ -9,6 +9,9 @@
 //          the per-wave counts, and writes prefix / index entries.  No atomics, so the output
 //          order is the position order by construction.  Sequences of up to 32768 tokens take
 //          one launch: pass (2) then counts the flags of the earlier chunks itself.
+// mark + compact in one launch (sequences of up to 8192 tokens): pass (2) reads the token ids, tests
+//          them against the id set itself and also writes the marker bitmap; at these sizes each
+//          of the two kernels lasts no longer than its launch.
 #include "common.h"
 
 namespace sepattn {
@@ -82,6 +85,7 @@ int launch_mark_interval(int B, int L, int delta, int phase, uint8_t *is_sep, hi
 // ---- compaction --------------------------------------------------------------------------------
 constexpr int kCompactThreads = 256;
 constexpr int kCompactSingleLaunch = 32768;  // longest sequence compacted with one launch
+constexpr int kMarkCompactSingleLaunch = 8192;  // longest sequence marked and compacted with one launch
 constexpr int kCompactIters = kCompactChunk / kCompactThreads;  // 8 ballots per wave per chunk
 constexpr int kCompactWaves = kCompactThreads / kWave;
 
@@ -108,15 +112,25 @@ __global__ __launch_bounds__(kCompactThreads) void compact_count_kernel(
     }
 }
 
-// pass 2: ranks and writes
+__device__ inline bool in_id_set(int v, const SepIdSet &set) {
+    unsigned f = 0;
+    for (int k = 0; k < set.n; ++k) f |= (v == set.ids[k]);
+    return f != 0;
+}
+
+// pass 2: ranks and writes.  FUSED: the flags are not read from is_sep but formed from the token ids
+// (and written to marks_out for the chunk's own positions); chunk_counts is nullptr then.
+template <bool FUSED>
 __global__ __launch_bounds__(kCompactThreads) void compact_write_kernel(
-    const uint8_t *__restrict__ is_sep, int L, int n_chunks, const int32_t *__restrict__ chunk_counts,
+    const uint8_t *__restrict__ is_sep, const int32_t *__restrict__ token_ids, SepIdSet set,
+    uint8_t *__restrict__ marks_out, int L, int n_chunks, const int32_t *__restrict__ chunk_counts,
     int32_t *__restrict__ sep_idx, int cap, int32_t *__restrict__ sep_count,
     int32_t *__restrict__ sep_prefix) {
     __shared__ int part[kCompactIters * kCompactWaves];  // count of (iteration, wave) groups
     __shared__ int base_s;
     int b = blockIdx.y, chunk = blockIdx.x;
-    const uint8_t *row = is_sep + (long)b * L;
+    const uint8_t *row = FUSED ? nullptr : is_sep + (long)b * L;
+    const int32_t *ids_row = FUSED ? token_ids + (long)b * L : nullptr;
     int base = chunk * kCompactChunk;
     int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
 
@@ -132,7 +146,34 @@ __global__ __launch_bounds__(kCompactThreads) void compact_write_kernel(
     } else {
         __shared__ int early[kCompactWaves];
         int s = 0;
-        if ((reinterpret_cast<uintptr_t>(row) & 3u) == 0) {  // base is a multiple of 4
+        if constexpr (FUSED) {
+            // at most three chunks lie in front (8192 tokens per launch).  All loads of a thread are
+            // requested first; the id set is walked in the OUTER loop (one scalar load per id, not
+            // one per id and token), a token's matches are collected as bits and counted once, so
+            // that an id given twice does not count twice.
+            constexpr int kEarly = (kMarkCompactSingleLaunch - kCompactChunk) / (kCompactThreads * 4);
+            if ((reinterpret_cast<uintptr_t>(ids_row) & 15u) == 0) {  // base is a multiple of 4
+                int4 v[kEarly];
+                uint32_t there = 0, hit = 0;
+#pragma unroll
+                for (int q = 0; q < kEarly; ++q) {
+                    const int j = (q * kCompactThreads + (int)threadIdx.x) * 4;
+                    v[q] = j < base ? *reinterpret_cast<const int4 *>(ids_row + j) : int4{0, 0, 0, 0};
+                    there |= (j < base ? 0xFu : 0u) << (4 * q);
+                }
+                for (int k = 0; k < set.n; ++k) {
+                    const int sid = set.ids[k];
+#pragma unroll
+                    for (int q = 0; q < kEarly; ++q)
+                        hit |= ((uint32_t)(v[q].x == sid) | ((uint32_t)(v[q].y == sid) << 1) | ((uint32_t)(v[q].z == sid) << 2) |
+                                ((uint32_t)(v[q].w == sid) << 3))
+                               << (4 * q);
+                }
+                s = __popc(hit & there);
+            } else {
+                for (int j = threadIdx.x; j < base; j += kCompactThreads) s += in_id_set(ids_row[j], set);
+            }
+        } else if ((reinterpret_cast<uintptr_t>(row) & 3u) == 0) {  // base is a multiple of 4
             for (int j = threadIdx.x * 4; j < base; j += kCompactThreads * 4) {
                 const uint32_t w = *reinterpret_cast<const uint32_t *>(row + j);
                 // one bit per non-zero byte
@@ -153,9 +194,26 @@ __global__ __launch_bounds__(kCompactThreads) void compact_write_kernel(
     unsigned long long lt_mask = (1ull << lane) - 1ull;
     bool flag[kCompactIters];
     int rank_in_wave[kCompactIters];
+    uint32_t own_hit = 0;
+    if constexpr (FUSED) {
+        int own_id[kCompactIters];
+#pragma unroll
+        for (int it = 0; it < kCompactIters; ++it) own_id[it] = ids_row[min(base + it * kCompactThreads + (int)threadIdx.x, L - 1)];
+        for (int k = 0; k < set.n; ++k) {
+            const int sid = set.ids[k];
+#pragma unroll
+            for (int it = 0; it < kCompactIters; ++it) own_hit |= (uint32_t)(own_id[it] == sid) << it;
+        }
+    }
+#pragma unroll
     for (int it = 0; it < kCompactIters; ++it) {
         int j = base + it * kCompactThreads + threadIdx.x;
-        flag[it] = (j < L) && row[j] != 0;
+        if constexpr (FUSED) {
+            flag[it] = (j < L) && ((own_hit >> it) & 1u);
+            if (j < L) marks_out[(long)b * L + j] = flag[it] ? 1 : 0;
+        } else {
+            flag[it] = (j < L) && row[j] != 0;
+        }
         unsigned long long m = __ballot(flag[it]);
         rank_in_wave[it] = __popcll(m & lt_mask);
         if (lane == 0) part[it * kCompactWaves + wave] = __popcll(m);
@@ -203,8 +261,26 @@ int launch_compact(const uint8_t *is_sep, int B, int L, int32_t *sep_idx, int ca
         if (hipGetLastError() != hipSuccess) return SEPATTN_ERR_HIP;
     }
     ProfScope prof(SEPATTN_K_COMPACT_WRITE, st);
-    hipLaunchKernelGGL(compact_write_kernel, grid, dim3(kCompactThreads), 0, st, is_sep, L, n_chunks,
-                       single ? nullptr : chunk_counts, sep_idx, cap, sep_count, sep_prefix);
+    hipLaunchKernelGGL(compact_write_kernel<false>, grid, dim3(kCompactThreads), 0, st, is_sep, nullptr, SepIdSet{},
+                       nullptr, L, n_chunks, single ? nullptr : chunk_counts, sep_idx, cap, sep_count, sep_prefix);
+    return launch_status();
+}
+
+// marking and compaction together: one launch for sequences of up to kMarkCompactSingleLaunch tokens
+// (a workgroup then tests the ids in front of its chunk once more to count them), the separate
+// kernels beyond
+int launch_mark_compact(const int32_t *token_ids, int B, int L, const SepIdSet &set, uint8_t *is_sep,
+                        int32_t *sep_idx, int cap, int32_t *sep_count, int32_t *sep_prefix,
+                        int32_t *chunk_counts, hipStream_t st) {
+    if (L > kMarkCompactSingleLaunch) {
+        int rc = launch_mark(token_ids, (long)B * L, set, is_sep, st);
+        if (rc != SEPATTN_OK) return rc;
+        return launch_compact(is_sep, B, L, sep_idx, cap, sep_count, sep_prefix, chunk_counts, st);
+    }
+    int n_chunks = (L + kCompactChunk - 1) / kCompactChunk;
+    ProfScope prof(SEPATTN_K_MARK_COMPACT, st);
+    hipLaunchKernelGGL(compact_write_kernel<true>, dim3(n_chunks, B), dim3(kCompactThreads), 0, st, nullptr, token_ids,
+                       set, is_sep, L, n_chunks, nullptr, sep_idx, cap, sep_count, sep_prefix);
     return launch_status();
 }
 

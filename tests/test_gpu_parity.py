@@ -131,6 +131,36 @@ def test_mark_and_compact_bit_exact(sp, B, L, p):
     assert np.array_equal(host(idx), want_idx)  # tail stays at the -1 fill on both sides
 
 
+@pytest.mark.parametrize("B,L,p", [(1, 1, 0.5), (3, 63, 0.3), (2, 2047, 0.08), (1, 2048, 0.08), (3, 2049, 0.1),
+                                   (2, 5000, 0.0), (2, 4100, 1.0), (8, 2048, 0.1), (1, 8192, 0.08), (2, 8193, 0.08),
+                                   (1, 65536, 0.08)])
+def test_mark_compact_in_one_call_bit_exact(sp, B, L, p):
+    """Marking and compaction in one call: the marker bitmap, the list, the count and the prefix counts
+    are those of the oracle (one launch up to 8192 tokens per sequence, the separate kernels beyond)."""
+    tok = wl.make_token_ids(B, L, p, 31 + L)
+    want_flags = oracle.mark_separators(tok, wl.SEPARATOR_IDS)
+    want_idx, want_cnt, want_pre = oracle.compact_indices(want_flags)
+    is_sep, idx, cnt, pre = sp.sepattn_mark_compact(dev(tok.astype(np.int32)), wl.SEPARATOR_IDS.tolist())
+    torch.cuda.synchronize()
+    assert np.array_equal(host(is_sep), want_flags)
+    assert np.array_equal(host(cnt), want_cnt)
+    assert np.array_equal(host(pre), want_pre)
+    assert np.array_equal(host(idx), want_idx)  # tail stays at the -1 fill on both sides
+    # a one-id set and the largest set; a list shorter than the count; no prefix wanted
+    ids64 = list(range(100, 164))
+    tok2 = np.random.default_rng(L).integers(90, 180, size=(B, L)).astype(np.int32)
+    f2 = oracle.mark_separators(tok2, np.array(ids64))
+    i2, c2, p2 = oracle.compact_indices(f2)
+    cap = max(1, int(c2.max()) // 2)
+    g_sep, g_idx, g_cnt, g_pre = sp.sepattn_mark_compact(dev(tok2), ids64, cap=cap, want_prefix=False)
+    torch.cuda.synchronize()
+    assert g_pre is None and np.array_equal(host(g_sep), f2) and np.array_equal(host(g_cnt), c2)
+    gi = host(g_idx)
+    for b in range(B):
+        k = min(cap, int(c2[b]))
+        assert np.array_equal(gi[b, :k], i2[b, :k]) and (gi[b, k:] == -1).all()
+
+
 def test_compact_capacity_smaller_than_count(sp):
     tok = wl.make_token_ids(2, 3000, 0.2, 5)
     flags = oracle.mark_separators(tok, wl.SEPARATOR_IDS)

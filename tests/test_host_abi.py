@@ -102,6 +102,10 @@ def test_mark_and_compact_validation(sp):
     assert lib.sepattn_compact_indices(FAKE, 1, 8, FAKE, 0, FAKE, FAKE, FAKE, 256, None) == 6
     assert lib.sepattn_compact_indices(FAKE, 1, 8, FAKE, 8, FAKE, FAKE, None, 0, None) == 5
     assert lib.sepattn_compact_indices(None, 1, 8, FAKE, 8, FAKE, FAKE, FAKE, 256, None) == 1
+    mc = lambda tok=FAKE, L=8, n=3, cap=8, ws=FAKE, wsb=256: lib.sepattn_mark_compact(
+        tok, 1, L, idp, n, FAKE, FAKE, cap, FAKE, FAKE, ws, wsb, None)
+    assert mc(tok=None) == 1 and mc(L=0) == 2 and mc(n=0) == 3 and mc(n=65) == 3
+    assert mc(cap=0) == 6 and mc(ws=None, wsb=0) == 5 and mc(tok=ctypes.c_void_p(0x1004)) == 3
 
 
 def test_cache_call_validation(sp):
@@ -136,8 +140,8 @@ def test_profile_hook_argument_checks(sp):
     ms = (ctypes.c_float * 4)()
     assert lib.sepattn_profile_read(None, ms, 4, ctypes.byref(n)) == 1
     lib.sepattn_profile_destroy(None)  # a no-op
-    names = {sp.sepattn_kernel_name(k) for k in range(16)}
-    assert len(names) == 16 and sp.sepattn_kernel_name(16) == "unknown"
+    names = {sp.sepattn_kernel_name(k) for k in range(17)}
+    assert len(names) == 17 and sp.sepattn_kernel_name(17) == "unknown"
 
 
 def test_binding_refuses_cpu_tensors(sp):

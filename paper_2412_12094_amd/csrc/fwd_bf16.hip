@@ -60,6 +60,8 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     __shared__ __attribute__((aligned(1024))) uint16_t Vs[VST][TILE];
     __shared__ __attribute__((aligned(16))) int lo_s[VST][kBN];
     __shared__ __attribute__((aligned(16))) int hi_s[VST][kBN];
+    // staging of one 32-column block of a wave's 32 output rows (see the epilogue)
+    __shared__ __attribute__((aligned(16))) uint16_t ostage[8][32 * 32];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps branches scalar
@@ -523,19 +525,37 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     }
     float l_tot = pair_sum(l_run);
     float inv = 1.f / l_tot;
-    if (iq < p.L) {
-        long orow = ((long)b * p.Hq + head) * p.L + iq;
-        uint16_t *dst = O + orow * D;
+    // A lane holds 4-column pieces of ONE output row, so a store straight from the accumulators would
+    // write 64 scattered 8-byte pieces per instruction, and the number of such pieces (1024 per wave
+    // and segment) is what the stores cost.  Each 32-column block of the wave's 32 rows therefore goes
+    // through a 2 KB staging area of the wave and leaves as 16-byte pieces of which four consecutive
+    // lanes cover 64 contiguous bytes of a row (16 rows per store instruction).  8-byte chunk ch of
+    // row r sits at chunk position ch ^ (2 * ((r / 4) % 4)): 16-byte pairs stay together, and the
+    // writes (one chunk of 32 rows) spread over the banks.  The LDS operations of a wave execute in
+    // order, so a block's reads are issued before the next block's writes without a wait in between.
+    {
+        uint16_t *stg = &ostage[wave][0];
+        const long orow0 = ((long)b * p.Hq + head) * p.L + pw;  // output row of the wave's first query
+        const int wsw = ((qi >> 2) & 3) << 1;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+        for (int db = 0; db < DB; ++db) {
 #pragma unroll
             for (int i4 = 0; i4 < 4; ++i4) {
-                uint2 v = pack_bf16x4(oacc[db][4 * i4] * inv, oacc[db][4 * i4 + 1] * inv,
-                                      oacc[db][4 * i4 + 2] * inv, oacc[db][4 * i4 + 3] * inv);
-                *reinterpret_cast<uint2 *>(dst + db * 32 + 8 * i4 + 4 * hh) = v;
+                const uint2 v = pack_bf16x4(oacc[db][4 * i4] * inv, oacc[db][4 * i4 + 1] * inv,
+                                            oacc[db][4 * i4 + 2] * inv, oacc[db][4 * i4 + 3] * inv);
+                *reinterpret_cast<uint2 *>(stg + qi * 32 + (((2 * i4 + hh) ^ wsw) * 4)) = v;
             }
-        if (hh == 0) LSE[orow] = (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2_f;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int r = 16 * t + (lane >> 2), c = lane & 3;
+                const int pos = (2 * c) ^ (((r >> 2) & 3) << 1);
+                const uint4 v = *reinterpret_cast<const uint4 *>(stg + r * 32 + pos * 4);
+                if (pw + r < p.L) *reinterpret_cast<uint4 *>(O + (orow0 + r) * D + db * 32 + c * 8) = v;
+            }
+            __builtin_amdgcn_sched_barrier(0);  // one block at a time: keeps the register pressure of the epilogue down
+        }
     }
+    if (iq < p.L && hh == 0) LSE[((long)b * p.Hq + head) * p.L + iq] = (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2_f;
     cseg = cnext;
     cnext = open_segment(round + 2);
     }  // segments

@@ -76,6 +76,8 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
     __shared__ __attribute__((aligned(1024))) uint16_t Vs[VST][TILE];
     __shared__ __attribute__((aligned(16))) int lo_s[MKS][kBN];
     __shared__ __attribute__((aligned(16))) int hi_s[MKS][kBN];
+    // staging of one 32-column block of a wave's 32 dQ rows (see the end of a segment)
+    __shared__ __attribute__((aligned(16))) uint16_t ostage[8][32 * 32];
     constexpr int MR = LOADS * RPL;  // rows per wave and tile
     constexpr int MST = 4;           // ring stages of the index entries
     __shared__ __attribute__((aligned(256))) int meta_s[MST][NLW][64];  // 3 * MR <= 48 entries per wave and stage
@@ -414,17 +416,32 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
         }
         gbase += n_tiles;
 
-        if (iq < p.L) {
-            char *dqb = reinterpret_cast<char *>(dQ + head_row0 * D);
-            const uint32_t voff = (uint32_t)iq * (uint32_t)(D * 2) + 8u * hh;
+        // A lane holds 4-column pieces of ONE dQ row: stored straight from the accumulators they are 64
+        // scattered 8-byte pieces per instruction, and their number is what the stores cost.  Each
+        // 32-column block of the wave's 32 rows goes through a 2 KB staging area of the wave instead
+        // and leaves as 16-byte pieces of which four consecutive lanes cover 64 contiguous bytes of a
+        // row.  8-byte chunk ch of row r sits at chunk position ch ^ (2 * ((r / 4) % 4)); the LDS
+        // operations of a wave execute in order, so a block's reads precede the next block's writes.
+        {
+            uint16_t *stg = &ostage[wave][0];
+            const int wsw = ((qi >> 2) & 3) << 1;
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+            for (int db = 0; db < DB; ++db) {
 #pragma unroll
                 for (int i4 = 0; i4 < 4; ++i4) {
-                    uint2 v = pack_bf16x4(acc[db][4 * i4] * p.scale, acc[db][4 * i4 + 1] * p.scale,
-                                          acc[db][4 * i4 + 2] * p.scale, acc[db][4 * i4 + 3] * p.scale);
-                    *reinterpret_cast<uint2 *>(dqb + (voff + 64u * db + 16u * i4)) = v;
+                    const uint2 v = pack_bf16x4(acc[db][4 * i4] * p.scale, acc[db][4 * i4 + 1] * p.scale,
+                                                acc[db][4 * i4 + 2] * p.scale, acc[db][4 * i4 + 3] * p.scale);
+                    *reinterpret_cast<uint2 *>(stg + qi * 32 + (((2 * i4 + hh) ^ wsw) * 4)) = v;
                 }
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const int r = 16 * t + (lane >> 2), c = lane & 3;
+                    const int pos = (2 * c) ^ (((r >> 2) & 3) << 1);
+                    const uint4 v = *reinterpret_cast<const uint4 *>(stg + r * 32 + pos * 4);
+                    if (pw + r < p.L) *reinterpret_cast<uint4 *>(dQ + (head_row0 + pw + r) * D + db * 32 + c * 8) = v;
+                }
+                __builtin_amdgcn_sched_barrier(0);  // one block at a time: keeps the register pressure down
+            }
         }
         cseg = open_segment(round + 1);
     }

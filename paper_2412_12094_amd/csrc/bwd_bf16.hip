@@ -365,30 +365,79 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
 
     const IntC<1> yes;
     const IntC<0> no;
+    // The wave's 32 rows of Q, dO and O of a segment.  The operand layout wants, per lane, 16-byte pieces
+    // of ONE row; fetched that way every load instruction is 64 scattered pieces, and their number (1536
+    // per wave and segment) is what such loads cost.  They are fetched instead so that four consecutive
+    // lanes cover 64 contiguous bytes of a row (column block cb of 32 columns, rows 16 t + lane / 4,
+    // piece lane % 4), and they are requested one segment ahead, before the previous segment's dQ rows
+    // are stored, so that the store path hides their latency.  (Past the last segment: row 0, unused.)
+    constexpr int CB = D / 32;  // column blocks of 32 columns (64 bytes of a row)
+    const long head_row0 = ((long)b * p.Hq + head) * p.L;  // rows of this wave's head
+    u32x4 q4[CB][2], do4[CB][2], o4[CB][2];
+    auto fetch_rows = [&](const Seg &sg) __attribute__((always_inline)) {
+        const char *qb = reinterpret_cast<const char *>(Q + head_row0 * D);
+        const char *dob = reinterpret_cast<const char *>(dO + head_row0 * D);
+        const char *ob = reinterpret_cast<const char *>(O + head_row0 * D);
+        const int pwn = max(sg.i0, 0) + 32 * (wave / GP);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const uint32_t roff = (uint32_t)min(pwn + 16 * t + (lane >> 2), p.L - 1) * (uint32_t)(D * 2) + 16u * (lane & 3);
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                q4[cb][t] = *reinterpret_cast<const u32x4 *>(qb + (roff + 64u * cb));
+                do4[cb][t] = *reinterpret_cast<const u32x4 *>(dob + (roff + 64u * cb));
+                o4[cb][t] = *reinterpret_cast<const u32x4 *>(ob + (roff + 64u * cb));
+            }
+        }
+    };
     Seg cseg = open_segment(0);
+    fetch_rows(cseg);
     for (int round = 0; cseg.i0 >= 0; ++round) {
         const int pw = cseg.i0 + 32 * (wave / GP);
         iq = pw + qi;
         iq_h = iq + hdelta;
         fullb = full_blocks(cseg.st, pw, p.n - hdelta);
         if (DOCS && pw + 31 >= cseg.de) fullb = no_full_blocks();
-        // rows of this wave's head: (uniform base) + 32-bit byte offset of the lane's piece
-        const long head_row0 = ((long)b * p.Hq + head) * p.L;
         {
-            const uint32_t voff = (uint32_t)min(iq, p.L - 1) * (uint32_t)(D * 2) + 16u * hh;
-            const char *qb = reinterpret_cast<const char *>(Q + head_row0 * D);
-            const char *dob = reinterpret_cast<const char *>(dO + head_row0 * D);
-            const char *ob = reinterpret_cast<const char *>(O + head_row0 * D);
-            float part = 0.f;
+            // Q and dO reach their operand layout through the wave's 2 KB staging area, one column block
+            // at a time (16-byte piece c of row r at piece position c ^ ((r / 4) % 4); the LDS operations
+            // of a wave execute in order).  D_i = sum_k dO_ik O_ik needs no particular layout: partial
+            // sums per lane, then over the four lanes of a row, then handed to the lane pair that owns
+            // the row.
+            float part[2] = {0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks) {
-                u32x4 dq4 = *reinterpret_cast<const u32x4 *>(dob + (voff + 32u * ks));
-                u32x4 o4 = *reinterpret_cast<const u32x4 *>(ob + (voff + 32u * ks));
-                qreg[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(qb + (voff + 32u * ks)));
-                doreg[ks] = as_bf16x8(dq4);
-                part += bf16_dot8(dq4, o4);
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) part[t] += bf16_dot8(do4[cb][t], o4[cb][t]);
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                part[t] += __shfl_xor(part[t], 1);
+                part[t] += __shfl_xor(part[t], 2);
             }
-            Di = pair_sum(part);
+            // row qi is held by the lanes 4 (qi % 16) .. +3 in part[qi / 16]
+            {
+                const float d0 = __shfl(part[0], 4 * (qi & 15)), d1 = __shfl(part[1], 4 * (qi & 15));
+                Di = qi < 16 ? d0 : d1;
+            }
+            uint16_t *stg = &ostage[wave][0];
+            const int wr0 = (lane >> 2), wc = lane & 3;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                static_for<2>([&](auto X) {
+                    constexpr bool is_q = decltype(X)::value == 0;
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        const int r = 16 * t + wr0;
+                        *reinterpret_cast<u32x4 *>(stg + r * 32 + ((wc ^ ((r >> 2) & 3)) * 8)) = is_q ? q4[cb][t] : do4[cb][t];
+                    }
+#pragma unroll
+                    for (int k2 = 0; k2 < 2; ++k2) {
+                        const u32x4 v = *reinterpret_cast<const u32x4 *>(stg + qi * 32 + (((2 * k2 + hh) ^ ((qi >> 2) & 3)) * 8));
+                        if constexpr (is_q) qreg[2 * cb + k2] = as_bf16x8(v);
+                        else doreg[2 * cb + k2] = as_bf16x8(v);
+                    }
+                });
+            }
             const uint32_t soff = (uint32_t)min(iq, p.L - 1) * 4u;
             lse2 = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(LSE + head_row0) + soff) * kLog2e_f;
             if (hh == 0 && iq < p.L) {
@@ -415,6 +464,9 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
             block_step(X, IntC<1>{}, no);
         }
         gbase += n_tiles;
+        const Seg nseg = open_segment(round + 1);
+        fetch_rows(nseg);
+        __builtin_amdgcn_sched_barrier(0);
 
         // A lane holds 4-column pieces of ONE dQ row: stored straight from the accumulators they are 64
         // scattered 8-byte pieces per instruction, and their number is what the stores cost.  Each
@@ -443,7 +495,7 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
                 __builtin_amdgcn_sched_barrier(0);  // one block at a time: keeps the register pressure down
             }
         }
-        cseg = open_segment(round + 1);
+        cseg = nseg;
     }
     // the loads of the padding tiles past the last segment must have landed before the workgroup
     // ends and its LDS is handed on

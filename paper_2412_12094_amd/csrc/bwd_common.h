@@ -7,38 +7,50 @@
 
 namespace sepattn {
 
-constexpr int kDkvWaves = 4;              // key blocks of 32 keys per dK/dV workgroup (two waves each)
-constexpr int kDkvThreads = 2 * 64 * kDkvWaves;
-constexpr int kBK = 32 * kDkvWaves;  // keys per dK/dV workgroup
-constexpr int kBQ = 64;              // queries per LDS tile in the dK/dV kernels
+// A dK/dV workgroup holds KW key blocks of 32 keys, two waves each (32 KW keys, 128 KW threads), in one
+// of two shapes:
+//   KW = 4: 8 waves, one workgroup per compute unit.  Fewest tile loads per matrix instruction; the
+//           better shape when a workgroup's pieces are long (d = 128, grouped heads, long sequences).
+//   KW = 2: 4 waves, two workgroups per compute unit that run independently: one's piece start-up and
+//           partial stores overlap the other's matrix work, the split of a (batch, KV head) is twice
+//           as fine (it fills the chip where 256 / (B Hkv) is not a whole number), and the two
+//           workgroups' barriers do not lock each other's phases.
+// The choice is a function of the problem alone, so that the workspace query, the dK/dV pass and the
+// combine pass agree on it.
+__host__ __device__ inline int dkv_key_blocks(const sepattn_params &p) {
+    const long G = p.Hq / p.Hkv;
+    return (p.d == 128 && G * p.L >= 32768) ? 4 : 2;
+}
 
 __host__ __device__ inline int align_down32(int x) { return x & ~31; }
 
-// The far work of one (batch, KV head): for list tile ft (128 consecutive list entries) the
-// "items" (query tile of 64 rows, query head) from the first query that can see the tile's first key
+// The far work of one (batch, KV head): for list tile ft (bk = 32 KW consecutive list entries) the
+// "items" (query tile, query head) from the first query that can see the tile's first key
 // to the end of the sequence.  The items of all list tiles, in this order, are cut into `wpg` slices
 // of equal length, one per workgroup; the part of a slice that lies in one list tile is a "piece" and
 // produces one fp32 partial of that tile's dK / dV rows.  Piece (w, ft) uses partial slot w + ft
 // (along the pieces either w or ft grows, so the slot numbers are distinct).
 struct FarGeom {
     int wpg;     // workgroups per (batch, KV head)
-    int NFcap;   // capacity of the far list, a multiple of kBK
+    int bk;      // keys per workgroup and entries per list tile: 32 KW
+    int NFcap;   // capacity of the far list, a multiple of bk
     int NFTcap;  // list tiles at full capacity
     int NP;      // partial slots per (batch, KV head)
-    long rows;   // fp32 partial rows per (batch, KV head): NP slots of kBK rows, then one band row per list entry
+    long rows;   // fp32 partial rows per (batch, KV head): NP slots of bk rows, then one band row per list entry
 };
 inline int dkv_workgroups_per_head(const sepattn_params &p) {
     const long n_bkv = (long)p.B * p.Hkv;
-    const long w = compute_units() / n_bkv;
+    const long w = (dkv_key_blocks(p) == 2 ? 2 : 1) * (long)compute_units() / n_bkv;
     return (int)(w < 1 ? 1 : w);
 }
 __host__ __device__ inline FarGeom far_geom(const sepattn_params &p, int wpg) {
     FarGeom g;
     g.wpg = wpg;
-    g.NFcap = (p.a + p.cap + kBK - 1) / kBK * kBK;
-    g.NFTcap = g.NFcap / kBK;
+    g.bk = 32 * dkv_key_blocks(p);
+    g.NFcap = (p.a + p.cap + g.bk - 1) / g.bk * g.bk;
+    g.NFTcap = g.NFcap / g.bk;
     g.NP = wpg + g.NFTcap;
-    g.rows = (long)g.NP * kBK + g.NFcap;
+    g.rows = (long)g.NP * g.bk + g.NFcap;
     return g;
 }
 
@@ -83,8 +95,8 @@ __device__ inline int far_index(const FarList &fl, const int32_t *__restrict__ p
 }
 // first query row the far pieces of list entry f's tile cover (>= L: the entry has no far piece)
 __device__ inline int far_first_query(const FarList &fl, int f, const int32_t *__restrict__ idx,
-                                      const sepattn_params &p) {
-    return align_down32(far_pos(fl, (f / kBK) * kBK, idx, p.L) + p.n);
+                                      const sepattn_params &p, int bk) {
+    return align_down32(far_pos(fl, (f / bk) * bk, idx, p.L) + p.n);
 }
 
 // one past the last query row the far pieces of list entry f's tile cover: the end of the sequence,
@@ -92,9 +104,9 @@ __device__ inline int far_first_query(const FarList &fl, int f, const int32_t *_
 // nullptr), the end of the document of the tile's last entry.  A tile whose first query row
 // (far_first_query) is not below this has no far piece.
 __device__ inline int far_last_query(const FarList &fl, int f, const int32_t *__restrict__ idx,
-                                     const sepattn_params &p, const int32_t *__restrict__ dend) {
+                                     const sepattn_params &p, const int32_t *__restrict__ dend, int bk) {
     if (!dend) return p.L;
-    const int last = min((f / kBK + 1) * kBK, fl.NF) - 1;
+    const int last = min((f / bk + 1) * bk, fl.NF) - 1;
     return min(max(dend[far_pos(fl, last, idx, p.L)], 0), p.L);
 }
 

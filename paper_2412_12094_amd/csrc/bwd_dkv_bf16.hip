@@ -54,8 +54,8 @@ __device__ inline int wave_max_i(int v) {
 // HW: head-wise windows.  p.n is the largest window: it fixes the far / band split and the schedule;
 // in a band unit a key that is neither an initial token nor a separator is visible to query i of head
 // h only while i <= j + p.n - 1 - delta[h] (a third comparison in the blocks that need the mask test).
-template <int D, bool DOCS, bool HW>
-__global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
+template <int D, bool DOCS, bool HW, int KW>
+__global__ __launch_bounds__(128 * KW, KW == 4 ? 1 : 2) void dkv_kernel(
     sepattn_params p, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
     const uint16_t *__restrict__ V, const float *__restrict__ LSE2, const uint16_t *__restrict__ dO,
     const float *__restrict__ Dws, const int32_t *__restrict__ sep_idx,
@@ -63,26 +63,32 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
     uint16_t *__restrict__ dK, uint16_t *__restrict__ dV,
     float *__restrict__ farK, float *__restrict__ farV, int32_t *__restrict__ piece_tab, int wpg, int n_band,
     HeadWin hw) {
-    constexpr int NW = 2 * kDkvWaves;        // waves per workgroup
+    constexpr int NW = 2 * KW;               // waves per workgroup
+    constexpr int BK = 32 * KW;              // keys per workgroup
     constexpr int CH = D / 8;                // 16-byte chunks per row
     constexpr int RPL = 64 / CH;             // rows covered by one wave-wide 1 KB load
-    constexpr int LOADS = kBQ / (RPL * NW);  // wave-wide loads per wave per tensor per tile
+    // Query rows per LDS tile.  Two workgroups per compute unit have 80 KB each: at d = 128 the ring of
+    // four tiles then holds tiles of 32 rows (one block), else of 64 rows (two blocks).
+    constexpr int BQ = (KW == 2 && D == 128) ? 32 : 64;
+    constexpr int BPT = BQ / 32;             // blocks of 32 query rows per tile
+    constexpr int LOADS = BQ / (RPL * NW);   // wave-wide loads per wave per tensor per tile
+    constexpr int RVL = (2 * BQ / 16) / NW;  // loads of sixteen row values (LSE*log2e or -D) per wave per tile
     constexpr int KSTEPS = D / 16;
     constexpr int DB = D / 32;
-    constexpr int TILE = kBQ * D;
+    constexpr int TILE = BQ * D;
     constexpr int NBUF = 4;
-    static_assert(LOADS >= 1 && LOADS * RPL * NW == kBQ, "tile must divide among the waves");
+    static_assert(LOADS >= 1 && LOADS * RPL * NW == BQ && RVL >= 1 && RVL * 16 * NW == 2 * BQ, "tile must divide among the waves");
 
     __shared__ __attribute__((aligned(1024))) uint16_t Qs[NBUF][TILE];
     __shared__ __attribute__((aligned(1024))) uint16_t dOs[NBUF][TILE];
-    __shared__ __attribute__((aligned(256))) float lse_s[NBUF][kBQ];
-    __shared__ __attribute__((aligned(256))) float d_s[NBUF][kBQ];
-    __shared__ __attribute__((aligned(1024))) uint16_t Pex[kDkvWaves][2][2][64 * 8];  // [key block][step parity][k-half][lane*8], bf16
+    __shared__ __attribute__((aligned(256))) float lse_s[NBUF][BQ];
+    __shared__ __attribute__((aligned(256))) float d_s[NBUF][BQ];
+    __shared__ __attribute__((aligned(1024))) uint16_t Pex[KW][2][2][64 * 8];  // [key block][step parity][k-half][lane*8], bf16
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int role = wave / kDkvWaves;  // 0: P-wave (S, dV), 1: dS-wave (dP, dK)
-    const int kbw = wave % kDkvWaves;   // key block of the wave
+    const int role = wave / KW;  // 0: P-wave (S, dV), 1: dS-wave (dP, dK)
+    const int kbw = wave % KW;   // key block of the wave
     const int kj = lane & 31, hh = lane >> 5;
     const int G = p.Hq / p.Hkv;
     // 1-D grid: consecutive workgroups belong to consecutive (batch, KV head) pairs, so with 8 KV heads
@@ -117,15 +123,15 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
 
     // ---- the far work of this (batch, KV head) and this workgroup's slice [s0, s1) of it.
     // Lane t of a group of 64 list tiles describes tile t: first query row and number of items.
-    const int NFT = (fl.NF + kBK - 1) / kBK;
+    const int NFT = (fl.NF + BK - 1) / BK;
     auto tile_items = [&](int t, int &fq) __attribute__((always_inline)) {
         fq = p.L;
         int qe = p.L;
         if (t < NFT) {
-            fq = align_down32(far_pos(fl, t * kBK, idx, p.L) + p.n);
-            qe = far_last_query(fl, t * kBK, idx, p, dend);
+            fq = align_down32(far_pos(fl, t * BK, idx, p.L) + p.n);
+            qe = far_last_query(fl, t * BK, idx, p, dend, BK);
         }
-        return fq < qe ? G * ((qe - fq + kBQ - 1) / kBQ) : 0;
+        return fq < qe ? G * ((qe - fq + BQ - 1) / BQ) : 0;
     };
     auto inclusive_scan = [&](int v) __attribute__((always_inline)) {
 #pragma unroll
@@ -210,19 +216,19 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
         bool valid;
         if (FAR) {
             q_lo = fq0;
-            q_hi = far_last_query(fl, ft * kBK, idx, p, dend);
-            fidx = ft * kBK + 32 * kbw + kj;
+            q_hi = far_last_query(fl, ft * BK, idx, p, dend, BK);
+            fidx = ft * BK + 32 * kbw + kj;
             valid = fidx < fl.NF;
             j = valid ? far_pos(fl, fidx, idx, p.L) : 0;
             lo = j + p.n;
             hi = q_hi - 1;
             if constexpr (DOCS) hi = min(hi, dend[j] - 1);
         } else {
-            int j0 = unit * kBK;
+            int j0 = unit * BK;
             j = j0 + 32 * kbw + kj;
             valid = j < p.L;
             q_lo = j0;
-            q_hi = min(p.L, j0 + kBK + p.n - 1);
+            q_hi = min(p.L, j0 + BK + p.n - 1);
             lo = j;
             hi = min(j + p.n - 1, p.L - 1);
             if constexpr (HW) {
@@ -232,7 +238,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
             if (!valid) j = 0;
             if constexpr (DOCS) hi = min(hi, dend[j] - 1);
             item0 = 0;
-            n_qt = (q_hi - q_lo + kBQ - 1) / kBQ;
+            n_qt = (q_hi - q_lo + BQ - 1) / BQ;
             n_items = G * n_qt;
         }
         if (!valid) {
@@ -272,15 +278,19 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
         // key blocks kb <= b start the new one (block b, which the others cannot see either: its
         // queries come before their keys).  A head then costs NBK steps instead of nbh.
         const int n_tiles = n_items;
-        const int nbh = FAR ? 2 * n_tiles : 2 * n_qt;            // blocks per "head" (a far piece is one run)
+        const int nbh = FAR ? BPT * n_tiles : BPT * n_qt;        // blocks per "head" (a far piece is one run)
         const int NBK = (p.n + 30) / 32 + 1;
-        // steps from one head's start to the next's: at least NBK; at most kDkvWaves-1 merged steps;
+        // steps from one head's start to the next's: at least NBK; at most KW-1 merged steps;
         // and more than half a head, so that a head's tail only overlaps the head that follows it and
         // the ring of NBUF tiles always holds what two consecutive steps need
         int st_P = NBK > nbh / 2 + 1 ? NBK : nbh / 2 + 1;
-        st_P = st_P > nbh - (kDkvWaves - 1) ? st_P : nbh - (kDkvWaves - 1);
+        st_P = st_P > nbh - (KW - 1) ? st_P : nbh - (KW - 1);
+        // a tile is requested one barrier before the barrier that waits for it, so the tiles of three
+        // consecutive steps must fit the ring: with one block per tile a head's first step needs two
+        // plain steps behind it
+        if (BPT == 1 && st_P < 3) st_P = 3;
         if (FAR || st_P > nbh) st_P = nbh;
-        const int st_ov = nbh - st_P;                            // 0 .. kDkvWaves-1
+        const int st_ov = nbh - st_P;                            // 0 .. KW-1
         const int st_G = FAR ? 1 : G;
         const int n_blocks = (st_G - 1) * st_P + nbh;            // steps of the piece
         const int tiles_per_head = FAR ? 0 : n_qt;
@@ -294,7 +304,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
         auto issue_tile = [&]() {
             const int buf = iss_tt % NBUF;
             const long hrow0 = ((long)b * p.Hq + kv * G + iss_g) * (long)p.L;
-            const int qbase = q_lo + iss_qt * kBQ;
+            const int qbase = q_lo + iss_qt * BQ;
             static_for<LOADS>([&](auto U) {
                 constexpr int u = U;
                 const int r = (LOADS * wave + u) * RPL + my_sub;
@@ -305,13 +315,15 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
                 dma_to_lds_16(Q + hrow0 * D, off, lds_addr(&Qs[buf][wave_off]));
                 dma_to_lds_16(dO + hrow0 * D, off, lds_addr(&dOs[buf][wave_off]));
             });
-            // the 64 + 64 row values (LSE*log2e, -D): sixteen per wave, so that every wave issues the same
-            // number of loads per tile
-            {
-                static_assert(NW == 8 && kBQ == 64, "the row values are dealt to eight waves");
-                const int part = wave & 3;
-                const float *src = (wave < 4 ? LSE2 : Dws) + hrow0;
-                float *dst = wave < 4 ? &lse_s[buf][16 * part] : &d_s[buf][16 * part];
+            // the BQ + BQ row values (LSE*log2e, -D) in groups of sixteen, dealt to the waves so that every
+            // wave issues the same number of loads per tile: group g holds rows 16 (g % (BQ/16)) .. +15
+            // of LSE*log2e (g < BQ/16) or of -D
+#pragma unroll
+            for (int v = 0; v < RVL; ++v) {
+                constexpr int GPT = BQ / 16;  // groups per tensor
+                const int g = wave * RVL + v, part = g % GPT;
+                const float *src = (g < GPT ? LSE2 : Dws) + hrow0;
+                float *dst = g < GPT ? &lse_s[buf][16 * part] : &d_s[buf][16 * part];
                 if (lane < 16) dma_to_lds_4(src, (uint32_t)min(qbase + 16 * part + lane, p.L - 1) * 4u, lds_addr(dst));
             }
             ++iss_tt;
@@ -322,20 +334,23 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
         };
         // wait until at most the loads of the n_out newest tiles are still in flight (loads complete in
         // the order they were issued; every wave issues 2*LOADS + 1 loads per tile)
-        static_assert(LOADS == 1 || LOADS == 2, "wait counts below are written for 1 or 2 loads per tensor");
         auto wait_tiles = [&](int n_out) __attribute__((always_inline)) {
-            constexpr int LW = 2 * LOADS + 1;
+            constexpr int LW = 2 * LOADS + RVL;
+            static_assert(LW == 3 || LW == 5 || LW == 6, "wait counts below are written for 3, 5 or 6 loads per wave and tile");
             if (n_out <= 0) {
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             } else if (n_out == 1) {
                 if constexpr (LW == 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
-                else asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+                else if constexpr (LW == 5) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
             } else if (n_out == 2) {
                 if constexpr (LW == 3) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-                else asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+                else if constexpr (LW == 5) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
             } else {
                 if constexpr (LW == 3) asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
-                else asm volatile("s_waitcnt vmcnt(15)" ::: "memory");
+                else if constexpr (LW == 5) asm volatile("s_waitcnt vmcnt(15)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(18)" ::: "memory");
             }
         };
 
@@ -357,7 +372,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
             const int g = s / st_P, b = s - g * st_P;
             const int base_t = g * tiles_per_head;
             const bool mg = g > 0 && b < st_ov;
-            const int own = base_t + (b >> 1), old = base_t - tiles_per_head + ((b + st_P) >> 1);
+            const int own = base_t + b / BPT, old = base_t - tiles_per_head + (b + st_P) / BPT;
             const bool prev = mg && (kbw > b || g == st_G);
             step_head = prev ? g - 1 : g;
             tile = prev ? old : own;
@@ -382,8 +397,8 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
             }
             step_of(sidx + 1, tile_n, blk_n, lo_n, hi_n);
             if (sidx + 1 >= n_blocks) hi_n = n_tiles - 1;
-            const int buf = tile % NBUF, qb = blk & 1;
-            const int r0 = q_lo + ((q0_tile + (blk >> 1)) % n_qt) * kBQ + 32 * qb;
+            const int buf = tile % NBUF, qb = blk % BPT;
+            const int r0 = q_lo + ((q0_tile + blk / BPT) % n_qt) * BQ + 32 * qb;
             bool full = (r0 >= lo_max) && (r0 + 31 <= hi_min);
             if constexpr (HW) full = full && (r0 + 31 + dl <= hi2_min);
             sch_d = dl;
@@ -404,7 +419,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
             const int tp = __builtin_amdgcn_readlane(sch_t, l);
             k.r0 = r0p & ~31;
             k.full = r0p & 1;
-            k.rv = ((r0p >> 2) & 3) * kBQ + ((r0p >> 1) & 1) * 32;
+            k.rv = ((r0p >> 2) & 3) * BQ + ((r0p >> 1) & 1) * 32;
             k.ps = st_n & 1;
             k.dlt = HW ? __builtin_amdgcn_readlane(sch_d, l) : 0;
             lo_cur = tp >> 2;
@@ -648,13 +663,13 @@ __global__ __launch_bounds__(kDkvThreads, 1) void dkv_kernel(
         // of those that are.
         const float oscale = role == 0 ? 1.f : p.scale;
         float *farX = role == 0 ? farV : farK;
-        long part_row = (long)(w_id + ft) * kBK + 32 * kbw + kj;
+        long part_row = (long)(w_id + ft) * BK + 32 * kbw + kj;
         bool to_partial = FAR;
         if (!FAR && valid) {
             const int f = far_index(fl, prefix, j);
-            if (f >= 0 && far_first_query(fl, f, idx, p) < far_last_query(fl, f, idx, p, dend)) {
+            if (f >= 0 && far_first_query(fl, f, idx, p, BK) < far_last_query(fl, f, idx, p, dend, BK)) {
                 to_partial = true;
-                part_row = (long)fg.NP * kBK + f;
+                part_row = (long)fg.NP * BK + f;
             }
         }
         if (valid) {
@@ -703,11 +718,12 @@ __global__ __launch_bounds__(256) void dkv_combine_kernel(sepattn_params p, cons
     const FarList fl = far_list(p, prefix);
     const int f = (blockIdx.x * 256 + threadIdx.x) / TPR, col = ((blockIdx.x * 256 + threadIdx.x) % TPR) * 4;
     if (f >= fl.NF) return;
-    const int A = far_first_query(fl, f, idx, p);
+    const int lt = fg.bk;  // entries per list tile
+    const int A = far_first_query(fl, f, idx, p, lt);
     // no far piece for this list tile: the band unit has written the row
-    if (A >= far_last_query(fl, f, idx, p, doc_end ? doc_end + (long)b * p.L : nullptr)) return;
+    if (A >= far_last_query(fl, f, idx, p, doc_end ? doc_end + (long)b * p.L : nullptr, lt)) return;
     const int j = far_pos(fl, f, idx, p.L);
-    const int ft = f / kBK;
+    const int ft = f / lt;
     const int32_t *tab = piece_tab + ((long)bkv * fg.NFTcap + ft) * 2;
     // the clamps keep a table that the far pass did not write (it always does) from faulting
     const int w0 = min(max(tab[0], 0), wpg - 1), w1 = min(max(tab[1], w0), wpg - 1);
@@ -716,7 +732,7 @@ __global__ __launch_bounds__(256) void dkv_combine_kernel(sepattn_params p, cons
     // the band partial and eight pieces at a time (clamped slots) are requested together, so that a
     // list tile with up to eight pieces costs one memory round trip; the sum runs in slot order
     constexpr int NB = 8;
-    const long brow = (base + (long)fg.NP * kBK + f) * D + col;
+    const long brow = (base + (long)fg.NP * lt + f) * D + col;
     const float4 bk = *reinterpret_cast<const float4 *>(farK + brow);
     const float4 bv = *reinterpret_cast<const float4 *>(farV + brow);
     for (int w = w0; w <= w1; w += NB) {
@@ -724,7 +740,7 @@ __global__ __launch_bounds__(256) void dkv_combine_kernel(sepattn_params p, cons
 #pragma unroll
         for (int c = 0; c < NB; ++c) {
             const int ww = min(w + c, w1);
-            const long prow = (base + (long)(ww + ft) * kBK + (f - ft * kBK)) * D + col;
+            const long prow = (base + (long)(ww + ft) * lt + (f - ft * lt)) * D + col;
             pk[c] = *reinterpret_cast<const float4 *>(farK + prow);
             pv[c] = *reinterpret_cast<const float4 *>(farV + prow);
         }
@@ -743,6 +759,24 @@ __global__ __launch_bounds__(256) void dkv_combine_kernel(sepattn_params p, cons
     *reinterpret_cast<uint2 *>(dV + orow) = pack_bf16x4(sv.x, sv.y, sv.z, sv.w);
 }
 
+template <int D, int KW>
+void launch_dkv_shape(const sepattn_params &p, const HeadWin &hw, bool headwise, const uint16_t *Q, const uint16_t *K,
+                      const uint16_t *V, const float *lse2, const uint16_t *dO, const float *Dws, const int32_t *sep_idx,
+                      const int32_t *sep_prefix, const int32_t *doc_end, uint16_t *dK, uint16_t *dV, float *farK,
+                      float *farV, int32_t *piece_tab, int wpg, hipStream_t st) {
+    const int band_grid = (p.L + 32 * KW - 1) / (32 * KW);
+    const dim3 grid((unsigned)((long)wpg * p.B * p.Hkv)), block(128 * KW);
+    if (doc_end)
+        hipLaunchKernelGGL((dkv_kernel<D, true, false, KW>), grid, block, 0, st, p, Q, K, V, lse2, dO, Dws, sep_idx,
+                           sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, wpg, band_grid, hw);
+    else if (headwise)
+        hipLaunchKernelGGL((dkv_kernel<D, false, true, KW>), grid, block, 0, st, p, Q, K, V, lse2, dO, Dws, sep_idx,
+                           sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, wpg, band_grid, hw);
+    else
+        hipLaunchKernelGGL((dkv_kernel<D, false, false, KW>), grid, block, 0, st, p, Q, K, V, lse2, dO, Dws, sep_idx,
+                           sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, wpg, band_grid, hw);
+}
+
 template <int D>
 int launch_dkv(const sepattn_params &p, const HeadWin &hw, bool headwise, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
                const float *lse2, const uint16_t *dO, const float *Dws, const int32_t *sep_idx,
@@ -750,20 +784,14 @@ int launch_dkv(const sepattn_params &p, const HeadWin &hw, bool headwise, const 
                float *farV, int32_t *piece_tab, hipStream_t st) {
     const int wpg = dkv_workgroups_per_head(p);
     const FarGeom fg = far_geom(p, wpg);
-    const long band_grid = (p.L + kBK - 1) / kBK;
-    const long total = (long)wpg * p.B * p.Hkv;
-    if (total > 0x7FFFFFFFL) return SEPATTN_ERR_SHAPE;
+    if ((long)wpg * p.B * p.Hkv > 0x7FFFFFFFL) return SEPATTN_ERR_SHAPE;
     {
         ProfScope prof(SEPATTN_K_BWD_DKV, st);
-        if (doc_end)
-            hipLaunchKernelGGL((dkv_kernel<D, true, false>), dim3((unsigned)total), dim3(kDkvThreads), 0, st, p, Q, K, V, lse2, dO,
-                               Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, wpg, (int)band_grid, hw);
-        else if (headwise)
-            hipLaunchKernelGGL((dkv_kernel<D, false, true>), dim3((unsigned)total), dim3(kDkvThreads), 0, st, p, Q, K, V, lse2, dO,
-                               Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, wpg, (int)band_grid, hw);
+        // the eight-wave shape exists for d = 128 only (dkv_key_blocks)
+        if (D == 128 && dkv_key_blocks(p) == 4)
+            launch_dkv_shape<128, 4>(p, hw, headwise, Q, K, V, lse2, dO, Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, wpg, st);
         else
-            hipLaunchKernelGGL((dkv_kernel<D, false, false>), dim3((unsigned)total), dim3(kDkvThreads), 0, st, p, Q, K, V, lse2, dO,
-                               Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, wpg, (int)band_grid, hw);
+            launch_dkv_shape<D, 2>(p, hw, headwise, Q, K, V, lse2, dO, Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, wpg, st);
     }
     if (hipGetLastError() != hipSuccess) return SEPATTN_ERR_HIP;
     ProfScope prof(SEPATTN_K_BWD_COMBINE, st);

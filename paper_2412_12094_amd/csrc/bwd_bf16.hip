@@ -48,15 +48,14 @@ __device__ inline float bf16_dot8(u32x4 a, u32x4 b) {
 // one wave's exponentials overlap the other's matrix work.
 // ---------------------------------------------------------------------------------------------
 // DOCS: packed documents, as in the forward kernel (doc_start / doc_end [B, L]; p.a == 0).
-template <int D, int GP, bool DOCS>
-__global__ __launch_bounds__(512, 2) void dq_kernel(
+template <int D, int GP, bool DOCS, int NW>
+__global__ __launch_bounds__(64 * NW, 2) void dq_kernel(
     sepattn_params p, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
     const uint16_t *__restrict__ V, const uint16_t *__restrict__ O, const float *__restrict__ LSE,
     const uint16_t *__restrict__ dO, const int32_t *__restrict__ sep_idx,
     const int32_t *__restrict__ sep_prefix, const int32_t *__restrict__ doc_start,
     const int32_t *__restrict__ doc_end, uint16_t *__restrict__ dQ, float *__restrict__ Dws,
     float *__restrict__ Lws, int wpg, HeadWin hw) {
-    constexpr int NW = 8;
     constexpr int TP = 32 * NW / GP;
     constexpr int CH = D / 8;
     constexpr int RPL = 64 / CH;
@@ -77,14 +76,14 @@ __global__ __launch_bounds__(512, 2) void dq_kernel(
     __shared__ __attribute__((aligned(16))) int lo_s[MKS][kBN];
     __shared__ __attribute__((aligned(16))) int hi_s[MKS][kBN];
     // staging of one 32-column block of a wave's 32 dQ rows (see the end of a segment)
-    __shared__ __attribute__((aligned(16))) uint16_t ostage[8][32 * 32];
+    __shared__ __attribute__((aligned(16))) uint16_t ostage[NW][32 * 32];
     constexpr int MR = LOADS * RPL;  // rows per wave and tile
     constexpr int MST = 4;           // ring stages of the index entries
     __shared__ __attribute__((aligned(256))) int meta_s[MST][NLW][64];  // 3 * MR <= 48 entries per wave and stage
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const bool loader = wave < NLW;
+    const bool loader = NW == NLW || wave < NLW;
     const int qi = lane & 31, hh = lane >> 5;
     // Persistent workgroups as in the forward kernel: a workgroup belongs to one (batch, KV head, head
     // group) and walks through several query tiles of it ("segments") in zig-zag order, `wpg`
@@ -517,22 +516,40 @@ int launch_bwd(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
 
     int G = p.Hq / p.Hkv;
     int GP = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
-    int TP = 32 * 8 / GP;
+    // Workgroups of eight waves, one per compute unit (the LDS footprint allows no more).  At d = 64
+    // the K/V stages are half as large and two independent workgroups of four waves fit a compute
+    // unit: one's segment start and row stores overlap the other's matrix work, their barriers do not
+    // lock each other's phases, and the split of a group is twice as fine (it fills the chip where
+    // 256 / groups is not a whole number).  A four-wave workgroup has half the query rows per K/V
+    // tile, i.e. twice the tile loads per matrix instruction: with grouped heads and long sequences
+    // the eight-wave shape stays the better one.
+    const bool narrow = D == 64 && (long)G * p.L < 32768;
+    const int NWr = narrow ? 4 : 8;
+    int TP = 32 * NWr / GP;
     const int n_pos_tiles = (p.L + TP - 1) / TP;
     const long n_groups = (long)p.B * p.Hkv * (G / GP);
-    // persistent workgroups: one per compute unit, spread evenly over the groups
-    int wpg = (int)(compute_units() / n_groups);
+    // persistent workgroups, spread evenly over the groups; never more than a group has tiles
+    int wpg = (int)((8 / NWr) * (long)compute_units() / n_groups);
     wpg = wpg < 1 ? 1 : (wpg > n_pos_tiles ? n_pos_tiles : wpg);
     if (n_groups * wpg > 0x7FFFFFFFL) return SEPATTN_ERR_SHAPE;
-    dim3 grid((unsigned)(n_groups * wpg)), block(512);
+    dim3 grid((unsigned)(n_groups * wpg)), block(64 * NWr);
     {
     ProfScope prof(SEPATTN_K_BWD_DQ, st);
-    if (GP == 4)
-        hipLaunchKernelGGL((dq_kernel<D, 4, DOCS>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, doc_start, doc_end, dQ, Dws, Lws, wpg, hw);
-    else if (GP == 2)
-        hipLaunchKernelGGL((dq_kernel<D, 2, DOCS>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, doc_start, doc_end, dQ, Dws, Lws, wpg, hw);
-    else
-        hipLaunchKernelGGL((dq_kernel<D, 1, DOCS>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, doc_start, doc_end, dQ, Dws, Lws, wpg, hw);
+    auto go = [&](auto NW_) {
+        constexpr int NW = decltype(NW_)::value;
+        if (GP == 4)
+            hipLaunchKernelGGL((dq_kernel<D, 4, DOCS, NW>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, doc_start, doc_end, dQ, Dws, Lws, wpg, hw);
+        else if (GP == 2)
+            hipLaunchKernelGGL((dq_kernel<D, 2, DOCS, NW>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, doc_start, doc_end, dQ, Dws, Lws, wpg, hw);
+        else
+            hipLaunchKernelGGL((dq_kernel<D, 1, DOCS, NW>), grid, block, 0, st, p, Q, K, V, O, LSE, dO, sep_idx, sep_prefix, doc_start, doc_end, dQ, Dws, Lws, wpg, hw);
+    };
+    if constexpr (D == 64) {
+        if (narrow) go(IntC<4>{});
+        else go(IntC<8>{});
+    } else {
+        go(IntC<8>{});
+    }
     }
     if (hipGetLastError() != hipSuccess) return SEPATTN_ERR_HIP;
     return launch_dkv_bf16(p, hw, Q, K, V, Lws, dO, Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, st);

@@ -33,13 +33,12 @@ constexpr float kRescaleThreshold = 8.f;  // log2 units
 
 // DOCS: packed documents (see make_stream_docs); doc_start / doc_end [B, L] give, per position, the
 // first position of its document and one past its last.  Requires p.a == 0.
-template <int D, int GP, bool DOCS>
-__global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
+template <int D, int GP, bool DOCS, int NW>
+__global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(
     sepattn_params p, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
     const uint16_t *__restrict__ V, const int32_t *__restrict__ sep_idx,
     const int32_t *__restrict__ sep_prefix, const int32_t *__restrict__ doc_start,
     const int32_t *__restrict__ doc_end, uint16_t *__restrict__ O, float *__restrict__ LSE, int wpg, HeadWin hw) {
-    constexpr int NW = 8;
     constexpr int TP = 32 * NW / GP;  // query positions per workgroup
     constexpr int CH = D / 8;         // 16-byte chunks per row
     constexpr int RPL = 64 / CH;      // rows covered by one wave-wide 1 KB load
@@ -61,11 +60,10 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     __shared__ __attribute__((aligned(16))) int lo_s[VST][kBN];
     __shared__ __attribute__((aligned(16))) int hi_s[VST][kBN];
     // staging of one 32-column block of a wave's 32 output rows (see the epilogue)
-    __shared__ __attribute__((aligned(16))) uint16_t ostage[8][32 * 32];
+    __shared__ __attribute__((aligned(16))) uint16_t ostage[NW][32 * 32];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps branches scalar
-    const int grp = wave >> 2;                                  // waves w and w+4 share a SIMD
     const int qi = lane & 31, hh = lane >> 5;
     // A workgroup is persistent: it belongs to one (batch, KV head, head group) and walks through
     // several query tiles of it ("segments"), `wpg` workgroups per group sharing the tiles in zig-zag
@@ -135,7 +133,7 @@ __global__ __launch_bounds__(512, 2) void fwd_bf16_kernel(
     constexpr int MR = LOADS * RPL;  // rows per wave and tile
     constexpr int MST = 4;           // ring stages
     __shared__ __attribute__((aligned(256))) int meta_s[MST][NLW][64];  // 3 * MR <= 48 entries per wave and stage
-    const bool loader = wave < NLW;
+    const bool loader = NW == NLW || wave < NLW;
     const int m_part = lane / MR, m_row = wave * MR + lane % MR;  // lanes 0 .. 3*MR-1 are used
     auto issue_meta = [&](const Stream &ss, int t, int g) __attribute__((always_inline)) {
         const int k = t * kBN + m_row;
@@ -570,22 +568,41 @@ int launch_fwd(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
                uint16_t *O, float *LSE, const HeadWin &hw, hipStream_t st) {
     int G = p.Hq / p.Hkv;
     int GP = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
-    int TP = 32 * 8 / GP;
+    // Workgroups of eight waves, one per compute unit (the LDS footprint allows no more).  At d = 64
+    // the K/V stages are half as large and two independent workgroups of four waves fit a compute
+    // unit: one's segment start and row stores overlap the other's matrix work, their barriers do not
+    // lock each other's phases, and the split of a group is twice as fine (it fills the chip where
+    // 256 / groups is not a whole number).  A four-wave workgroup has half the query rows per K/V
+    // tile, i.e. twice the tile loads per matrix instruction: with grouped heads and long sequences
+    // the eight-wave shape stays the better one.
+    const bool narrow = D == 64 && (long)G * p.L < 32768;
+    const int NWr = narrow ? 4 : 8;
+    int TP = 32 * NWr / GP;
     const int n_pos_tiles = (p.L + TP - 1) / TP;
     const long n_groups = (long)p.B * p.Hkv * (G / GP);
-    // persistent workgroups: one per compute unit (the kernel's LDS footprint allows no more), spread
-    // evenly over the groups; never more than a group has tiles
-    int wpg = (int)(compute_units() / n_groups);
+    // persistent workgroups, spread evenly over the groups; never more than a group has tiles
+    int wpg = (int)((8 / NWr) * (long)compute_units() / n_groups);
     wpg = wpg < 1 ? 1 : (wpg > n_pos_tiles ? n_pos_tiles : wpg);
     if (n_groups * wpg > 0x7FFFFFFFL) return SEPATTN_ERR_SHAPE;
-    dim3 grid((unsigned)(n_groups * wpg)), block(512);
+    dim3 grid((unsigned)(n_groups * wpg)), block(64 * NWr);
+    {
     ProfScope prof(SEPATTN_K_FORWARD, st);
-    if (GP == 4)
-        hipLaunchKernelGGL((fwd_bf16_kernel<D, 4, DOCS>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, doc_start, doc_end, O, LSE, wpg, hw);
-    else if (GP == 2)
-        hipLaunchKernelGGL((fwd_bf16_kernel<D, 2, DOCS>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, doc_start, doc_end, O, LSE, wpg, hw);
-    else
-        hipLaunchKernelGGL((fwd_bf16_kernel<D, 1, DOCS>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, doc_start, doc_end, O, LSE, wpg, hw);
+    auto go = [&](auto NW_) {
+        constexpr int NW = decltype(NW_)::value;
+        if (GP == 4)
+            hipLaunchKernelGGL((fwd_bf16_kernel<D, 4, DOCS, NW>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, doc_start, doc_end, O, LSE, wpg, hw);
+        else if (GP == 2)
+            hipLaunchKernelGGL((fwd_bf16_kernel<D, 2, DOCS, NW>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, doc_start, doc_end, O, LSE, wpg, hw);
+        else
+            hipLaunchKernelGGL((fwd_bf16_kernel<D, 1, DOCS, NW>), grid, block, 0, st, p, Q, K, V, sep_idx, sep_prefix, doc_start, doc_end, O, LSE, wpg, hw);
+    };
+    if constexpr (D == 64) {
+        if (narrow) go(IntC<4>{});
+        else go(IntC<8>{});
+    } else {
+        go(IntC<8>{});
+    }
+    }
     return launch_status();
 }
 

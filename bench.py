@@ -39,12 +39,13 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
 # The figures and the commands are in profiles/; None = not measured for the current kernels.
 CALIB_BYTES = 256 << 20
 MEASURED_TRAFFIC_BYTES = {
-    "forward": 176.6e6,      # cfg3: read 108.5 MB + written 68.2 MB   (algorithmic: 168.8 MB)
-    "bwd_dq": 324.7e6,       # cfg3: read 248.5 MB + written 76.3 MB
-    "bwd_dkv": 543.2e6,      # cfg3: read 468.8 MB (Q, dO tiles re-read by every list tile and band unit) + written 74.4 MB
+    "forward": 190.5e6,      # cfg3: read 119.0 MB + written 71.5 MB   (algorithmic: 168.8 MB; the staged output rows leave as
+                             # 64-byte pieces, two store instructions per 128-byte line)
+    "bwd_dq": 346.7e6,       # cfg3: read 271.5 MB + written 75.1 MB
+    "bwd_dkv": 542.5e6,      # cfg3: read 468.1 MB (Q, dO tiles re-read by every list tile and band unit) + written 74.3 MB
     "bwd_combine": 46.4e6,   # cfg3: read 43.6 MB + written 2.8 MB
-    "cfg2_step": 554.8e6,    # forward 109.4 + dQ 167.5 + dK/dV 245.7 + combine 32.2 MB (algorithmic: 303.6 MB)
-    "cfg4_forward": 1801.0e6,  # read 1255.8 MB + written 545.3 MB    (algorithmic: 1351 MB)
+    "cfg2_step": 581.4e6,    # mark+compact 0.2 + forward 108.8 + dQ 167.8 + dK/dV 267.3 + combine 37.3 MB (algorithmic: 303.6 MB)
+    "cfg4_forward": 1895.8e6,  # read 1347.3 MB + written 548.5 MB    (algorithmic: 1351 MB)
     "evict_move": 42.1e6,    # cfg5: read 21.3 MB + written 20.8 MB by the counters; the kernel loads and stores 10.4 MB each
                              # (a build that counts its stores: 40 704 rows of 256 B), i.e. the counters read twice the bytes of
                              # these scattered 256-byte rows

@@ -11,15 +11,20 @@ namespace sepattn {
 // of two shapes:
 //   KW = 4: 8 waves, one workgroup per compute unit.  Fewest tile loads per matrix instruction; the
 //           better shape when a workgroup's pieces are long (d = 128, grouped heads, long sequences).
-//   KW = 2: 4 waves, two workgroups per compute unit that run independently: one's piece start-up and
-//           partial stores overlap the other's matrix work, the split of a (batch, KV head) is twice
-//           as fine (it fills the chip where 256 / (B Hkv) is not a whole number), and the two
-//           workgroups' barriers do not lock each other's phases.
+//   KW = 2: 4 waves, two workgroups per compute unit (three at d = 64, where the registers and the ring
+//           of query tiles allow it) that run independently: one's piece start-up and partial stores
+//           overlap the others' matrix work, the split of a (batch, KV head) is finer (it fills the
+//           chip where 256 / (B Hkv) is not a whole number), and the workgroups' barriers do not lock
+//           each other's phases.
 // The choice is a function of the problem alone, so that the workspace query, the dK/dV pass and the
 // combine pass agree on it.
 __host__ __device__ inline int dkv_key_blocks(const sepattn_params &p) {
     const long G = p.Hq / p.Hkv;
     return (p.d == 128 && G * p.L >= 32768) ? 4 : 2;
+}
+// workgroups of that shape that share a compute unit
+__host__ __device__ inline int dkv_workgroups_per_cu(const sepattn_params &p) {
+    return dkv_key_blocks(p) == 4 ? 1 : (p.d == 64 ? 3 : 2);
 }
 
 __host__ __device__ inline int align_down32(int x) { return x & ~31; }
@@ -40,7 +45,7 @@ struct FarGeom {
 };
 inline int dkv_workgroups_per_head(const sepattn_params &p) {
     const long n_bkv = (long)p.B * p.Hkv;
-    const long w = (dkv_key_blocks(p) == 2 ? 2 : 1) * (long)compute_units() / n_bkv;
+    const long w = dkv_workgroups_per_cu(p) * (long)compute_units() / n_bkv;
     return (int)(w < 1 ? 1 : w);
 }
 __host__ __device__ inline FarGeom far_geom(const sepattn_params &p, int wpg) {

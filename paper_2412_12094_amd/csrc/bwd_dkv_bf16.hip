@@ -55,7 +55,7 @@ __device__ inline int wave_max_i(int v) {
 // in a band unit a key that is neither an initial token nor a separator is visible to query i of head
 // h only while i <= j + p.n - 1 - delta[h] (a third comparison in the blocks that need the mask test).
 template <int D, bool DOCS, bool HW, int KW>
-__global__ __launch_bounds__(128 * KW, KW == 4 ? 1 : 2) void dkv_kernel(
+__global__ __launch_bounds__(128 * KW, KW == 4 ? 1 : (D == 64 ? 3 : 2)) void dkv_kernel(
     sepattn_params p, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
     const uint16_t *__restrict__ V, const float *__restrict__ LSE2, const uint16_t *__restrict__ dO,
     const float *__restrict__ Dws, const int32_t *__restrict__ sep_idx,
@@ -67,9 +67,10 @@ __global__ __launch_bounds__(128 * KW, KW == 4 ? 1 : 2) void dkv_kernel(
     constexpr int BK = 32 * KW;              // keys per workgroup
     constexpr int CH = D / 8;                // 16-byte chunks per row
     constexpr int RPL = 64 / CH;             // rows covered by one wave-wide 1 KB load
-    // Query rows per LDS tile.  Two workgroups per compute unit have 80 KB each: at d = 128 the ring of
-    // four tiles then holds tiles of 32 rows (one block), else of 64 rows (two blocks).
-    constexpr int BQ = (KW == 2 && D == 128) ? 32 : 64;
+    // Query rows per LDS tile.  Workgroups that share a compute unit (two at d = 128 with 80 KB each,
+    // three at d = 64 with 53 KB and 168 registers) stream tiles of 32 rows (one block) through the
+    // ring of four, the single workgroup tiles of 64 rows (two blocks).
+    constexpr int BQ = KW == 2 ? 32 : 64;
     constexpr int BPT = BQ / 32;             // blocks of 32 query rows per tile
     constexpr int LOADS = BQ / (RPL * NW);   // wave-wide loads per wave per tensor per tile
     constexpr int RVL = (2 * BQ / 16) / NW;  // loads of sixteen row values (LSE*log2e or -D) per wave per tile

@@ -34,8 +34,8 @@ __device__ inline float bf16_dot8(u32x4 a, u32x4 b) {
 // ---------------------------------------------------------------------------------------------
 // dQ
 //
-// Same workgroup shape and key stream as the forward: 8 waves, each with 32 query rows (one head,
-// 32 positions) whose Q and dO rows stay in registers as B operands; K/V tiles of 64 stream
+// Same workgroup shapes and key stream as the forward: NW = 8 or 4 waves, each with 32 query rows (one
+// head, 32 positions) whose Q and dO rows stay in registers as B operands; K/V tiles of 64 stream
 // elements pass through LDS (global->LDS loads two tiles ahead, one workgroup barrier per tile).
 // Per block of 32 keys a wave runs
 //     S^T = K Q^T,  dP^T = V dO^T   (16 matrix instructions, operands row-major from LDS)
@@ -44,8 +44,9 @@ __device__ inline float bf16_dot8(u32x4 a, u32x4 b) {
 // with the operand fragments requested a few matrix instructions ahead.  K tiles are stored with
 // the XOR permutation that serves both kinds of read (V tiles too, so that one set of per-lane
 // offsets addresses both); four stages each (tile X+2 is requested while tile X is multiplied, by
-// the first four waves only).  The two waves that share a SIMD drift apart by themselves, so that
-// one wave's exponentials overlap the other's matrix work.
+// the first four waves only).  The two waves that share a SIMD (of one workgroup, or of the two
+// workgroups on the compute unit) drift apart by themselves, so that one wave's exponentials overlap
+// the other's matrix work.
 // ---------------------------------------------------------------------------------------------
 // DOCS: packed documents, as in the forward kernel (doc_start / doc_end [B, L]; p.a == 0).
 template <int D, int GP, bool DOCS, int NW>
@@ -59,8 +60,9 @@ __global__ __launch_bounds__(64 * NW, 2) void dq_kernel(
     constexpr int TP = 32 * NW / GP;
     constexpr int CH = D / 8;
     constexpr int RPL = 64 / CH;
-    // the tile loads are issued by the first NLW waves only: of the two waves that share a SIMD the
-    // older one (w < 4) is served first and reaches every barrier long before its partner
+    // the tile loads are issued by the first NLW waves only (all of them when NW = 4): of the two waves
+    // of a workgroup that share a SIMD the older one (w < 4) is served first and reaches every barrier
+    // long before its partner
     constexpr int NLW = 4;
     constexpr int LOADS = kBN / (RPL * NLW);
     constexpr int KSTEPS = D / 16;

@@ -1,6 +1,7 @@
 // SepAttention forward, bf16 MFMA (Eq. 1 with the mask of Eq. 2), flash-style with online softmax.
 //
-// A workgroup (8 waves) owns TP consecutive query positions of GP query heads that share one KV
+// A workgroup (NW = 8 waves, or 4 where two workgroups share a compute unit: see launch_fwd) owns
+// TP = 32 NW / GP consecutive query positions of GP query heads that share one KV
 // head (grouped-query attention: the heads are packed into the row dimension, so K/V tiles and the
 // mask are shared).  Each wave owns 32 rows: one head, 32 positions.  The keys a tile can see are
 // turned into ONE dense stream,
@@ -33,6 +34,7 @@ constexpr float kRescaleThreshold = 8.f;  // log2 units
 
 // DOCS: packed documents (see make_stream_docs); doc_start / doc_end [B, L] give, per position, the
 // first position of its document and one past its last.  Requires p.a == 0.
+// NW: waves per workgroup (8 or 4); 2 waves per SIMD either way.
 template <int D, int GP, bool DOCS, int NW>
 __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(
     sepattn_params p, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
@@ -42,9 +44,10 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(
     constexpr int TP = 32 * NW / GP;  // query positions per workgroup
     constexpr int CH = D / 8;         // 16-byte chunks per row
     constexpr int RPL = 64 / CH;      // rows covered by one wave-wide 1 KB load
-    // The tile loads are issued by the first NLW waves only.  Waves w and w+4 share a SIMD and the
-    // arbiter serves the older one (w) first: it reaches every barrier long before its partner, so
-    // the load path costs nothing there, while on the younger wave it would lengthen the critical path.
+    // The tile loads are issued by the first NLW waves only (all of them when NW = 4).  With eight
+    // waves, w and w+4 share a SIMD and the arbiter serves the older one (w) first: it reaches every
+    // barrier long before its partner, so the load path costs nothing there, while on the younger wave
+    // it would lengthen the critical path.
     constexpr int NLW = 4;
     constexpr int LOADS = kBN / (RPL * NLW);  // wave-wide loads per loading wave per tensor per tile
     constexpr int KSTEPS = D / 16;

@@ -16,16 +16,16 @@ namespace sepattn {
 //           overlap the others' matrix work, the split of a (batch, KV head) is finer (it fills the
 //           chip where 256 / (B Hkv) is not a whole number), and the workgroups' barriers do not lock
 //           each other's phases.
-// The choice is a function of the problem alone, so that the workspace query, the dK/dV pass and the
-// combine pass agree on it.
-__host__ __device__ inline int dkv_key_blocks(const sepattn_params &p) {
+// With packed documents the far pieces end with their documents, so the pieces are short at any
+// length.  The launcher chooses (docs: the call has document bounds) and hands KW to both kernels;
+// the workspace is laid out for the larger of the two shapes' needs, so its size does not depend
+// on the choice.
+inline int dkv_key_blocks(const sepattn_params &p, bool docs) {
     const long G = p.Hq / p.Hkv;
-    return (p.d == 128 && G * p.L >= 32768) ? 4 : 2;
+    return (p.d == 128 && !docs && G * p.L >= 32768) ? 4 : 2;
 }
-// workgroups of that shape that share a compute unit
-__host__ __device__ inline int dkv_workgroups_per_cu(const sepattn_params &p) {
-    return dkv_key_blocks(p) == 4 ? 1 : (p.d == 64 ? 3 : 2);
-}
+// workgroups of a shape that share a compute unit
+inline int dkv_workgroups_per_cu(const sepattn_params &p, int kw) { return kw == 4 ? 1 : (p.d == 64 ? 3 : 2); }
 
 __host__ __device__ inline int align_down32(int x) { return x & ~31; }
 
@@ -43,15 +43,15 @@ struct FarGeom {
     int NP;      // partial slots per (batch, KV head)
     long rows;   // fp32 partial rows per (batch, KV head): NP slots of bk rows, then one band row per list entry
 };
-inline int dkv_workgroups_per_head(const sepattn_params &p) {
+inline int dkv_workgroups_per_head(const sepattn_params &p, int kw) {
     const long n_bkv = (long)p.B * p.Hkv;
-    const long w = dkv_workgroups_per_cu(p) * (long)compute_units() / n_bkv;
+    const long w = dkv_workgroups_per_cu(p, kw) * (long)compute_units() / n_bkv;
     return (int)(w < 1 ? 1 : w);
 }
-__host__ __device__ inline FarGeom far_geom(const sepattn_params &p, int wpg) {
+__host__ __device__ inline FarGeom far_geom(const sepattn_params &p, int wpg, int kw) {
     FarGeom g;
     g.wpg = wpg;
-    g.bk = 32 * dkv_key_blocks(p);
+    g.bk = 32 * kw;
     g.NFcap = (p.a + p.cap + g.bk - 1) / g.bk * g.bk;
     g.NFTcap = g.NFcap / g.bk;
     g.NP = wpg + g.NFTcap;
@@ -65,11 +65,17 @@ struct BwdWorkspace {
     size_t d_bytes, far_bytes, tab_bytes, total;
 };
 inline BwdWorkspace bwd_workspace(const sepattn_params &p) {
-    FarGeom fg = far_geom(p, dkv_workgroups_per_head(p));
     BwdWorkspace w;
     w.d_bytes = align_up((size_t)p.B * p.Hq * p.L * sizeof(float), 256);
-    w.far_bytes = align_up((size_t)p.B * p.Hkv * fg.rows * p.d * sizeof(float), 256);
-    w.tab_bytes = align_up((size_t)p.B * p.Hkv * fg.NFTcap * 2 * sizeof(int32_t), 256);
+    w.far_bytes = w.tab_bytes = 0;
+    // the eight-wave shape exists at d = 128 only
+    for (int kw = 2; kw <= (p.d == 128 ? 4 : 2); kw += 2) {
+        const FarGeom fg = far_geom(p, dkv_workgroups_per_head(p, kw), kw);
+        const size_t far = align_up((size_t)p.B * p.Hkv * fg.rows * p.d * sizeof(float), 256);
+        const size_t tab = align_up((size_t)p.B * p.Hkv * fg.NFTcap * 2 * sizeof(int32_t), 256);
+        w.far_bytes = far > w.far_bytes ? far : w.far_bytes;
+        w.tab_bytes = tab > w.tab_bytes ? tab : w.tab_bytes;
+    }
     w.total = 2 * w.d_bytes + 2 * w.far_bytes + w.tab_bytes;
     return w;
 }

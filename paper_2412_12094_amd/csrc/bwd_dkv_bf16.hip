@@ -102,7 +102,7 @@ __global__ __launch_bounds__(128 * KW, KW == 4 ? 1 : (D == 64 ? 3 : 2)) void dkv
     const int32_t *dend = DOCS ? doc_end + (long)b * p.L : nullptr;
     const long kvrow0 = ((long)b * p.Hkv + kv) * (long)p.L;
     const float sl2 = p.scale * kLog2e_f;
-    const FarGeom fg = far_geom(p, wpg);
+    const FarGeom fg = far_geom(p, wpg, KW);
     const FarList fl = far_list(p, prefix);
     const int a_row = pi_row(kj);
     const int my_pc = lane % CH, my_sub = lane / CH;
@@ -710,12 +710,12 @@ __global__ __launch_bounds__(256) void dkv_combine_kernel(sepattn_params p, cons
                                                           uint16_t *__restrict__ dK, uint16_t *__restrict__ dV,
                                                           const float *__restrict__ farK,
                                                           const float *__restrict__ farV,
-                                                          const int32_t *__restrict__ piece_tab, int wpg) {
+                                                          const int32_t *__restrict__ piece_tab, int wpg, int kw) {
     constexpr int TPR = D / 4;  // threads per row
     const int bkv = blockIdx.y, kv = bkv % p.Hkv, b = bkv / p.Hkv;
     const int32_t *prefix = sep_prefix + (long)b * (p.L + 1);
     const int32_t *idx = sep_idx + (long)b * p.cap;
-    const FarGeom fg = far_geom(p, wpg);
+    const FarGeom fg = far_geom(p, wpg, kw);
     const FarList fl = far_list(p, prefix);
     const int f = (blockIdx.x * 256 + threadIdx.x) / TPR, col = ((blockIdx.x * 256 + threadIdx.x) % TPR) * 4;
     if (f >= fl.NF) return;
@@ -783,13 +783,14 @@ int launch_dkv(const sepattn_params &p, const HeadWin &hw, bool headwise, const 
                const float *lse2, const uint16_t *dO, const float *Dws, const int32_t *sep_idx,
                const int32_t *sep_prefix, const int32_t *doc_end, uint16_t *dK, uint16_t *dV, float *farK,
                float *farV, int32_t *piece_tab, hipStream_t st) {
-    const int wpg = dkv_workgroups_per_head(p);
-    const FarGeom fg = far_geom(p, wpg);
+    const int kw = dkv_key_blocks(p, doc_end != nullptr);
+    const int wpg = dkv_workgroups_per_head(p, kw);
+    const FarGeom fg = far_geom(p, wpg, kw);
     if ((long)wpg * p.B * p.Hkv > 0x7FFFFFFFL) return SEPATTN_ERR_SHAPE;
     {
         ProfScope prof(SEPATTN_K_BWD_DKV, st);
         // the eight-wave shape exists for d = 128 only (dkv_key_blocks)
-        if (D == 128 && dkv_key_blocks(p) == 4)
+        if (D == 128 && kw == 4)
             launch_dkv_shape<128, 4>(p, hw, headwise, Q, K, V, lse2, dO, Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, wpg, st);
         else
             launch_dkv_shape<D, 2>(p, hw, headwise, Q, K, V, lse2, dO, Dws, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, wpg, st);
@@ -798,7 +799,7 @@ int launch_dkv(const sepattn_params &p, const HeadWin &hw, bool headwise, const 
     ProfScope prof(SEPATTN_K_BWD_COMBINE, st);
     const int rows_per_block = 256 / (D / 4);
     hipLaunchKernelGGL((dkv_combine_kernel<D>), dim3((fg.NFcap + rows_per_block - 1) / rows_per_block, p.B * p.Hkv),
-                       dim3(256), 0, st, p, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, wpg);
+                       dim3(256), 0, st, p, sep_idx, sep_prefix, doc_end, dK, dV, farK, farV, piece_tab, wpg, kw);
     return launch_status();
 }
 

@@ -446,6 +446,31 @@ def test_config3_full_forward_backward(sp):
         assert_grads_close((dQ[:, hs], dK[:, kv:kv + 1], dV[:, kv:kv + 1]), refs, "bf16", note=f"cfg3 kv {kv}")
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,L,d,a,n,p", [
+    (1, 8, 1, 4096, 64, 4, 128, 0.08),    # d = 64 at grouped heads x length = 32K: eight-wave forward and dQ workgroups
+    (1, 8, 1, 4095, 64, 4, 128, 0.08),    # just below: four-wave workgroups, two (dK/dV: three) per compute unit
+    (1, 8, 1, 4096, 128, 3, 200, 0.10),   # d = 128 at 32K: the eight-wave dK/dV shape (four key blocks)
+    (1, 8, 1, 4095, 128, 3, 200, 0.10),   # just below: two key blocks per workgroup, 32-row query tiles
+    (2, 4, 4, 2500, 128, 4, 33, 0.05),    # MHA, window of one block and a bit: no merged head starts with 32-row tiles
+])
+def test_both_workgroup_shapes_match_the_oracle(sp, B, Hq, Hkv, L, d, a, n, p):
+    """The kernels run as one eight-wave workgroup or several four-wave workgroups per compute unit,
+    chosen from grouped heads x length (and d): whole tensors on both sides of the switch."""
+    tok, Q, K, V, dO = make_case(B, Hq, Hkv, L, d, p, "bf16", 4000 + L + d)
+    scale = 1.0 / math.sqrt(d)
+    is_sep, idx, cnt, pre = gpu_index(sp, tok)
+    q, k, v, do = (dev(x, "bf16") for x in (Q, K, V, dO))
+    O, LSE = sp.sepattn_forward(q, k, v, idx, cnt, pre, a, n, scale)
+    grads = sp.sepattn_backward(q, k, v, O, LSE, do, idx, cnt, pre, a, n, scale)
+    torch.cuda.synchronize()
+    flags = host(is_sep)
+    rO, rL = oracle.forward(Q, K, V, flags, a, n, scale)
+    assert_close(host(O), rO, "bf16", "O")
+    assert np.abs(host(LSE) - rL).max() <= LSE_TOL["bf16"]
+    refs = oracle.backward(Q, K, V, dO, flags, a, n, scale, return_term_rss=True)
+    assert_grads_close(grads, refs, "bf16")
+
+
 def test_config4_backward_agrees_with_the_fp32_kernels(sp):
     """64K context is out of the dense oracle's reach for the backward.  The fp32 kernels (parity-
     tested against the oracle at the sizes above) run the same bf16-rounded inputs here; the bf16 MFMA

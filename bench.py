@@ -44,7 +44,7 @@ MEASURED_TRAFFIC_BYTES = {
     "bwd_dq": 346.7e6,       # cfg3: read 271.5 MB + written 75.1 MB
     "bwd_dkv": 542.5e6,      # cfg3: read 468.1 MB (Q, dO tiles re-read by every list tile and band unit) + written 74.3 MB
     "bwd_combine": 46.4e6,   # cfg3: read 43.6 MB + written 2.8 MB
-    "cfg2_step": 581.4e6,    # mark+compact 0.2 + forward 108.8 + dQ 167.8 + dK/dV 267.3 + combine 37.3 MB (algorithmic: 303.6 MB)
+    "cfg2_step": 613.9e6,    # mark+compact 0.2 + forward 108.8 + dQ 167.9 + dK/dV 289.9 + combine 47.1 MB (algorithmic: 303.6 MB)
     "cfg4_forward": 1895.8e6,  # read 1347.3 MB + written 548.5 MB    (algorithmic: 1351 MB)
     "evict_move": 42.1e6,    # cfg5: read 21.3 MB + written 20.8 MB by the counters; the kernel loads and stores 10.4 MB each
                              # (a build that counts its stores: 40 704 rows of 256 B), i.e. the counters read twice the bytes of

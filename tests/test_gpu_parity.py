@@ -297,6 +297,8 @@ HEADWISE_CASES = [
     (1, 4, 1, 300, 64, 0, 0.0, [7, 300, 64, 2]),                              # no separators, no initial tokens
     (1, 2, 1, 65, 64, 5, 0.3, [1, 2]),
     (1, 16, 2, 900, 128, 4, 0.1, [900, 900, 900, 900, 128, 128, 128, 128, 32, 900, 32, 900, 64, 64, 64, 64]),  # H_s of H heads windowed
+    (1, 8, 1, 4096, 128, 4, 0.08, [256, 4096, 64, 256, 1000, 33, 256, 128]),  # grouped heads x length = 32K: the eight-wave dK/dV shape
+    (1, 8, 1, 4096, 64, 4, 0.08, [128, 4096, 64, 128, 1000, 33, 128, 7]),      # ... and the eight-wave forward and dQ workgroups at d = 64
 ]
 
 
@@ -844,6 +846,7 @@ def test_doc_bounds_and_forward_packed_match_oracle(sp, dtype, B, Hq, Hkv, L, d,
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 @pytest.mark.parametrize("B,Hq,Hkv,L,d,a,n,p,cus", PACKED_CASES + [
     (1, 8, 2, 2300, 128, 4, 64, 0.15, None),   # several list tiles, documents that end inside them
+    (1, 8, 1, 4096, 64, 3, 100, 0.08, None),   # d = 64 at grouped heads x length = 32K: eight-wave forward and dQ workgroups
 ])
 def test_backward_packed_matches_oracle(sp, dtype, B, Hq, Hkv, L, d, a, n, p, cus):
     rng = np.random.default_rng(L + n + 1)

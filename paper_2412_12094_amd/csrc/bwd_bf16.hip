@@ -458,11 +458,14 @@ __global__ __launch_bounds__(64 * NW, 2) void dq_kernel(
         // every wave has left when it passes the barrier.  The barrier publishes tile gbase+X: each
         // wave has waited for everything older than the previous step's requests.
         const int n_tiles = cseg.n_tiles;
+        // the second block of the last tile is skipped when it is all padding (the same decision in
+        // every wave; the tile loads ride on the first block)
+        const int n_keys = cseg.st.n_total;
         for (int X = 0; X < n_tiles; ++X) {
             wait_older_loads();
             wg_barrier();
             block_step(X, IntC<0>{}, yes);
-            block_step(X, IntC<1>{}, no);
+            if (X * kBN + 32 < n_keys) block_step(X, IntC<1>{}, no);
         }
         gbase += n_tiles;
         const Seg nseg = open_segment(round + 1);

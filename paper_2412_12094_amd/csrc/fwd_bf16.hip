@@ -576,9 +576,10 @@ int launch_fwd(const sepattn_params &p, const uint16_t *Q, const uint16_t *K, co
     // unit: one's segment start and row stores overlap the other's matrix work, their barriers do not
     // lock each other's phases, and the split of a group is twice as fine (it fills the chip where
     // 256 / groups is not a whole number).  A four-wave workgroup has half the query rows per K/V
-    // tile, i.e. twice the tile loads per matrix instruction: with grouped heads and long sequences
-    // the eight-wave shape stays the better one.
-    const bool narrow = D == 64 && (long)G * p.L < 32768;
+    // tile, i.e. twice the tile loads per matrix instruction: where four grouped heads share the
+    // tile (32 positions per workgroup instead of 64) the eight-wave shape stays the better one
+    // (by 2-5 % at any length), with one or two heads per tile the four-wave shape wins (5-25 %).
+    const bool narrow = D == 64 && GP <= 2;
     const int NWr = narrow ? 4 : 8;
     int TP = 32 * NWr / GP;
     const int n_pos_tiles = (p.L + TP - 1) / TP;

@@ -298,7 +298,7 @@ HEADWISE_CASES = [
     (1, 2, 1, 65, 64, 5, 0.3, [1, 2]),
     (1, 16, 2, 900, 128, 4, 0.1, [900, 900, 900, 900, 128, 128, 128, 128, 32, 900, 32, 900, 64, 64, 64, 64]),  # H_s of H heads windowed
     (1, 8, 1, 4096, 128, 4, 0.08, [256, 4096, 64, 256, 1000, 33, 256, 128]),  # grouped heads x length = 32K: the eight-wave dK/dV shape
-    (1, 8, 1, 4096, 64, 4, 0.08, [128, 4096, 64, 128, 1000, 33, 128, 7]),      # ... and the eight-wave forward and dQ workgroups at d = 64
+    (1, 8, 1, 4096, 64, 4, 0.08, [128, 4096, 64, 128, 1000, 33, 128, 7]),      # d = 64, four grouped heads per tile: eight-wave forward and dQ workgroups
 ]
 
 
@@ -449,15 +449,15 @@ def test_config3_full_forward_backward(sp):
 
 
 @pytest.mark.parametrize("B,Hq,Hkv,L,d,a,n,p", [
-    (1, 8, 1, 4096, 64, 4, 128, 0.08),    # d = 64 at grouped heads x length = 32K: eight-wave forward and dQ workgroups
-    (1, 8, 1, 4095, 64, 4, 128, 0.08),    # just below: four-wave workgroups, two (dK/dV: three) per compute unit
+    (1, 8, 1, 4096, 64, 4, 128, 0.08),    # d = 64, four grouped heads per tile: eight-wave forward and dQ workgroups
+    (1, 2, 1, 4095, 64, 4, 128, 0.08),    # two heads per tile: four-wave workgroups, two (dK/dV: three) per compute unit
     (1, 8, 1, 4096, 128, 3, 200, 0.10),   # d = 128 at 32K: the eight-wave dK/dV shape (four key blocks)
     (1, 8, 1, 4095, 128, 3, 200, 0.10),   # just below: two key blocks per workgroup, 32-row query tiles
     (2, 4, 4, 2500, 128, 4, 33, 0.05),    # MHA, window of one block and a bit: no merged head starts with 32-row tiles
 ])
 def test_both_workgroup_shapes_match_the_oracle(sp, B, Hq, Hkv, L, d, a, n, p):
     """The kernels run as one eight-wave workgroup or several four-wave workgroups per compute unit,
-    chosen from grouped heads x length (and d): whole tensors on both sides of the switch."""
+    chosen from the head grouping, grouped heads x length and d: whole tensors on both sides of the switches."""
     tok, Q, K, V, dO = make_case(B, Hq, Hkv, L, d, p, "bf16", 4000 + L + d)
     scale = 1.0 / math.sqrt(d)
     is_sep, idx, cnt, pre = gpu_index(sp, tok)
@@ -846,7 +846,7 @@ def test_doc_bounds_and_forward_packed_match_oracle(sp, dtype, B, Hq, Hkv, L, d,
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 @pytest.mark.parametrize("B,Hq,Hkv,L,d,a,n,p,cus", PACKED_CASES + [
     (1, 8, 2, 2300, 128, 4, 64, 0.15, None),   # several list tiles, documents that end inside them
-    (1, 8, 1, 4096, 64, 3, 100, 0.08, None),   # d = 64 at grouped heads x length = 32K: eight-wave forward and dQ workgroups
+    (1, 8, 1, 4096, 64, 3, 100, 0.08, None),   # d = 64, four grouped heads per tile: eight-wave forward and dQ workgroups
 ])
 def test_backward_packed_matches_oracle(sp, dtype, B, Hq, Hkv, L, d, a, n, p, cus):
     rng = np.random.default_rng(L + n + 1)

@@ -10,7 +10,9 @@ namespace sepattn {
 // A dK/dV workgroup holds KW key blocks of 32 keys, two waves each (32 KW keys, 128 KW threads), in one
 // of two shapes:
 //   KW = 4: 8 waves, one workgroup per compute unit.  Fewest tile loads per matrix instruction; the
-//           better shape when a workgroup's pieces are long (d = 128, grouped heads, long sequences).
+//           better shape when a workgroup's pieces are long: d = 128, sequences from 8K on with
+//           grouped heads (by 3-5 % there; at L = 4096, or with one head per KV head at 8K, the other
+//           shape is 1-13 % ahead, at 16K with one head per KV head the two are level).
 //   KW = 2: 4 waves, two workgroups per compute unit (three at d = 64, where the registers and the ring
 //           of query tiles allow it) that run independently: one's piece start-up and partial stores
 //           overlap the others' matrix work, the split of a (batch, KV head) is finer (it fills the
@@ -22,7 +24,7 @@ namespace sepattn {
 // on the choice.
 inline int dkv_key_blocks(const sepattn_params &p, bool docs) {
     const long G = p.Hq / p.Hkv;
-    return (p.d == 128 && !docs && G * p.L >= 32768) ? 4 : 2;
+    return (p.d == 128 && !docs && p.L >= 8192 && G * p.L >= 32768) ? 4 : 2;
 }
 // workgroups of a shape that share a compute unit
 inline int dkv_workgroups_per_cu(const sepattn_params &p, int kw) { return kw == 4 ? 1 : (p.d == 64 ? 3 : 2); }

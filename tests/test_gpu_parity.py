@@ -297,7 +297,7 @@ HEADWISE_CASES = [
     (1, 4, 1, 300, 64, 0, 0.0, [7, 300, 64, 2]),                              # no separators, no initial tokens
     (1, 2, 1, 65, 64, 5, 0.3, [1, 2]),
     (1, 16, 2, 900, 128, 4, 0.1, [900, 900, 900, 900, 128, 128, 128, 128, 32, 900, 32, 900, 64, 64, 64, 64]),  # H_s of H heads windowed
-    (1, 8, 1, 4096, 128, 4, 0.08, [256, 4096, 64, 256, 1000, 33, 256, 128]),  # grouped heads x length = 32K: the eight-wave dK/dV shape
+    (1, 4, 1, 8192, 128, 4, 0.08, [256, 8192, 64, 33]),  # grouped heads at 8K: the eight-wave dK/dV shape
     (1, 8, 1, 4096, 64, 4, 0.08, [128, 4096, 64, 128, 1000, 33, 128, 7]),      # d = 64, four grouped heads per tile: eight-wave forward and dQ workgroups
 ]
 
@@ -451,8 +451,8 @@ def test_config3_full_forward_backward(sp):
 @pytest.mark.parametrize("B,Hq,Hkv,L,d,a,n,p", [
     (1, 8, 1, 4096, 64, 4, 128, 0.08),    # d = 64, four grouped heads per tile: eight-wave forward and dQ workgroups
     (1, 2, 1, 4095, 64, 4, 128, 0.08),    # two heads per tile: four-wave workgroups, two (dK/dV: three) per compute unit
-    (1, 8, 1, 4096, 128, 3, 200, 0.10),   # d = 128 at 32K: the eight-wave dK/dV shape (four key blocks)
-    (1, 8, 1, 4095, 128, 3, 200, 0.10),   # just below: two key blocks per workgroup, 32-row query tiles
+    (1, 4, 1, 8192, 128, 3, 200, 0.10),   # d = 128, grouped heads, 8K: the eight-wave dK/dV shape (four key blocks)
+    (1, 4, 1, 8191, 128, 3, 200, 0.10),   # just below: two key blocks per workgroup, 32-row query tiles
     (2, 4, 4, 2500, 128, 4, 33, 0.05),    # MHA, window of one block and a bit: no merged head starts with 32-row tiles
 ])
 def test_both_workgroup_shapes_match_the_oracle(sp, B, Hq, Hkv, L, d, a, n, p):
